@@ -1,0 +1,146 @@
+"""Pins for the oracle's histogram, TopHot cache selection, cache fill and gather (CPU only)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from synth import TAG_CACHE, TAG_LOCAL, TAG_REMOTE, TAG_SHIFT, ROW_MASK
+
+
+def _tag(words):
+    return (np.asarray(words).astype(np.int64) & 0xFFFFFFFF) >> TAG_SHIFT
+
+
+def _row(words):
+    return (np.asarray(words).astype(np.int64) & 0xFFFFFFFF) & ROW_MASK
+
+
+def test_histogram_is_bincount_and_accumulates():
+    rng = np.random.default_rng(0)
+    n = 5000
+    a = rng.integers(0, n, size=40_000).astype(np.int32)
+    b = rng.integers(0, 50, size=10_000).astype(np.int32)
+    counts = np.zeros(n, dtype=np.uint32)
+    oracle.access_histogram(a, counts)
+    assert np.array_equal(counts, np.bincount(a, minlength=n).astype(np.uint32))
+    oracle.access_histogram(b, counts)
+    assert np.array_equal(counts, (np.bincount(a, minlength=n) + np.bincount(b, minlength=n)).astype(np.uint32))
+    assert counts.sum() == a.size + b.size
+    oracle.access_histogram(np.empty(0, dtype=np.int32), counts)
+    assert counts.sum() == a.size + b.size
+
+
+def _topk_bruteforce(counts, home, capacity):
+    ids = np.flatnonzero((_tag(home) == TAG_REMOTE) & (counts >= 1))
+    order = ids[np.lexsort((ids, -counts[ids].astype(np.int64)))]      # count desc, then id asc
+    chosen = np.sort(order[:max(0, min(capacity, order.size))])
+    loc = home.copy().astype(np.int64) & 0xFFFFFFFF
+    loc[chosen] = (TAG_CACHE << TAG_SHIFT) | np.arange(chosen.size)
+    return chosen, loc
+
+
+@pytest.mark.parametrize("capacity", [0, 1, 7, 100, 399, 400, 401, 10_000])
+def test_topk_matches_full_sort(capacity):
+    rng = np.random.default_rng(capacity)
+    n = 3000
+    is_local = torch_mask(n, rng)
+    home = synth.stores.make_home(is_local).numpy()
+    counts = rng.integers(0, 6, size=n).astype(np.uint32)           # many ties, many zeros
+    counts[rng.integers(0, n, 5)] = 2 ** 31 + 5                     # counts above 2^31 order correctly
+    ids, loc = oracle.build_cache(counts, home, capacity)
+    want_ids, want_loc = _topk_bruteforce(counts, home, capacity)
+    assert ids.tolist() == want_ids.tolist()
+    assert np.array_equal(loc.astype(np.int64) & 0xFFFFFFFF, want_loc)
+    # invariants
+    cand = np.flatnonzero((_tag(home) == TAG_REMOTE) & (counts >= 1))
+    assert ids.size == min(capacity, cand.size)
+    assert np.all(np.diff(ids) > 0)
+    assert np.all(_tag(home[ids]) == TAG_REMOTE) and np.all(counts[ids] >= 1)
+    outside = np.setdiff1d(cand, ids)
+    if ids.size and outside.size:
+        worst_in = min((int(counts[v]), -int(v)) for v in ids)
+        best_out = max((int(counts[v]), -int(v)) for v in outside)
+        assert worst_in > best_out
+    assert np.array_equal(_row(loc[ids]), np.arange(ids.size))
+    rest = np.setdiff1d(np.arange(n), ids)
+    assert np.array_equal(loc[rest], home[rest])
+
+
+def torch_mask(n, rng):
+    import torch
+    return torch.from_numpy(rng.random(n) < 0.3)
+
+
+def test_topk_ties_break_to_lower_id():
+    import torch
+    home = synth.stores.make_home(torch.zeros(10, dtype=torch.bool)).numpy()    # all remote
+    counts = np.array([2, 5, 2, 2, 0, 5, 2, 1, 2, 2], dtype=np.uint32)
+    ids, _ = oracle.build_cache(counts, home, 4)
+    assert ids.tolist() == [0, 1, 2, 5]                   # both 5s, then the two lowest ids with count 2
+    ids, _ = oracle.build_cache(counts, home, 100)
+    assert ids.tolist() == [0, 1, 2, 3, 5, 6, 7, 8, 9]     # never caches the zero-count node
+
+
+def test_gather_is_plain_indexing_and_hit_rate_closed_form():
+    wl = synth.build_workload("tiny", seed=7)
+    cfg = wl.cfg
+    X = wl.features.numpy()
+    rp = wl.row_ptr.numpy().astype(np.int64)
+    ci = wl.col_idx.numpy()
+    home = wl.home.numpy()
+    counts = np.zeros(cfg.num_nodes, dtype=np.uint32)
+    batches = oracle.epoch_batches(wl.train_ids.numpy(), cfg.batch_size, wl.seed, 0, cfg.max_batches)
+    assert len(batches) == 4
+    inputs = []
+    for seeds in batches:
+        blk = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, 0)
+        inputs.append(blk.input_nodes)
+        oracle.access_histogram(blk.input_nodes, counts)
+    assert counts.sum() == sum(x.size for x in inputs)                       # (d) totals
+    assert counts.max() <= len(batches)                                      # ids unique per batch
+    ids, loc = oracle.build_cache(counts, home, wl.capacity_rows)
+    assert wl.capacity_rows == 500 and ids.size == 500
+    rows = oracle.fill_cache(X, ids, wl.stride)
+    assert np.array_equal(rows[:, :cfg.feat_dim], X[ids])
+    # the packed stores hold the same rows the location words point at
+    loc_u = loc.astype(np.int64) & 0xFFFFFFFF
+    local_rows = wl.local_store.numpy()
+    remote_rows = wl.remote_store.numpy()
+    for v in (0, 1, 2, 3, 4999, 9998, 9999):
+        store = local_rows if _tag(home[v]) == TAG_LOCAL else remote_rows
+        assert np.array_equal(store[_row(home[v]), :cfg.feat_dim], X[v])
+    tot_hit = tot_miss = tot_local = 0
+    for nodes in inputs:
+        out, (n_local, n_hit, n_miss) = oracle.gather_features(X, nodes, loc, wl.stride)
+        assert np.array_equal(out[:, :cfg.feat_dim], X[nodes])
+        assert n_local + n_hit + n_miss == nodes.size
+        tags = loc_u[nodes] >> TAG_SHIFT
+        assert (n_local, n_hit, n_miss) == tuple(int((tags == t).sum()) for t in (TAG_LOCAL, TAG_CACHE, TAG_REMOTE))
+        tot_local += n_local
+        tot_hit += n_hit
+        tot_miss += n_miss
+    remote = _tag(home) == TAG_REMOTE
+    assert tot_hit == int(counts[ids].sum())                                 # hits predicted by the histogram
+    assert tot_hit + tot_miss == int(counts[remote].sum())
+    assert tot_local == int(counts[~remote].sum())
+    assert 0 < tot_hit < tot_hit + tot_miss
+
+
+def test_miss_bytes_follow_paper_accounting(golden_dir):
+    """Remote rows fetched * 4*D bytes reproduces the figures the paper prints."""
+    kv = {}
+    with open(os.path.join(golden_dir, "paper_byte_accounting.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                kv[k] = float(v)
+
+    def miss_bytes(n_miss, dim):
+        return n_miss * 4 * dim
+    assert miss_bytes(kv["remote_rows_per_batch"], kv["feature_tensor_dim"]) == kv["per_batch_bytes"]
+    assert round(kv["per_batch_bytes"] / 2 ** 20, 2) == kv["per_batch_mib"]
+    assert round(kv["batches_per_epoch"] * kv["per_batch_bytes"] / 1e9, 1) == kv["epoch_gb"]
+    assert round(miss_bytes(kv["table4_rows_rapidgnn"], kv["table4_dim"]) / 2 ** 20) == kv["table4_mb_rapidgnn"]
+    assert round(miss_bytes(kv["table4_rows_baseline"], kv["table4_dim"]) / 2 ** 20) == kv["table4_mb_baseline"]
