@@ -1,0 +1,220 @@
+/*
+ * rapidgnn.h -- C ABI of the MI355X (gfx950) data path of RapidGNN (arxiv 2505.10806).
+ *
+ * The library implements the steps of the paper's Algorithm 1 that move data:
+ *   line 1     precompute the mini-batches of an epoch with a seeded sampler  -> rg_epoch_schedule, rg_sample_blocks
+ *   line 2-3   access frequencies of the precomputed input nodes, TopHot      -> rg_access_histogram, rg_build_cache
+ *   line 4     VectorPull of the hot rows into the steady cache C_s           -> rg_build_cache (fill)
+ *   line 12-14 per-batch feature assembly from local store, cache and         -> rg_gather_features
+ *              fallback pull of the misses from the remote store
+ * Every step runs in HIP kernels on the device; there is no CPU fallback.
+ *
+ * Conventions
+ *  - "device" pointers are HBM allocations of the ctx's GPU; "host" pointers are ordinary
+ *    host memory read during the call; "mapped" pointers are device-accessible memory that
+ *    may live in pinned host memory (hipHostMalloc / torch pin_memory) or in HBM.
+ *  - All buffers are caller-owned and only borrowed for the call (until the work queued on
+ *    the stream has finished).  The library owns nothing but the scratch inside rg_ctx.
+ *  - Calls are asynchronous on the given hipStream_t (passed as void*; NULL = the default
+ *    stream).  Device-resident outputs are valid once that stream has been synchronised.
+ *  - Every call validates its arguments on the host before launching anything and returns
+ *    RG_ERR_INVALID_ARG / RG_ERR_CAPACITY without side effects when they are wrong;
+ *    rg_last_error() then holds a message.  Node ids out of [0, num_nodes) inside device
+ *    arrays are a precondition violation and are not checked.
+ *  - One rg_ctx serves one host thread.  Calls of the same kind (two samplers, two gathers)
+ *    share scratch and must be ordered on the stream(s) they use; calls of different kinds
+ *    use disjoint scratch.
+ *  - Location word (used by home[] and loc[]): (tag << 30) | row as uint32 stored in int32;
+ *    tag 0 = row of the local store, 1 = row (slot) of the cache, 2 = row of the remote store.
+ *  - Row strides are in floats.  Rows are copied with 16-byte accesses when every base
+ *    pointer is 16-byte aligned and every stride is a multiple of 4 floats; in that case the
+ *    copy covers round_up(dim, 4) floats, i.e. up to 3 floats of row padding are read from
+ *    the source row and written to the destination row.  Otherwise 8- or 4-byte accesses
+ *    copy exactly dim floats.
+ */
+#ifndef RAPIDGNN_H
+#define RAPIDGNN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#ifndef RG_API
+#if defined(__GNUC__) || defined(__clang__)
+#define RG_API __attribute__((visibility("default")))
+#else
+#define RG_API
+#endif
+#endif
+
+typedef enum {
+    RG_OK = 0,
+    RG_ERR_INVALID_ARG = 1,   /* null pointer, negative size, bad stride, unsupported value */
+    RG_ERR_CAPACITY = 2,      /* an output buffer is smaller than the static bound (see rg_blocks_bounds) */
+    RG_ERR_OOM = 3,           /* scratch allocation failed */
+    RG_ERR_HIP = 4,           /* a HIP runtime call failed; message in rg_last_error */
+    RG_ERR_STATE = 5          /* call not valid in the ctx's current state */
+} rg_status;
+
+#define RG_TAG_LOCAL 0u
+#define RG_TAG_CACHE 1u
+#define RG_TAG_REMOTE 2u
+#define RG_TAG_SHIFT 30
+#define RG_ROW_MASK ((1u << RG_TAG_SHIFT) - 1u)
+
+/* Largest per-hop fan-out drawn with Floyd's algorithm.  RG_FANOUT_ALL takes every neighbour. */
+#define RG_MAX_FANOUT 1024
+#define RG_FANOUT_ALL (-1)
+#define RG_MAX_HOPS 8
+
+typedef struct rg_ctx rg_ctx;
+
+/* Create / destroy a context bound to HIP device `device`.  rg_destroy synchronises the
+ * device and frees the scratch.  rg_last_error returns a ctx-owned string (never freed by
+ * the caller; valid until the next failing call); with ctx == NULL it returns the message of
+ * the last failed rg_create. */
+RG_API rg_status rg_create(int device, rg_ctx** out);
+RG_API void rg_destroy(rg_ctx* ctx);
+RG_API const char* rg_last_error(const rg_ctx* ctx);
+RG_API const char* rg_version(void);
+
+/* Pre-size the scratch so later calls allocate nothing: graphs of up to num_nodes nodes,
+ * cumulative frontiers of up to max_frontier nodes, gathers of up to max_rows rows.
+ * Optional: every call grows the scratch on demand (a synchronising allocation). */
+RG_API rg_status rg_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int64_t max_rows);
+
+/* CSR adjacency in HBM: row v lists the nodes whose features v aggregates (Eq. 1, eta(v)). */
+typedef struct {
+    int64_t num_nodes;
+    int64_t num_edges;
+    const void* row_ptr;      /* device, int32[num_nodes+1] or int64[num_nodes+1] */
+    int32_t row_ptr_bits;     /* 32 or 64 */
+    const int32_t* col_idx;   /* device, int32[num_edges] */
+} rg_csr;
+
+/* ---- Alg. 1 line 1, the epoch's batch order -------------------------------------------
+ * order_out = train_ids sorted ascending by (key64(v), v), key64(v) = first two words of the
+ * Philox4x32-10 block with counter (v, 0xFFFFFFFF, 0, epoch) and key (seed lo, seed hi).
+ * Batches are consecutive chunks of the order; the partial last chunk is a batch
+ * (Section II-E counts ceil(n/B) batches).
+ * train_ids: device int32[n] (distinct ids); order_out: device int32[n]; n >= 0. */
+RG_API rg_status rg_epoch_schedule(rg_ctx* ctx, const int32_t* train_ids, int64_t n, uint64_t seed,
+                            uint32_t epoch, int32_t* order_out, void* stream);
+
+/* ---- Alg. 1 line 1, one precomputed mini-batch b_i^e ------------------------------------
+ * Node-wise neighbour sampling SAMPLE(eta(v), k) (Section II-B) over num_hops hops.
+ *   frontier_0 = seeds (given order).  For hop h: every node v of frontier_h draws
+ *   m = min(fanouts[h], deg v) distinct neighbours (all of them, in row order, when
+ *   deg v <= fanouts[h] or fanouts[h] == RG_FANOUT_ALL; otherwise Floyd's subset algorithm on
+ *   row positions, draw i = word i&3 of the Philox4x32-10 block with counter
+ *   (v, h, i>>2, epoch) and key (seed lo, seed hi), bounded by the high word of draw*(j+1));
+ *   indptr[h] = exclusive prefix sum of m in frontier order; nbr[h] = neighbours in frontier
+ *   order, per node in insertion order; tier_{h+1} = ids in nbr[h] not in frontier_h, unique,
+ *   ascending; frontier_{h+1} = frontier_h ++ tier_{h+1}; nbr_local[h][e] = position of
+ *   nbr[h][e] in frontier_{h+1}.  nodes = frontier_H is the batch's input-node list N_i^e;
+ *   tier_off[t] = start of tier t in nodes (tier 0 = seeds), tier_off[num_hops+1] = |N_i^e|.
+ * The result depends only on (graph, seeds, fanouts, seed, epoch): bit-reproducible.
+ */
+typedef struct {
+    int32_t* nodes;            /* device int32[nodes_cap] */
+    int64_t nodes_cap;
+    int32_t* tier_off;         /* device int32[num_hops + 2] */
+    int32_t* const* indptr;    /* host array[num_hops] of device int32[indptr_cap[h]] */
+    const int64_t* indptr_cap; /* host int64[num_hops] */
+    int32_t* const* nbr;       /* host array[num_hops] of device int32[nbr_cap[h]] */
+    int32_t* const* nbr_local; /* host array[num_hops] of device int32[nbr_cap[h]], or NULL to skip relabelling */
+    const int64_t* nbr_cap;    /* host int64[num_hops] */
+} rg_blocks;
+
+/* Static bounds the output buffers of rg_sample_blocks must meet:
+ *   frontier_ub[0] = min(N, B);
+ *   edges_ub[h]    (h = 0..num_hops-1) bounds |nbr[h]|:     min(nnz, frontier_ub[h] * F_h), nnz for RG_FANOUT_ALL;
+ *   frontier_ub[h+1] bounds |frontier_{h+1}|:                min(N, frontier_ub[h] + edges_ub[h])
+ *                                                            (<= min(N, B * prod_{t<=h} (1+F_t))).
+ * Required: nodes_cap >= frontier_ub[num_hops], indptr_cap[h] >= frontier_ub[h] + 1,
+ * nbr_cap[h] >= edges_ub[h].  Host arrays, written by the call. */
+RG_API rg_status rg_blocks_bounds(int64_t num_nodes, int64_t num_edges, int64_t num_seeds,
+                           const int32_t* fanouts, int32_t num_hops,
+                           int64_t* frontier_ub, int64_t* edges_ub);
+
+/* seeds: device int32[num_seeds], distinct, num_seeds >= 0; fanouts: host int32[num_hops],
+ * each in [0, RG_MAX_FANOUT] or RG_FANOUT_ALL; 1 <= num_hops <= RG_MAX_HOPS.
+ * Errors: RG_ERR_INVALID_ARG, RG_ERR_CAPACITY (buffers below the bounds), RG_ERR_OOM. */
+RG_API rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds, int32_t num_seeds,
+                           const int32_t* fanouts, int32_t num_hops, uint64_t seed, uint32_t epoch,
+                           const rg_blocks* out, void* stream);
+
+/* ---- Alg. 1 line 2 / Section IV: access frequency freq(n) -------------------------------
+ * counts[v] += number of occurrences of v in nodes[0..n).  counts accumulates over calls
+ * (the caller zeroes it to start a new period) and covers every node; the remote filter is
+ * applied by rg_build_cache.
+ * nodes: device int32[>= n]; counts: device uint32[num_nodes].
+ * n_dev: optional device int32* holding the actual entry count (e.g. tier_off + num_hops + 1
+ * of a batch sampled on the same stream); when non-NULL, n is only an upper bound used to
+ * size the launch and min(n, *n_dev) entries are read. */
+RG_API rg_status rg_access_histogram(rg_ctx* ctx, const int32_t* nodes, int64_t n, const int32_t* n_dev,
+                              uint32_t* counts, int64_t num_nodes, void* stream);
+
+/* ---- Alg. 1 lines 3-4: TopHot + VectorPull -----------------------------------------------
+ * Candidates = nodes whose home word is remote and whose count >= 1, ranked by
+ * (count descending, id ascending).  K_eff = min(capacity_rows, #candidates) are selected;
+ * cache_ids = selected ids ascending, slot = rank in that order; loc[v] = cache word for the
+ * selected nodes and home[v] for all others; cache_rows[slot] = remote_store row of the node
+ * (one bulk pull over the host link).  *num_cached = K_eff.
+ */
+typedef struct {
+    int32_t* cache_ids;       /* device int32[capacity_rows] */
+    float* cache_rows;        /* device float[capacity_rows * row_stride] */
+    int64_t capacity_rows;    /* >= 0 */
+    int64_t row_stride;       /* floats, >= dim */
+    int32_t* loc;             /* device int32[num_nodes] location words */
+    int64_t* num_cached;      /* device int64[1], written by rg_build_cache */
+} rg_cache;
+
+/* counts: device uint32[num_nodes]; home: device int32[num_nodes] (never modified);
+ * remote_store: mapped float[n_remote * remote_stride]; dim >= 1. */
+RG_API rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32_t* home, int64_t num_nodes,
+                         const float* remote_store, int64_t remote_stride, int32_t dim,
+                         const rg_cache* cache, void* stream);
+
+/* ---- Alg. 1 lines 12-14: feature assembly for one batch ---------------------------------
+ * out[i][0:dim] = feature row of input_nodes[i], read from the store loc[] names: local
+ * store (HBM), cache (HBM, GetFeatureFromCache) or remote store (fallback pull of the
+ * misses only).  stats = {#local rows, #cache hits, #misses}.
+ * Rows served from HBM are copied on hit_stream; the miss rows are copied on miss_stream
+ * concurrently (if it differs from hit_stream) and joined back: when the call returns, all
+ * work is ordered before anything queued later on hit_stream.
+ * input_nodes: device int32[>= n]; n_dev: as for rg_access_histogram; out: device
+ * float[n * out_stride]; stats: device int64[3]. */
+typedef struct { int64_t n_local, n_hit, n_miss; } rg_gather_stats;
+
+RG_API rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
+                             const rg_cache* cache,
+                             const float* local_store, int64_t local_stride,
+                             const float* remote_store, int64_t remote_stride,
+                             int32_t dim, float* out, int64_t out_stride,
+                             rg_gather_stats* stats, void* hit_stream, void* miss_stream);
+
+/* ---- kernel timing for the benchmark ------------------------------------------------------
+ * With profiling on, every launch of the listed kernels is bracketed by hipEvents on its own
+ * stream.  rg_profile_read synchronises the recorded events and returns the summed duration
+ * and launch count since the last rg_profile_reset. */
+typedef enum {
+    RG_K_GATHER_HBM = 0,   /* rows served from the local store and the cache */
+    RG_K_GATHER_MISS = 1,  /* rows pulled from the remote store */
+    RG_K_SAMPLE = 2,       /* per-hop draw + neighbour read kernel */
+    RG_K_HISTOGRAM = 3,
+    RG_K_CACHE_FILL = 4,
+    RG_K_COUNT_
+} rg_kernel_id;
+
+RG_API rg_status rg_profile_enable(rg_ctx* ctx, int on);
+RG_API rg_status rg_profile_reset(rg_ctx* ctx);
+RG_API rg_status rg_profile_read(rg_ctx* ctx, int kernel_id, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAPIDGNN_H */

@@ -1,0 +1,277 @@
+"""Thin ctypes binding of librapidgnn.so: argument marshalling only.
+
+Function names mirror the C ABI (include/rapidgnn.h).  Tensors are torch tensors that own
+the device (or pinned host) memory; every step of the path runs inside the library's HIP
+kernels.  There is no fallback: if the shared library is missing or cannot be loaded the
+import of this module raises.
+"""
+import ctypes
+import os
+
+import torch  # noqa: F401  (loaded first so the HIP runtime already in the process is shared)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librapidgnn.so")
+
+RG_OK, RG_ERR_INVALID_ARG, RG_ERR_CAPACITY, RG_ERR_OOM, RG_ERR_HIP, RG_ERR_STATE = range(6)
+RG_MAX_FANOUT = 1024
+RG_FANOUT_ALL = -1
+RG_MAX_HOPS = 8
+RG_K_GATHER_HBM, RG_K_GATHER_MISS, RG_K_SAMPLE, RG_K_HISTOGRAM, RG_K_CACHE_FILL = range(5)
+
+_STATUS_NAMES = {0: "RG_OK", 1: "RG_ERR_INVALID_ARG", 2: "RG_ERR_CAPACITY", 3: "RG_ERR_OOM",
+                 4: "RG_ERR_HIP", 5: "RG_ERR_STATE"}
+
+c_i64, c_i32, c_u64, c_u32 = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_uint32
+c_p = ctypes.c_void_p
+
+
+class RgError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{_STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+class rg_csr(ctypes.Structure):
+    _fields_ = [("num_nodes", c_i64), ("num_edges", c_i64), ("row_ptr", c_p),
+                ("row_ptr_bits", c_i32), ("col_idx", c_p)]
+
+
+class rg_blocks(ctypes.Structure):
+    _fields_ = [("nodes", c_p), ("nodes_cap", c_i64), ("tier_off", c_p),
+                ("indptr", ctypes.POINTER(c_p)), ("indptr_cap", ctypes.POINTER(c_i64)),
+                ("nbr", ctypes.POINTER(c_p)), ("nbr_local", ctypes.POINTER(c_p)),
+                ("nbr_cap", ctypes.POINTER(c_i64))]
+
+
+class rg_cache(ctypes.Structure):
+    _fields_ = [("cache_ids", c_p), ("cache_rows", c_p), ("capacity_rows", c_i64),
+                ("row_stride", c_i64), ("loc", c_p), ("num_cached", c_p)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                          "(python -m paper_2505_10806_amd.build); there is no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    L.rg_create.argtypes = [ctypes.c_int, ctypes.POINTER(c_p)]
+    L.rg_destroy.argtypes = [c_p]
+    L.rg_destroy.restype = None
+    L.rg_last_error.argtypes = [c_p]
+    L.rg_last_error.restype = ctypes.c_char_p
+    L.rg_version.argtypes = []
+    L.rg_version.restype = ctypes.c_char_p
+    L.rg_reserve.argtypes = [c_p, c_i64, c_i64, c_i64]
+    L.rg_epoch_schedule.argtypes = [c_p, c_p, c_i64, c_u64, c_u32, c_p, c_p]
+    L.rg_blocks_bounds.argtypes = [c_i64, c_i64, c_i64, c_p, c_i32, c_p, c_p]
+    L.rg_sample_blocks.argtypes = [c_p, ctypes.POINTER(rg_csr), c_p, c_i32, c_p, c_i32, c_u64, c_u32,
+                                   ctypes.POINTER(rg_blocks), c_p]
+    L.rg_access_histogram.argtypes = [c_p, c_p, c_i64, c_p, c_p, c_i64, c_p]
+    L.rg_build_cache.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i64, c_i32, ctypes.POINTER(rg_cache), c_p]
+    L.rg_gather_features.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_i64, c_p, c_i64,
+                                     c_i32, c_p, c_i64, c_p, c_p, c_p]
+    L.rg_profile_enable.argtypes = [c_p, ctypes.c_int]
+    L.rg_profile_reset.argtypes = [c_p]
+    L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
+    for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks",
+                 "rg_access_histogram", "rg_build_cache", "rg_gather_features", "rg_profile_enable",
+                 "rg_profile_reset", "rg_profile_read"):
+        getattr(L, name).restype = ctypes.c_int
+    return L
+
+
+_lib = _load()
+
+EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "rg_reserve", "rg_epoch_schedule",
+                    "rg_blocks_bounds", "rg_sample_blocks", "rg_access_histogram", "rg_build_cache",
+                    "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
+
+
+def _ptr(t, dtype=None, device_type=None, name="tensor"):
+    """Raw address of a contiguous tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if device_type is not None and t.device.type != device_type and not (device_type == "mapped"):
+        raise ValueError(f"{name}: expected a {device_type} tensor, got {t.device}")
+    if device_type == "mapped" and t.device.type != "cuda" and not t.is_pinned():
+        raise ValueError(f"{name}: host tensor must be pinned to be read from the device")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream_handle(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+class Context:
+    """Owns an rg_ctx.  Methods carry the C names without the rg_ prefix."""
+
+    def __init__(self, device=0):
+        h = c_p()
+        st = _lib.rg_create(int(device), ctypes.byref(h))
+        if st != RG_OK:
+            raise RgError(st, _lib.rg_last_error(None).decode())
+        self._h = h
+        self.device = int(device)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.rg_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st):
+        if st != RG_OK:
+            raise RgError(st, _lib.rg_last_error(self._h).decode())
+
+    # -- rg_reserve
+    def reserve(self, num_nodes, max_frontier, max_rows):
+        self._check(_lib.rg_reserve(self._h, int(num_nodes), int(max_frontier), int(max_rows)))
+
+    # -- rg_epoch_schedule
+    def epoch_schedule(self, train_ids, seed, epoch, order_out=None, stream=None):
+        n = train_ids.numel()
+        if order_out is None:
+            order_out = torch.empty_like(train_ids)
+        self._check(_lib.rg_epoch_schedule(self._h, _ptr(train_ids, torch.int32, "cuda", "train_ids"), n,
+                                           int(seed), int(epoch), _ptr(order_out, torch.int32, "cuda", "order_out"),
+                                           _stream_handle(stream)))
+        return order_out
+
+    # -- rg_sample_blocks
+    def sample_blocks(self, csr, seeds, num_seeds, fanouts, seed, epoch, out, stream=None):
+        """csr: CsrGraph; seeds: int32 cuda tensor; out: BlockBuffers."""
+        fo = (c_i32 * len(fanouts))(*[int(f) for f in fanouts])
+        self._check(_lib.rg_sample_blocks(self._h, ctypes.byref(csr.c_struct), _ptr(seeds, torch.int32, "cuda", "seeds"),
+                                          int(num_seeds), fo, len(fanouts), int(seed), int(epoch),
+                                          ctypes.byref(out.c_struct), _stream_handle(stream)))
+
+    # -- rg_access_histogram
+    def access_histogram(self, nodes, n, counts, n_dev=None, stream=None):
+        self._check(_lib.rg_access_histogram(self._h, _ptr(nodes, torch.int32, "cuda", "nodes"), int(n),
+                                             _ptr(n_dev, torch.int32, "cuda", "n_dev"),
+                                             _ptr(counts, torch.int32, "cuda", "counts"), counts.numel(),
+                                             _stream_handle(stream)))
+
+    # -- rg_build_cache
+    def build_cache(self, counts, home, remote_store, dim, cache, stream=None):
+        self._check(_lib.rg_build_cache(self._h, _ptr(counts, torch.int32, "cuda", "counts"),
+                                        _ptr(home, torch.int32, "cuda", "home"), home.numel(),
+                                        _ptr(remote_store, torch.float32, "mapped", "remote_store"),
+                                        remote_store.stride(0) if remote_store.dim() == 2 else dim, int(dim),
+                                        ctypes.byref(cache.c_struct), _stream_handle(stream)))
+
+    # -- rg_gather_features
+    def gather_features(self, input_nodes, n, cache, local_store, remote_store, dim, out, stats,
+                        n_dev=None, hit_stream=None, miss_stream=None):
+        self._check(_lib.rg_gather_features(
+            self._h, _ptr(input_nodes, torch.int32, "cuda", "input_nodes"), int(n),
+            _ptr(n_dev, torch.int32, "cuda", "n_dev"), ctypes.byref(cache.c_struct),
+            _ptr(local_store, torch.float32, "cuda", "local_store"), local_store.stride(0),
+            _ptr(remote_store, torch.float32, "mapped", "remote_store"), remote_store.stride(0),
+            int(dim), _ptr(out, torch.float32, "cuda", "out"), out.stride(0),
+            _ptr(stats, torch.int64, "cuda", "stats"), _stream_handle(hit_stream),
+            None if miss_stream is None else _stream_handle(miss_stream)))
+
+    # -- rg_profile_*
+    def profile_enable(self, on=True):
+        self._check(_lib.rg_profile_enable(self._h, 1 if on else 0))
+
+    def profile_reset(self):
+        self._check(_lib.rg_profile_reset(self._h))
+
+    def profile_read(self, kernel_id):
+        ms = ctypes.c_double()
+        cnt = c_i64()
+        self._check(_lib.rg_profile_read(self._h, int(kernel_id), ctypes.byref(ms), ctypes.byref(cnt)))
+        return ms.value, cnt.value
+
+
+def blocks_bounds(num_nodes, num_edges, num_seeds, fanouts):
+    """rg_blocks_bounds: (frontier_ub[H+1], edges_ub[H]) as Python lists."""
+    H = len(fanouts)
+    fo = (c_i32 * H)(*[int(f) for f in fanouts])
+    fub = (c_i64 * (H + 1))()
+    eub = (c_i64 * H)()
+    st = _lib.rg_blocks_bounds(int(num_nodes), int(num_edges), int(num_seeds), fo, H, fub, eub)
+    if st != RG_OK:
+        raise RgError(st, "rg_blocks_bounds: invalid argument")
+    return list(fub), list(eub)
+
+
+def version():
+    return _lib.rg_version().decode()
+
+
+class CsrGraph:
+    """rg_csr over two cuda tensors (kept alive by this object)."""
+
+    def __init__(self, row_ptr, col_idx):
+        if row_ptr.dtype not in (torch.int32, torch.int64):
+            raise TypeError("row_ptr must be int32 or int64")
+        self.row_ptr, self.col_idx = row_ptr, col_idx
+        self.num_nodes = row_ptr.numel() - 1
+        self.num_edges = col_idx.numel()
+        self.c_struct = rg_csr(self.num_nodes, self.num_edges, _ptr(row_ptr, None, "cuda", "row_ptr"),
+                               32 if row_ptr.dtype == torch.int32 else 64, _ptr(col_idx, torch.int32, "cuda", "col_idx"))
+
+
+class BlockBuffers:
+    """Caller-owned output buffers of rg_sample_blocks, sized by rg_blocks_bounds."""
+
+    def __init__(self, num_nodes, num_edges, max_seeds, fanouts, device, with_local=True, nodes=None):
+        self.fanouts = tuple(int(f) for f in fanouts)
+        H = len(self.fanouts)
+        self.frontier_ub, self.edges_ub = blocks_bounds(num_nodes, num_edges, max_seeds, self.fanouts)
+        i32 = dict(dtype=torch.int32, device=device)
+        self.nodes = nodes if nodes is not None else torch.empty(max(self.frontier_ub[H], 1), **i32)
+        self.tier_off = torch.zeros(H + 2, **i32)
+        self.indptr = [torch.empty(self.frontier_ub[h] + 1, **i32) for h in range(H)]
+        self.nbr = [torch.empty(max(self.edges_ub[h], 1), **i32) for h in range(H)]
+        self.nbr_local = [torch.empty(max(self.edges_ub[h], 1), **i32) for h in range(H)] if with_local else None
+        self._build_struct()
+
+    def _build_struct(self):
+        H = len(self.fanouts)
+        self._indptr_arr = (c_p * H)(*[t.data_ptr() for t in self.indptr])
+        self._nbr_arr = (c_p * H)(*[t.data_ptr() for t in self.nbr])
+        self._loc_arr = (c_p * H)(*[t.data_ptr() for t in self.nbr_local]) if self.nbr_local else None
+        self._indptr_cap = (c_i64 * H)(*[t.numel() for t in self.indptr])
+        self._nbr_cap = (c_i64 * H)(*[t.numel() for t in self.nbr])
+        self.c_struct = rg_blocks(
+            self.nodes.data_ptr(), self.nodes.numel(), self.tier_off.data_ptr(),
+            ctypes.cast(self._indptr_arr, ctypes.POINTER(c_p)), ctypes.cast(self._indptr_cap, ctypes.POINTER(c_i64)),
+            ctypes.cast(self._nbr_arr, ctypes.POINTER(c_p)),
+            ctypes.cast(self._loc_arr, ctypes.POINTER(c_p)) if self._loc_arr is not None else None,
+            ctypes.cast(self._nbr_cap, ctypes.POINTER(c_i64)))
+
+    def set_nodes(self, nodes):
+        """Point the input-node output at another buffer (e.g. a per-batch slot of an epoch arena)."""
+        self.nodes = nodes
+        self.c_struct.nodes = nodes.data_ptr()
+        self.c_struct.nodes_cap = nodes.numel()
+
+
+class FeatureCache:
+    """rg_cache over caller-owned cuda tensors."""
+
+    def __init__(self, num_nodes, capacity_rows, row_stride, device):
+        self.capacity_rows = int(capacity_rows)
+        self.cache_ids = torch.empty(max(self.capacity_rows, 1), dtype=torch.int32, device=device)
+        self.cache_rows = torch.empty(max(self.capacity_rows, 1), int(row_stride), dtype=torch.float32, device=device)
+        self.loc = torch.empty(max(num_nodes, 1), dtype=torch.int32, device=device)
+        self.num_cached = torch.zeros(1, dtype=torch.int64, device=device)
+        self.c_struct = rg_cache(self.cache_ids.data_ptr(), self.cache_rows.data_ptr(), self.capacity_rows,
+                                 int(row_stride), self.loc.data_ptr(), self.num_cached.data_ptr())

@@ -1,0 +1,238 @@
+// Per-batch feature assembly (Alg. 1 lines 12-14): rows of the batch's input nodes are copied from the
+// local store (HBM), the steady cache (HBM) or, for misses only, the remote store (pinned host memory).
+//
+// Three kernels: classify resolves every output row to a location word (one random 4-byte read of loc[]
+// per row), counts the three classes and compacts the indices of the miss rows; the HBM kernel copies
+// local and cached rows; the miss kernel copies the remote rows and may run on a second stream so the
+// host-link transfers overlap the HBM copies.
+#include <stdlib.h>
+
+#include "rg_rowcopy.h"
+
+namespace {
+
+__device__ __forceinline__ int64_t rg_actual_n(int64_t n, const int32_t* __restrict__ n_dev) {
+    if (!n_dev) return n;
+    const int64_t d = *n_dev;
+    return d < n ? d : n;
+}
+
+__global__ void k_gather_reset(uint32_t* __restrict__ gctl, unsigned long long* __restrict__ stats) {
+    if (threadIdx.x == 0) gctl[0] = 0u;
+    if (threadIdx.x < 3) stats[threadIdx.x] = 0ull;
+}
+
+__global__ void __launch_bounds__(256) k_classify(const int32_t* __restrict__ nodes, int64_t n, const int32_t* __restrict__ n_dev,
+                                                  const int32_t* __restrict__ loc, uint32_t* __restrict__ src,
+                                                  int32_t* __restrict__ miss_list, uint32_t* __restrict__ gctl,
+                                                  unsigned long long* __restrict__ stats) {
+    __shared__ int smem[256 / RG_WAVE + 1];
+    __shared__ int cls[3][4];
+    __shared__ uint32_t miss_base;
+    const int64_t n_act = rg_actual_n(n, n_dev);
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if ((int64_t)blockIdx.x * blockDim.x >= n_act) return;       // uniform per workgroup
+    uint32_t tag = 3u;
+    if (i < n_act) {
+        const uint32_t w = (uint32_t)loc[nodes[i]];
+        src[i] = w;
+        tag = w >> RG_TAG_SHIFT;
+    }
+    const int is_miss = tag == RG_TAG_REMOTE;
+    const int wave = threadIdx.x >> 6;
+    const int c_local = __popcll(__ballot(tag == RG_TAG_LOCAL));
+    const int c_hit = __popcll(__ballot(tag == RG_TAG_CACHE));
+    const int c_miss = __popcll(__ballot(is_miss));
+    if (rg_lane() == 0) { cls[0][wave] = c_local; cls[1][wave] = c_hit; cls[2][wave] = c_miss; }
+    int total_miss;
+    const int excl = rg_block_excl_scan<256 / RG_WAVE>(is_miss, smem, &total_miss);   // barriers inside publish cls[]
+    if (threadIdx.x < 3) {
+        const int t = cls[threadIdx.x][0] + cls[threadIdx.x][1] + cls[threadIdx.x][2] + cls[threadIdx.x][3];
+        if (t) atomicAdd(&stats[threadIdx.x], (unsigned long long)t);
+    }
+    if (total_miss == 0) return;                                   // uniform
+    if (threadIdx.x == 0) miss_base = atomicAdd(&gctl[0], (uint32_t)total_miss);
+    __syncthreads();
+    if (is_miss) miss_list[miss_base + excl] = (int32_t)i;
+}
+
+// Rows whose source is in HBM.  Each wave step moves 64/L rows of cpr chunks; U steps are unrolled.
+template <int VEC, int U>
+__global__ void __launch_bounds__(256) k_gather_hbm(const uint32_t* __restrict__ src, int64_t n, const int32_t* __restrict__ n_dev,
+                                                    const float* __restrict__ local_store, int64_t local_stride,
+                                                    const float* __restrict__ cache_rows, int64_t cache_stride,
+                                                    float* __restrict__ out, int64_t out_stride, int cpr, int log2L) {
+    typedef typename RgVec<VEC>::type V;
+    const int64_t n_act = rg_actual_n(n, n_dev);
+    const int lane = rg_lane();
+    const int L = 1 << log2L;
+    const int R = RG_WAVE >> log2L;
+    const int sub = lane >> log2L;
+    const int c0 = lane & (L - 1);
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t row0 = wave * (R * U); row0 < n_act; row0 += nwaves * (R * U)) {
+        const V* sp[U];
+        V* dp[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = row0 + u * R + sub;
+            sp[u] = nullptr;
+            dp[u] = nullptr;
+            if (i < n_act) {
+                const uint32_t w = src[i];
+                const uint32_t tag = w >> RG_TAG_SHIFT;
+                const int64_t row = (int64_t)(w & RG_ROW_MASK);
+                if (tag != RG_TAG_REMOTE) {
+                    sp[u] = (const V*)(tag == RG_TAG_LOCAL ? local_store + row * local_stride : cache_rows + row * cache_stride);
+                    dp[u] = (V*)(out + i * out_stride);
+                }
+            }
+        }
+        for (int c = c0; c < cpr; c += L) {
+            V val[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (sp[u]) val[u] = sp[u][c];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (dp[u]) __builtin_nontemporal_store(val[u], &dp[u][c]);
+        }
+    }
+}
+
+// Rows whose source is the remote store: walks the compacted miss list.
+template <int VEC, int U>
+__global__ void __launch_bounds__(256) k_gather_miss(const uint32_t* __restrict__ src, const int32_t* __restrict__ miss_list,
+                                                     const uint32_t* __restrict__ gctl, const float* __restrict__ remote_store,
+                                                     int64_t remote_stride, float* __restrict__ out, int64_t out_stride,
+                                                     int cpr, int log2L) {
+    typedef typename RgVec<VEC>::type V;
+    const int64_t n_miss = gctl[0];
+    const int lane = rg_lane();
+    const int L = 1 << log2L;
+    const int R = RG_WAVE >> log2L;
+    const int sub = lane >> log2L;
+    const int c0 = lane & (L - 1);
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t j0 = wave * (R * U); j0 < n_miss; j0 += nwaves * (R * U)) {
+        const V* sp[U];
+        V* dp[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t j = j0 + u * R + sub;
+            sp[u] = nullptr;
+            dp[u] = nullptr;
+            if (j < n_miss) {
+                const int64_t i = miss_list[j];
+                const int64_t row = (int64_t)(src[i] & RG_ROW_MASK);
+                sp[u] = (const V*)(remote_store + row * remote_stride);
+                dp[u] = (V*)(out + i * out_stride);
+            }
+        }
+        for (int c = c0; c < cpr; c += L) {
+            V val[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (sp[u]) val[u] = sp[u][c];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (dp[u]) __builtin_nontemporal_store(val[u], &dp[u][c]);
+        }
+    }
+}
+
+int env_int(const char* name, int dflt) {
+    const char* v = getenv(name);
+    if (!v || !*v) return dflt;
+    const int x = atoi(v);
+    return x > 0 ? x : dflt;
+}
+
+}  // namespace
+
+extern "C" {
+
+rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
+                             const rg_cache* cache, const float* local_store, int64_t local_stride,
+                             const float* remote_store, int64_t remote_stride, int32_t dim, float* out,
+                             int64_t out_stride, rg_gather_stats* stats, void* hit_stream, void* miss_stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_gather_features: n = %lld out of range", (long long)n);
+    RG_REQUIRE(ctx, stats, "rg_gather_features: stats is NULL");
+    RG_REQUIRE(ctx, dim >= 1, "rg_gather_features: dim = %d must be positive", dim);
+    RG_REQUIRE(ctx, cache && cache->loc, "rg_gather_features: cache / cache->loc is NULL");
+    RG_REQUIRE(ctx, out_stride >= dim, "rg_gather_features: out_stride < dim");
+    RG_REQUIRE(ctx, !local_store || local_stride >= dim, "rg_gather_features: local_stride < dim");
+    RG_REQUIRE(ctx, !remote_store || remote_stride >= dim, "rg_gather_features: remote_stride < dim");
+    RG_REQUIRE(ctx, !cache->cache_rows || cache->row_stride >= dim, "rg_gather_features: cache row_stride < dim");
+    RG_REQUIRE(ctx, n == 0 || (input_nodes && out), "rg_gather_features: null input_nodes / out");
+    // A store may be absent only if no location word can point into it; that cannot be verified on the
+    // host, so all three are required whenever rows are requested.
+    RG_REQUIRE(ctx, n == 0 || (local_store && remote_store), "rg_gather_features: null feature store");
+    RG_REQUIRE(ctx, n == 0 || cache->cache_rows || cache->capacity_rows == 0, "rg_gather_features: cache_rows is NULL");
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t sh = (hipStream_t)hit_stream;
+    hipStream_t sm = miss_stream ? (hipStream_t)miss_stream : sh;
+    const bool two_streams = sm != sh;
+
+    rg_status st;
+    if ((st = rg_ensure(ctx, ctx->gather_ctl, 64)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->gather_src, (size_t)rg_max64(n, 1) * 4)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->miss_list, (size_t)rg_max64(n, 1) * 4)) != RG_OK) return st;
+    uint32_t* gctl = (uint32_t*)ctx->gather_ctl.p;
+    uint32_t* src = (uint32_t*)ctx->gather_src.p;
+    int32_t* miss_list = (int32_t*)ctx->miss_list.p;
+    unsigned long long* dstats = (unsigned long long*)stats;
+
+    k_gather_reset<<<1, 64, 0, sh>>>(gctl, dstats);
+    RG_LAUNCH_CHECK(ctx, "k_gather_reset");
+    if (n == 0) return RG_OK;
+
+    k_classify<<<(int)rg_div_up(n, 256), 256, 0, sh>>>(input_nodes, n, n_dev, cache->loc, src, miss_list, gctl, dstats);
+    RG_LAUNCH_CHECK(ctx, "k_classify");
+    if (two_streams) {
+        RG_HIP(ctx, hipEventRecord(ctx->ev_classified, sh));
+        RG_HIP(ctx, hipStreamWaitEvent(sm, ctx->ev_classified, 0));
+    }
+
+    const void* ptrs[4] = {local_store, remote_store, cache->cache_rows, out};
+    const int64_t strides[4] = {local_stride, remote_stride, cache->cache_rows ? cache->row_stride : 0, out_stride};
+    const int vec = rg_pick_vec(dim, ptrs, 4, strides, 4);
+    const RgRowShape shp = rg_row_shape(dim, vec);
+    constexpr int U = 4;
+    const int rows_per_block = 4 * (RG_WAVE >> shp.log2L) * U;
+    const int per_cu = env_int("RG_GATHER_BLOCKS_PER_CU", 16);
+    const int grid = (int)rg_max64(1, rg_min64(rg_div_up(n, rows_per_block), (int64_t)ctx->num_cus * per_cu));
+    const float* cache_rows = cache->cache_rows ? cache->cache_rows : local_store;   // never dereferenced without cache words
+
+    int tok = rg_prof_begin(ctx, RG_K_GATHER_HBM, sh);
+    if (vec == 4)
+        k_gather_hbm<4, U><<<grid, 256, 0, sh>>>(src, n, n_dev, local_store, local_stride, cache_rows, cache->row_stride, out, out_stride, shp.cpr, shp.log2L);
+    else if (vec == 2)
+        k_gather_hbm<2, U><<<grid, 256, 0, sh>>>(src, n, n_dev, local_store, local_stride, cache_rows, cache->row_stride, out, out_stride, shp.cpr, shp.log2L);
+    else
+        k_gather_hbm<1, U><<<grid, 256, 0, sh>>>(src, n, n_dev, local_store, local_stride, cache_rows, cache->row_stride, out, out_stride, shp.cpr, shp.log2L);
+    rg_prof_end(ctx, tok, sh);
+    RG_LAUNCH_CHECK(ctx, "k_gather_hbm");
+
+    const int miss_per_cu = env_int("RG_MISS_BLOCKS_PER_CU", 8);
+    const int miss_grid = (int)rg_max64(1, rg_min64(rg_div_up(n, rows_per_block), (int64_t)ctx->num_cus * miss_per_cu));
+    tok = rg_prof_begin(ctx, RG_K_GATHER_MISS, sm);
+    if (vec == 4)
+        k_gather_miss<4, U><<<miss_grid, 256, 0, sm>>>(src, miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
+    else if (vec == 2)
+        k_gather_miss<2, U><<<miss_grid, 256, 0, sm>>>(src, miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
+    else
+        k_gather_miss<1, U><<<miss_grid, 256, 0, sm>>>(src, miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
+    rg_prof_end(ctx, tok, sm);
+    RG_LAUNCH_CHECK(ctx, "k_gather_miss");
+    if (two_streams) {
+        RG_HIP(ctx, hipEventRecord(ctx->ev_miss_done, sm));
+        RG_HIP(ctx, hipStreamWaitEvent(sh, ctx->ev_miss_done, 0));
+    }
+    return RG_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,143 @@
+// Internal declarations shared by the HIP translation units of librapidgnn (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string>
+#include <vector>
+
+#include "rapidgnn.h"
+
+// A growable device allocation owned by the context.
+struct RgBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+};
+
+struct RgProfSpan {
+    hipEvent_t start, stop;
+    int kernel;
+};
+
+struct rg_ctx {
+    int device = 0;
+    int num_cus = 256;
+    std::string err;
+
+    // sampler scratch
+    RgBuf visited;      // uint32[ceil(N/32)] bitmap of cumulative-frontier members
+    RgBuf fresh;        // uint32[ceil(N/32)] bitmap of ids first seen in the current hop (kept all-zero between hops)
+    RgBuf pos;          // int32[N] position of a node in the cumulative frontier (valid for members only)
+    RgBuf chunk_sum;    // int32[] per-256-node chunk edge counts / bitmap block counts
+    int64_t fresh_words_clean = 0;   // number of leading words of `fresh` known to be zero
+    // schedule scratch
+    RgBuf sched_keys;   // uint64[npad]
+    RgBuf sched_ids;    // int32[npad]
+    // top-K scratch
+    RgBuf topk_ctl;     // TopkCtl
+    RgBuf topk_blk;     // int32[2 * nblocks]
+    // gather scratch
+    RgBuf gather_src;   // uint32[n] resolved location word per output row
+    RgBuf miss_list;    // int32[n] output rows whose source is the remote store
+    RgBuf gather_ctl;   // uint32[4]: [0] = number of misses
+    hipEvent_t ev_classified = nullptr, ev_miss_done = nullptr;
+
+    // profiling
+    bool profiling = false;
+    std::vector<RgProfSpan> spans;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> free_events;
+    double prof_ms[RG_K_COUNT_] = {0};
+    int64_t prof_launches[RG_K_COUNT_] = {0};
+};
+
+rg_status rg_set_error(rg_ctx* ctx, rg_status code, const char* fmt, ...);
+rg_status rg_ensure(rg_ctx* ctx, RgBuf& buf, size_t bytes, bool zero_new = false);
+// Profiling brackets (no-ops unless profiling is enabled).
+int rg_prof_begin(rg_ctx* ctx, int kernel, hipStream_t s);
+void rg_prof_end(rg_ctx* ctx, int token, hipStream_t s);
+
+#define RG_HIP(ctx, expr)                                                                     \
+    do {                                                                                      \
+        hipError_t rg_e_ = (expr);                                                            \
+        if (rg_e_ != hipSuccess)                                                              \
+            return rg_set_error((ctx), RG_ERR_HIP, "%s failed: %s (%s:%d)", #expr,            \
+                                hipGetErrorString(rg_e_), __FILE__, __LINE__);                \
+    } while (0)
+
+#define RG_LAUNCH_CHECK(ctx, name)                                                            \
+    do {                                                                                      \
+        hipError_t rg_e_ = hipGetLastError();                                                 \
+        if (rg_e_ != hipSuccess)                                                              \
+            return rg_set_error((ctx), RG_ERR_HIP, "launch of %s failed: %s", name,           \
+                                hipGetErrorString(rg_e_));                                    \
+    } while (0)
+
+#define RG_REQUIRE(ctx, cond, ...)                                                            \
+    do {                                                                                      \
+        if (!(cond)) return rg_set_error((ctx), RG_ERR_INVALID_ARG, __VA_ARGS__);             \
+    } while (0)
+
+static inline int64_t rg_div_up(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline int64_t rg_min64(int64_t a, int64_t b) { return a < b ? a : b; }
+static inline int64_t rg_max64(int64_t a, int64_t b) { return a > b ? a : b; }
+
+// ---------------------------------------------------------------- device helpers
+#define RG_WAVE 64
+
+// Philox4x32-10 block function (Salmon et al., SC'11, Section 3.3).
+__device__ __forceinline__ void rg_philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+__device__ __forceinline__ int rg_lane() { return threadIdx.x & (RG_WAVE - 1); }
+
+// Inclusive prefix sum across the 64 lanes of a wavefront.
+__device__ __forceinline__ int rg_wave_incl_scan(int x) {
+    const int lane = rg_lane();
+#pragma unroll
+    for (int off = 1; off < RG_WAVE; off <<= 1) {
+        const int y = __shfl_up(x, off, RG_WAVE);
+        if (lane >= off) x += y;
+    }
+    return x;
+}
+
+__device__ __forceinline__ int rg_wave_sum(int x) {
+#pragma unroll
+    for (int off = RG_WAVE / 2; off > 0; off >>= 1) x += __shfl_xor(x, off, RG_WAVE);
+    return x;
+}
+
+// Exclusive prefix sum over a workgroup of NW wavefronts; returns the exclusive prefix of x and
+// stores the workgroup total in *total.  smem must hold NW + 1 ints.  Contains barriers: every
+// thread of the workgroup must call it.
+template <int NW>
+__device__ __forceinline__ int rg_block_excl_scan(int x, int* smem, int* total) {
+    const int lane = rg_lane();
+    const int wave = threadIdx.x >> 6;
+    const int incl = rg_wave_incl_scan(x);
+    __syncthreads();                      // protect smem from a previous use
+    if (lane == RG_WAVE - 1) smem[wave] = incl;
+    __syncthreads();
+    int wave_base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const int s = smem[w];
+        if (w < wave) wave_base += s;
+        tot += s;
+    }
+    *total = tot;
+    return wave_base + incl - x;
+}

@@ -1,0 +1,43 @@
+// Row-copy building blocks shared by the cache fill and the per-batch gather.
+//
+// A feature row is moved as `cpr` chunks of VEC floats (VEC = 4 -> 16-byte accesses).  A wavefront is
+// split into groups of L = 2^log2L lanes, one group per row, so 64/L rows move per wave step and short
+// rows (256 B, 400 B, 512 B) still fill all lanes.  U row groups are unrolled so every lane has U
+// independent loads in flight before the first store.
+#pragma once
+
+#include "rg_internal.h"
+
+template <int VEC> struct RgVec;
+template <> struct RgVec<4> { typedef float type __attribute__((ext_vector_type(4))); };
+template <> struct RgVec<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct RgVec<1> { typedef float type; };
+
+struct RgRowShape {
+    int cpr;      // chunks per row = ceil(dim / VEC)
+    int log2L;    // lanes per row group = 1 << log2L (<= 64)
+};
+
+static inline int rg_pick_vec(int32_t dim, const void* const* ptrs, int nptrs, const int64_t* strides, int nstrides) {
+    int vec = 4;
+    for (int i = 0; i < nptrs; ++i) {
+        const uintptr_t a = (uintptr_t)ptrs[i];
+        if (!a) continue;
+        while (vec > 1 && (a % (vec * 4)) != 0) vec >>= 1;
+    }
+    for (int i = 0; i < nstrides; ++i)
+        while (vec > 1 && (strides[i] % vec) != 0) vec >>= 1;
+    // 16-byte chunks may cover the row padding (stride >= round_up(dim, 4) is implied by stride % 4 == 0
+    // and stride >= dim); narrower chunks must tile dim exactly.
+    if (vec == 2 && (dim % 2) != 0) vec = 1;
+    return vec;
+}
+
+static inline RgRowShape rg_row_shape(int32_t dim, int vec) {
+    RgRowShape s;
+    s.cpr = (dim + vec - 1) / vec;
+    int l = 0;
+    while ((1 << l) < s.cpr && l < 6) ++l;
+    s.log2L = l;
+    return s;
+}

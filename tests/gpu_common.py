@@ -1,0 +1,50 @@
+"""Helpers for the GPU parity tests: run the HIP path through the C-ABI binding and the oracle on the
+same seeded inputs.  Nothing here computes expected values: those come from `oracle` only."""
+import sys
+
+import numpy as np
+import torch
+
+import oracle
+import synth
+
+
+def log(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def np_i64(t):
+    return t.detach().cpu().numpy().astype(np.int64)
+
+
+class HipBatch:
+    """Host copies of one sampled batch produced by the HIP path."""
+
+    def __init__(self, bufs, num_hops):
+        torch.cuda.synchronize()
+        self.tier_off = np_i64(bufs.tier_off)
+        n = int(self.tier_off[num_hops + 1])
+        self.nodes = bufs.nodes[:n].cpu().numpy()
+        self.indptr, self.nbr, self.nbr_local = [], [], []
+        for h in range(num_hops):
+            n_h = int(self.tier_off[h + 1])
+            ip = bufs.indptr[h][:n_h + 1].cpu().numpy()
+            e = int(ip[-1])
+            self.indptr.append(ip)
+            self.nbr.append(bufs.nbr[h][:e].cpu().numpy())
+            self.nbr_local.append(bufs.nbr_local[h][:e].cpu().numpy() if bufs.nbr_local else None)
+
+
+def assert_batch_equal(hip, orc, num_hops, tag=""):
+    assert hip.tier_off.tolist() == orc.tier_off.tolist(), f"{tag} tier_off"
+    assert np.array_equal(hip.nodes, orc.nodes), f"{tag} nodes"
+    for h in range(num_hops):
+        assert np.array_equal(hip.indptr[h].astype(np.int64), orc.indptr[h]), f"{tag} indptr[{h}]"
+        assert np.array_equal(hip.nbr[h], orc.nbr[h]), f"{tag} nbr[{h}]"
+        if hip.nbr_local[h] is not None:
+            assert np.array_equal(hip.nbr_local[h], orc.nbr_local[h]), f"{tag} nbr_local[{h}]"
+
+
+def host_graph(wl):
+    return wl.row_ptr.cpu().numpy().astype(np.int64), wl.col_idx.cpu().numpy()

@@ -1,0 +1,342 @@
+"""Bit-exact parity of the HIP path (through the C ABI) against the CPU oracle: tolerance 0.
+
+Everything on this path is integer, index or copy work, so every comparison is exact equality.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_common import HipBatch, assert_batch_equal, host_graph, log, np_i64
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2505_10806_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(B):
+    c = B.Context(0)
+    yield c
+    c.close()
+
+
+def _i32(a):
+    return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32), device=DEV)
+
+
+# ------------------------------------------------------------------------------ schedule
+@pytest.mark.parametrize("n", [1, 2, 7, 2047, 2048, 2049, 5000, 120_000])
+def test_epoch_schedule(ctx, n):
+    log(f"[schedule] n={n}")
+    rng = np.random.default_rng(n)
+    ids = rng.choice(max(4 * n, 16), size=n, replace=False).astype(np.int32)
+    for seed, epoch in [(2025, 0), ((7 << 33) + 5, 3)]:
+        got = ctx.epoch_schedule(_i32(ids), seed, epoch)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), oracle.epoch_schedule(ids, seed, epoch))
+
+
+def test_epoch_schedule_empty(ctx):
+    ctx.epoch_schedule(torch.empty(0, dtype=torch.int32, device=DEV), 1, 0)
+
+
+# ------------------------------------------------------------------------------ sampler
+def _run_blocks(B, ctx, csr, seeds_np, fanouts, seed, epoch, bufs=None, with_local=True):
+    if bufs is None:
+        bufs = B.BlockBuffers(csr.num_nodes, csr.num_edges, max(len(seeds_np), 1), fanouts, DEV, with_local=with_local)
+    ctx.sample_blocks(csr, _i32(seeds_np), len(seeds_np), fanouts, seed, epoch, bufs)
+    return HipBatch(bufs, len(fanouts))
+
+
+def _handmade_graph(n, p_dense, n_dense, p, rng):
+    adj = [[] for _ in range(n)]
+    for u in range(n):
+        for v in range(u + 1, n):
+            if rng.random() < (p_dense if u < n_dense else p):
+                adj[u].append(v)
+                adj[v].append(u)
+    rp = np.zeros(n + 1, dtype=np.int64)
+    rp[1:] = np.cumsum([len(a) for a in adj])
+    ci = np.array([u for a in adj for u in sorted(a)], dtype=np.int32)
+    return rp, ci
+
+
+@pytest.mark.parametrize("rp_dtype", [torch.int32, torch.int64])
+@pytest.mark.parametrize("fanouts", [(3, 2), (0, 4), (5,), (-1, 2), (-1, -1, -1), (64, 3), (100, 100), (1024,)])
+def test_blocks_handmade_graph(B, ctx, fanouts, rp_dtype):
+    """Dense core (degrees up to ~400) so that large fan-outs still take the Floyd branch."""
+    log(f"[blocks handmade] fanouts={fanouts} rp={rp_dtype}")
+    rng = np.random.default_rng(17)
+    rp, ci = _handmade_graph(500, 0.8, 40, 0.01, rng)
+    csr = B.CsrGraph(torch.as_tensor(rp, device=DEV).to(rp_dtype), _i32(ci))
+    seeds = np.array([3, 499, 41, 0, 250, 77], dtype=np.int32)
+    for seed, epoch in [(5, 0), ((1 << 40) + 9, 7)]:
+        hip = _run_blocks(B, ctx, csr, seeds, fanouts, seed, epoch)
+        orc = oracle.sample_blocks(rp, ci, seeds, fanouts, seed, epoch)
+        assert_batch_equal(hip, orc, len(fanouts), f"seed={seed} epoch={epoch}")
+
+
+def test_blocks_degenerate_inputs(B, ctx):
+    log("[blocks degenerate]")
+    rp = np.array([0, 0, 1, 2, 2], dtype=np.int64)          # 0 and 3 isolated, 1 <-> 2
+    ci = np.array([2, 1], dtype=np.int32)
+    csr = B.CsrGraph(torch.as_tensor(rp, device=DEV).to(torch.int32), _i32(ci))
+    for seeds in ([0], [], [1], [3, 0], [2, 1, 0, 3]):
+        seeds = np.array(seeds, dtype=np.int32)
+        hip = _run_blocks(B, ctx, csr, seeds, (4, 4), 1, 0)
+        orc = oracle.sample_blocks(rp, ci, seeds, (4, 4), 1, 0)
+        assert_batch_equal(hip, orc, 2, f"seeds={seeds.tolist()}")
+    # a graph without edges
+    rp0 = np.zeros(6, dtype=np.int64)
+    csr0 = B.CsrGraph(torch.as_tensor(rp0, device=DEV), torch.empty(0, dtype=torch.int32, device=DEV))
+    hip = _run_blocks(B, ctx, csr0, np.array([4, 1], dtype=np.int32), (3,), 1, 0)
+    orc = oracle.sample_blocks(rp0, np.empty(0, dtype=np.int32), [4, 1], (3,), 1, 0)
+    assert_batch_equal(hip, orc, 1, "edgeless")
+
+
+def test_blocks_without_relabelling(B, ctx):
+    rng = np.random.default_rng(3)
+    rp, ci = _handmade_graph(300, 0.5, 10, 0.02, rng)
+    csr = B.CsrGraph(torch.as_tensor(rp, device=DEV), _i32(ci))
+    seeds = np.arange(0, 300, 7, dtype=np.int32)
+    hip = _run_blocks(B, ctx, csr, seeds, (4, 3), 9, 1, with_local=False)
+    orc = oracle.sample_blocks(rp, ci, seeds, (4, 3), 9, 1)
+    assert_batch_equal(hip, orc, 2)
+
+
+# ------------------------------------------------------------------------------ whole path
+def _full_path(B, ctx, name, two_streams, device_counts):
+    """Every batch of every epoch of a named workload: sample, histogram, TopHot + fill, gather."""
+    wl = synth.build_workload(name, seed=2025, device=DEV)
+    cfg = wl.cfg
+    log(f"[full path] {name}: N={cfg.num_nodes} nnz={wl.nnz} D={cfg.feat_dim} capacity={wl.capacity_rows}")
+    rp, ci = host_graph(wl)
+    X = wl.features.cpu().numpy()
+    home_np = wl.home.cpu().numpy()
+    train_np = wl.train_ids.cpu().numpy()
+    csr = B.CsrGraph(wl.row_ptr, wl.col_idx)
+    H = len(cfg.fanouts)
+    bufs = B.BlockBuffers(cfg.num_nodes, wl.nnz, cfg.batch_size, cfg.fanouts, DEV)
+    cap_alloc = min(wl.capacity_rows, wl.n_remote)
+    cache = B.FeatureCache(cfg.num_nodes, cap_alloc, wl.stride, DEV)
+    out = torch.empty(bufs.frontier_ub[H], wl.stride, dtype=torch.float32, device=DEV)
+    stats = torch.zeros(3, dtype=torch.int64, device=DEV)
+    side = torch.cuda.Stream() if two_streams else None
+    n_batches = wl.batches_per_epoch()
+    for epoch in range(cfg.epochs):
+        order = ctx.epoch_schedule(wl.train_ids, wl.seed, epoch)
+        torch.cuda.synchronize()
+        orc_batches = oracle.epoch_batches(train_np, cfg.batch_size, wl.seed, epoch, cfg.max_batches)
+        assert len(orc_batches) == n_batches
+        assert np.array_equal(order.cpu().numpy()[:sum(len(b) for b in orc_batches)], np.concatenate(orc_batches))
+        counts = torch.zeros(cfg.num_nodes, dtype=torch.int32, device=DEV)
+        counts_orc = np.zeros(cfg.num_nodes, dtype=np.uint32)
+        hip_inputs, orc_inputs = [], []
+        for b in range(n_batches):
+            seeds = order[b * cfg.batch_size:(b + 1) * cfg.batch_size]
+            ctx.sample_blocks(csr, seeds, seeds.numel(), cfg.fanouts, wl.seed, epoch, bufs)
+            if device_counts:        # count stays on the device, no synchronisation before the histogram
+                ctx.access_histogram(bufs.nodes, bufs.frontier_ub[H], counts, n_dev=bufs.tier_off[H + 1:])
+            hip = HipBatch(bufs, H)
+            if not device_counts:
+                ctx.access_histogram(bufs.nodes, hip.nodes.size, counts)
+            orc = oracle.sample_blocks(rp, ci, orc_batches[b], cfg.fanouts, wl.seed, epoch)
+            assert_batch_equal(hip, orc, H, f"{name} epoch {epoch} batch {b}")
+            oracle.access_histogram(orc.input_nodes, counts_orc)
+            hip_inputs.append(bufs.nodes[:hip.nodes.size].clone())
+            orc_inputs.append(orc.input_nodes)
+        torch.cuda.synchronize()
+        assert np.array_equal(counts.cpu().numpy().view(np.uint32), counts_orc), "histogram"
+        # TopHot + VectorPull for this epoch's counts
+        ctx.build_cache(counts, wl.home, wl.remote_store, cfg.feat_dim, cache)
+        torch.cuda.synchronize()
+        ids_orc, loc_orc = oracle.build_cache(counts_orc, home_np, wl.capacity_rows)
+        k = int(cache.num_cached.item())
+        assert k == ids_orc.size
+        assert np.array_equal(cache.cache_ids[:k].cpu().numpy(), ids_orc), "cache_ids"
+        assert np.array_equal(cache.loc.cpu().numpy(), loc_orc), "loc"
+        rows_orc = oracle.fill_cache(X, ids_orc, wl.stride)
+        assert np.array_equal(cache.cache_rows[:k, :cfg.feat_dim].cpu().numpy(), rows_orc[:, :cfg.feat_dim]), "cache rows"
+        # per-batch feature assembly
+        tot = np.zeros(3, dtype=np.int64)
+        for b in range(n_batches):
+            n = hip_inputs[b].numel()
+            out.fill_(float("nan"))
+            ctx.gather_features(hip_inputs[b], n, cache, wl.local_store, wl.remote_store, cfg.feat_dim, out, stats,
+                                miss_stream=side)
+            torch.cuda.synchronize()
+            want, st_orc = oracle.gather_features(X, orc_inputs[b], loc_orc, wl.stride)
+            assert np.array_equal(out[:n, :cfg.feat_dim].cpu().numpy(), want[:, :cfg.feat_dim]), f"gather batch {b}"
+            assert tuple(stats.cpu().tolist()) == st_orc
+            tot += np.array(st_orc)
+        remote = (home_np.astype(np.int64) & 0xFFFFFFFF) >> 30 == 2
+        assert tot[1] == int(counts_orc[ids_orc].sum())                  # hit count predicted by the histogram
+        assert tot[1] + tot[2] == int(counts_orc[remote].sum())
+        log(f"[full path] {name} epoch {epoch}: batches={n_batches} cached={k} "
+            f"hit%={100.0 * tot[1] / max(1, tot[1] + tot[2]):.2f} rows={tot.sum()}")
+
+
+def test_full_path_tiny(B, ctx):
+    _full_path(B, ctx, "tiny", two_streams=False, device_counts=False)
+
+
+def test_full_path_tiny_two_streams_device_counts(B, ctx):
+    _full_path(B, ctx, "tiny", two_streams=True, device_counts=True)
+
+
+def test_full_path_small(B, ctx):
+    _full_path(B, ctx, "small", two_streams=True, device_counts=True)
+
+
+# ------------------------------------------------------------------------------ TopHot edge cases
+@pytest.mark.parametrize("capacity", [0, 1, 5, 1000, 4000, 1 << 20])
+def test_build_cache_edge_cases(B, ctx, capacity):
+    log(f"[build_cache] capacity={capacity}")
+    rng = np.random.default_rng(capacity + 1)
+    n, dim = 5000, 12
+    is_local = torch.from_numpy(rng.random(n) < 0.25)
+    home = synth.stores.make_home(is_local)
+    counts = rng.integers(0, 4, size=n).astype(np.uint32)                 # heavy ties and zeros
+    counts[rng.integers(0, n, 6)] = np.uint32(2 ** 31 + 7)                # counts beyond int32
+    counts[rng.integers(0, n, 3)] = np.uint32(2 ** 32 - 1)
+    X = rng.standard_normal((n, dim)).astype(np.float32)
+    stride = synth.stores.row_stride(dim)
+    remote = torch.zeros(int((~is_local).sum()), stride, pin_memory=True)
+    remote[:, :dim] = torch.from_numpy(X)[~is_local]
+    cache = B.FeatureCache(n, min(capacity, n), stride, DEV)
+    cache.c_struct.capacity_rows = capacity          # the buffers hold min(capacity, n) rows, which bounds K_eff
+    ctx.build_cache(torch.from_numpy(counts.view(np.int32)).to(DEV), home.to(DEV), remote, dim, cache)
+    torch.cuda.synchronize()
+    ids_orc, loc_orc = oracle.build_cache(counts, home.numpy(), min(capacity, n))
+    k = int(cache.num_cached.item())
+    assert k == ids_orc.size
+    assert np.array_equal(cache.cache_ids[:k].cpu().numpy(), ids_orc)
+    assert np.array_equal(cache.loc.cpu().numpy(), loc_orc)
+    assert np.array_equal(cache.cache_rows[:k, :dim].cpu().numpy(), X[ids_orc])
+
+
+def test_build_cache_all_local(B, ctx):
+    n = 300
+    home = synth.stores.make_home(torch.ones(n, dtype=torch.bool))
+    counts = torch.ones(n, dtype=torch.int32, device=DEV)
+    remote = torch.zeros(1, 4, pin_memory=True)
+    cache = B.FeatureCache(n, 10, 4, DEV)
+    ctx.build_cache(counts, home.to(DEV), remote, 4, cache)
+    torch.cuda.synchronize()
+    assert int(cache.num_cached.item()) == 0
+    assert np.array_equal(cache.loc.cpu().numpy(), home.numpy())
+
+
+# ------------------------------------------------------------------------------ gather shapes
+@pytest.mark.parametrize("dim,pad", [(64, True), (100, True), (128, True), (256, True), (602, True), (602, False),
+                                     (7, False), (7, True), (257, False), (1, False), (1000, True)])
+@pytest.mark.parametrize("two_streams", [False, True])
+def test_gather_shapes_and_tags(B, ctx, dim, pad, two_streams):
+    log(f"[gather] dim={dim} pad={pad} two_streams={two_streams}")
+    rng = np.random.default_rng(dim * 2 + pad)
+    n_nodes, n_local, n_cache, n_remote = 3000, 900, 500, 2100
+    stride = synth.stores.row_stride(dim) if pad else dim
+    X = rng.standard_normal((n_nodes, dim)).astype(np.float32)
+    perm = rng.permutation(n_nodes)
+    loc = np.zeros(n_nodes, dtype=np.int64)
+    local_ids, remote_ids = perm[:n_local], perm[n_local:]
+    cached_ids = remote_ids[:n_cache]
+    loc[local_ids] = (0 << 30) | np.arange(n_local)
+    loc[remote_ids] = (2 << 30) | np.arange(n_remote)
+    loc[cached_ids] = (1 << 30) | np.arange(n_cache)
+    loc32 = loc.astype(np.uint32).view(np.int32)
+
+    def pack(ids, pinned):
+        t = torch.zeros(len(ids), stride, pin_memory=True) if pinned else torch.zeros(len(ids), stride)
+        t[:, :dim] = torch.from_numpy(X[ids])
+        return t if pinned else t.to(DEV)
+    local_store, remote_store = pack(local_ids, False), pack(remote_ids, True)
+    cache = B.FeatureCache(n_nodes, n_cache, stride, DEV)
+    cache.cache_rows[:, :dim] = torch.from_numpy(X[cached_ids]).to(DEV)
+    cache.loc.copy_(torch.from_numpy(loc32))
+    stats = torch.zeros(3, dtype=torch.int64, device=DEV)
+    side = torch.cuda.Stream() if two_streams else None
+    for n in (0, 1, 63, 257, 4097):
+        nodes = rng.integers(0, n_nodes, size=n).astype(np.int32)         # repeats allowed
+        out = torch.full((max(n, 1), stride), float("nan"), device=DEV)
+        nodes_dev = torch.as_tensor(nodes, device=DEV) if n else torch.empty(1, dtype=torch.int32, device=DEV)
+        ctx.gather_features(nodes_dev, n, cache, local_store, remote_store, dim, out, stats, miss_stream=side)
+        torch.cuda.synchronize()
+        want, st = oracle.gather_features(X, nodes, loc32)
+        assert np.array_equal(out[:n, :dim].cpu().numpy(), want), f"n={n}"
+        assert tuple(stats.cpu().tolist()) == st
+    # count read from the device: the launch is sized for 4097 rows but only 1000 are valid
+    nodes = rng.integers(0, n_nodes, size=4097).astype(np.int32)
+    n_dev = torch.tensor([1000], dtype=torch.int32, device=DEV)
+    out = torch.full((4097, stride), float("nan"), device=DEV)
+    ctx.gather_features(torch.as_tensor(nodes, device=DEV), 4097, cache, local_store, remote_store, dim, out, stats,
+                        n_dev=n_dev, miss_stream=side)
+    torch.cuda.synchronize()
+    want, st = oracle.gather_features(X, nodes[:1000], loc32)
+    assert np.array_equal(out[:1000, :dim].cpu().numpy(), want)
+    assert torch.isnan(out[1000:, :dim]).all()
+    assert tuple(stats.cpu().tolist()) == st
+
+
+# ------------------------------------------------------------------------------ histogram
+def test_histogram_with_repeats_and_device_count(B, ctx):
+    rng = np.random.default_rng(4)
+    n_nodes = 1000
+    ids = (rng.zipf(1.3, size=200_000) % n_nodes).astype(np.int32)       # heavy repeats
+    counts = torch.zeros(n_nodes, dtype=torch.int32, device=DEV)
+    ctx.access_histogram(torch.as_tensor(ids, device=DEV), ids.size, counts)
+    ctx.access_histogram(torch.as_tensor(ids, device=DEV), ids.size, counts,
+                         n_dev=torch.tensor([1234], dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    want = np.zeros(n_nodes, dtype=np.uint32)
+    oracle.access_histogram(ids, want)
+    oracle.access_histogram(ids[:1234], want)
+    assert np.array_equal(counts.cpu().numpy().view(np.uint32), want)
+
+
+# ------------------------------------------------------------------------------ argument errors
+def test_argument_errors_are_reported_not_launched(B, ctx):
+    rp = torch.tensor([0, 1, 2], dtype=torch.int32, device=DEV)
+    ci = torch.tensor([1, 0], dtype=torch.int32, device=DEV)
+    csr = B.CsrGraph(rp, ci)
+    bufs = B.BlockBuffers(2, 2, 2, (2,), DEV)
+    seeds = torch.tensor([0, 1], dtype=torch.int32, device=DEV)
+    with pytest.raises(B.RgError) as e:
+        ctx.sample_blocks(csr, seeds, 2, (B.RG_MAX_FANOUT + 1,), 1, 0, bufs)
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    with pytest.raises(B.RgError) as e:
+        ctx.sample_blocks(csr, seeds, 2, (-5,), 1, 0, bufs)
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    with pytest.raises(B.RgError) as e:
+        ctx.sample_blocks(csr, seeds, -1, (2,), 1, 0, bufs)
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    small = B.BlockBuffers(2, 2, 1, (2,), DEV)          # sized for one seed, used with two
+    with pytest.raises(B.RgError) as e:
+        ctx.sample_blocks(csr, seeds, 2, (2,), 1, 0, small)
+    assert e.value.status == B.RG_ERR_CAPACITY
+    cache = B.FeatureCache(2, 1, 4, DEV)
+    store = torch.zeros(2, 4, device=DEV)
+    pinned = torch.zeros(2, 4, pin_memory=True)
+    stats = torch.zeros(3, dtype=torch.int64, device=DEV)
+    out = torch.zeros(2, 4, device=DEV)
+    with pytest.raises(B.RgError) as e:
+        ctx.gather_features(seeds, 2, cache, store, pinned, 8, out, stats)      # dim larger than the strides
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    with pytest.raises(B.RgError) as e:
+        ctx.gather_features(seeds, -3, cache, store, pinned, 4, out, stats)
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    with pytest.raises(B.RgError) as e:
+        ctx.build_cache(torch.zeros(2, dtype=torch.int32, device=DEV), seeds, pinned, 0, cache)
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    # the context still works after the rejected calls
+    ctx.sample_blocks(csr, seeds, 2, (2,), 1, 0, bufs)
+    torch.cuda.synchronize()
+    assert bufs.tier_off.cpu().tolist() == [0, 2, 2]
