@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the RapidGNN data path on one MI355X.
+
+A step is one mini-batch taken through the whole hot path: epoch schedule (once per epoch), k-hop
+sampling, access histogram, TopHot + cache fill (once per epoch, amortised over its batches) and the
+per-batch feature gather.  Inputs are synthetic (seeded Chung-Lu graph, N(0,1) features) and resident
+in HBM / pinned host memory before the timed region starts.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E peak
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def run_steps(pipe, steps, totals=None):
+    """Run `steps` batches through the whole path, epoch after epoch.  Returns sampled edge count holder."""
+    import torch
+    epoch, left = 0, steps
+    while left > 0:
+        nb = min(left, pipe.max_batches)
+        pipe.run_epoch(epoch, nb)
+        if totals is not None:
+            totals["stats"] += pipe.stats[:nb].sum(0)
+            totals["rows"] += sum(pipe.sizes[:nb])
+            totals["cached"] += pipe.cache.num_cached.clone()
+            totals["epochs"] += 1
+        left -= nb
+        epoch += 1
+    torch.cuda.current_stream().synchronize()
+
+
+def cpu_baseline(wl, n_batches):
+    """The CPU oracle, as it stands, on the first n_batches batches of epoch 0 (single thread)."""
+    import numpy as np
+    import oracle
+    cfg = wl.cfg
+    rp = wl.row_ptr.cpu().numpy().astype(np.int64)
+    ci = wl.col_idx.cpu().numpy()
+    X = wl.features.cpu().numpy()
+    home = wl.home.cpu().numpy()
+    train = wl.train_ids.cpu().numpy()
+    t0 = time.perf_counter()
+    batches = oracle.epoch_batches(train, cfg.batch_size, wl.seed, 0)[:n_batches]
+    counts = np.zeros(cfg.num_nodes, dtype=np.uint32)
+    inputs = []
+    for seeds in batches:
+        blk = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, 0)
+        oracle.access_histogram(blk.input_nodes, counts)
+        inputs.append(blk.input_nodes)
+    ids, loc = oracle.build_cache(counts, home, wl.capacity_rows)
+    oracle.fill_cache(X, ids, wl.stride)
+    rows = 0
+    for nodes in inputs:
+        oracle.gather_features(X, nodes, loc, wl.stride)
+        rows += nodes.size
+    dt = time.perf_counter() - t0
+    return {"value": len(batches) / dt, "unit": "batches/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {len(batches)} batches of epoch 0 of '{cfg.name}' through the whole path "
+                      f"(schedule, sample, histogram, TopHot+fill, gather of {rows} rows); {dt:.1f} s on one thread",
+            "host_cpus": os.cpu_count()}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="mini-batches in the timed region (default: one epoch)")
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="stress")
+    ap.add_argument("--seed", type=int, default=2025)
+    ap.add_argument("--cpu-batches", type=int, default=None, help="batches the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--one-stream", action="store_true", help="copy miss rows on the same stream as the HBM rows")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the remote partition is pinned host memory); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    from paper_2505_10806_amd import binding as B
+    from paper_2505_10806_amd.pipeline import EpochPipeline
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    t_gen = time.perf_counter()
+    wl = synth.build_workload(args.workload, seed=args.seed, device=dev)
+    cfg = wl.cfg
+    torch.cuda.synchronize()
+    log(f"[bench] workload {cfg.name}: N={cfg.num_nodes} nnz={wl.nnz} D={cfg.feat_dim} fanouts={cfg.fanouts} "
+        f"batch={cfg.batch_size} local={wl.n_local} remote={wl.n_remote} capacity={wl.capacity_rows} "
+        f"(generated in {time.perf_counter() - t_gen:.1f} s)")
+
+    bpe = wl.batches_per_epoch()
+    steps = args.steps if args.steps is not None else bpe
+    warmup = args.warmup
+    main_stream = torch.cuda.Stream()
+    with torch.cuda.stream(main_stream):
+        pipe = EpochPipeline(wl, device=dev, max_batches=min(max(steps, warmup, 1), bpe), two_streams=not args.one_stream)
+        ctx = pipe.ctx
+        if warmup > 0:
+            run_steps(pipe, warmup)
+        totals = {"stats": torch.zeros(3, dtype=torch.int64, device=dev), "rows": 0,
+                  "cached": torch.zeros(1, dtype=torch.int64, device=dev), "epochs": 0}
+        ctx.profile_enable(True)
+        ctx.profile_reset()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(pipe, steps, totals)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ctx.profile_enable(False)
+
+    n_local, n_hit, n_miss = [int(x) for x in totals["stats"].cpu().tolist()]
+    rows = totals["rows"]
+    assert rows == n_local + n_hit + n_miss, "gather statistics do not add up"
+    row_bytes = 4 * cfg.feat_dim
+    prof = {name: ctx.profile_read(kid) for name, kid in
+            [("gather_hbm", B.RG_K_GATHER_HBM), ("gather_miss", B.RG_K_GATHER_MISS), ("sample", B.RG_K_SAMPLE),
+             ("histogram", B.RG_K_HISTOGRAM), ("cache_fill", B.RG_K_CACHE_FILL)]}
+    g_ms, g_launches = prof["gather_hbm"]
+    hbm_rows = n_local + n_hit
+    alg_bytes = 2.0 * row_bytes * hbm_rows                       # every HBM-served row is read once and written once
+    achieved = alg_bytes / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0
+    cached_rows = int(totals["cached"].item())
+    m_ms, _ = prof["gather_miss"]
+    f_ms, _ = prof["cache_fill"]
+    result = {
+        "metric": "mini-batch sample+gather/sec; feature gather GB/s vs HBM peak; cache hit %",
+        "value": steps / dt,
+        "unit": "batches/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": dt * 1e3 / steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32 indices / fp32 rows (copy)",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "num_nodes": cfg.num_nodes, "nnz": wl.nnz, "feat_dim": cfg.feat_dim,
+                   "fanouts": list(cfg.fanouts), "batch_size": cfg.batch_size, "epochs_timed": totals["epochs"],
+                   "cache_capacity_rows": wl.capacity_rows, "miss_stream": "shared" if args.one_stream else "separate"},
+        "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes / max(g_launches, 1),
+                     "avg_launch_ms": g_ms / max(g_launches, 1), "launches": g_launches},
+        "gather": {"rows": rows, "n_local": n_local, "n_hit": n_hit, "n_miss": n_miss,
+                   "cache_hit_pct": 100.0 * n_hit / max(1, n_hit + n_miss),
+                   "payload_GBps_hbm_kernel": row_bytes * hbm_rows / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0,
+                   "miss_hostlink_GBps": row_bytes * n_miss / (m_ms * 1e-3) / 1e9 if m_ms > 0 and n_miss else None,
+                   "cache_fill_hostlink_GBps": row_bytes * cached_rows / (f_ms * 1e-3) / 1e9 if f_ms > 0 and cached_rows else None,
+                   "cached_rows": cached_rows},
+        "kernel_ms": {k: {"total_ms": v[0], "launches": v[1]} for k, v in prof.items()},
+    }
+
+    n_cpu = args.cpu_batches
+    if n_cpu is None:
+        n_cpu = 2 if cfg.num_nodes >= 1_000_000 else min(8, bpe)
+    if n_cpu > 0:
+        del pipe
+        torch.cuda.empty_cache()
+        log(f"[bench] timing the CPU oracle on {n_cpu} batches ...")
+        result["cpu_baseline"] = cpu_baseline(wl, n_cpu)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -257,11 +257,14 @@ class BlockBuffers:
             ctypes.cast(self._loc_arr, ctypes.POINTER(c_p)) if self._loc_arr is not None else None,
             ctypes.cast(self._nbr_cap, ctypes.POINTER(c_i64)))
 
-    def set_nodes(self, nodes):
-        """Point the input-node output at another buffer (e.g. a per-batch slot of an epoch arena)."""
-        self.nodes = nodes
+    def set_outputs(self, nodes, tier_off):
+        """Point the input-node list and tier offsets at other buffers (e.g. a batch's slot of an epoch arena)."""
+        if nodes.dtype != torch.int32 or tier_off.dtype != torch.int32 or tier_off.numel() < len(self.fanouts) + 2:
+            raise TypeError("set_outputs: int32 tensors required, tier_off of num_hops + 2 entries")
+        self.nodes, self.tier_off = nodes, tier_off
         self.c_struct.nodes = nodes.data_ptr()
         self.c_struct.nodes_cap = nodes.numel()
+        self.c_struct.tier_off = tier_off.data_ptr()
 
 
 class FeatureCache:

@@ -1,0 +1,66 @@
+"""Epoch driver over the C-ABI binding: the offline stage of Alg. 1 (lines 1-4: precompute the
+batches, count accesses, TopHot, VectorPull) followed by the online per-batch feature assembly
+(lines 12-14).  Host code only sequences library calls and owns the buffers; every step runs in the
+library's kernels.  No host synchronisation happens inside the offline stage: frontier sizes stay
+on the device and are read back once, before the online stage.
+"""
+import torch
+
+from . import binding as B
+
+
+class EpochPipeline:
+    def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True):
+        cfg = wl.cfg
+        self.wl, self.cfg, self.device = wl, cfg, device
+        self.H = len(cfg.fanouts)
+        self.ctx = ctx or B.Context(torch.device(device).index or 0)
+        self.csr = B.CsrGraph(wl.row_ptr, wl.col_idx)
+        self.batches_per_epoch = wl.batches_per_epoch()
+        self.max_batches = min(max_batches or self.batches_per_epoch, self.batches_per_epoch)
+        self.bufs = B.BlockBuffers(cfg.num_nodes, wl.nnz, cfg.batch_size, cfg.fanouts, device)
+        self.slot = self.bufs.frontier_ub[self.H]
+        # one slot of input nodes and one row of tier offsets per precomputed batch
+        self.arena = torch.empty(self.max_batches, max(self.slot, 1), dtype=torch.int32, device=device)
+        self.tier_offs = torch.zeros(self.max_batches, self.H + 2, dtype=torch.int32, device=device)
+        self.counts = torch.zeros(cfg.num_nodes, dtype=torch.int32, device=device)
+        self.cache = B.FeatureCache(cfg.num_nodes, min(wl.capacity_rows, wl.n_remote), wl.stride, device)
+        self.out = torch.empty(max(self.slot, 1), wl.stride, dtype=torch.float32, device=device)
+        self.stats = torch.zeros(self.max_batches, 3, dtype=torch.int64, device=device)
+        self.order = torch.empty_like(wl.train_ids)
+        self.side = torch.cuda.Stream(device=device) if two_streams else None
+        self.ctx.reserve(cfg.num_nodes, self.slot, self.slot)
+        self.sizes = None
+
+    def precompute(self, epoch, n_batches):
+        """Offline stage for the first n_batches batches of `epoch` (asynchronous)."""
+        cfg, ctx = self.cfg, self.ctx
+        assert n_batches <= self.max_batches
+        ctx.epoch_schedule(self.wl.train_ids, self.wl.seed, epoch, self.order)
+        self.counts.zero_()
+        n_train = self.order.numel()
+        for b in range(n_batches):
+            seeds = self.order[b * cfg.batch_size:min((b + 1) * cfg.batch_size, n_train)]
+            self.bufs.set_outputs(self.arena[b], self.tier_offs[b])
+            ctx.sample_blocks(self.csr, seeds, seeds.numel(), cfg.fanouts, self.wl.seed, epoch, self.bufs)
+            ctx.access_histogram(self.arena[b], self.slot, self.counts, n_dev=self.tier_offs[b, self.H + 1:])
+        ctx.build_cache(self.counts, self.wl.home, self.wl.remote_store, cfg.feat_dim, self.cache)
+        self.n_batches = n_batches
+
+    def read_sizes(self):
+        """One device-to-host copy of every batch's tier offsets (synchronises)."""
+        self.sizes = self.tier_offs[:self.n_batches, self.H + 1].cpu().tolist()
+        return self.sizes
+
+    def gather(self, b):
+        """Online stage for batch b: features of its input nodes into self.out[:n]."""
+        n = self.sizes[b]
+        self.ctx.gather_features(self.arena[b], n, self.cache, self.wl.local_store, self.wl.remote_store,
+                                 self.cfg.feat_dim, self.out, self.stats[b], miss_stream=self.side)
+        return n
+
+    def run_epoch(self, epoch, n_batches):
+        self.precompute(epoch, n_batches)
+        self.read_sizes()
+        for b in range(n_batches):
+            self.gather(b)
