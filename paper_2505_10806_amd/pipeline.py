@@ -32,20 +32,22 @@ class EpochPipeline:
         self.ctx.reserve(cfg.num_nodes, self.slot, self.slot)
         self.sizes = None
 
-    def precompute(self, epoch, n_batches):
-        """Offline stage for the first n_batches batches of `epoch` (asynchronous)."""
+    def precompute(self, epoch, n_batches=None, batch_ids=None):
+        """Offline stage (asynchronous) for the first n_batches batches of `epoch`, or for the listed
+        batch indices; slot i of the arena holds the i-th of them."""
         cfg, ctx = self.cfg, self.ctx
-        assert n_batches <= self.max_batches
+        ids = list(batch_ids) if batch_ids is not None else list(range(n_batches))
+        assert len(ids) <= self.max_batches and all(0 <= b < self.batches_per_epoch for b in ids)
         ctx.epoch_schedule(self.wl.train_ids, self.wl.seed, epoch, self.order)
         self.counts.zero_()
         n_train = self.order.numel()
-        for b in range(n_batches):
+        for i, b in enumerate(ids):
             seeds = self.order[b * cfg.batch_size:min((b + 1) * cfg.batch_size, n_train)]
-            self.bufs.set_outputs(self.arena[b], self.tier_offs[b])
+            self.bufs.set_outputs(self.arena[i], self.tier_offs[i])
             ctx.sample_blocks(self.csr, seeds, seeds.numel(), cfg.fanouts, self.wl.seed, epoch, self.bufs)
-            ctx.access_histogram(self.arena[b], self.slot, self.counts, n_dev=self.tier_offs[b, self.H + 1:])
+            ctx.access_histogram(self.arena[i], self.slot, self.counts, n_dev=self.tier_offs[i, self.H + 1:])
         ctx.build_cache(self.counts, self.wl.home, self.wl.remote_store, cfg.feat_dim, self.cache)
-        self.n_batches = n_batches
+        self.n_batches = len(ids)
 
     def read_sizes(self):
         """One device-to-host copy of every batch's tier offsets (synchronises)."""
