@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--seed", type=int, default=2025)
     ap.add_argument("--cpu-batches", type=int, default=None, help="batches the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--one-stream", action="store_true", help="copy miss rows on the same stream as the HBM rows")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy a few times (reference for hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the remote partition is pinned host memory); "
@@ -93,6 +95,21 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "ms": ms,
+                          "GBps_read_plus_write": 2 * (1 << 30) / (ms * 1e-3) / 1e9}), flush=True)
+        return
     t_gen = time.perf_counter()
     wl = synth.build_workload(args.workload, seed=args.seed, device=dev)
     cfg = wl.cfg

@@ -57,7 +57,7 @@ __global__ void __launch_bounds__(256) k_classify(const int32_t* __restrict__ no
 }
 
 // Rows whose source is in HBM.  Each wave step moves 64/L rows of cpr chunks; U steps are unrolled.
-template <int VEC, int U>
+template <int VEC, int U, bool NT>
 __global__ void __launch_bounds__(256) k_gather_hbm(const uint32_t* __restrict__ src, int64_t n, const int32_t* __restrict__ n_dev,
                                                     const float* __restrict__ local_store, int64_t local_stride,
                                                     const float* __restrict__ cache_rows, int64_t cache_stride,
@@ -96,7 +96,10 @@ __global__ void __launch_bounds__(256) k_gather_hbm(const uint32_t* __restrict__
                 if (sp[u]) val[u] = sp[u][c];
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (dp[u]) __builtin_nontemporal_store(val[u], &dp[u][c]);
+                if (dp[u]) {
+                    if (NT) __builtin_nontemporal_store(val[u], &dp[u][c]);
+                    else dp[u][c] = val[u];
+                }
         }
     }
 }
@@ -202,23 +205,35 @@ rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n,
     const int vec = rg_pick_vec(dim, ptrs, 4, strides, 4);
     const RgRowShape shp = rg_row_shape(dim, vec);
     constexpr int U = 4;
-    const int rows_per_block = 4 * (RG_WAVE >> shp.log2L) * U;
-    const int per_cu = env_int("RG_GATHER_BLOCKS_PER_CU", 16);
+    int unroll = env_int("RG_GATHER_UNROLL", 2);
+    if (vec != 4) unroll = 4;
+    else if (unroll != 2 && unroll != 4 && unroll != 8) unroll = 2;
+    const bool nt = env_int("RG_GATHER_NT", 1) == 1;
+    const int rows_per_block = 4 * (RG_WAVE >> shp.log2L) * unroll;
+    const int per_cu = env_int("RG_GATHER_BLOCKS_PER_CU", 4096);
     const int grid = (int)rg_max64(1, rg_min64(rg_div_up(n, rows_per_block), (int64_t)ctx->num_cus * per_cu));
     const float* cache_rows = cache->cache_rows ? cache->cache_rows : local_store;   // never dereferenced without cache words
 
     int tok = rg_prof_begin(ctx, RG_K_GATHER_HBM, sh);
-    if (vec == 4)
-        k_gather_hbm<4, U><<<grid, 256, 0, sh>>>(src, n, n_dev, local_store, local_stride, cache_rows, cache->row_stride, out, out_stride, shp.cpr, shp.log2L);
-    else if (vec == 2)
-        k_gather_hbm<2, U><<<grid, 256, 0, sh>>>(src, n, n_dev, local_store, local_stride, cache_rows, cache->row_stride, out, out_stride, shp.cpr, shp.log2L);
-    else
-        k_gather_hbm<1, U><<<grid, 256, 0, sh>>>(src, n, n_dev, local_store, local_stride, cache_rows, cache->row_stride, out, out_stride, shp.cpr, shp.log2L);
+#define RG_LAUNCH_HBM(V, UU, NTT)                                                                                  \
+    k_gather_hbm<V, UU, NTT><<<grid, 256, 0, sh>>>(src, n, n_dev, local_store, local_stride, cache_rows,          \
+                                                   cache->row_stride, out, out_stride, shp.cpr, shp.log2L)
+    if (vec == 4) {
+        if (unroll == 2) { if (nt) RG_LAUNCH_HBM(4, 2, true); else RG_LAUNCH_HBM(4, 2, false); }
+        else if (unroll == 8) { if (nt) RG_LAUNCH_HBM(4, 8, true); else RG_LAUNCH_HBM(4, 8, false); }
+        else { if (nt) RG_LAUNCH_HBM(4, 4, true); else RG_LAUNCH_HBM(4, 4, false); }
+    } else if (vec == 2) {
+        RG_LAUNCH_HBM(2, 4, true);
+    } else {
+        RG_LAUNCH_HBM(1, 4, true);
+    }
+#undef RG_LAUNCH_HBM
     rg_prof_end(ctx, tok, sh);
     RG_LAUNCH_CHECK(ctx, "k_gather_hbm");
 
     const int miss_per_cu = env_int("RG_MISS_BLOCKS_PER_CU", 8);
-    const int miss_grid = (int)rg_max64(1, rg_min64(rg_div_up(n, rows_per_block), (int64_t)ctx->num_cus * miss_per_cu));
+    const int miss_rows_per_block = 4 * (RG_WAVE >> shp.log2L) * U;
+    const int miss_grid = (int)rg_max64(1, rg_min64(rg_div_up(n, miss_rows_per_block), (int64_t)ctx->num_cus * miss_per_cu));
     tok = rg_prof_begin(ctx, RG_K_GATHER_MISS, sm);
     if (vec == 4)
         k_gather_miss<4, U><<<miss_grid, 256, 0, sm>>>(src, miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);

@@ -235,6 +235,71 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const RP* __restric
     }
 }
 
+// Fast sampler for fan-outs up to 32 on graphs with fewer than 2^32 edges: one thread per frontier node
+// draws (Philox + Floyd entirely in registers), the 256 nodes of a workgroup stage the col_idx offsets
+// of their picks in LDS in output order, then the whole workgroup reads col_idx and writes nbr with
+// consecutive lanes on consecutive output slots.
+template <typename RP, int KMAX>
+__global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const RP* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                                                              const int32_t* __restrict__ nodes,
+                                                              const int32_t* __restrict__ n_frontier_ptr, int fanout, uint32_t hop,
+                                                              uint32_t k0, uint32_t k1, uint32_t epoch,
+                                                              int32_t* __restrict__ indptr, const int32_t* __restrict__ chunk_sum,
+                                                              int32_t* __restrict__ nbr, const uint32_t* __restrict__ visited,
+                                                              uint32_t* __restrict__ fresh) {
+    extern __shared__ uint32_t staged[];                 // kChunk * fanout col_idx offsets
+    const int n_h = *n_frontier_ptr;
+    const int64_t first = (int64_t)blockIdx.x * kChunk;
+    if (first >= n_h) return;                            // uniform per workgroup
+    const int64_t i = first + threadIdx.x;
+    const int k = fanout;
+    // chunk_sum[b] is the exclusive offset of chunk b; the chunk's edge count follows from its successor
+    // (or from the hop total behind the last indptr entry for the last chunk)
+    const int base = chunk_sum[blockIdx.x];
+    const bool last_chunk = first + kChunk >= n_h;
+    const int chunk_edges = (last_chunk ? indptr[n_h] : chunk_sum[blockIdx.x + 1]) - base;
+    if (i < n_h) {
+        const int32_t v = nodes[i];
+        int64_t start, deg;
+        rg_row_extent(row_ptr, v, start, deg);
+        const int off = indptr[i];                       // chunk-local exclusive prefix from k_hop_count
+        indptr[i] = base + off;
+        if (deg <= k) {                                  // whole row, CSR order
+            for (int t = 0; t < (int)deg; ++t) staged[off + t] = (uint32_t)(start + t);
+        } else {
+            uint32_t c[KMAX];
+#pragma unroll
+            for (int blk = 0; blk < KMAX / 4; ++blk) {
+                if (blk * 4 < k) {
+                    uint32_t w[4];
+                    rg_philox4x32_10((uint32_t)v, hop, (uint32_t)blk, epoch, k0, k1, w);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int s = blk * 4 + q;
+                        if (s < k) {                     // Floyd: j = d-k+s, t uniform in [0, j]
+                            const uint32_t j = (uint32_t)(deg - k + s);
+                            const uint32_t t = __umulhi(w[q], j + 1u);
+                            bool found = false;
+#pragma unroll
+                            for (int l = 0; l < s; ++l) found |= (c[l] == t);
+                            c[s] = found ? j : t;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < KMAX; ++s)
+                if (s < k) staged[off + s] = (uint32_t)(start + (int64_t)c[s]);
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < chunk_edges; e += kChunk) {
+        const int32_t u = col_idx[staged[e]];
+        nbr[base + e] = u;
+        rg_mark_fresh(u, visited, fresh);
+    }
+}
+
 // ---------------------------------------------------------------------------- per hop: new tier
 __global__ void __launch_bounds__(256) k_tier_count(const uint32_t* __restrict__ fresh, int64_t words,
                                                     int32_t* __restrict__ blk_sum) {
@@ -412,18 +477,34 @@ rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds,
         k_scan_sums<<<1, 1024, 0, s>>>(chunk_sum, n_frontier, 0, kChunk, nullptr, indptr, 1);
         RG_LAUNCH_CHECK(ctx, "k_scan_sums");
 
-        const int sample_blocks = grid_for(fub[h], 1, (int64_t)ctx->num_cus * 64);
         const int tok = rg_prof_begin(ctx, RG_K_SAMPLE, s);
-        if (rp64)
-            k_hop_sample_wave<int64_t><<<sample_blocks, RG_WAVE, 0, s>>>((const int64_t*)csr->row_ptr, csr->col_idx, out->nodes, n_frontier,
-                                                                        fanouts[h], (uint32_t)h, k0, k1, epoch, indptr, chunk_sum,
-                                                                        out->nbr[h], visited, fresh);
-        else
-            k_hop_sample_wave<int32_t><<<sample_blocks, RG_WAVE, 0, s>>>((const int32_t*)csr->row_ptr, csr->col_idx, out->nodes, n_frontier,
-                                                                        fanouts[h], (uint32_t)h, k0, k1, epoch, indptr, chunk_sum,
-                                                                        out->nbr[h], visited, fresh);
+        const int F = fanouts[h];
+        if (F >= 1 && F <= 32 && csr->num_edges < (1ll << 32)) {
+            const int kmax = F <= 8 ? 8 : (F <= 16 ? 16 : 32);
+            const size_t lds = (size_t)kChunk * F * sizeof(uint32_t);
+#define RG_LAUNCH_FAST(RPT, KM)                                                                                       \
+    k_hop_sample_thread<RPT, KM><<<count_blocks, kChunk, lds, s>>>((const RPT*)csr->row_ptr, csr->col_idx, out->nodes,    \
+                                                                   n_frontier, F, (uint32_t)h, k0, k1, epoch, indptr,    \
+                                                                   chunk_sum, out->nbr[h], visited, fresh)
+            if (rp64) {
+                if (kmax == 8) RG_LAUNCH_FAST(int64_t, 8); else if (kmax == 16) RG_LAUNCH_FAST(int64_t, 16); else RG_LAUNCH_FAST(int64_t, 32);
+            } else {
+                if (kmax == 8) RG_LAUNCH_FAST(int32_t, 8); else if (kmax == 16) RG_LAUNCH_FAST(int32_t, 16); else RG_LAUNCH_FAST(int32_t, 32);
+            }
+#undef RG_LAUNCH_FAST
+        } else {
+            const int sample_blocks = grid_for(fub[h], 1, (int64_t)ctx->num_cus * 64);
+            if (rp64)
+                k_hop_sample_wave<int64_t><<<sample_blocks, RG_WAVE, 0, s>>>((const int64_t*)csr->row_ptr, csr->col_idx, out->nodes, n_frontier,
+                                                                            F, (uint32_t)h, k0, k1, epoch, indptr, chunk_sum,
+                                                                            out->nbr[h], visited, fresh);
+            else
+                k_hop_sample_wave<int32_t><<<sample_blocks, RG_WAVE, 0, s>>>((const int32_t*)csr->row_ptr, csr->col_idx, out->nodes, n_frontier,
+                                                                            F, (uint32_t)h, k0, k1, epoch, indptr, chunk_sum,
+                                                                            out->nbr[h], visited, fresh);
+        }
         rg_prof_end(ctx, tok, s);
-        RG_LAUNCH_CHECK(ctx, "k_hop_sample_wave");
+        RG_LAUNCH_CHECK(ctx, "k_hop_sample");
 
         // new tier: count fresh bits per block, scan, emit ascending
         k_tier_count<<<tier_blocks, 256, 0, s>>>(fresh, words, chunk_sum);

@@ -4,13 +4,16 @@ import math
 import torch
 
 
-def _expected_degree_weights(num_nodes, target_nnz, gamma, device):
-    """w_r = min(c * (r+1)^(-1/(gamma-1)), sqrt(target_nnz)), c chosen so that sum(w) = target_nnz."""
+def _expected_degree_weights(num_nodes, target_nnz, gamma):
+    """w_r = min(c * (r+1)^(-1/(gamma-1)), sqrt(target_nnz)), c chosen so that sum(w) = target_nnz.
+
+    Computed on the CPU: parallel floating-point reductions on the GPU are not bit-reproducible from
+    run to run, and the weights decide which edges are drawn."""
     alpha = 1.0 / (gamma - 1.0)
-    base = torch.arange(1, num_nodes + 1, dtype=torch.float64, device=device).pow_(-alpha)
+    base = torch.arange(1, num_nodes + 1, dtype=torch.float64).pow_(-alpha)
     cap = math.sqrt(float(target_nnz))
     lo, hi = 0.0, float(target_nnz)          # base[0] == 1, so c = target_nnz certainly overshoots
-    for _ in range(64):
+    for _ in range(48):
         mid = 0.5 * (lo + hi)
         total = torch.clamp(base * mid, max=cap).sum().item()
         if total < target_nnz:
@@ -37,9 +40,10 @@ def chung_lu_csr(num_nodes, mean_degree, gamma, seed, device="cpu", offsets64=Fa
     target_nnz = int(round(mean_degree * n))
     n_und = target_nnz // 2
 
-    w = _expected_degree_weights(n, target_nnz, gamma, device)
+    w = _expected_degree_weights(n, target_nnz, gamma)
     cdf = torch.cumsum(w, 0)
     cdf /= cdf[-1].clone()
+    cdf = cdf.to(device)
     del w
     perm = torch.randperm(n, generator=gen, device=device)
 
