@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--seed", type=int, default=2025)
     ap.add_argument("--cpu-batches", type=int, default=None, help="batches the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--one-stream", action="store_true", help="copy miss rows on the same stream as the HBM rows")
+    ap.add_argument("--bulk-fill", action="store_true",
+                    help="pull all cached rows in one go after TopHot instead of batch by batch ahead of the gathers")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -123,7 +125,8 @@ def main():
     warmup = args.warmup
     main_stream = torch.cuda.Stream()
     with torch.cuda.stream(main_stream):
-        pipe = EpochPipeline(wl, device=dev, max_batches=min(max(steps, warmup, 1), bpe), two_streams=not args.one_stream)
+        pipe = EpochPipeline(wl, device=dev, max_batches=min(max(steps, warmup, 1), bpe), two_streams=not args.one_stream,
+                             prefetch=not args.bulk_fill)
         ctx = pipe.ctx
         if warmup > 0:
             run_steps(pipe, warmup)
@@ -167,7 +170,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg.name, "num_nodes": cfg.num_nodes, "nnz": wl.nnz, "feat_dim": cfg.feat_dim,
                    "fanouts": list(cfg.fanouts), "batch_size": cfg.batch_size, "epochs_timed": totals["epochs"],
-                   "cache_capacity_rows": wl.capacity_rows, "miss_stream": "shared" if args.one_stream else "separate"},
+                   "cache_capacity_rows": wl.capacity_rows, "miss_stream": "shared" if args.one_stream else "separate",
+                   "cache_fill": "bulk" if args.bulk_fill else "prefetch by first use"},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "algorithmic_bytes_per_launch": alg_bytes / max(g_launches, 1),

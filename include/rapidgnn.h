@@ -4,7 +4,7 @@
  * The library implements the steps of the paper's Algorithm 1 that move data:
  *   line 1     precompute the mini-batches of an epoch with a seeded sampler  -> rg_epoch_schedule, rg_sample_blocks
  *   line 2-3   access frequencies of the precomputed input nodes, TopHot      -> rg_access_histogram, rg_build_cache
- *   line 4     VectorPull of the hot rows into the steady cache C_s           -> rg_build_cache (fill)
+ *   line 4     VectorPull of the hot rows into the steady cache C_s           -> rg_build_cache (bulk) or rg_prefetch_cache_rows (by first use)
  *   line 12-14 per-batch feature assembly from local store, cache and         -> rg_gather_features
  *              fallback pull of the misses from the remote store
  * Every step runs in HIP kernels on the device; there is no CPU fallback.
@@ -161,8 +161,11 @@ RG_API rg_status rg_access_histogram(rg_ctx* ctx, const int32_t* nodes, int64_t 
  * Candidates = nodes whose home word is remote and whose count >= 1, ranked by
  * (count descending, id ascending).  K_eff = min(capacity_rows, #candidates) are selected;
  * cache_ids = selected ids ascending, slot = rank in that order; loc[v] = cache word for the
- * selected nodes and home[v] for all others; cache_rows[slot] = remote_store row of the node
- * (one bulk pull over the host link).  *num_cached = K_eff.
+ * selected nodes and home[v] for all others; *num_cached = K_eff.
+ * With remote_store != NULL the rows are pulled at once: cache_rows[slot] = remote_store row of
+ * the node (one bulk pull over the host link) and, if `filled` is given, every selected slot is
+ * marked resident.  With remote_store == NULL only the selection is made and `filled` (required
+ * then) is cleared: rows are pulled later, batch by batch, by rg_prefetch_cache_rows.
  */
 typedef struct {
     int32_t* cache_ids;       /* device int32[capacity_rows] */
@@ -171,13 +174,28 @@ typedef struct {
     int64_t row_stride;       /* floats, >= dim */
     int32_t* loc;             /* device int32[num_nodes] location words */
     int64_t* num_cached;      /* device int64[1], written by rg_build_cache */
+    uint32_t* filled;         /* device uint32[ceil(min(capacity_rows, num_nodes) / 32)] or NULL: bit s set = row of slot s is resident */
 } rg_cache;
 
 /* counts: device uint32[num_nodes]; home: device int32[num_nodes] (never modified);
- * remote_store: mapped float[n_remote * remote_stride]; dim >= 1. */
+ * remote_store: mapped float[n_remote * remote_stride] or NULL (select only); dim >= 1. */
 RG_API rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32_t* home, int64_t num_nodes,
                          const float* remote_store, int64_t remote_stride, int32_t dim,
                          const rg_cache* cache, void* stream);
+
+/* ---- prefetcher (Section III: features of upcoming batches are prepared ahead of their use) ----
+ * Pulls, over the host link, the rows of those cached nodes among input_nodes[0..n) whose slot is
+ * not yet resident, and marks them resident.  Called batch by batch ahead of rg_gather_features
+ * (typically on its own stream, with an event per batch), it fills the cache in order of first
+ * use, so the transfer of later rows overlaps the gathers of earlier batches; over an epoch every
+ * selected row is pulled exactly once, the same traffic as the bulk pull.
+ * Calls on one cache must be ordered with each other and with rg_build_cache; a gather may only
+ * read a batch after the prefetch of that batch has completed.
+ * input_nodes: device int32[>= n]; n_dev as for rg_access_histogram; cache->filled required. */
+RG_API rg_status rg_prefetch_cache_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
+                                        const rg_cache* cache, const int32_t* home,
+                                        const float* remote_store, int64_t remote_stride, int32_t dim,
+                                        void* stream);
 
 /* ---- Alg. 1 lines 12-14: feature assembly for one batch ---------------------------------
  * out[i][0:dim] = feature row of input_nodes[i], read from the store loc[] names: local
@@ -206,7 +224,7 @@ typedef enum {
     RG_K_GATHER_MISS = 1,  /* rows pulled from the remote store */
     RG_K_SAMPLE = 2,       /* per-hop draw + neighbour read kernel */
     RG_K_HISTOGRAM = 3,
-    RG_K_CACHE_FILL = 4,
+    RG_K_CACHE_FILL = 4,   /* bulk pull and per-batch prefetch pulls */
     RG_K_COUNT_
 } rg_kernel_id;
 

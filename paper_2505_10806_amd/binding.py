@@ -46,7 +46,7 @@ class rg_blocks(ctypes.Structure):
 
 class rg_cache(ctypes.Structure):
     _fields_ = [("cache_ids", c_p), ("cache_rows", c_p), ("capacity_rows", c_i64),
-                ("row_stride", c_i64), ("loc", c_p), ("num_cached", c_p)]
+                ("row_stride", c_i64), ("loc", c_p), ("num_cached", c_p), ("filled", c_p)]
 
 
 def _load():
@@ -68,14 +68,15 @@ def _load():
                                    ctypes.POINTER(rg_blocks), c_p]
     L.rg_access_histogram.argtypes = [c_p, c_p, c_i64, c_p, c_p, c_i64, c_p]
     L.rg_build_cache.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i64, c_i32, ctypes.POINTER(rg_cache), c_p]
+    L.rg_prefetch_cache_rows.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_p, c_i64, c_i32, c_p]
     L.rg_gather_features.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_i64, c_p, c_i64,
                                      c_i32, c_p, c_i64, c_p, c_p, c_p]
     L.rg_profile_enable.argtypes = [c_p, ctypes.c_int]
     L.rg_profile_reset.argtypes = [c_p]
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks",
-                 "rg_access_histogram", "rg_build_cache", "rg_gather_features", "rg_profile_enable",
-                 "rg_profile_reset", "rg_profile_read"):
+                 "rg_access_histogram", "rg_build_cache", "rg_prefetch_cache_rows", "rg_gather_features",
+                 "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -84,7 +85,7 @@ _lib = _load()
 
 EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "rg_reserve", "rg_epoch_schedule",
                     "rg_blocks_bounds", "rg_sample_blocks", "rg_access_histogram", "rg_build_cache",
-                    "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
+                    "rg_prefetch_cache_rows", "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
 
 
 def _ptr(t, dtype=None, device_type=None, name="tensor"):
@@ -167,11 +168,21 @@ class Context:
 
     # -- rg_build_cache
     def build_cache(self, counts, home, remote_store, dim, cache, stream=None):
+        """remote_store=None selects only (rows are pulled later by prefetch_cache_rows)."""
+        rs = 0 if remote_store is None else (remote_store.stride(0) if remote_store.dim() == 2 else dim)
         self._check(_lib.rg_build_cache(self._h, _ptr(counts, torch.int32, "cuda", "counts"),
                                         _ptr(home, torch.int32, "cuda", "home"), home.numel(),
-                                        _ptr(remote_store, torch.float32, "mapped", "remote_store"),
-                                        remote_store.stride(0) if remote_store.dim() == 2 else dim, int(dim),
+                                        _ptr(remote_store, torch.float32, "mapped", "remote_store"), rs, int(dim),
                                         ctypes.byref(cache.c_struct), _stream_handle(stream)))
+
+    # -- rg_prefetch_cache_rows
+    def prefetch_cache_rows(self, input_nodes, n, cache, home, remote_store, dim, n_dev=None, stream=None):
+        self._check(_lib.rg_prefetch_cache_rows(
+            self._h, _ptr(input_nodes, torch.int32, "cuda", "input_nodes"), int(n),
+            _ptr(n_dev, torch.int32, "cuda", "n_dev"), ctypes.byref(cache.c_struct),
+            _ptr(home, torch.int32, "cuda", "home"),
+            _ptr(remote_store, torch.float32, "mapped", "remote_store"), remote_store.stride(0), int(dim),
+            _stream_handle(stream)))
 
     # -- rg_gather_features
     def gather_features(self, input_nodes, n, cache, local_store, remote_store, dim, out, stats,
@@ -276,5 +287,6 @@ class FeatureCache:
         self.cache_rows = torch.empty(max(self.capacity_rows, 1), int(row_stride), dtype=torch.float32, device=device)
         self.loc = torch.empty(max(num_nodes, 1), dtype=torch.int32, device=device)
         self.num_cached = torch.zeros(1, dtype=torch.int64, device=device)
+        self.filled = torch.zeros(max((min(self.capacity_rows, num_nodes) + 31) // 32, 1), dtype=torch.int32, device=device)
         self.c_struct = rg_cache(self.cache_ids.data_ptr(), self.cache_rows.data_ptr(), self.capacity_rows,
-                                 int(row_stride), self.loc.data_ptr(), self.num_cached.data_ptr())
+                                 int(row_stride), self.loc.data_ptr(), self.num_cached.data_ptr(), self.filled.data_ptr())

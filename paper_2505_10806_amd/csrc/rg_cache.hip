@@ -1,5 +1,7 @@
 // Access-frequency histogram (Section IV, offline stage), TopHot selection (Alg. 1 line 3) and the
 // bulk pull of the selected rows into the HBM cache (VectorPull, Alg. 1 line 4).
+#include <stdlib.h>
+
 #include "rg_rowcopy.h"
 
 namespace {
@@ -229,6 +231,104 @@ __global__ void __launch_bounds__(256) k_cache_fill(const int32_t* __restrict__ 
     }
 }
 
+// filled[w] = all-ones for slots below *num_cached (value = 1) or all-zero (value = 0).
+__global__ void __launch_bounds__(256) k_set_filled(uint32_t* __restrict__ filled, int64_t words, const int64_t* __restrict__ num_cached,
+                                                    int value) {
+    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= words) return;
+    uint32_t bits = 0u;
+    if (value) {
+        const int64_t k = *num_cached;
+        const int64_t lo = w * 32;
+        if (k >= lo + 32) bits = 0xFFFFFFFFu;
+        else if (k > lo) bits = (1u << (uint32_t)(k - lo)) - 1u;
+    }
+    filled[w] = bits;
+}
+
+__global__ void k_prefetch_reset(uint32_t* __restrict__ pctl) {
+    if (threadIdx.x == 0) pctl[0] = 0u;
+}
+
+// For every listed node whose location word names a cache slot that is not yet resident: claim the slot
+// (atomic test-and-set of its bit) and append (slot, remote row) to the pull list.
+__global__ void __launch_bounds__(256) k_prefetch_select(const int32_t* __restrict__ nodes, int64_t n, const int32_t* __restrict__ n_dev,
+                                                         const int32_t* __restrict__ loc, const int32_t* __restrict__ home,
+                                                         uint32_t* __restrict__ filled, int32_t* __restrict__ list,
+                                                         uint32_t* __restrict__ pctl) {
+    __shared__ int smem[256 / RG_WAVE + 1];
+    __shared__ uint32_t base_s;
+    int64_t n_act = n;
+    if (n_dev) { const int64_t d = *n_dev; n_act = d < n ? d : n; }
+    if ((int64_t)blockIdx.x * blockDim.x >= n_act) return;        // uniform per workgroup
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int take = 0;
+    uint32_t slot = 0u, rrow = 0u;
+    if (i < n_act) {
+        const int32_t v = nodes[i];
+        const uint32_t w = (uint32_t)loc[v];
+        if ((w >> RG_TAG_SHIFT) == RG_TAG_CACHE) {
+            slot = w & RG_ROW_MASK;
+            const uint32_t bit = 1u << (slot & 31u);
+            if (!(filled[slot >> 5] & bit)) {
+                const uint32_t old = atomicOr(&filled[slot >> 5], bit);
+                if (!(old & bit)) { take = 1; rrow = (uint32_t)home[v] & RG_ROW_MASK; }
+            }
+        }
+    }
+    int total;
+    const int excl = rg_block_excl_scan<256 / RG_WAVE>(take, smem, &total);
+    if (total == 0) return;                                        // uniform
+    if (threadIdx.x == 0) base_s = atomicAdd(&pctl[0], (uint32_t)total);
+    __syncthreads();
+    if (take) {
+        const int64_t j = (int64_t)base_s + excl;
+        list[2 * j] = (int32_t)slot;
+        list[2 * j + 1] = (int32_t)rrow;
+    }
+}
+
+// cache_rows[slot] = remote_store[rrow] for every pair of the pull list.
+template <int VEC>
+__global__ void __launch_bounds__(1024) k_prefetch_pull(const int32_t* __restrict__ list, const uint32_t* __restrict__ pctl,
+                                                       const float* __restrict__ remote_store, int64_t remote_stride,
+                                                       float* __restrict__ cache_rows, int64_t cache_stride, int cpr, int log2L) {
+    typedef typename RgVec<VEC>::type V;
+    constexpr int U = 4;
+    const int64_t n = pctl[0];
+    const int lane = rg_lane();
+    const int L = 1 << log2L;
+    const int R = RG_WAVE >> log2L;
+    const int sub = lane >> log2L;
+    const int c0 = lane & (L - 1);
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t j0 = wave * (R * U); j0 < n; j0 += nwaves * (R * U)) {
+        const V* src[U];
+        V* dst[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t j = j0 + u * R + sub;
+            src[u] = nullptr;
+            dst[u] = nullptr;
+            if (j < n) {
+                const int64_t slot = list[2 * j], rrow = list[2 * j + 1];
+                src[u] = (const V*)(remote_store + rrow * remote_stride);
+                dst[u] = (V*)(cache_rows + slot * cache_stride);
+            }
+        }
+        for (int c = c0; c < cpr; c += L) {
+            V val[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (src[u]) val[u] = src[u][c];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (dst[u]) dst[u][c] = val[u];
+        }
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -259,11 +359,13 @@ rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32_t* hom
     RG_REQUIRE(ctx, cache->capacity_rows >= 0 && cache->capacity_rows <= (int64_t)RG_ROW_MASK + 1,
                "rg_build_cache: capacity_rows = %lld out of range", (long long)cache->capacity_rows);
     RG_REQUIRE(ctx, dim >= 1, "rg_build_cache: dim = %d must be positive", dim);
-    RG_REQUIRE(ctx, cache->row_stride >= dim && remote_stride >= dim, "rg_build_cache: row stride smaller than dim");
+    RG_REQUIRE(ctx, cache->row_stride >= dim && (!remote_store || remote_stride >= dim), "rg_build_cache: row stride smaller than dim");
+    RG_REQUIRE(ctx, remote_store || cache->filled || cache->capacity_rows == 0 || num_nodes == 0,
+               "rg_build_cache: select-only mode (remote_store == NULL) needs cache->filled");
     RG_REQUIRE(ctx, cache->num_cached, "rg_build_cache: num_cached is NULL");
     RG_REQUIRE(ctx, num_nodes == 0 || (counts && home && cache->loc), "rg_build_cache: null node array");
     const bool may_select = cache->capacity_rows > 0 && num_nodes > 0;
-    RG_REQUIRE(ctx, !may_select || (cache->cache_ids && cache->cache_rows && remote_store), "rg_build_cache: null cache buffer");
+    RG_REQUIRE(ctx, !may_select || (cache->cache_ids && cache->cache_rows), "rg_build_cache: null cache buffer");
     RG_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t s = (hipStream_t)stream;
 
@@ -291,7 +393,8 @@ rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32_t* hom
     k_topk_emit<<<(int)nblocks, 256, 0, s>>>(counts, home, num_nodes, ctl, blk_gt, blk_eq, cache->cache_ids, cache->loc);
     RG_LAUNCH_CHECK(ctx, "k_topk_emit");
 
-    if (may_select) {
+    const int64_t filled_words = rg_div_up(rg_min64(cache->capacity_rows, num_nodes), 32);
+    if (may_select && remote_store) {
         const void* ptrs[2] = {remote_store, cache->cache_rows};
         const int64_t strides[2] = {remote_stride, cache->row_stride};
         const int vec = rg_pick_vec(dim, ptrs, 2, strides, 2);
@@ -309,6 +412,54 @@ rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32_t* hom
         rg_prof_end(ctx, tok, s);
         RG_LAUNCH_CHECK(ctx, "k_cache_fill");
     }
+    if (cache->filled && filled_words > 0) {
+        k_set_filled<<<(int)rg_div_up(filled_words, 256), 256, 0, s>>>(cache->filled, filled_words, cache->num_cached, remote_store ? 1 : 0);
+        RG_LAUNCH_CHECK(ctx, "k_set_filled");
+    }
+    return RG_OK;
+}
+
+rg_status rg_prefetch_cache_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
+                                 const rg_cache* cache, const int32_t* home, const float* remote_store,
+                                 int64_t remote_stride, int32_t dim, void* stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_prefetch_cache_rows: n = %lld out of range", (long long)n);
+    if (n == 0) return RG_OK;
+    RG_REQUIRE(ctx, cache && cache->loc && cache->filled && cache->cache_rows, "rg_prefetch_cache_rows: cache needs loc, filled and cache_rows");
+    RG_REQUIRE(ctx, input_nodes && home && remote_store, "rg_prefetch_cache_rows: null pointer");
+    RG_REQUIRE(ctx, dim >= 1 && cache->row_stride >= dim && remote_stride >= dim, "rg_prefetch_cache_rows: bad dim / stride");
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    rg_status st;
+    if ((st = rg_ensure(ctx, ctx->pf_ctl, 64)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->pf_list, (size_t)n * 8)) != RG_OK) return st;
+    uint32_t* pctl = (uint32_t*)ctx->pf_ctl.p;
+    int32_t* list = (int32_t*)ctx->pf_list.p;
+    k_prefetch_reset<<<1, 64, 0, s>>>(pctl);
+    RG_LAUNCH_CHECK(ctx, "k_prefetch_reset");
+    k_prefetch_select<<<(int)rg_div_up(n, 256), 256, 0, s>>>(input_nodes, n, n_dev, cache->loc, home, cache->filled, list, pctl);
+    RG_LAUNCH_CHECK(ctx, "k_prefetch_select");
+    const void* ptrs[2] = {remote_store, cache->cache_rows};
+    const int64_t strides[2] = {remote_stride, cache->row_stride};
+    const int vec = rg_pick_vec(dim, ptrs, 2, strides, 2);
+    const RgRowShape shp = rg_row_shape(dim, vec);
+    const int rows_per_block = 4 * (RG_WAVE >> shp.log2L) * 4;
+    // The pull waits on the host link, not on the GPU: a few hundred wavefronts keep the link busy, and a small
+    // grid leaves the wave slots of every CU to the gathers that run beside it.
+    const char* pb = getenv("RG_PULL_BLOCKS");
+    const int64_t pull_blocks = (pb && atoi(pb) > 0) ? atoi(pb) : 48;
+    const char* pt = getenv("RG_PULL_THREADS");
+    const int pull_threads = (pt && (atoi(pt) == 64 || atoi(pt) == 256 || atoi(pt) == 1024)) ? atoi(pt) : 256;
+    const int grid = (int)rg_max64(1, rg_min64(rg_div_up(n, rows_per_block), pull_blocks));
+    const int tok = rg_prof_begin(ctx, RG_K_CACHE_FILL, s);
+    if (vec == 4)
+        k_prefetch_pull<4><<<grid, pull_threads, 0, s>>>(list, pctl, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L);
+    else if (vec == 2)
+        k_prefetch_pull<2><<<grid, pull_threads, 0, s>>>(list, pctl, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L);
+    else
+        k_prefetch_pull<1><<<grid, pull_threads, 0, s>>>(list, pctl, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L);
+    rg_prof_end(ctx, tok, s);
+    RG_LAUNCH_CHECK(ctx, "k_prefetch_pull");
     return RG_OK;
 }
 

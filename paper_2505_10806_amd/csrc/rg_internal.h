@@ -37,6 +37,9 @@ struct rg_ctx {
     // top-K scratch
     RgBuf topk_ctl;     // TopkCtl
     RgBuf topk_blk;     // int32[2 * nblocks]
+    // prefetch scratch
+    RgBuf pf_list;      // int32[2 * n]: (slot, remote row) pairs still to pull
+    RgBuf pf_ctl;       // uint32[4]: [0] = number of pairs
     // gather scratch
     RgBuf gather_src;   // uint32[n] resolved location word per output row
     RgBuf miss_list;    // int32[n] output rows whose source is the remote store

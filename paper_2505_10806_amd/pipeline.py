@@ -10,7 +10,7 @@ from . import binding as B
 
 
 class EpochPipeline:
-    def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True):
+    def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -29,6 +29,11 @@ class EpochPipeline:
         self.stats = torch.zeros(self.max_batches, 3, dtype=torch.int64, device=device)
         self.order = torch.empty_like(wl.train_ids)
         self.side = torch.cuda.Stream(device=device) if two_streams else None
+        # prefetch = pull cached rows batch by batch, in order of first use, on a stream of their own so the
+        # host-link transfer overlaps the gathers; otherwise one bulk pull right after TopHot
+        self.prefetch = prefetch
+        self.pf_stream = torch.cuda.Stream(device=device) if prefetch else None
+        self.pf_events = [torch.cuda.Event() for _ in range(self.max_batches)] if prefetch else None
         self.ctx.reserve(cfg.num_nodes, self.slot, self.slot)
         self.sizes = None
 
@@ -46,7 +51,7 @@ class EpochPipeline:
             self.bufs.set_outputs(self.arena[i], self.tier_offs[i])
             ctx.sample_blocks(self.csr, seeds, seeds.numel(), cfg.fanouts, self.wl.seed, epoch, self.bufs)
             ctx.access_histogram(self.arena[i], self.slot, self.counts, n_dev=self.tier_offs[i, self.H + 1:])
-        ctx.build_cache(self.counts, self.wl.home, self.wl.remote_store, cfg.feat_dim, self.cache)
+        ctx.build_cache(self.counts, self.wl.home, None if self.prefetch else self.wl.remote_store, cfg.feat_dim, self.cache)
         self.n_batches = len(ids)
 
     def read_sizes(self):
@@ -61,8 +66,27 @@ class EpochPipeline:
                                  self.cfg.feat_dim, self.out, self.stats[b], miss_stream=self.side)
         return n
 
+    def prefetch_rows(self, b, stream=None):
+        """Pull the not-yet-resident cached rows batch b needs (asynchronous on `stream`)."""
+        self.ctx.prefetch_cache_rows(self.arena[b], self.sizes[b], self.cache, self.wl.home, self.wl.remote_store,
+                                     self.cfg.feat_dim, stream=stream)
+
+    def online(self, n_batches):
+        """Online stage: gathers in batch order; with prefetch on, batch b's gather waits only for the pulls
+        of batches 0..b, which run ahead on the prefetch stream."""
+        if not self.prefetch:
+            for b in range(n_batches):
+                self.gather(b)
+            return
+        main = torch.cuda.current_stream()
+        self.pf_stream.wait_stream(main)
+        for b in range(n_batches):
+            self.prefetch_rows(b, stream=self.pf_stream)
+            self.pf_events[b].record(self.pf_stream)
+            main.wait_event(self.pf_events[b])
+            self.gather(b)
+
     def run_epoch(self, epoch, n_batches):
         self.precompute(epoch, n_batches)
         self.read_sizes()
-        for b in range(n_batches):
-            self.gather(b)
+        self.online(n_batches)

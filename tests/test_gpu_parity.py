@@ -196,6 +196,73 @@ def test_full_path_small(B, ctx):
     _full_path(B, ctx, "small", two_streams=True, device_counts=True)
 
 
+def test_prefetch_by_first_use_matches_bulk_fill(B, ctx):
+    """Select-only TopHot followed by per-batch prefetch pulls each selected row exactly when a batch first
+    needs it; gathers and the final cache contents equal those of the bulk pull."""
+    wl = synth.build_workload("tiny", seed=11, device=DEV)
+    cfg = wl.cfg
+    H = len(cfg.fanouts)
+    rp, ci = host_graph(wl)
+    X = wl.features.cpu().numpy()
+    home_np = wl.home.cpu().numpy()
+    csr = B.CsrGraph(wl.row_ptr, wl.col_idx)
+    bufs = B.BlockBuffers(cfg.num_nodes, wl.nnz, cfg.batch_size, cfg.fanouts, DEV)
+    order = ctx.epoch_schedule(wl.train_ids, wl.seed, 0)
+    torch.cuda.synchronize()
+    orc_batches = oracle.epoch_batches(wl.train_ids.cpu().numpy(), cfg.batch_size, wl.seed, 0, 4)
+    counts = torch.zeros(cfg.num_nodes, dtype=torch.int32, device=DEV)
+    counts_orc = np.zeros(cfg.num_nodes, dtype=np.uint32)
+    inputs_dev, inputs_orc = [], []
+    for b in range(4):
+        seeds = order[b * cfg.batch_size:(b + 1) * cfg.batch_size]
+        ctx.sample_blocks(csr, seeds, seeds.numel(), cfg.fanouts, wl.seed, 0, bufs)
+        torch.cuda.synchronize()
+        n = int(bufs.tier_off[H + 1].item())
+        inputs_dev.append(bufs.nodes[:n].clone())
+        ctx.access_histogram(inputs_dev[-1], n, counts)
+        orc = oracle.sample_blocks(rp, ci, orc_batches[b], cfg.fanouts, wl.seed, 0)
+        oracle.access_histogram(orc.input_nodes, counts_orc)
+        inputs_orc.append(orc.input_nodes)
+    cache = B.FeatureCache(cfg.num_nodes, wl.capacity_rows, wl.stride, DEV)
+    cache.cache_rows.fill_(float("nan"))
+    cache.filled.fill_(-1)                                            # stale bits must be cleared by the select
+    ctx.build_cache(counts, wl.home, None, cfg.feat_dim, cache)       # select only
+    torch.cuda.synchronize()
+    ids_orc, loc_orc = oracle.build_cache(counts_orc, home_np, wl.capacity_rows)
+    k = ids_orc.size
+    assert int(cache.num_cached.item()) == k and np.array_equal(cache.cache_ids[:k].cpu().numpy(), ids_orc)
+    assert not cache.filled.cpu().numpy().any()
+    assert torch.isnan(cache.cache_rows).all()
+    slot_of = {int(v): s for s, v in enumerate(ids_orc)}
+    resident = np.zeros(k, dtype=bool)
+    out = torch.empty(bufs.frontier_ub[H], wl.stride, device=DEV)
+    stats = torch.zeros(3, dtype=torch.int64, device=DEV)
+    side = torch.cuda.Stream()
+    for b in range(4):
+        n = inputs_dev[b].numel()
+        ctx.prefetch_cache_rows(inputs_dev[b], n, cache, wl.home, wl.remote_store, cfg.feat_dim, stream=side)
+        side.synchronize()
+        for v in inputs_orc[b]:
+            if int(v) in slot_of:
+                resident[slot_of[int(v)]] = True
+        bits = np.unpackbits(cache.filled.cpu().numpy().view(np.uint8), bitorder="little")[:k].astype(bool)
+        assert np.array_equal(bits, resident), f"resident set after batch {b}"
+        rows = cache.cache_rows[:k, :cfg.feat_dim].cpu().numpy()
+        assert np.array_equal(rows[resident], X[ids_orc[resident]])
+        assert np.isnan(rows[~resident]).all()                        # nothing pulled before its first use
+        ctx.gather_features(inputs_dev[b], n, cache, wl.local_store, wl.remote_store, cfg.feat_dim, out, stats)
+        torch.cuda.synchronize()
+        want, st = oracle.gather_features(X, inputs_orc[b], loc_orc)
+        assert np.array_equal(out[:n, :cfg.feat_dim].cpu().numpy(), want)
+        assert tuple(stats.cpu().tolist()) == st
+    assert resident.all()
+    # a second pass pulls nothing (every slot is resident)
+    cache.cache_rows.fill_(0)
+    ctx.prefetch_cache_rows(inputs_dev[0], inputs_dev[0].numel(), cache, wl.home, wl.remote_store, cfg.feat_dim)
+    torch.cuda.synchronize()
+    assert not cache.cache_rows.any()
+
+
 # ------------------------------------------------------------------------------ TopHot edge cases
 @pytest.mark.parametrize("capacity", [0, 1, 5, 1000, 4000, 1 << 20])
 def test_build_cache_edge_cases(B, ctx, capacity):

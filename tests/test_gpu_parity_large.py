@@ -36,6 +36,8 @@ def _compare_block(pipe, B, wl, rp, ci, epoch, slot, seeds_orc, scratch):
 
 def _gather_and_compare(pipe, wl, X, X1, slot, nodes_orc, loc_orc, rows):
     cfg = wl.cfg
+    if pipe.prefetch:                                   # same order as EpochPipeline.online, synchronous here
+        pipe.prefetch_rows(slot)
     n = pipe.gather(slot)
     torch.cuda.synchronize()
     assert n == nodes_orc.size
@@ -46,6 +48,20 @@ def _gather_and_compare(pipe, wl, X, X1, slot, nodes_orc, loc_orc, rows):
         got = pipe.out[:n, :cfg.feat_dim].cpu().numpy()
         assert np.array_equal(got, want), f"gathered rows of slot {slot}"
     return st
+
+
+def _check_cache_resident(pipe, X, ids_orc, dim):
+    """Every selected node was requested by some batch of the period, so after the gathers every slot has
+    been pulled exactly once: all resident bits set and every cached row equal to the node's feature row."""
+    torch.cuda.synchronize()
+    k = ids_orc.size
+    bits = pipe.cache.filled.cpu().numpy().view(np.uint32)
+    resident = np.unpackbits(bits.view(np.uint8), bitorder="little")[:k]
+    assert resident.all(), "a selected slot was never pulled"
+    assert not np.unpackbits(bits.view(np.uint8), bitorder="little")[k:].any()
+    for lo in range(0, k, 1 << 20):
+        hi = min(k, lo + (1 << 20))
+        assert np.array_equal(pipe.cache.cache_rows[lo:hi, :dim].cpu().numpy(), X[ids_orc[lo:hi]]), "cached rows"
 
 
 @pytest.mark.parametrize("name,row_every", [("dense_social", 16), ("sparse_copurchase", 24)])
@@ -86,10 +102,10 @@ def test_large_workload_full_epoch(name, row_every):
     assert k == ids_orc.size
     assert np.array_equal(pipe.cache.cache_ids[:k].cpu().numpy(), ids_orc)
     assert np.array_equal(pipe.cache.loc.cpu().numpy(), loc_orc)
-    assert np.array_equal(pipe.cache.cache_rows[:k, :cfg.feat_dim].cpu().numpy(), X[ids_orc])
     tot = np.zeros(3, dtype=np.int64)
     for b in range(nb):
         tot += np.array(_gather_and_compare(pipe, wl, X, X1, b, inputs[b], loc_orc, rows=(b % row_every == 0 or b == nb - 1)))
+    _check_cache_resident(pipe, X, ids_orc, cfg.feat_dim)
     remote = _tag(home_np) == 2
     assert tot[1] == int(counts_orc[ids_orc].sum()) and tot[1] + tot[2] == int(counts_orc[remote].sum())
     log(f"[large] {name} epoch 0: cached={k} hit%={100.0 * tot[1] / (tot[1] + tot[2]):.2f} rows={tot.sum()}")
@@ -138,12 +154,10 @@ def test_stress_workload():
     assert k == ids_orc.size == int(((counts_orc > 0) & (_tag(home_np) == 2)).sum())    # capacity exceeds the candidates
     assert np.array_equal(pipe.cache.cache_ids[:k].cpu().numpy(), ids_orc)
     assert np.array_equal(pipe.cache.loc.cpu().numpy(), loc_orc)
-    for lo in range(0, k, 1 << 20):                                                      # cached rows, in slices
-        hi = min(k, lo + (1 << 20))
-        assert np.array_equal(pipe.cache.cache_rows[lo:hi, :cfg.feat_dim].cpu().numpy(), X[ids_orc[lo:hi]])
     for slot in range(len(sample)):
         st = _gather_and_compare(pipe, wl, X, X1, slot, inputs[slot], loc_orc, rows=True)
         assert st[2] == 0
+    _check_cache_resident(pipe, X, ids_orc, cfg.feat_dim)
     log("[stress] three-batch parity ok (all rows served from HBM)")
 
     # (2) the same three batches with a small cache, so that the miss path runs at full row counts
@@ -177,8 +191,7 @@ def test_stress_workload():
     assert np.all(np.diff(cache_ids) > 0) and np.all(remote[cache_ids]) and np.all(counts[cache_ids] > 0)
     loc = pipe.cache.loc.cpu().numpy()
     assert np.array_equal(loc[cache_ids].astype(np.int64) & 0x3FFFFFFF, np.arange(k))
-    for b in range(nb):
-        pipe.gather(b)
+    pipe.online(nb)                                                          # prefetch stream ahead of the gathers
     torch.cuda.synchronize()
     stats = pipe.stats[:nb].cpu().numpy()
     assert np.array_equal(stats.sum(1), np.array(sizes))
