@@ -157,6 +157,19 @@ RG_API rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t*
 RG_API rg_status rg_access_histogram(rg_ctx* ctx, const int32_t* nodes, int64_t n, const int32_t* n_dev,
                               uint32_t* counts, int64_t num_nodes, void* stream);
 
+/* The same histogram over a whole precomputed epoch in one call: batch b's input nodes are
+ * nodes[b * batch_stride .. + tier_off[b][num_hops + 1]), with tier_off[b] the num_hops + 2 tier
+ * offsets rg_sample_blocks wrote for that batch.  Equivalent to one rg_access_histogram call per
+ * batch, but ids that recur across batches are accumulated in LDS-private counters: each workgroup
+ * owns an id range, finds its entries in every ascending tier by binary search and adds the range to
+ * counts once.  Precondition: tiers 1..num_hops of every batch are ascending by id (as produced by
+ * rg_sample_blocks); tier 0 (at most max_seeds seeds per batch) may be in any order.
+ * nodes: device int32; tier_off: device int32[num_batches * (num_hops + 2)]; counts: device
+ * uint32[num_nodes], accumulated; 0 <= num_batches <= 65535. */
+RG_API rg_status rg_access_histogram_epoch(rg_ctx* ctx, const int32_t* nodes, int64_t batch_stride,
+                                           const int32_t* tier_off, int32_t num_batches, int32_t num_hops,
+                                           int32_t max_seeds, uint32_t* counts, int64_t num_nodes, void* stream);
+
 /* ---- Alg. 1 lines 3-4: TopHot + VectorPull -----------------------------------------------
  * Candidates = nodes whose home word is remote and whose count >= 1, ranked by
  * (count descending, id ascending).  K_eff = min(capacity_rows, #candidates) are selected;

@@ -67,6 +67,7 @@ def _load():
     L.rg_sample_blocks.argtypes = [c_p, ctypes.POINTER(rg_csr), c_p, c_i32, c_p, c_i32, c_u64, c_u32,
                                    ctypes.POINTER(rg_blocks), c_p]
     L.rg_access_histogram.argtypes = [c_p, c_p, c_i64, c_p, c_p, c_i64, c_p]
+    L.rg_access_histogram_epoch.argtypes = [c_p, c_p, c_i64, c_p, c_i32, c_i32, c_i32, c_p, c_i64, c_p]
     L.rg_build_cache.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i64, c_i32, ctypes.POINTER(rg_cache), c_p]
     L.rg_prefetch_cache_rows.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_p, c_i64, c_i32, c_p]
     L.rg_gather_features.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_i64, c_p, c_i64,
@@ -75,8 +76,8 @@ def _load():
     L.rg_profile_reset.argtypes = [c_p]
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks",
-                 "rg_access_histogram", "rg_build_cache", "rg_prefetch_cache_rows", "rg_gather_features",
-                 "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
+                 "rg_access_histogram", "rg_access_histogram_epoch", "rg_build_cache", "rg_prefetch_cache_rows",
+                 "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -84,8 +85,8 @@ def _load():
 _lib = _load()
 
 EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "rg_reserve", "rg_epoch_schedule",
-                    "rg_blocks_bounds", "rg_sample_blocks", "rg_access_histogram", "rg_build_cache",
-                    "rg_prefetch_cache_rows", "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
+                    "rg_blocks_bounds", "rg_sample_blocks", "rg_access_histogram", "rg_access_histogram_epoch",
+                    "rg_build_cache", "rg_prefetch_cache_rows", "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
 
 
 def _ptr(t, dtype=None, device_type=None, name="tensor"):
@@ -165,6 +166,18 @@ class Context:
                                              _ptr(n_dev, torch.int32, "cuda", "n_dev"),
                                              _ptr(counts, torch.int32, "cuda", "counts"), counts.numel(),
                                              _stream_handle(stream)))
+
+    # -- rg_access_histogram_epoch
+    def access_histogram_epoch(self, arena, tier_offs, num_batches, num_hops, max_seeds, counts, stream=None):
+        """arena: int32 [>= num_batches, batch_stride]; tier_offs: int32 [>= num_batches, num_hops + 2]."""
+        if tier_offs.dim() != 2 or tier_offs.shape[1] != num_hops + 2 or arena.dim() != 2:
+            raise ValueError("access_histogram_epoch: arena must be 2-D and tier_offs [batches, num_hops + 2]")
+        if num_batches > arena.shape[0] or num_batches > tier_offs.shape[0]:
+            raise ValueError("access_histogram_epoch: num_batches exceeds the buffers")
+        self._check(_lib.rg_access_histogram_epoch(
+            self._h, _ptr(arena, torch.int32, "cuda", "arena"), arena.stride(0),
+            _ptr(tier_offs, torch.int32, "cuda", "tier_offs"), int(num_batches), int(num_hops), int(max_seeds),
+            _ptr(counts, torch.int32, "cuda", "counts"), counts.numel(), _stream_handle(stream)))
 
     # -- rg_build_cache
     def build_cache(self, counts, home, remote_store, dim, cache, stream=None):

@@ -15,6 +15,74 @@ __global__ void __launch_bounds__(256) k_histogram(const int32_t* __restrict__ n
         atomicAdd(&counts[nodes[i]], 1u);
 }
 
+// Epoch-level histogram over many sampled batches.  Every tier after the seeds is ascending by id, so a
+// workgroup that owns the id range [v0, v0 + kHistRange) finds its entries of each (batch, tier) run by
+// binary search, accumulates them in an LDS-private copy of its counters with LDS atomics, and adds the
+// range to `counts` once with plain coalesced read-modify-writes: no global atomics, every id read once.
+constexpr int kHistRange = 8192;     // counters per workgroup (32 KB of LDS)
+constexpr int kHistRunTile = 1024;   // runs whose bounds are resolved per pass
+
+__device__ __forceinline__ int rg_lower_bound(const int32_t* __restrict__ a, int n, int key) {
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void __launch_bounds__(1024) k_histogram_runs(const int32_t* __restrict__ nodes, int64_t batch_stride,
+                                                         const int32_t* __restrict__ tier_off, int num_batches, int num_hops,
+                                                         uint32_t* __restrict__ counts, int64_t num_nodes) {
+    __shared__ uint32_t priv[kHistRange];
+    __shared__ int seg_lo[kHistRunTile];
+    __shared__ int seg_hi[kHistRunTile];
+    const int64_t v0 = (int64_t)blockIdx.x * kHistRange;
+    const int64_t v1 = v0 + kHistRange < num_nodes ? v0 + kHistRange : num_nodes;
+    for (int j = threadIdx.x; j < kHistRange; j += blockDim.x) priv[j] = 0u;
+    const int num_runs = num_batches * num_hops;
+    const int wave = threadIdx.x >> 6, lane = rg_lane(), nwaves = blockDim.x >> 6;
+    for (int tile = 0; tile < num_runs; tile += kHistRunTile) {
+        __syncthreads();                                  // priv zeroed / previous tile's segments consumed
+        const int r = tile + threadIdx.x;
+        if (threadIdx.x < kHistRunTile && r < num_runs) {
+            const int b = r / num_hops, t = r % num_hops + 1;          // tier t of batch b
+            const int32_t* to = tier_off + (int64_t)b * (num_hops + 2);
+            const int begin = to[t], len = to[t + 1] - to[t];
+            const int32_t* run = nodes + (int64_t)b * batch_stride + begin;
+            seg_lo[threadIdx.x] = begin + rg_lower_bound(run, len, (int)v0);
+            seg_hi[threadIdx.x] = begin + rg_lower_bound(run, len, (int)v1);
+        }
+        __syncthreads();
+        const int in_tile = num_runs - tile < kHistRunTile ? num_runs - tile : kHistRunTile;
+        for (int q = wave; q < in_tile; q += nwaves) {                  // one wavefront per run segment
+            const int b = (tile + q) / num_hops;
+            const int32_t* base = nodes + (int64_t)b * batch_stride;
+            const int hi = seg_hi[q];
+            for (int e = seg_lo[q] + lane; e < hi; e += RG_WAVE) {
+                const uint32_t off = (uint32_t)(base[e] - (int)v0);
+                if (off < (uint32_t)kHistRange) atomicAdd(&priv[off], 1u);   // always true for ascending tiers
+            }
+        }
+    }
+    __syncthreads();
+    for (int64_t j = threadIdx.x; v0 + j < v1; j += blockDim.x) {
+        const uint32_t c = priv[j];
+        if (c) counts[v0 + j] += c;
+    }
+}
+
+// Seeds are in caller order (not sorted): one global atomic each.
+__global__ void __launch_bounds__(256) k_histogram_seeds(const int32_t* __restrict__ nodes, int64_t batch_stride,
+                                                         const int32_t* __restrict__ tier_off, int num_hops,
+                                                         uint32_t* __restrict__ counts) {
+    const int b = blockIdx.y;
+    const int n_seeds = tier_off[(int64_t)b * (num_hops + 2) + 1];
+    const int32_t* base = nodes + (int64_t)b * batch_stride;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_seeds; i += gridDim.x * blockDim.x)
+        atomicAdd(&counts[base[i]], 1u);
+}
+
 // ---------------------------------------------------------------------------- radix select
 // Finds the count threshold T of the K_eff-th best candidate, most significant byte first.
 struct TopkCtl {
@@ -347,6 +415,30 @@ rg_status rg_access_histogram(rg_ctx* ctx, const int32_t* nodes, int64_t n, cons
     k_histogram<<<grid, 256, 0, s>>>(nodes, n, n_dev, counts);
     rg_prof_end(ctx, tok, s);
     RG_LAUNCH_CHECK(ctx, "k_histogram");
+    return RG_OK;
+}
+
+rg_status rg_access_histogram_epoch(rg_ctx* ctx, const int32_t* nodes, int64_t batch_stride, const int32_t* tier_off,
+                                    int32_t num_batches, int32_t num_hops, int32_t max_seeds, uint32_t* counts,
+                                    int64_t num_nodes, void* stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, num_batches >= 0 && num_batches <= 65535, "rg_access_histogram_epoch: num_batches = %d not in [0, 65535]", num_batches);
+    RG_REQUIRE(ctx, num_hops >= 1 && num_hops <= RG_MAX_HOPS, "rg_access_histogram_epoch: num_hops = %d not in [1,%d]", num_hops, RG_MAX_HOPS);
+    RG_REQUIRE(ctx, batch_stride >= 0 && max_seeds >= 0 && num_nodes >= 0, "rg_access_histogram_epoch: negative size");
+    RG_REQUIRE(ctx, num_nodes <= (int64_t)RG_ROW_MASK + 1, "rg_access_histogram_epoch: num_nodes exceeds 2^30");
+    if (num_batches == 0 || num_nodes == 0) return RG_OK;
+    RG_REQUIRE(ctx, nodes && tier_off && counts, "rg_access_histogram_epoch: null pointer");
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    const int tok = rg_prof_begin(ctx, RG_K_HISTOGRAM, s);
+    if (max_seeds > 0) {
+        dim3 grid((unsigned)rg_min64(rg_div_up(max_seeds, 256), 64), (unsigned)num_batches);
+        k_histogram_seeds<<<grid, 256, 0, s>>>(nodes, batch_stride, tier_off, num_hops, counts);
+    }
+    k_histogram_runs<<<(int)rg_div_up(num_nodes, kHistRange), 1024, 0, s>>>(nodes, batch_stride, tier_off, num_batches, num_hops,
+                                                                          counts, num_nodes);
+    rg_prof_end(ctx, tok, s);
+    RG_LAUNCH_CHECK(ctx, "k_histogram_runs");
     return RG_OK;
 }
 

@@ -10,7 +10,8 @@ from . import binding as B
 
 
 class EpochPipeline:
-    def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True):
+    def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True,
+                 epoch_histogram=True):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -32,6 +33,8 @@ class EpochPipeline:
         # prefetch = pull cached rows batch by batch, in order of first use, on a stream of their own so the
         # host-link transfer overlaps the gathers; otherwise one bulk pull right after TopHot
         self.prefetch = prefetch
+        # one LDS-privatised histogram over the whole epoch instead of one global-atomic pass per batch
+        self.epoch_histogram = epoch_histogram
         self.pf_stream = torch.cuda.Stream(device=device) if prefetch else None
         self.pf_events = [torch.cuda.Event() for _ in range(self.max_batches)] if prefetch else None
         self.ctx.reserve(cfg.num_nodes, self.slot, self.slot)
@@ -50,7 +53,10 @@ class EpochPipeline:
             seeds = self.order[b * cfg.batch_size:min((b + 1) * cfg.batch_size, n_train)]
             self.bufs.set_outputs(self.arena[i], self.tier_offs[i])
             ctx.sample_blocks(self.csr, seeds, seeds.numel(), cfg.fanouts, self.wl.seed, epoch, self.bufs)
-            ctx.access_histogram(self.arena[i], self.slot, self.counts, n_dev=self.tier_offs[i, self.H + 1:])
+            if not self.epoch_histogram:
+                ctx.access_histogram(self.arena[i], self.slot, self.counts, n_dev=self.tier_offs[i, self.H + 1:])
+        if self.epoch_histogram:
+            ctx.access_histogram_epoch(self.arena, self.tier_offs, len(ids), self.H, cfg.batch_size, self.counts)
         ctx.build_cache(self.counts, self.wl.home, None if self.prefetch else self.wl.remote_store, cfg.feat_dim, self.cache)
         self.n_batches = len(ids)
 

@@ -369,6 +369,34 @@ def test_histogram_with_repeats_and_device_count(B, ctx):
     assert np.array_equal(counts.cpu().numpy().view(np.uint32), want)
 
 
+@pytest.mark.parametrize("n_nodes,n_batches", [(100, 0), (100, 1), (8192, 3), (8193, 5), (30_000, 17), (70_000, 40)])
+def test_epoch_histogram_matches_per_batch_definition(B, ctx, n_nodes, n_batches):
+    """One call over an arena of batches (seed tier unsorted, later tiers ascending, some tiers empty)."""
+    log(f"[epoch histogram] N={n_nodes} batches={n_batches}")
+    rng = np.random.default_rng(n_nodes + n_batches)
+    H, stride, max_seeds = 3, 2048, 16
+    arena = np.full((max(n_batches, 1), stride), -1, dtype=np.int32)
+    tier_offs = np.zeros((max(n_batches, 1), H + 2), dtype=np.int32)
+    want = np.zeros(n_nodes, dtype=np.uint32)
+    want[::7] = 3                                            # the call accumulates onto existing counts
+    counts = torch.from_numpy(want.view(np.int32).copy()).to(DEV)
+    for b in range(n_batches):
+        sizes = [int(rng.integers(0, max_seeds + 1))] + [int(rng.integers(0, 600)) if rng.random() < 0.8 else 0 for _ in range(H)]
+        sizes = [min(s, n_nodes // 8) for s in sizes]
+        ids = rng.permutation(n_nodes)[:sum(sizes)].astype(np.int32)     # unique within a batch
+        off = 0
+        for t, sz in enumerate(sizes):
+            part = ids[off:off + sz]
+            arena[b, off:off + sz] = part if t == 0 else np.sort(part)
+            off += sz
+            tier_offs[b, t + 1] = off
+        oracle.access_histogram(arena[b, :off], want)
+    ctx.access_histogram_epoch(torch.from_numpy(arena).to(DEV), torch.from_numpy(tier_offs).to(DEV), n_batches, H,
+                               max_seeds, counts)
+    torch.cuda.synchronize()
+    assert np.array_equal(counts.cpu().numpy().view(np.uint32), want)
+
+
 # ------------------------------------------------------------------------------ argument errors
 def test_argument_errors_are_reported_not_launched(B, ctx):
     rp = torch.tensor([0, 1, 2], dtype=torch.int32, device=DEV)
