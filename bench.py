@@ -17,6 +17,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E peak
+HOSTLINK_PEAK_GBS = 64.0   # PCIe Gen5 x16, one direction
+
+# HBM bytes moved by one k_gather_hbm launch on the stress workload, measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE, one counter per run, each scaled by what the same counter reads for a plain 1 GiB copy: x2.000 and
+# x1.000).  The figures and the commands are in profiles/stress_gather_hbm_pmc_traffic.txt.
+PMC_TRAFFIC = {"stress": {"fetch_kib": 404240.0, "fetch_scale": 2.0, "write_kib": 796000.1, "write_scale": 1.0,
+                          "rows_per_launch": 795995}}
 
 
 def log(msg):
@@ -82,6 +89,7 @@ def main():
     ap.add_argument("--one-stream", action="store_true", help="copy miss rows on the same stream as the HBM rows")
     ap.add_argument("--bulk-fill", action="store_true",
                     help="pull all cached rows in one go after TopHot instead of batch by batch ahead of the gathers")
+    ap.add_argument("--sampler-streams", type=int, default=3, help="batches sampled side by side during the offline stage")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -126,26 +134,26 @@ def main():
     main_stream = torch.cuda.Stream()
     with torch.cuda.stream(main_stream):
         pipe = EpochPipeline(wl, device=dev, max_batches=min(max(steps, warmup, 1), bpe), two_streams=not args.one_stream,
-                             prefetch=not args.bulk_fill)
+                             prefetch=not args.bulk_fill, sampler_streams=args.sampler_streams)
         ctx = pipe.ctx
         if warmup > 0:
             run_steps(pipe, warmup)
         totals = {"stats": torch.zeros(3, dtype=torch.int64, device=dev), "rows": 0,
                   "cached": torch.zeros(1, dtype=torch.int64, device=dev), "epochs": 0}
-        ctx.profile_enable(True)
-        ctx.profile_reset()
+        pipe.profile_enable(True)
+        pipe.profile_reset()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         run_steps(pipe, steps, totals)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        ctx.profile_enable(False)
+        pipe.profile_enable(False)
 
     n_local, n_hit, n_miss = [int(x) for x in totals["stats"].cpu().tolist()]
     rows = totals["rows"]
     assert rows == n_local + n_hit + n_miss, "gather statistics do not add up"
     row_bytes = 4 * cfg.feat_dim
-    prof = {name: ctx.profile_read(kid) for name, kid in
+    prof = {name: pipe.profile_read(kid) for name, kid in
             [("gather_hbm", B.RG_K_GATHER_HBM), ("gather_miss", B.RG_K_GATHER_MISS), ("sample", B.RG_K_SAMPLE),
              ("histogram", B.RG_K_HISTOGRAM), ("cache_fill", B.RG_K_CACHE_FILL)]}
     g_ms, g_launches = prof["gather_hbm"]
@@ -155,6 +163,11 @@ def main():
     cached_rows = int(totals["cached"].item())
     m_ms, _ = prof["gather_miss"]
     f_ms, _ = prof["cache_fill"]
+    traffic = None
+    if cfg.name in PMC_TRAFFIC and g_launches:
+        t = PMC_TRAFFIC[cfg.name]
+        per_row = (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]) * 1024.0 / t["rows_per_launch"]
+        traffic = per_row * hbm_rows / g_launches            # measured bytes per row x rows per launch of this run
     result = {
         "metric": "mini-batch sample+gather/sec; feature gather GB/s vs HBM peak; cache hit %",
         "value": steps / dt,
@@ -171,9 +184,10 @@ def main():
         "config": {"workload": cfg.name, "num_nodes": cfg.num_nodes, "nnz": wl.nnz, "feat_dim": cfg.feat_dim,
                    "fanouts": list(cfg.fanouts), "batch_size": cfg.batch_size, "epochs_timed": totals["epochs"],
                    "cache_capacity_rows": wl.capacity_rows, "miss_stream": "shared" if args.one_stream else "separate",
-                   "cache_fill": "bulk" if args.bulk_fill else "prefetch by first use"},
+                   "cache_fill": "bulk" if args.bulk_fill else "prefetch by first use",
+                   "sampler_streams": args.sampler_streams},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes / max(g_launches, 1),
                      "avg_launch_ms": g_ms / max(g_launches, 1), "launches": g_launches},
         "gather": {"rows": rows, "n_local": n_local, "n_hit": n_hit, "n_miss": n_miss,
@@ -182,6 +196,9 @@ def main():
                    "miss_hostlink_GBps": row_bytes * n_miss / (m_ms * 1e-3) / 1e9 if m_ms > 0 and n_miss else None,
                    "cache_fill_hostlink_GBps": row_bytes * cached_rows / (f_ms * 1e-3) / 1e9 if f_ms > 0 and cached_rows else None,
                    "cached_rows": cached_rows},
+        "hostlink": {"bound": "pcie", "kernel": "k_prefetch_pull / k_cache_fill", "peak": HOSTLINK_PEAK_GBS, "unit": "GB/s",
+                     "achieved": row_bytes * cached_rows / (f_ms * 1e-3) / 1e9 if f_ms > 0 and cached_rows else None,
+                     "note": "sum of pull-kernel durations; the pulls run beside the gathers on their own stream"},
         "kernel_ms": {k: {"total_ms": v[0], "launches": v[1]} for k, v in prof.items()},
     }
 
