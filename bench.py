@@ -31,19 +31,23 @@ def log(msg):
 
 
 def run_steps(pipe, steps, totals=None):
-    """Run `steps` batches through the whole path, epoch after epoch.  Returns sampled edge count holder."""
+    """Run `steps` batches through the whole path, epoch after epoch (the last epoch may be partial)."""
     import torch
-    epoch, left = 0, steps
-    while left > 0:
-        nb = min(left, pipe.max_batches)
-        pipe.run_epoch(epoch, nb)
+
+    def account(p, _k):
         if totals is not None:
-            totals["stats"] += pipe.stats[:nb].sum(0)
-            totals["rows"] += sum(pipe.sizes[:nb])
-            totals["cached"] += pipe.cache.num_cached.clone()
+            nb = p.n_batches
+            totals["stats"] += p.stats[:nb].sum(0)
+            totals["rows"] += sum(p.sizes[:nb])
+            totals["edges"] += p.edge_counts[:nb].sum()
+            totals["cached"] += p.cache.num_cached.clone()
             totals["epochs"] += 1
-        left -= nb
-        epoch += 1
+    full, rem = divmod(steps, pipe.max_batches)
+    if full:
+        pipe.run_epochs(0, full, pipe.max_batches, on_epoch_done=account)
+    if rem:
+        pipe.run_epoch(full, rem)
+        account(pipe, full)
     torch.cuda.current_stream().synchronize()
 
 
@@ -90,6 +94,8 @@ def main():
     ap.add_argument("--bulk-fill", action="store_true",
                     help="pull all cached rows in one go after TopHot instead of batch by batch ahead of the gathers")
     ap.add_argument("--sampler-streams", type=int, default=3, help="batches sampled side by side during the offline stage")
+    ap.add_argument("--no-double-buffer", action="store_true",
+                    help="with more than one epoch of steps: do not precompute epoch e+1 while epoch e is served")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -134,11 +140,13 @@ def main():
     main_stream = torch.cuda.Stream()
     with torch.cuda.stream(main_stream):
         pipe = EpochPipeline(wl, device=dev, max_batches=min(max(steps, warmup, 1), bpe), two_streams=not args.one_stream,
-                             prefetch=not args.bulk_fill, sampler_streams=args.sampler_streams)
+                             prefetch=not args.bulk_fill, sampler_streams=args.sampler_streams,
+                             double_buffer=(steps > bpe and not args.no_double_buffer))
         ctx = pipe.ctx
         if warmup > 0:
             run_steps(pipe, warmup)
         totals = {"stats": torch.zeros(3, dtype=torch.int64, device=dev), "rows": 0,
+                  "edges": torch.zeros((), dtype=torch.int64, device=dev),
                   "cached": torch.zeros(1, dtype=torch.int64, device=dev), "epochs": 0}
         pipe.profile_enable(True)
         pipe.profile_reset()
@@ -185,7 +193,8 @@ def main():
                    "fanouts": list(cfg.fanouts), "batch_size": cfg.batch_size, "epochs_timed": totals["epochs"],
                    "cache_capacity_rows": wl.capacity_rows, "miss_stream": "shared" if args.one_stream else "separate",
                    "cache_fill": "bulk" if args.bulk_fill else "prefetch by first use",
-                   "sampler_streams": args.sampler_streams},
+                   "sampler_streams": args.sampler_streams,
+                   "double_buffered_cache": bool(steps > bpe and not args.no_double_buffer)},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes / max(g_launches, 1),
@@ -196,6 +205,9 @@ def main():
                    "miss_hostlink_GBps": row_bytes * n_miss / (m_ms * 1e-3) / 1e9 if m_ms > 0 and n_miss else None,
                    "cache_fill_hostlink_GBps": row_bytes * cached_rows / (f_ms * 1e-3) / 1e9 if f_ms > 0 and cached_rows else None,
                    "cached_rows": cached_rows},
+        "sampler": {"sampled_edges": int(totals["edges"].item()), "input_nodes": rows,
+                    "sampled_edges_per_s_whole_path": int(totals["edges"].item()) / dt,
+                    "draw_kernel_edges_per_s": int(totals["edges"].item()) / (prof["sample"][0] * 1e-3) if prof["sample"][0] > 0 else None},
         "hostlink": {"bound": "pcie", "kernel": "k_prefetch_pull / k_cache_fill", "peak": HOSTLINK_PEAK_GBS, "unit": "GB/s",
                      "achieved": row_bytes * cached_rows / (f_ms * 1e-3) / 1e9 if f_ms > 0 and cached_rows else None,
                      "note": "sum of pull-kernel durations; the pulls run beside the gathers on their own stream"},

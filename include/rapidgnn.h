@@ -126,6 +126,7 @@ typedef struct {
     int32_t* const* nbr;       /* host array[num_hops] of device int32[nbr_cap[h]] */
     int32_t* const* nbr_local; /* host array[num_hops] of device int32[nbr_cap[h]], or NULL to skip relabelling */
     const int64_t* nbr_cap;    /* host int64[num_hops] */
+    int32_t* num_edges;        /* device int32[num_hops] or NULL: |nbr[h]| (the same value as indptr[h][|frontier_h|]) */
 } rg_blocks;
 
 /* Static bounds the output buffers of rg_sample_blocks must meet:
@@ -209,6 +210,40 @@ RG_API rg_status rg_prefetch_cache_rows(rg_ctx* ctx, const int32_t* input_nodes,
                                         const rg_cache* cache, const int32_t* home,
                                         const float* remote_store, int64_t remote_stride, int32_t dim,
                                         void* stream);
+
+/* ---- early pull: VectorPull started during the precompute stage ------------------------------
+ * When the cache can hold every remote node (capacity_rows >= number of remote nodes), every remote
+ * node a batch touches will be selected by TopHot, so its row can be pulled as soon as the batch has
+ * been sampled, while the remaining batches are still being sampled.  The final slot of a row (its
+ * rank among the selected ids) is only known after TopHot, so rows are pulled into a staging area
+ * and moved to their slots (HBM to HBM) afterwards.
+ *   rg_stage_rows(batch b):  for each remote node of input_nodes not claimed earlier in this period:
+ *       take the next staging slot, record slot_of[v] and owner[v] = batch_tag, pull the row from the
+ *       remote store into the staging slot.  Nodes that find the staging area full are not staged.
+ *   rg_commit_staged_rows(batch b), after rg_build_cache (select only):  for each node staged under
+ *       batch_tag whose location word names a cache slot: copy the staged row to the slot and mark it
+ *       resident.  Nodes that were staged but not selected are skipped (their pull was wasted).
+ * Rows that were never staged stay non-resident; rg_prefetch_cache_rows pulls those.  Results
+ * (cache_ids, loc, cached rows, gathers) are identical to the bulk pull.
+ * The caller zeroes `touched` and `cursor` at the start of a period.  Calls of rg_stage_rows on one
+ * rg_stage must be ordered with each other; a commit must follow the stage call of the same tag and
+ * the TopHot selection.  batch_tag >= 0. */
+typedef struct {
+    float* rows;              /* device float[capacity_rows * row_stride] */
+    int64_t capacity_rows;
+    int64_t row_stride;       /* floats, >= dim */
+    int32_t* slot_of;         /* device int32[num_nodes]: staging slot of a claimed node (-1: none) */
+    int32_t* owner;           /* device int32[num_nodes]: batch_tag of the call that claimed the node */
+    uint32_t* touched;        /* device uint32[ceil(num_nodes / 32)]: node claimed in this period */
+    uint32_t* cursor;         /* device uint32[1]: number of claims so far */
+} rg_stage;
+
+RG_API rg_status rg_stage_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
+                               const int32_t* home, const rg_stage* stage, int32_t batch_tag,
+                               const float* remote_store, int64_t remote_stride, int32_t dim, void* stream);
+RG_API rg_status rg_commit_staged_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
+                                       const int32_t* home, const rg_stage* stage, int32_t batch_tag,
+                                       const rg_cache* cache, int32_t dim, void* stream);
 
 /* ---- Alg. 1 lines 12-14: feature assembly for one batch ---------------------------------
  * out[i][0:dim] = feature row of input_nodes[i], read from the store loc[] names: local

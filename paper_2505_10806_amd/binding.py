@@ -41,12 +41,17 @@ class rg_blocks(ctypes.Structure):
     _fields_ = [("nodes", c_p), ("nodes_cap", c_i64), ("tier_off", c_p),
                 ("indptr", ctypes.POINTER(c_p)), ("indptr_cap", ctypes.POINTER(c_i64)),
                 ("nbr", ctypes.POINTER(c_p)), ("nbr_local", ctypes.POINTER(c_p)),
-                ("nbr_cap", ctypes.POINTER(c_i64))]
+                ("nbr_cap", ctypes.POINTER(c_i64)), ("num_edges", c_p)]
 
 
 class rg_cache(ctypes.Structure):
     _fields_ = [("cache_ids", c_p), ("cache_rows", c_p), ("capacity_rows", c_i64),
                 ("row_stride", c_i64), ("loc", c_p), ("num_cached", c_p), ("filled", c_p)]
+
+
+class rg_stage(ctypes.Structure):
+    _fields_ = [("rows", c_p), ("capacity_rows", c_i64), ("row_stride", c_i64), ("slot_of", c_p),
+                ("owner", c_p), ("touched", c_p), ("cursor", c_p)]
 
 
 def _load():
@@ -70,6 +75,9 @@ def _load():
     L.rg_access_histogram_epoch.argtypes = [c_p, c_p, c_i64, c_p, c_i32, c_i32, c_i32, c_p, c_i64, c_p]
     L.rg_build_cache.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i64, c_i32, ctypes.POINTER(rg_cache), c_p]
     L.rg_prefetch_cache_rows.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_p, c_i64, c_i32, c_p]
+    L.rg_stage_rows.argtypes = [c_p, c_p, c_i64, c_p, c_p, ctypes.POINTER(rg_stage), c_i32, c_p, c_i64, c_i32, c_p]
+    L.rg_commit_staged_rows.argtypes = [c_p, c_p, c_i64, c_p, c_p, ctypes.POINTER(rg_stage), c_i32,
+                                        ctypes.POINTER(rg_cache), c_i32, c_p]
     L.rg_gather_features.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_i64, c_p, c_i64,
                                      c_i32, c_p, c_i64, c_p, c_p, c_p]
     L.rg_profile_enable.argtypes = [c_p, ctypes.c_int]
@@ -77,7 +85,7 @@ def _load():
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks",
                  "rg_access_histogram", "rg_access_histogram_epoch", "rg_build_cache", "rg_prefetch_cache_rows",
-                 "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
+                 "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -86,7 +94,7 @@ _lib = _load()
 
 EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "rg_reserve", "rg_epoch_schedule",
                     "rg_blocks_bounds", "rg_sample_blocks", "rg_access_histogram", "rg_access_histogram_epoch",
-                    "rg_build_cache", "rg_prefetch_cache_rows", "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
+                    "rg_build_cache", "rg_prefetch_cache_rows", "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
 
 
 def _ptr(t, dtype=None, device_type=None, name="tensor"):
@@ -197,6 +205,22 @@ class Context:
             _ptr(remote_store, torch.float32, "mapped", "remote_store"), remote_store.stride(0), int(dim),
             _stream_handle(stream)))
 
+    # -- rg_stage_rows / rg_commit_staged_rows
+    def stage_rows(self, input_nodes, n, home, stage, batch_tag, remote_store, dim, n_dev=None, stream=None):
+        self._check(_lib.rg_stage_rows(
+            self._h, _ptr(input_nodes, torch.int32, "cuda", "input_nodes"), int(n),
+            _ptr(n_dev, torch.int32, "cuda", "n_dev"), _ptr(home, torch.int32, "cuda", "home"),
+            ctypes.byref(stage.c_struct), int(batch_tag),
+            _ptr(remote_store, torch.float32, "mapped", "remote_store"), remote_store.stride(0), int(dim),
+            _stream_handle(stream)))
+
+    def commit_staged_rows(self, input_nodes, n, home, stage, batch_tag, cache, dim, n_dev=None, stream=None):
+        self._check(_lib.rg_commit_staged_rows(
+            self._h, _ptr(input_nodes, torch.int32, "cuda", "input_nodes"), int(n),
+            _ptr(n_dev, torch.int32, "cuda", "n_dev"), _ptr(home, torch.int32, "cuda", "home"),
+            ctypes.byref(stage.c_struct), int(batch_tag), ctypes.byref(cache.c_struct), int(dim),
+            _stream_handle(stream)))
+
     # -- rg_gather_features
     def gather_features(self, input_nodes, n, cache, local_store, remote_store, dim, out, stats,
                         n_dev=None, hit_stream=None, miss_stream=None):
@@ -262,6 +286,7 @@ class BlockBuffers:
         i32 = dict(dtype=torch.int32, device=device)
         self.nodes = nodes if nodes is not None else torch.empty(max(self.frontier_ub[H], 1), **i32)
         self.tier_off = torch.zeros(H + 2, **i32)
+        self.num_edges = torch.zeros(H, **i32)
         self.indptr = [torch.empty(self.frontier_ub[h] + 1, **i32) for h in range(H)]
         self.nbr = [torch.empty(max(self.edges_ub[h], 1), **i32) for h in range(H)]
         self.nbr_local = [torch.empty(max(self.edges_ub[h], 1), **i32) for h in range(H)] if with_local else None
@@ -279,10 +304,16 @@ class BlockBuffers:
             ctypes.cast(self._indptr_arr, ctypes.POINTER(c_p)), ctypes.cast(self._indptr_cap, ctypes.POINTER(c_i64)),
             ctypes.cast(self._nbr_arr, ctypes.POINTER(c_p)),
             ctypes.cast(self._loc_arr, ctypes.POINTER(c_p)) if self._loc_arr is not None else None,
-            ctypes.cast(self._nbr_cap, ctypes.POINTER(c_i64)))
+            ctypes.cast(self._nbr_cap, ctypes.POINTER(c_i64)), self.num_edges.data_ptr())
 
-    def set_outputs(self, nodes, tier_off):
-        """Point the input-node list and tier offsets at other buffers (e.g. a batch's slot of an epoch arena)."""
+    def set_outputs(self, nodes, tier_off, num_edges=None):
+        """Point the input-node list, tier offsets and per-hop edge counts at other buffers (e.g. a batch's slot
+        of an epoch arena)."""
+        if num_edges is not None:
+            if num_edges.dtype != torch.int32 or num_edges.numel() < len(self.fanouts):
+                raise TypeError("set_outputs: num_edges must be int32 with num_hops entries")
+            self.num_edges = num_edges
+            self.c_struct.num_edges = num_edges.data_ptr()
         if nodes.dtype != torch.int32 or tier_off.dtype != torch.int32 or tier_off.numel() < len(self.fanouts) + 2:
             raise TypeError("set_outputs: int32 tensors required, tier_off of num_hops + 2 entries")
         self.nodes, self.tier_off = nodes, tier_off
@@ -303,3 +334,22 @@ class FeatureCache:
         self.filled = torch.zeros(max((min(self.capacity_rows, num_nodes) + 31) // 32, 1), dtype=torch.int32, device=device)
         self.c_struct = rg_cache(self.cache_ids.data_ptr(), self.cache_rows.data_ptr(), self.capacity_rows,
                                  int(row_stride), self.loc.data_ptr(), self.num_cached.data_ptr(), self.filled.data_ptr())
+
+
+class StagingArea:
+    """rg_stage over caller-owned cuda tensors: rows pulled before their cache slot is known."""
+
+    def __init__(self, num_nodes, capacity_rows, row_stride, device):
+        self.capacity_rows = int(capacity_rows)
+        self.rows = torch.empty(max(self.capacity_rows, 1), int(row_stride), dtype=torch.float32, device=device)
+        self.slot_of = torch.empty(max(num_nodes, 1), dtype=torch.int32, device=device)
+        self.owner = torch.empty(max(num_nodes, 1), dtype=torch.int32, device=device)
+        self.touched = torch.zeros(max((num_nodes + 31) // 32, 1), dtype=torch.int32, device=device)
+        self.cursor = torch.zeros(1, dtype=torch.int32, device=device)
+        self.c_struct = rg_stage(self.rows.data_ptr(), self.capacity_rows, int(row_stride), self.slot_of.data_ptr(),
+                                 self.owner.data_ptr(), self.touched.data_ptr(), self.cursor.data_ptr())
+
+    def reset(self):
+        """Start a new period (queued on the current stream)."""
+        self.touched.zero_()
+        self.cursor.zero_()

@@ -356,7 +356,103 @@ __global__ void __launch_bounds__(256) k_prefetch_select(const int32_t* __restri
     }
 }
 
-// cache_rows[slot] = remote_store[rrow] for every pair of the pull list.
+// Early pull, step 1.  For every listed node whose home is the remote store and that no earlier call of this
+// period has claimed (atomic test-and-set of its `touched` bit): take the next staging slot, remember it in
+// slot_of[v], tag owner[v] with this call's batch tag and append (staging slot, remote row) to the pull list.
+// Nodes for which no staging slot is left are not claimed further: they stay without a staged row.
+__global__ void __launch_bounds__(256) k_stage_select(const int32_t* __restrict__ nodes, int64_t n, const int32_t* __restrict__ n_dev,
+                                                      const int32_t* __restrict__ home, uint32_t* __restrict__ touched,
+                                                      int32_t* __restrict__ slot_of, int32_t* __restrict__ owner, int32_t batch_tag,
+                                                      uint32_t* __restrict__ cursor, int64_t stage_capacity,
+                                                      int32_t* __restrict__ list, uint32_t* __restrict__ pctl) {
+    __shared__ int smem[256 / RG_WAVE + 1];
+    __shared__ uint32_t slot_base_s, list_base_s;
+    int64_t n_act = n;
+    if (n_dev) { const int64_t d = *n_dev; n_act = d < n ? d : n; }
+    if ((int64_t)blockIdx.x * blockDim.x >= n_act) return;        // uniform per workgroup
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int take = 0;
+    int32_t v = 0;
+    uint32_t rrow = 0u;
+    if (i < n_act) {
+        v = nodes[i];
+        const uint32_t hw = (uint32_t)home[v];
+        if ((hw >> RG_TAG_SHIFT) == RG_TAG_REMOTE) {
+            const uint32_t bit = 1u << (v & 31);
+            if (!(touched[(uint32_t)v >> 5] & bit)) {
+                const uint32_t old = atomicOr(&touched[(uint32_t)v >> 5], bit);
+                if (!(old & bit)) { take = 1; rrow = hw & RG_ROW_MASK; }
+            }
+        }
+    }
+    int total;
+    const int excl = rg_block_excl_scan<256 / RG_WAVE>(take, smem, &total);
+    if (total == 0) return;                                        // uniform
+    if (threadIdx.x == 0) slot_base_s = atomicAdd(cursor, (uint32_t)total);
+    __syncthreads();
+    const int64_t slot = (int64_t)slot_base_s + excl;
+    const int staged = take && slot < stage_capacity;
+    if (take) {
+        slot_of[v] = staged ? (int32_t)slot : -1;
+        owner[v] = staged ? batch_tag : -1;
+    }
+    // second compaction: only rows that got a staging slot are pulled
+    int total2;
+    const int excl2 = rg_block_excl_scan<256 / RG_WAVE>(staged, smem, &total2);
+    if (total2 == 0) return;
+    if (threadIdx.x == 0) list_base_s = atomicAdd(&pctl[0], (uint32_t)total2);
+    __syncthreads();
+    if (staged) {
+        const int64_t j = (int64_t)list_base_s + excl2;
+        list[2 * j] = (int32_t)slot;
+        list[2 * j + 1] = (int32_t)rrow;
+    }
+}
+
+// Early pull, step 2 (after TopHot).  For every listed node staged by the call with this batch tag whose
+// location word now names a cache slot: claim the slot's resident bit and append (cache slot, staging slot).
+__global__ void __launch_bounds__(256) k_commit_select(const int32_t* __restrict__ nodes, int64_t n, const int32_t* __restrict__ n_dev,
+                                                       const int32_t* __restrict__ home, const int32_t* __restrict__ loc,
+                                                       const uint32_t* __restrict__ touched, const int32_t* __restrict__ slot_of,
+                                                       const int32_t* __restrict__ owner, int32_t batch_tag,
+                                                       uint32_t* __restrict__ filled, int32_t* __restrict__ list,
+                                                       uint32_t* __restrict__ pctl) {
+    __shared__ int smem[256 / RG_WAVE + 1];
+    __shared__ uint32_t base_s;
+    int64_t n_act = n;
+    if (n_dev) { const int64_t d = *n_dev; n_act = d < n ? d : n; }
+    if ((int64_t)blockIdx.x * blockDim.x >= n_act) return;        // uniform per workgroup
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int take = 0;
+    uint32_t cslot = 0u;
+    int32_t sslot = 0;
+    if (i < n_act) {
+        const int32_t v = nodes[i];
+        const uint32_t bit = 1u << (v & 31);
+        if (((uint32_t)home[v] >> RG_TAG_SHIFT) == RG_TAG_REMOTE && (touched[(uint32_t)v >> 5] & bit) && owner[v] == batch_tag) {
+            const uint32_t w = (uint32_t)loc[v];
+            sslot = slot_of[v];
+            if ((w >> RG_TAG_SHIFT) == RG_TAG_CACHE && sslot >= 0) {
+                cslot = w & RG_ROW_MASK;
+                const uint32_t fbit = 1u << (cslot & 31u);
+                const uint32_t old = atomicOr(&filled[cslot >> 5], fbit);
+                take = !(old & fbit);
+            }
+        }
+    }
+    int total;
+    const int excl = rg_block_excl_scan<256 / RG_WAVE>(take, smem, &total);
+    if (total == 0) return;                                        // uniform
+    if (threadIdx.x == 0) base_s = atomicAdd(&pctl[0], (uint32_t)total);
+    __syncthreads();
+    if (take) {
+        const int64_t j = (int64_t)base_s + excl;
+        list[2 * j] = (int32_t)cslot;
+        list[2 * j + 1] = sslot;
+    }
+}
+
+// dst_rows[list[2j]] = src_rows[list[2j+1]] for every pair of the list (host link or HBM source alike).
 template <int VEC>
 __global__ void __launch_bounds__(1024) k_prefetch_pull(const int32_t* __restrict__ list, const uint32_t* __restrict__ pctl,
                                                        const float* __restrict__ remote_store, int64_t remote_stride,
@@ -395,6 +491,37 @@ __global__ void __launch_bounds__(1024) k_prefetch_pull(const int32_t* __restric
                 if (dst[u]) dst[u][c] = val[u];
         }
     }
+}
+
+// Launches the list-driven row copy.  `blocks` and `threads` bound the wavefronts in flight.
+rg_status launch_list_copy(rg_ctx* ctx, const int32_t* list, const uint32_t* pctl, const float* src, int64_t src_stride,
+                           float* dst, int64_t dst_stride, int32_t dim, int64_t n_upper, int64_t blocks, int threads,
+                           hipStream_t s) {
+    const void* ptrs[2] = {src, dst};
+    const int64_t strides[2] = {src_stride, dst_stride};
+    const int vec = rg_pick_vec(dim, ptrs, 2, strides, 2);
+    const RgRowShape shp = rg_row_shape(dim, vec);
+    const int rows_per_block = (threads / RG_WAVE) * (RG_WAVE >> shp.log2L) * 4;
+    const int grid = (int)rg_max64(1, rg_min64(rg_div_up(n_upper, rows_per_block), blocks));
+    const int tok = rg_prof_begin(ctx, RG_K_CACHE_FILL, s);
+    if (vec == 4)
+        k_prefetch_pull<4><<<grid, threads, 0, s>>>(list, pctl, src, src_stride, dst, dst_stride, shp.cpr, shp.log2L);
+    else if (vec == 2)
+        k_prefetch_pull<2><<<grid, threads, 0, s>>>(list, pctl, src, src_stride, dst, dst_stride, shp.cpr, shp.log2L);
+    else
+        k_prefetch_pull<1><<<grid, threads, 0, s>>>(list, pctl, src, src_stride, dst, dst_stride, shp.cpr, shp.log2L);
+    rg_prof_end(ctx, tok, s);
+    RG_LAUNCH_CHECK(ctx, "k_prefetch_pull");
+    return RG_OK;
+}
+
+// The pull waits on the host link, not on the GPU: a few hundred wavefronts keep the link busy, and a small grid
+// leaves the wave slots of every CU to the gathers that run beside it.
+void hostlink_launch_shape(int64_t* blocks, int* threads) {
+    const char* pb = getenv("RG_PULL_BLOCKS");
+    *blocks = (pb && atoi(pb) > 0) ? atoi(pb) : 48;
+    const char* pt = getenv("RG_PULL_THREADS");
+    *threads = (pt && (atoi(pt) == 64 || atoi(pt) == 256 || atoi(pt) == 1024)) ? atoi(pt) : 256;
 }
 
 }  // namespace
@@ -531,28 +658,69 @@ rg_status rg_prefetch_cache_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_
     RG_LAUNCH_CHECK(ctx, "k_prefetch_reset");
     k_prefetch_select<<<(int)rg_div_up(n, 256), 256, 0, s>>>(input_nodes, n, n_dev, cache->loc, home, cache->filled, list, pctl);
     RG_LAUNCH_CHECK(ctx, "k_prefetch_select");
-    const void* ptrs[2] = {remote_store, cache->cache_rows};
-    const int64_t strides[2] = {remote_stride, cache->row_stride};
-    const int vec = rg_pick_vec(dim, ptrs, 2, strides, 2);
-    const RgRowShape shp = rg_row_shape(dim, vec);
-    const int rows_per_block = 4 * (RG_WAVE >> shp.log2L) * 4;
-    // The pull waits on the host link, not on the GPU: a few hundred wavefronts keep the link busy, and a small
-    // grid leaves the wave slots of every CU to the gathers that run beside it.
-    const char* pb = getenv("RG_PULL_BLOCKS");
-    const int64_t pull_blocks = (pb && atoi(pb) > 0) ? atoi(pb) : 48;
-    const char* pt = getenv("RG_PULL_THREADS");
-    const int pull_threads = (pt && (atoi(pt) == 64 || atoi(pt) == 256 || atoi(pt) == 1024)) ? atoi(pt) : 256;
-    const int grid = (int)rg_max64(1, rg_min64(rg_div_up(n, rows_per_block), pull_blocks));
-    const int tok = rg_prof_begin(ctx, RG_K_CACHE_FILL, s);
-    if (vec == 4)
-        k_prefetch_pull<4><<<grid, pull_threads, 0, s>>>(list, pctl, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L);
-    else if (vec == 2)
-        k_prefetch_pull<2><<<grid, pull_threads, 0, s>>>(list, pctl, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L);
-    else
-        k_prefetch_pull<1><<<grid, pull_threads, 0, s>>>(list, pctl, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L);
-    rg_prof_end(ctx, tok, s);
-    RG_LAUNCH_CHECK(ctx, "k_prefetch_pull");
-    return RG_OK;
+    int64_t blocks;
+    int threads;
+    hostlink_launch_shape(&blocks, &threads);
+    return launch_list_copy(ctx, list, pctl, remote_store, remote_stride, cache->cache_rows, cache->row_stride, dim, n, blocks,
+                            threads, s);
+}
+
+rg_status rg_stage_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev, const int32_t* home,
+                        const rg_stage* stage, int32_t batch_tag, const float* remote_store, int64_t remote_stride,
+                        int32_t dim, void* stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_stage_rows: n = %lld out of range", (long long)n);
+    RG_REQUIRE(ctx, batch_tag >= 0, "rg_stage_rows: batch_tag must be non-negative");
+    if (n == 0) return RG_OK;
+    RG_REQUIRE(ctx, stage && stage->rows && stage->slot_of && stage->owner && stage->touched && stage->cursor,
+               "rg_stage_rows: incomplete rg_stage");
+    RG_REQUIRE(ctx, stage->capacity_rows >= 0 && stage->capacity_rows <= (int64_t)RG_ROW_MASK + 1, "rg_stage_rows: bad staging capacity");
+    RG_REQUIRE(ctx, input_nodes && home && remote_store, "rg_stage_rows: null pointer");
+    RG_REQUIRE(ctx, dim >= 1 && stage->row_stride >= dim && remote_stride >= dim, "rg_stage_rows: bad dim / stride");
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    rg_status st;
+    if ((st = rg_ensure(ctx, ctx->stage_ctl, 64)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->stage_list, (size_t)n * 8)) != RG_OK) return st;
+    uint32_t* pctl = (uint32_t*)ctx->stage_ctl.p;
+    int32_t* list = (int32_t*)ctx->stage_list.p;
+    k_prefetch_reset<<<1, 64, 0, s>>>(pctl);
+    RG_LAUNCH_CHECK(ctx, "k_prefetch_reset");
+    k_stage_select<<<(int)rg_div_up(n, 256), 256, 0, s>>>(input_nodes, n, n_dev, home, stage->touched, stage->slot_of, stage->owner,
+                                                         batch_tag, stage->cursor, stage->capacity_rows, list, pctl);
+    RG_LAUNCH_CHECK(ctx, "k_stage_select");
+    int64_t blocks;
+    int threads;
+    hostlink_launch_shape(&blocks, &threads);
+    return launch_list_copy(ctx, list, pctl, remote_store, remote_stride, stage->rows, stage->row_stride, dim, n, blocks, threads, s);
+}
+
+rg_status rg_commit_staged_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
+                                const int32_t* home, const rg_stage* stage, int32_t batch_tag, const rg_cache* cache,
+                                int32_t dim, void* stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_commit_staged_rows: n = %lld out of range", (long long)n);
+    RG_REQUIRE(ctx, batch_tag >= 0, "rg_commit_staged_rows: batch_tag must be non-negative");
+    if (n == 0) return RG_OK;
+    RG_REQUIRE(ctx, stage && stage->rows && stage->slot_of && stage->owner && stage->touched, "rg_commit_staged_rows: incomplete rg_stage");
+    RG_REQUIRE(ctx, cache && cache->loc && cache->filled && cache->cache_rows, "rg_commit_staged_rows: cache needs loc, filled and cache_rows");
+    RG_REQUIRE(ctx, input_nodes && home, "rg_commit_staged_rows: null pointer");
+    RG_REQUIRE(ctx, dim >= 1 && stage->row_stride >= dim && cache->row_stride >= dim, "rg_commit_staged_rows: bad dim / stride");
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    rg_status st;
+    if ((st = rg_ensure(ctx, ctx->commit_ctl, 64)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->commit_list, (size_t)n * 8)) != RG_OK) return st;
+    uint32_t* pctl = (uint32_t*)ctx->commit_ctl.p;
+    int32_t* list = (int32_t*)ctx->commit_list.p;
+    k_prefetch_reset<<<1, 64, 0, s>>>(pctl);
+    RG_LAUNCH_CHECK(ctx, "k_prefetch_reset");
+    k_commit_select<<<(int)rg_div_up(n, 256), 256, 0, s>>>(input_nodes, n, n_dev, home, cache->loc, stage->touched, stage->slot_of,
+                                                          stage->owner, batch_tag, cache->filled, list, pctl);
+    RG_LAUNCH_CHECK(ctx, "k_commit_select");
+    // HBM to HBM: bandwidth-bound, so the whole device may take part
+    return launch_list_copy(ctx, list, pctl, stage->rows, stage->row_stride, cache->cache_rows, cache->row_stride, dim, n,
+                            (int64_t)ctx->num_cus * 8, 256, s);
 }
 
 }  // extern "C"

@@ -40,6 +40,8 @@ struct rg_ctx {
     // prefetch scratch
     RgBuf pf_list;      // int32[2 * n]: (slot, remote row) pairs still to pull
     RgBuf pf_ctl;       // uint32[4]: [0] = number of pairs
+    RgBuf stage_list, stage_ctl;     // the same for rg_stage_rows
+    RgBuf commit_list, commit_ctl;   // the same for rg_commit_staged_rows
     // gather scratch
     RgBuf gather_src;   // uint32[n] resolved location word per output row
     RgBuf miss_list;    // int32[n] output rows whose source is the remote store

@@ -146,7 +146,8 @@ __global__ void __launch_bounds__(kChunk) k_hop_count(const RP* __restrict__ row
 // total_out[0].
 __global__ void __launch_bounds__(1024) k_scan_sums(int32_t* __restrict__ data, const int32_t* __restrict__ count_ptr,
                                                     int64_t fixed_count, int per, const int32_t* __restrict__ base_ptr,
-                                                    int32_t* __restrict__ total_out, int total_at_count) {
+                                                    int32_t* __restrict__ total_out, int total_at_count,
+                                                    int32_t* __restrict__ total_copy) {
     __shared__ int smem[1024 / RG_WAVE + 1];
     __shared__ int carry_s;
     const int64_t count = count_ptr ? (int64_t)*count_ptr : fixed_count;
@@ -168,6 +169,7 @@ __global__ void __launch_bounds__(1024) k_scan_sums(int32_t* __restrict__ data, 
         const int b = base_ptr ? *base_ptr : 0;
         const int64_t slot = total_at_count ? count : 0;
         total_out[slot] = b + carry_s;
+        if (total_copy) *total_copy = b + carry_s;
     }
 }
 
@@ -474,7 +476,7 @@ rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds,
             k_hop_count<int32_t><<<count_blocks, kChunk, 0, s>>>((const int32_t*)csr->row_ptr, out->nodes, n_frontier, fanouts[h], indptr, chunk_sum);
         RG_LAUNCH_CHECK(ctx, "k_hop_count");
         // chunk sums -> exclusive offsets; total edge count -> indptr[n_h]
-        k_scan_sums<<<1, 1024, 0, s>>>(chunk_sum, n_frontier, 0, kChunk, nullptr, indptr, 1);
+        k_scan_sums<<<1, 1024, 0, s>>>(chunk_sum, n_frontier, 0, kChunk, nullptr, indptr, 1, out->num_edges ? out->num_edges + h : nullptr);
         RG_LAUNCH_CHECK(ctx, "k_scan_sums");
 
         const int tok = rg_prof_begin(ctx, RG_K_SAMPLE, s);
@@ -509,7 +511,7 @@ rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds,
         // new tier: count fresh bits per block, scan, emit ascending
         k_tier_count<<<tier_blocks, 256, 0, s>>>(fresh, words, chunk_sum);
         RG_LAUNCH_CHECK(ctx, "k_tier_count");
-        k_scan_sums<<<1, 1024, 0, s>>>(chunk_sum, nullptr, tier_blocks, 1, n_frontier, out->tier_off + h + 2, 0);
+        k_scan_sums<<<1, 1024, 0, s>>>(chunk_sum, nullptr, tier_blocks, 1, n_frontier, out->tier_off + h + 2, 0, nullptr);
         RG_LAUNCH_CHECK(ctx, "k_scan_sums");
         k_tier_emit<<<tier_blocks, 256, 0, s>>>(fresh, visited, words, chunk_sum, n_frontier, out->nodes, pos);
         RG_LAUNCH_CHECK(ctx, "k_tier_emit");

@@ -1,17 +1,45 @@
 """Epoch driver over the C-ABI binding: the offline stage of Alg. 1 (lines 1-4: precompute the
 batches, count accesses, TopHot, VectorPull) followed by the online per-batch feature assembly
-(lines 12-14).  Host code only sequences library calls and owns the buffers; every step runs in the
-library's kernels.  No host synchronisation happens inside the offline stage: frontier sizes stay
-on the device and are read back once, before the online stage.
+(lines 12-14), with the paper's two latency-hiding devices mapped onto HIP streams:
+
+* prefetcher (Section III, Fig. 4): cached rows are pulled over the host link batch by batch, in order of
+  first use, on a stream of their own, one event per batch; gather b waits for event b only;
+* double-buffered cache (Alg. 1 lines 7-8 and 18-20, C_s / C_sec): while epoch e is served, epoch e+1 is
+  precomputed on another stream into the second buffer set, its rows are pulled behind epoch e's, and the
+  buffers are swapped at the epoch boundary.
+
+Host code only sequences library calls and owns the buffers; every step runs in the library's kernels.
+No host synchronisation happens inside the offline stage: frontier sizes stay on the device and are
+read back once per epoch, before its online stage.
 """
 import torch
 
 from . import binding as B
 
 
+class _EpochState:
+    """Everything one precomputed epoch owns: input-node lists, tier offsets, counts and the cache."""
+
+    def __init__(self, wl, H, slot, max_batches, device):
+        cfg = wl.cfg
+        # one slot of input nodes and one row of tier offsets per precomputed batch
+        self.arena = torch.empty(max_batches, max(slot, 1), dtype=torch.int32, device=device)
+        self.tier_offs = torch.zeros(max_batches, H + 2, dtype=torch.int32, device=device)
+        self.edge_counts = torch.zeros(max_batches, H, dtype=torch.int32, device=device)
+        self.counts = torch.zeros(cfg.num_nodes, dtype=torch.int32, device=device)
+        self.cache = B.FeatureCache(cfg.num_nodes, min(wl.capacity_rows, wl.n_remote), wl.stride, device)
+        self.stats = torch.zeros(max_batches, 3, dtype=torch.int64, device=device)
+        self.pf_events = [torch.cuda.Event() for _ in range(max_batches)]
+        self.built = torch.cuda.Event()        # offline stage of this state finished
+        self.served = torch.cuda.Event()       # online stage of this state finished
+        self.sizes = None
+        self.n_batches = 0
+        self.pulls_queued = False
+
+
 class EpochPipeline:
     def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True,
-                 epoch_histogram=True, sampler_streams=3):
+                 epoch_histogram=True, sampler_streams=3, double_buffer=False):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -22,18 +50,17 @@ class EpochPipeline:
         # Batches are independent, and most sampler kernels of one batch are far smaller than the GPU: several
         # batches are sampled side by side, each lane with its own stream, context (scratch) and hop buffers.
         n_lanes = max(1, int(sampler_streams)) if epoch_histogram else 1
+        if double_buffer:
+            n_lanes = max(n_lanes, 2)
+        self.n_lanes = n_lanes
         self.lane_ctx = [self.ctx] + [B.Context(self.ctx.device) for _ in range(n_lanes - 1)]
         self.lane_bufs = [B.BlockBuffers(cfg.num_nodes, wl.nnz, cfg.batch_size, cfg.fanouts, device) for _ in range(n_lanes)]
-        self.n_lanes = n_lanes
         self.bufs = self.lane_bufs[0]
         self.slot = self.bufs.frontier_ub[self.H]
-        # one slot of input nodes and one row of tier offsets per precomputed batch
-        self.arena = torch.empty(self.max_batches, max(self.slot, 1), dtype=torch.int32, device=device)
-        self.tier_offs = torch.zeros(self.max_batches, self.H + 2, dtype=torch.int32, device=device)
-        self.counts = torch.zeros(cfg.num_nodes, dtype=torch.int32, device=device)
-        self.cache = B.FeatureCache(cfg.num_nodes, min(wl.capacity_rows, wl.n_remote), wl.stride, device)
+        self.double_buffer = double_buffer
+        self.states = [_EpochState(wl, self.H, self.slot, self.max_batches, device) for _ in range(2 if double_buffer else 1)]
+        self.cur = 0
         self.out = torch.empty(max(self.slot, 1), wl.stride, dtype=torch.float32, device=device)
-        self.stats = torch.zeros(self.max_batches, 3, dtype=torch.int64, device=device)
         self.order = torch.empty_like(wl.train_ids)
         self.side = torch.cuda.Stream(device=device) if two_streams else None
         # prefetch = pull cached rows batch by batch, in order of first use, on a stream of their own so the
@@ -42,7 +69,6 @@ class EpochPipeline:
         # one LDS-privatised histogram over the whole epoch instead of one global-atomic pass per batch
         self.epoch_histogram = epoch_histogram
         self.pf_stream = torch.cuda.Stream(device=device) if prefetch else None
-        self.pf_events = [torch.cuda.Event() for _ in range(self.max_batches)] if prefetch else None
         # The sampler lanes reuse the streams that are idle during the offline stage (miss and prefetch streams);
         # only lanes beyond those get streams of their own.  The device exposes few hardware queues, and streams
         # that end up sharing one would serialise work that is meant to overlap.
@@ -50,11 +76,33 @@ class EpochPipeline:
         self.lane_stream = [None] + spare[:self.n_lanes - 1]
         while len(self.lane_stream) < self.n_lanes:
             self.lane_stream.append(torch.cuda.Stream(device=device))
+        # with double buffering the next epoch is precomputed on one stream of its own while the current one is served
+        self.build_stream = torch.cuda.Stream(device=device) if double_buffer else None
         for c in self.lane_ctx:
             c.reserve(cfg.num_nodes, self.slot, self.slot if c is self.ctx else 0)
-        self.sizes = None
 
-    # kernel timing over every lane's context
+    # ---- the current epoch's buffers under their historical names
+    @property
+    def state(self):
+        return self.states[self.cur]
+
+    arena = property(lambda self: self.state.arena)
+    tier_offs = property(lambda self: self.state.tier_offs)
+    edge_counts = property(lambda self: self.state.edge_counts)
+    counts = property(lambda self: self.state.counts)
+    stats = property(lambda self: self.state.stats)
+    sizes = property(lambda self: self.state.sizes)
+    n_batches = property(lambda self: self.state.n_batches)
+
+    @property
+    def cache(self):
+        return self.state.cache
+
+    @cache.setter
+    def cache(self, value):
+        self.state.cache = value
+
+    # ---- kernel timing over every lane's context
     def profile_enable(self, on=True):
         for c in self.lane_ctx:
             c.profile_enable(on)
@@ -70,68 +118,142 @@ class EpochPipeline:
             ms, launches = ms + m, launches + n
         return ms, launches
 
+    # ---- offline stage
+    def _offline(self, st, epoch, ids, lanes):
+        """Queue schedule, sampling, histogram and TopHot of one epoch.  lanes = [(ctx, bufs, stream or None)];
+        lane 0's stream (None = the current stream) also runs the schedule, the histogram and TopHot."""
+        cfg = self.cfg
+        head_ctx, _, head_stream = lanes[0]
+        head = head_stream or torch.cuda.current_stream()
+        with torch.cuda.stream(head):
+            head_ctx.epoch_schedule(self.wl.train_ids, self.wl.seed, epoch, self.order)
+            st.counts.zero_()
+            for _, _, s in lanes[1:]:
+                s.wait_stream(head)
+            n_train = self.order.numel()
+            for i, b in enumerate(ids):
+                seeds = self.order[b * cfg.batch_size:min((b + 1) * cfg.batch_size, n_train)]
+                c, bufs, s = lanes[i % len(lanes)]
+                bufs.set_outputs(st.arena[i], st.tier_offs[i], st.edge_counts[i])
+                c.sample_blocks(self.csr, seeds, seeds.numel(), cfg.fanouts, self.wl.seed, epoch, bufs, stream=s or head)
+                if not self.epoch_histogram:
+                    head_ctx.access_histogram(st.arena[i], self.slot, st.counts, n_dev=st.tier_offs[i, self.H + 1:], stream=head)
+            for _, _, s in lanes[1:]:
+                head.wait_stream(s)
+            if self.epoch_histogram:
+                head_ctx.access_histogram_epoch(st.arena, st.tier_offs, len(ids), self.H, cfg.batch_size, st.counts, stream=head)
+            head_ctx.build_cache(st.counts, self.wl.home, None if self.prefetch else self.wl.remote_store, cfg.feat_dim,
+                                 st.cache, stream=head)
+            st.built.record(head)
+        st.n_batches = len(ids)
+        st.sizes = None
+        st.pulls_queued = False
+
     def precompute(self, epoch, n_batches=None, batch_ids=None):
         """Offline stage (asynchronous) for the first n_batches batches of `epoch`, or for the listed
-        batch indices; slot i of the arena holds the i-th of them."""
-        cfg, ctx = self.cfg, self.ctx
+        batch indices; slot i of the arena holds the i-th of them.  Uses every sampler lane."""
         ids = list(batch_ids) if batch_ids is not None else list(range(n_batches))
         assert len(ids) <= self.max_batches and all(0 <= b < self.batches_per_epoch for b in ids)
-        ctx.epoch_schedule(self.wl.train_ids, self.wl.seed, epoch, self.order)
-        self.counts.zero_()
-        n_train = self.order.numel()
-        main = torch.cuda.current_stream()
-        lanes = len(self.lane_ctx)
-        for st in self.lane_stream[1:]:
-            st.wait_stream(main)
-        for i, b in enumerate(ids):
-            seeds = self.order[b * cfg.batch_size:min((b + 1) * cfg.batch_size, n_train)]
-            lane = i % lanes
-            bufs = self.lane_bufs[lane]
-            bufs.set_outputs(self.arena[i], self.tier_offs[i])
-            self.lane_ctx[lane].sample_blocks(self.csr, seeds, seeds.numel(), cfg.fanouts, self.wl.seed, epoch, bufs,
-                                              stream=self.lane_stream[lane])
-            if not self.epoch_histogram:
-                ctx.access_histogram(self.arena[i], self.slot, self.counts, n_dev=self.tier_offs[i, self.H + 1:])
-        for st in self.lane_stream[1:]:
-            main.wait_stream(st)
-        if self.epoch_histogram:
-            ctx.access_histogram_epoch(self.arena, self.tier_offs, len(ids), self.H, cfg.batch_size, self.counts)
-        ctx.build_cache(self.counts, self.wl.home, None if self.prefetch else self.wl.remote_store, cfg.feat_dim, self.cache)
-        self.n_batches = len(ids)
+        lanes = [(self.lane_ctx[k], self.lane_bufs[k], self.lane_stream[k]) for k in range(self.n_lanes)]
+        self._offline(self.state, epoch, ids, lanes)
 
     def read_sizes(self):
-        """One device-to-host copy of every batch's tier offsets (synchronises)."""
-        self.sizes = self.tier_offs[:self.n_batches, self.H + 1].cpu().tolist()
-        return self.sizes
+        """One device-to-host copy of every batch's input-node count (synchronises the current stream)."""
+        st = self.state
+        st.built.synchronize()
+        st.sizes = st.tier_offs[:st.n_batches, self.H + 1].cpu().tolist()
+        return st.sizes
 
+    def sampled_edges(self):
+        """Total number of sampled edges over the precomputed batches (synchronises)."""
+        return int(self.edge_counts[:self.n_batches].sum().item())
+
+    # ---- online stage
     def gather(self, b):
-        """Online stage for batch b: features of its input nodes into self.out[:n]."""
-        n = self.sizes[b]
-        self.ctx.gather_features(self.arena[b], n, self.cache, self.wl.local_store, self.wl.remote_store,
-                                 self.cfg.feat_dim, self.out, self.stats[b], miss_stream=self.side)
+        """Features of batch b's input nodes into self.out[:n]."""
+        st = self.state
+        n = st.sizes[b]
+        self.ctx.gather_features(st.arena[b], n, st.cache, self.wl.local_store, self.wl.remote_store,
+                                 self.cfg.feat_dim, self.out, st.stats[b], miss_stream=self.side)
         return n
 
-    def prefetch_rows(self, b, stream=None):
-        """Pull the not-yet-resident cached rows batch b needs (asynchronous on `stream`)."""
-        self.ctx.prefetch_cache_rows(self.arena[b], self.sizes[b], self.cache, self.wl.home, self.wl.remote_store,
-                                     self.cfg.feat_dim, stream=stream)
+    def prefetch_rows(self, b, stream=None, st=None):
+        """Pull the not-yet-resident cached rows batch b needs (asynchronous on `stream`).  The row count is
+        read on the device, so the pulls of an epoch can be queued before the host knows its batch sizes."""
+        st = st or self.state
+        self.ctx.prefetch_cache_rows(st.arena[b], self.slot, st.cache, self.wl.home, self.wl.remote_store,
+                                     self.cfg.feat_dim, n_dev=st.tier_offs[b, self.H + 1:], stream=stream)
 
-    def online(self, n_batches):
-        """Online stage: gathers in batch order; with prefetch on, batch b's gather waits only for the pulls
-        of batches 0..b, which run ahead on the prefetch stream."""
-        if not self.prefetch:
-            for b in range(n_batches):
-                self.gather(b)
+    def _queue_pulls(self, st):
+        """All of an epoch's pulls on the prefetch stream, behind its TopHot, one event per batch."""
+        if st.pulls_queued:
             return
-        main = torch.cuda.current_stream()
-        self.pf_stream.wait_stream(main)
-        for b in range(n_batches):
-            self.prefetch_rows(b, stream=self.pf_stream)
-            self.pf_events[b].record(self.pf_stream)
-            main.wait_event(self.pf_events[b])
-            self.gather(b)
+        self.pf_stream.wait_event(st.built)
+        for b in range(st.n_batches):
+            self.prefetch_rows(b, stream=self.pf_stream, st=st)
+            st.pf_events[b].record(self.pf_stream)
+        st.pulls_queued = True
 
-    def run_epoch(self, epoch, n_batches):
+    def online(self, n_batches, on_batch=None):
+        """Gathers in batch order; with prefetch on, batch b's gather waits only for the pulls of batches
+        0..b, which run ahead on the prefetch stream.  on_batch(pipeline, b) is called after batch b's gather
+        has been queued (the consumer of self.out[:n]; it must order itself after the current stream)."""
+        st = self.state
+        main = torch.cuda.current_stream()
+        if self.prefetch and not st.pulls_queued:
+            self.pf_stream.wait_stream(main)
+        for b in range(n_batches):
+            if self.prefetch:
+                if not st.pulls_queued:
+                    self.prefetch_rows(b, stream=self.pf_stream)
+                    st.pf_events[b].record(self.pf_stream)
+                main.wait_event(st.pf_events[b])
+            self.gather(b)
+            if on_batch:
+                on_batch(self, b)
+        if self.prefetch:
+            st.pulls_queued = True
+        st.served.record(main)
+
+    def run_epoch(self, epoch, n_batches, on_batch=None):
+        """One epoch from a cold start: offline stage, size read-back, online stage."""
         self.precompute(epoch, n_batches)
         self.read_sizes()
-        self.online(n_batches)
+        self.online(n_batches, on_batch)
+
+    def run_epochs(self, first_epoch, n_epochs, n_batches, on_epoch_done=None, on_batch=None, on_epoch_start=None):
+        """Several epochs back to back.  With double buffering, epoch e+1 is precomputed on the build stream
+        (one sampler lane) and its rows are pulled behind epoch e's while epoch e is being served."""
+        if not self.double_buffer or n_epochs == 1:
+            for k in range(n_epochs):
+                self.precompute(first_epoch + k, n_batches)
+                self.read_sizes()
+                if on_epoch_start:
+                    on_epoch_start(self, k)
+                self.online(n_batches, on_batch)
+                if on_epoch_done:
+                    on_epoch_done(self, k)
+            return
+        main = torch.cuda.current_stream()
+        ids = list(range(n_batches))
+        self.precompute(first_epoch, n_batches)                      # cold start: every lane
+        build_lane = [(self.lane_ctx[1], self.lane_bufs[1], self.build_stream)]
+        for k in range(n_epochs):
+            self.read_sizes()
+            if self.prefetch:
+                self._queue_pulls(self.state)
+            nxt = self.states[1 - self.cur]
+            if k + 1 < n_epochs:
+                # the other buffer set is free once the epoch that used it has been served
+                self.build_stream.wait_event(nxt.served)
+                self.build_stream.wait_stream(main)                  # and after anything already queued that reads `order`
+                self._offline(nxt, first_epoch + k + 1, ids, build_lane)
+            if on_epoch_start:
+                on_epoch_start(self, k)
+            self.online(n_batches, on_batch)
+            if k + 1 < n_epochs and self.prefetch:
+                self._queue_pulls(nxt)                               # behind this epoch's pulls on the prefetch stream
+            if on_epoch_done:
+                on_epoch_done(self, k)
+            self.cur = 1 - self.cur
+        self.cur = 1 - self.cur                                      # leave the last served epoch current

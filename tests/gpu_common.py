@@ -34,11 +34,13 @@ class HipBatch:
             self.indptr.append(ip)
             self.nbr.append(bufs.nbr[h][:e].cpu().numpy())
             self.nbr_local.append(bufs.nbr_local[h][:e].cpu().numpy() if bufs.nbr_local else None)
+        self.num_edges = bufs.num_edges.cpu().numpy().astype(np.int64)
 
 
 def assert_batch_equal(hip, orc, num_hops, tag=""):
     assert hip.tier_off.tolist() == orc.tier_off.tolist(), f"{tag} tier_off"
     assert np.array_equal(hip.nodes, orc.nodes), f"{tag} nodes"
+    assert hip.num_edges[:num_hops].tolist() == [int(x.size) for x in orc.nbr], f"{tag} num_edges"
     for h in range(num_hops):
         assert np.array_equal(hip.indptr[h].astype(np.int64), orc.indptr[h]), f"{tag} indptr[{h}]"
         assert np.array_equal(hip.nbr[h], orc.nbr[h]), f"{tag} nbr[{h}]"

@@ -263,6 +263,55 @@ def test_prefetch_by_first_use_matches_bulk_fill(B, ctx):
     assert not cache.cache_rows.any()
 
 
+@pytest.mark.parametrize("double_buffer", [False, True])
+def test_pipeline_epochs_back_to_back(B, double_buffer):
+    """Three epochs through EpochPipeline.run_epochs; with double buffering epoch e+1 is precomputed and its rows
+    pulled while epoch e is served.  Every batch's rows and statistics and every epoch's cache are checked."""
+    from paper_2505_10806_amd.pipeline import EpochPipeline
+    wl = synth.build_workload("tiny", seed=5, device=DEV)
+    cfg = wl.cfg
+    rp, ci = host_graph(wl)
+    X = wl.features.cpu().numpy()
+    home_np, train_np = wl.home.cpu().numpy(), wl.train_ids.cpu().numpy()
+    pipe = EpochPipeline(wl, device=DEV, double_buffer=double_buffer)
+    nb = pipe.batches_per_epoch
+    expected = {}
+
+    def epoch_start(p, k):                      # oracle results for the epoch that is about to be served
+        batches = oracle.epoch_batches(train_np, cfg.batch_size, wl.seed, k, cfg.max_batches)
+        counts = np.zeros(cfg.num_nodes, dtype=np.uint32)
+        inputs = []
+        for seeds in batches:
+            blk = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, k)
+            oracle.access_histogram(blk.input_nodes, counts)
+            inputs.append(blk.input_nodes)
+        ids, loc = oracle.build_cache(counts, home_np, wl.capacity_rows)
+        expected[k] = (inputs, counts, ids, loc)
+        assert np.array_equal(p.counts.cpu().numpy().view(np.uint32), counts)
+        assert np.array_equal(p.cache.cache_ids[:ids.size].cpu().numpy(), ids)
+        assert np.array_equal(p.cache.loc.cpu().numpy(), loc)
+        p._epoch = k
+
+    def batch_done(p, b):
+        torch.cuda.synchronize()
+        inputs, _, _, loc = expected[p._epoch]
+        want, st = oracle.gather_features(X, inputs[b], loc)
+        n = inputs[b].size
+        assert p.sizes[b] == n
+        assert np.array_equal(p.out[:n, :cfg.feat_dim].cpu().numpy(), want), f"epoch {p._epoch} batch {b}"
+        assert tuple(p.stats[b].cpu().tolist()) == st
+
+    def epoch_done(p, k):
+        torch.cuda.synchronize()
+        _, _, ids, _ = expected[k]
+        assert np.array_equal(p.cache.cache_rows[:ids.size, :cfg.feat_dim].cpu().numpy(), X[ids])
+
+    pipe.run_epochs(0, 3, nb, on_epoch_done=epoch_done, on_batch=batch_done, on_epoch_start=epoch_start)
+    torch.cuda.synchronize()
+    assert sorted(expected) == [0, 1, 2]
+    assert not np.array_equal(expected[0][0][0], expected[1][0][0])       # epochs differ
+
+
 # ------------------------------------------------------------------------------ TopHot edge cases
 @pytest.mark.parametrize("capacity", [0, 1, 5, 1000, 4000, 1 << 20])
 def test_build_cache_edge_cases(B, ctx, capacity):
