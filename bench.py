@@ -12,6 +12,11 @@ import os
 import sys
 import time
 
+# The pipeline keeps up to five streams busy at once (gathers, miss rows, host-link pulls, two more sampler lanes);
+# with HIP's default of 4 hardware queues two of them would share a queue and serialise.
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 8:
+    os.environ["GPU_MAX_HW_QUEUES"] = "8"
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
@@ -96,6 +101,8 @@ def main():
     ap.add_argument("--sampler-streams", type=int, default=3, help="batches sampled side by side during the offline stage")
     ap.add_argument("--no-double-buffer", action="store_true",
                     help="with more than one epoch of steps: do not precompute epoch e+1 while epoch e is served")
+    ap.add_argument("--early-pull", action="store_true",
+                    help="pull rows into a staging area during the offline stage (only when the cache can hold every remote node)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -141,7 +148,7 @@ def main():
     with torch.cuda.stream(main_stream):
         pipe = EpochPipeline(wl, device=dev, max_batches=min(max(steps, warmup, 1), bpe), two_streams=not args.one_stream,
                              prefetch=not args.bulk_fill, sampler_streams=args.sampler_streams,
-                             double_buffer=(steps > bpe and not args.no_double_buffer))
+                             double_buffer=(steps > bpe and not args.no_double_buffer), early_pull=args.early_pull)
         ctx = pipe.ctx
         if warmup > 0:
             run_steps(pipe, warmup)
@@ -194,7 +201,8 @@ def main():
                    "cache_capacity_rows": wl.capacity_rows, "miss_stream": "shared" if args.one_stream else "separate",
                    "cache_fill": "bulk" if args.bulk_fill else "prefetch by first use",
                    "sampler_streams": args.sampler_streams,
-                   "double_buffered_cache": bool(steps > bpe and not args.no_double_buffer)},
+                   "double_buffered_cache": bool(steps > bpe and not args.no_double_buffer),
+                   "early_pull": pipe.early_pull},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes / max(g_launches, 1),

@@ -36,7 +36,10 @@ def _compare_block(pipe, B, wl, rp, ci, epoch, slot, seeds_orc, scratch):
 
 def _gather_and_compare(pipe, wl, X, X1, slot, nodes_orc, loc_orc, rows):
     cfg = wl.cfg
-    if pipe.prefetch:                                   # same order as EpochPipeline.online, synchronous here
+    if pipe.early_pull:                                 # same order as EpochPipeline.online, synchronous here
+        torch.cuda.synchronize()                        # the staging pulls were queued during precompute
+        pipe.commit_rows(slot)
+    elif pipe.prefetch:
         pipe.prefetch_rows(slot)
     n = pipe.gather(slot)
     torch.cuda.synchronize()
