@@ -263,6 +263,20 @@ RG_API rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int
                              int32_t dim, float* out, int64_t out_stride,
                              rg_gather_stats* stats, void* hit_stream, void* miss_stream);
 
+/* ---- consumer of the gathered rows: Eq. 1 with AGG = mean (GraphSAGE, Section II-A) -------------
+ * For the block of one hop (destination i = position in frontier_h, sources = positions in
+ * frontier_{h+1} given by nbr_local[h]):
+ *   agg[i][0:dim] = (1 / m_i) * sum_{e = indptr[i]}^{indptr[i+1]-1} feat[nbr_local[e]][0:dim],
+ *   m_i = indptr[i+1] - indptr[i]; a destination without sampled neighbours gets a zero row.
+ * The sum is accumulated in fp32 in edge order and divided by m_i (IEEE division).
+ * For the outermost hop, feat is the output of rg_gather_features (rows in input-node order).
+ * indptr: device int32[n_dst + 1]; nbr_local: device int32[indptr[n_dst]]; n_dst_dev: optional
+ * device count as for rg_access_histogram; feat: device float[rows * feat_stride]; agg: device
+ * float[n_dst * agg_stride].  Row padding rule as for the gather. */
+RG_API rg_status rg_mean_aggregate(rg_ctx* ctx, const int32_t* indptr, const int32_t* nbr_local, int64_t n_dst,
+                                   const int32_t* n_dst_dev, const float* feat, int64_t feat_stride, int32_t dim,
+                                   float* agg, int64_t agg_stride, void* stream);
+
 /* ---- kernel timing for the benchmark ------------------------------------------------------
  * With profiling on, every launch of the listed kernels is bracketed by hipEvents on its own
  * stream.  rg_profile_read synchronises the recorded events and returns the summed duration
@@ -273,6 +287,7 @@ typedef enum {
     RG_K_SAMPLE = 2,       /* per-hop draw + neighbour read kernel */
     RG_K_HISTOGRAM = 3,
     RG_K_CACHE_FILL = 4,   /* bulk pull and per-batch prefetch pulls */
+    RG_K_AGGREGATE = 5,
     RG_K_COUNT_
 } rg_kernel_id;
 

@@ -74,6 +74,8 @@ def lib():
     L.orc_fill_cache.restype = None
     L.orc_gather_features.argtypes = [P, c_i64, P, c_i64, P, P, c_i64, P]
     L.orc_gather_features.restype = None
+    L.orc_mean_aggregate.argtypes = [P, P, c_i64, P, c_i64, c_i64, P]
+    L.orc_mean_aggregate.restype = None
     _lib = L
     return L
 
@@ -203,3 +205,14 @@ def gather_features(X, input_nodes, loc, out_stride=None):
     stats = np.zeros(3, dtype=np.int64)
     lib().orc_gather_features(_p(X), d, _p(nd), nd.size, _p(lc), _p(out), stride, _p(stats))
     return out[:nd.size], tuple(int(s) for s in stats)
+
+
+def mean_aggregate(indptr, nbr_local, feat):
+    """Mean of the source rows of every destination of a block, fp64 [n_dst, dim]; feat is fp32 [rows, dim]."""
+    ip = _arr(indptr, np.int64)
+    nl = _arr(nbr_local, np.int32)
+    F = _arr(feat, np.float32)
+    n_dst = ip.size - 1
+    out = np.zeros((max(n_dst, 1), F.shape[1]), dtype=np.float64)
+    lib().orc_mean_aggregate(_p(ip), _p(nl), n_dst, _p(F), F.shape[1], F.shape[1], _p(out))
+    return out[:n_dst]

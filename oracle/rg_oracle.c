@@ -279,3 +279,17 @@ void orc_gather_features(const float* X, int64_t dim, const int32_t* input_nodes
         else stats[2] += 1;
     }
 }
+
+/* ---- Eq. 1, AGG = mean over the sampled neighbours of each destination of a block (fp64) */
+void orc_mean_aggregate(const int64_t* indptr, const int32_t* nbr_local, int64_t n_dst,
+                        const float* feat, int64_t feat_stride, int64_t dim, double* agg) {
+    for (int64_t i = 0; i < n_dst; ++i) {
+        int64_t m = indptr[i + 1] - indptr[i];
+        for (int64_t c = 0; c < dim; ++c) {
+            double sum = 0.0;
+            for (int64_t e = indptr[i]; e < indptr[i + 1]; ++e)
+                sum += (double)feat[(int64_t)nbr_local[e] * feat_stride + c];
+            agg[i * dim + c] = m > 0 ? sum / (double)m : 0.0;
+        }
+    }
+}

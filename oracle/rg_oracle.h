@@ -14,7 +14,8 @@
  * and inclusion probability k/d; every sampled neighbour is a real edge; count =
  * min(fanout, degree); BFS-ball special case against a textbook BFS; histogram against
  * numpy bincount; top-K against a full lexicographic sort; gather against plain
- * indexing; the hit-rate closed form; the paper's byte-accounting example.
+ * indexing; the hit-rate closed form; the paper's byte-accounting example; the mean aggregation
+ * against a float64 sparse matrix product (scipy).
  * Statistical fidelity of the synthetic graphs to the paper's datasets: parity unpinned.
  */
 #ifndef RG_ORACLE_H
@@ -78,6 +79,11 @@ void orc_fill_cache(const float* X, int64_t dim, const int32_t* cache_ids, int64
  * stats = {#local, #cache hits, #remote misses} according to loc. */
 void orc_gather_features(const float* X, int64_t dim, const int32_t* input_nodes, int64_t n,
                          const int32_t* loc, float* out, int64_t out_stride, int64_t stats[3]);
+
+/* Eq. 1 with AGG = mean (GraphSAGE, Section II-A) over one sampled block, in fp64:
+ * agg[i] = (1/m_i) sum_{e in [indptr[i], indptr[i+1])} feat[nbr_local[e]], zero row when m_i = 0. */
+void orc_mean_aggregate(const int64_t* indptr, const int32_t* nbr_local, int64_t n_dst,
+                        const float* feat, int64_t feat_stride, int64_t dim, double* agg);
 
 #ifdef __cplusplus
 }

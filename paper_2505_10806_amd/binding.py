@@ -17,7 +17,7 @@ RG_OK, RG_ERR_INVALID_ARG, RG_ERR_CAPACITY, RG_ERR_OOM, RG_ERR_HIP, RG_ERR_STATE
 RG_MAX_FANOUT = 1024
 RG_FANOUT_ALL = -1
 RG_MAX_HOPS = 8
-RG_K_GATHER_HBM, RG_K_GATHER_MISS, RG_K_SAMPLE, RG_K_HISTOGRAM, RG_K_CACHE_FILL = range(5)
+RG_K_GATHER_HBM, RG_K_GATHER_MISS, RG_K_SAMPLE, RG_K_HISTOGRAM, RG_K_CACHE_FILL, RG_K_AGGREGATE = range(6)
 
 _STATUS_NAMES = {0: "RG_OK", 1: "RG_ERR_INVALID_ARG", 2: "RG_ERR_CAPACITY", 3: "RG_ERR_OOM",
                  4: "RG_ERR_HIP", 5: "RG_ERR_STATE"}
@@ -78,6 +78,7 @@ def _load():
     L.rg_stage_rows.argtypes = [c_p, c_p, c_i64, c_p, c_p, ctypes.POINTER(rg_stage), c_i32, c_p, c_i64, c_i32, c_p]
     L.rg_commit_staged_rows.argtypes = [c_p, c_p, c_i64, c_p, c_p, ctypes.POINTER(rg_stage), c_i32,
                                         ctypes.POINTER(rg_cache), c_i32, c_p]
+    L.rg_mean_aggregate.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_p, c_i64, c_i32, c_p, c_i64, c_p]
     L.rg_gather_features.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_i64, c_p, c_i64,
                                      c_i32, c_p, c_i64, c_p, c_p, c_p]
     L.rg_profile_enable.argtypes = [c_p, ctypes.c_int]
@@ -85,7 +86,7 @@ def _load():
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks",
                  "rg_access_histogram", "rg_access_histogram_epoch", "rg_build_cache", "rg_prefetch_cache_rows",
-                 "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
+                 "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -94,7 +95,8 @@ _lib = _load()
 
 EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "rg_reserve", "rg_epoch_schedule",
                     "rg_blocks_bounds", "rg_sample_blocks", "rg_access_histogram", "rg_access_histogram_epoch",
-                    "rg_build_cache", "rg_prefetch_cache_rows", "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
+                    "rg_build_cache", "rg_prefetch_cache_rows", "rg_stage_rows", "rg_commit_staged_rows",
+                    "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
 
 
 def _ptr(t, dtype=None, device_type=None, name="tensor"):
@@ -232,6 +234,14 @@ class Context:
             int(dim), _ptr(out, torch.float32, "cuda", "out"), out.stride(0),
             _ptr(stats, torch.int64, "cuda", "stats"), _stream_handle(hit_stream),
             None if miss_stream is None else _stream_handle(miss_stream)))
+
+    # -- rg_mean_aggregate
+    def mean_aggregate(self, indptr, nbr_local, n_dst, feat, dim, agg, n_dst_dev=None, stream=None):
+        self._check(_lib.rg_mean_aggregate(
+            self._h, _ptr(indptr, torch.int32, "cuda", "indptr"), _ptr(nbr_local, torch.int32, "cuda", "nbr_local"),
+            int(n_dst), _ptr(n_dst_dev, torch.int32, "cuda", "n_dst_dev"),
+            _ptr(feat, torch.float32, "cuda", "feat"), feat.stride(0), int(dim),
+            _ptr(agg, torch.float32, "cuda", "agg"), agg.stride(0), _stream_handle(stream)))
 
     # -- rg_profile_*
     def profile_enable(self, on=True):

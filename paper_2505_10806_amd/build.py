@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "librapidgnn.so")
 
-SOURCES = ["rg_api.hip", "rg_sampler.hip", "rg_cache.hip", "rg_gather.hip"]
+SOURCES = ["rg_api.hip", "rg_sampler.hip", "rg_cache.hip", "rg_gather.hip", "rg_aggregate.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -39,7 +39,7 @@ def _compile(src):
 def build(verbose=False):
     """Compile every HIP source and link the shared library.  Always rebuilds."""
     os.makedirs(BUILD_DIR, exist_ok=True)
-    with concurrent.futures.ThreadPoolExecutor(max_workers=4) as ex:
+    with concurrent.futures.ThreadPoolExecutor(max_workers=5) as ex:
         results = list(ex.map(_compile, SOURCES))
     objs = [o for o, _ in results]
     if verbose:

@@ -520,6 +520,82 @@ def test_epoch_histogram_matches_per_batch_definition(B, ctx, n_nodes, n_batches
     assert np.array_equal(counts.cpu().numpy().view(np.uint32), want)
 
 
+# ------------------------------------------------------------------------------ mean aggregation (consumer)
+def _agg_tolerance(indptr, nbr, X):
+    """fp32 sequential sum of m terms then one division: |error| <= u * (sum|x_e| + |mean|), u = 2^-24
+    (standard summation bound (m-1) u sum|x| divided by m, plus the rounding of the division)."""
+    m = np.diff(indptr).astype(np.float64)[:, None]
+    mean_abs = oracle.mean_aggregate(indptr, nbr, np.abs(X))
+    mean = oracle.mean_aggregate(indptr, nbr, X)
+    return mean, 1.01 * 2.0 ** -24 * (m * mean_abs + np.abs(mean)) + 1e-37
+
+
+@pytest.mark.parametrize("dim,pad", [(64, True), (100, True), (256, True), (602, True), (602, False), (7, False), (1, False)])
+def test_mean_aggregate_synthetic_segments(B, ctx, dim, pad):
+    log(f"[mean aggregate] dim={dim} pad={pad}")
+    rng = np.random.default_rng(dim)
+    n_dst, n_src = 2500, 6000
+    m = rng.integers(0, 12, size=n_dst)
+    m[:4] = [0, 1, 100, 33]
+    indptr = np.concatenate([[0], np.cumsum(m)]).astype(np.int64)
+    nbr = rng.integers(0, n_src, size=int(indptr[-1])).astype(np.int32)
+    X = (rng.standard_normal((n_src, dim)) * 10 ** rng.uniform(-3, 3, size=(n_src, 1))).astype(np.float32)
+    stride = synth.stores.row_stride(dim) if pad else dim
+    feat = torch.zeros(n_src, stride, device=DEV)
+    feat[:, :dim] = torch.from_numpy(X).to(DEV)
+    agg = torch.full((n_dst, stride), float("nan"), device=DEV)
+    ctx.mean_aggregate(torch.as_tensor(indptr.astype(np.int32), device=DEV), torch.as_tensor(nbr, device=DEV), n_dst,
+                       feat, dim, agg)
+    torch.cuda.synchronize()
+    want, tol = _agg_tolerance(indptr, nbr, X)
+    got = agg[:, :dim].cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - want) <= tol), float(np.max(np.abs(got - want) / tol))
+    assert not got[0].any()
+    assert np.array_equal(agg[1, :dim].cpu().numpy(), X[nbr[indptr[1]]])      # one neighbour: exact
+    # device-side destination count
+    agg.fill_(float("nan"))
+    ctx.mean_aggregate(torch.as_tensor(indptr.astype(np.int32), device=DEV), torch.as_tensor(nbr, device=DEV), n_dst,
+                       feat, dim, agg, n_dst_dev=torch.tensor([1000], dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    got = agg[:, :dim].cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got[:1000] - want[:1000]) <= tol[:1000]) and np.isnan(got[1000:]).all()
+
+
+def test_mean_aggregate_over_sampled_block(B, ctx):
+    """Sample a batch, gather its input features, aggregate the outermost hop: the first GraphSAGE layer's AGG."""
+    wl = synth.build_workload("small", seed=3, device=DEV)
+    cfg = wl.cfg
+    H = len(cfg.fanouts)
+    rp, ci = host_graph(wl)
+    X = wl.features.cpu().numpy()
+    csr = B.CsrGraph(wl.row_ptr, wl.col_idx)
+    bufs = B.BlockBuffers(cfg.num_nodes, wl.nnz, cfg.batch_size, cfg.fanouts, DEV)
+    seeds = wl.train_ids[:cfg.batch_size].contiguous()
+    ctx.sample_blocks(csr, seeds, seeds.numel(), cfg.fanouts, wl.seed, 0, bufs)
+    torch.cuda.synchronize()
+    tier = bufs.tier_off.cpu().tolist()
+    n, n_dst = tier[H + 1], tier[H]
+    cache = B.FeatureCache(cfg.num_nodes, 0, wl.stride, DEV)
+    cache.loc.copy_(wl.home)                                       # no cache: rows come from their home stores
+    out = torch.empty(n, wl.stride, device=DEV)
+    stats = torch.zeros(3, dtype=torch.int64, device=DEV)
+    ctx.gather_features(bufs.nodes, n, cache, wl.local_store, wl.remote_store, cfg.feat_dim, out, stats)
+    agg = torch.empty(n_dst, wl.stride, device=DEV)
+    ctx.mean_aggregate(bufs.indptr[H - 1], bufs.nbr_local[H - 1], n_dst, out, cfg.feat_dim, agg,
+                       n_dst_dev=bufs.tier_off[H:])
+    torch.cuda.synchronize()
+    blk = oracle.sample_blocks(rp, ci, seeds.cpu().numpy(), cfg.fanouts, wl.seed, 0)
+    feats = X[blk.input_nodes]                                     # gathered rows, by the oracle's plain definition
+    want, tol = _agg_tolerance(blk.indptr[H - 1], blk.nbr_local[H - 1], feats)
+    got = agg[:, :cfg.feat_dim].cpu().numpy().astype(np.float64)
+    assert got.shape == want.shape
+    assert np.all(np.abs(got - want) <= tol)
+    # the same thing written with global ids: mean of X over the sampled neighbours of each frontier node
+    i = 17
+    nb = blk.nbr[H - 1][blk.indptr[H - 1][i]:blk.indptr[H - 1][i + 1]]
+    assert np.allclose(got[i], X[nb].astype(np.float64).mean(0), rtol=1e-5, atol=1e-6)
+
+
 # ------------------------------------------------------------------------------ argument errors
 def test_argument_errors_are_reported_not_launched(B, ctx):
     rp = torch.tensor([0, 1, 2], dtype=torch.int32, device=DEV)

@@ -144,3 +144,28 @@ def test_miss_bytes_follow_paper_accounting(golden_dir):
     assert round(kv["batches_per_epoch"] * kv["per_batch_bytes"] / 1e9, 1) == kv["epoch_gb"]
     assert round(miss_bytes(kv["table4_rows_rapidgnn"], kv["table4_dim"]) / 2 ** 20) == kv["table4_mb_rapidgnn"]
     assert round(miss_bytes(kv["table4_rows_baseline"], kv["table4_dim"]) / 2 ** 20) == kv["table4_mb_baseline"]
+
+
+def test_mean_aggregate_is_normalised_sparse_product():
+    """Mean aggregation = (D^-1 A) X for the block's 0/1 incidence matrix A: checked against scipy's float64
+    sparse product, plus the closed forms for one neighbour, no neighbour and identical sources."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng(2)
+    n_dst, n_src, dim = 300, 900, 37
+    m = rng.integers(0, 8, size=n_dst)
+    m[:5] = [0, 1, 1, 0, 7]
+    indptr = np.concatenate([[0], np.cumsum(m)]).astype(np.int64)
+    nbr = rng.integers(0, n_src, size=int(indptr[-1])).astype(np.int32)      # repeats allowed
+    X = rng.standard_normal((n_src, dim)).astype(np.float32)
+    got = oracle.mean_aggregate(indptr, nbr, X)
+    A = sp.csr_matrix((np.ones(nbr.size), nbr, indptr), shape=(n_dst, n_src))
+    inv = np.divide(1.0, m, out=np.zeros(n_dst), where=m > 0)
+    want = sp.diags(inv) @ (A @ X.astype(np.float64))
+    assert np.allclose(got, want, rtol=1e-13, atol=1e-13)
+    assert not got[0].any() and not got[3].any()                             # no sampled neighbour -> zero row
+    assert np.array_equal(got[1], X[nbr[indptr[1]]].astype(np.float64))      # one neighbour -> that row
+    same = oracle.mean_aggregate(np.array([0, 4]), np.array([9, 9, 9, 9], dtype=np.int32), X)
+    assert np.array_equal(same[0], X[9].astype(np.float64))
+    # transposed operand / wrong normaliser would fail this: two destinations sharing sources in different order
+    two = oracle.mean_aggregate(np.array([0, 2, 5]), np.array([1, 2, 2, 1, 3], dtype=np.int32), X)
+    assert np.allclose(two[0], (X[1].astype(np.float64) + X[2]) / 2) and np.allclose(two[1], (X[2].astype(np.float64) + X[1] + X[3]) / 3)
