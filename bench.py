@@ -103,6 +103,9 @@ def main():
                     help="with more than one epoch of steps: do not precompute epoch e+1 while epoch e is served")
     ap.add_argument("--early-pull", action="store_true",
                     help="pull rows into a staging area during the offline stage (only when the cache can hold every remote node)")
+    ap.add_argument("--consumer", choices=["none", "mean"], default="none",
+                    help="reduce every batch's gathered rows with the mean aggregator over its outermost block, on its own stream")
+    ap.add_argument("--queue-depth", type=int, default=3, help="output buffers the gathers may run ahead of the consumer")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -148,7 +151,9 @@ def main():
     with torch.cuda.stream(main_stream):
         pipe = EpochPipeline(wl, device=dev, max_batches=min(max(steps, warmup, 1), bpe), two_streams=not args.one_stream,
                              prefetch=not args.bulk_fill, sampler_streams=args.sampler_streams,
-                             double_buffer=(steps > bpe and not args.no_double_buffer), early_pull=args.early_pull)
+                             double_buffer=(steps > bpe and not args.no_double_buffer), early_pull=args.early_pull,
+                             consumer=None if args.consumer == "none" else args.consumer,
+                             queue_depth=args.queue_depth if args.consumer != "none" else 1)
         ctx = pipe.ctx
         if warmup > 0:
             run_steps(pipe, warmup)
@@ -170,7 +175,7 @@ def main():
     row_bytes = 4 * cfg.feat_dim
     prof = {name: pipe.profile_read(kid) for name, kid in
             [("gather_hbm", B.RG_K_GATHER_HBM), ("gather_miss", B.RG_K_GATHER_MISS), ("sample", B.RG_K_SAMPLE),
-             ("histogram", B.RG_K_HISTOGRAM), ("cache_fill", B.RG_K_CACHE_FILL)]}
+             ("histogram", B.RG_K_HISTOGRAM), ("cache_fill", B.RG_K_CACHE_FILL), ("mean_aggregate", B.RG_K_AGGREGATE)]}
     g_ms, g_launches = prof["gather_hbm"]
     hbm_rows = n_local + n_hit
     alg_bytes = 2.0 * row_bytes * hbm_rows                       # every HBM-served row is read once and written once
@@ -202,7 +207,8 @@ def main():
                    "cache_fill": "bulk" if args.bulk_fill else "prefetch by first use",
                    "sampler_streams": args.sampler_streams,
                    "double_buffered_cache": bool(steps > bpe and not args.no_double_buffer),
-                   "early_pull": pipe.early_pull},
+                   "early_pull": pipe.early_pull, "consumer": args.consumer,
+                   "queue_depth": pipe.queue_depth},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes / max(g_launches, 1),
@@ -222,6 +228,15 @@ def main():
         "kernel_ms": {k: {"total_ms": v[0], "launches": v[1]} for k, v in prof.items()},
     }
 
+    a_ms, a_launches = prof["mean_aggregate"]
+    if a_launches:
+        # per launch: one feature row read per sampled edge of the outermost hop, one row written per destination
+        last = pipe.H - 1
+        e_last = sum(int(st.edge_counts[:st.n_batches, last].sum().item()) for st in pipe.states[:1]) if steps <= bpe else None
+        result["consumer"] = {"kernel": "k_mean_aggregate", "total_ms": a_ms, "launches": a_launches,
+                              "outermost_hop_edges": e_last,
+                              "algorithmic_GBps": (row_bytes * (e_last + sum(int(x) for x in pipe.state.tier_offs[:pipe.n_batches, pipe.H].cpu().tolist()))
+                                                   / (a_ms * 1e-3) / 1e9) if e_last else None}
     n_cpu = args.cpu_batches
     if n_cpu is None:
         n_cpu = 2 if cfg.num_nodes >= 1_000_000 else min(8, bpe)

@@ -316,6 +316,25 @@ class BlockBuffers:
             ctypes.cast(self._loc_arr, ctypes.POINTER(c_p)) if self._loc_arr is not None else None,
             ctypes.cast(self._nbr_cap, ctypes.POINTER(c_i64)), self.num_edges.data_ptr())
 
+    def set_hop(self, h, indptr=None, nbr=None, nbr_local=None):
+        """Point hop h's outputs at other buffers (e.g. to keep a batch's outermost block for its consumer)."""
+        for name, t, arr, cap in (("indptr", indptr, self._indptr_arr, self._indptr_cap),
+                                  ("nbr", nbr, self._nbr_arr, self._nbr_cap),
+                                  ("nbr_local", nbr_local, self._loc_arr, self._nbr_cap)):
+            if t is None:
+                continue
+            if t.dtype != torch.int32 or not t.is_contiguous() or arr is None:
+                raise TypeError(f"set_hop: {name} must be a contiguous int32 tensor (and relabelling enabled for nbr_local)")
+            need = self.frontier_ub[h] + 1 if name == "indptr" else self.edges_ub[h]
+            if t.numel() < need:
+                raise ValueError(f"set_hop: {name} holds {t.numel()} entries, {need} required")
+            getattr(self, name)[h] = t
+            arr[h] = t.data_ptr()
+            if name != "nbr_local":
+                cap[h] = t.numel()
+        if nbr is not None and nbr_local is not None and nbr.numel() != nbr_local.numel():
+            raise ValueError("set_hop: nbr and nbr_local must have the same capacity")
+
     def set_outputs(self, nodes, tier_off, num_edges=None):
         """Point the input-node list, tier offsets and per-hop edge counts at other buffers (e.g. a batch's slot
         of an epoch arena)."""

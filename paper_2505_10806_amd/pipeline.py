@@ -20,8 +20,15 @@ from . import binding as B
 class _EpochState:
     """Everything one precomputed epoch owns: input-node lists, tier offsets, counts and the cache."""
 
-    def __init__(self, wl, H, slot, max_batches, device):
+    def __init__(self, wl, H, slot, max_batches, device, keep_block=None):
         cfg = wl.cfg
+        # the outermost hop's block of every batch, kept for the consumer of the gathered rows
+        self.blk_indptr = self.blk_nbr = self.blk_nbr_local = None
+        if keep_block is not None:
+            n_ip, n_e = keep_block
+            self.blk_indptr = torch.empty(max_batches, n_ip, dtype=torch.int32, device=device)
+            self.blk_nbr = torch.empty(max_batches, max(n_e, 1), dtype=torch.int32, device=device)
+            self.blk_nbr_local = torch.empty(max_batches, max(n_e, 1), dtype=torch.int32, device=device)
         # one slot of input nodes and one row of tier offsets per precomputed batch
         self.arena = torch.empty(max_batches, max(slot, 1), dtype=torch.int32, device=device)
         self.tier_offs = torch.zeros(max_batches, H + 2, dtype=torch.int32, device=device)
@@ -41,7 +48,8 @@ class _EpochState:
 
 class EpochPipeline:
     def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True,
-                 epoch_histogram=True, sampler_streams=3, double_buffer=False, early_pull=False):
+                 epoch_histogram=True, sampler_streams=3, double_buffer=False, early_pull=False,
+                 queue_depth=1, consumer=None):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -60,9 +68,25 @@ class EpochPipeline:
         self.bufs = self.lane_bufs[0]
         self.slot = self.bufs.frontier_ub[self.H]
         self.double_buffer = double_buffer
-        self.states = [_EpochState(wl, self.H, self.slot, self.max_batches, device) for _ in range(2 if double_buffer else 1)]
+        # consumer = "mean": the gathered rows of every batch are reduced by the mean aggregator over the batch's
+        # outermost block (the first GraphSAGE layer's AGG) on a stream of its own; the gathers run up to
+        # queue_depth batches ahead of it through a ring of output buffers (the paper's prefetch queue, Q = 3)
+        if consumer not in (None, "mean"):
+            raise ValueError("consumer must be None or 'mean'")
+        self.consumer = consumer
+        self.queue_depth = max(1, int(queue_depth))
+        keep = (self.bufs.frontier_ub[self.H - 1] + 1, self.bufs.edges_ub[self.H - 1]) if consumer else None
+        self.states = [_EpochState(wl, self.H, self.slot, self.max_batches, device, keep) for _ in range(2 if double_buffer else 1)]
         self.cur = 0
-        self.out = torch.empty(max(self.slot, 1), wl.stride, dtype=torch.float32, device=device)
+        self.out_ring = [torch.empty(max(self.slot, 1), wl.stride, dtype=torch.float32, device=device)
+                         for _ in range(self.queue_depth)]
+        self.out = self.out_ring[0]                # the buffer the most recent gather wrote
+        self.consumer_stream = torch.cuda.Stream(device=device) if consumer else None
+        self.ready = [torch.cuda.Event() for _ in range(self.queue_depth)]
+        self.consumed = [torch.cuda.Event() for _ in range(self.queue_depth)]
+        self.agg = (torch.empty(max(self.bufs.frontier_ub[self.H - 1], 1), wl.stride, dtype=torch.float32, device=device)
+                    if consumer else None)
+        self._gathered = 0
         self.order = torch.empty_like(wl.train_ids)
         self.side = torch.cuda.Stream(device=device) if two_streams else None
         # prefetch = pull cached rows batch by batch, in order of first use, on a stream of their own so the
@@ -149,6 +173,8 @@ class EpochPipeline:
                 seeds = self.order[b * cfg.batch_size:min((b + 1) * cfg.batch_size, n_train)]
                 c, bufs, s = lanes[i % len(lanes)]
                 bufs.set_outputs(st.arena[i], st.tier_offs[i], st.edge_counts[i])
+                if st.blk_indptr is not None:
+                    bufs.set_hop(self.H - 1, st.blk_indptr[i], st.blk_nbr[i], st.blk_nbr_local[i])
                 c.sample_blocks(self.csr, seeds, seeds.numel(), cfg.fanouts, self.wl.seed, epoch, bufs, stream=s or head)
                 if self.early_pull:
                     st.sampled[i].record(s or head)
@@ -193,8 +219,21 @@ class EpochPipeline:
         """Features of batch b's input nodes into self.out[:n]."""
         st = self.state
         n = st.sizes[b]
+        main = torch.cuda.current_stream()
+        q = self._gathered % self.queue_depth
+        self._gathered += 1
+        self.out = self.out_ring[q]
+        if self.consumer:
+            main.wait_event(self.consumed[q])           # the ring slot is free once its previous batch was consumed
         self.ctx.gather_features(st.arena[b], n, st.cache, self.wl.local_store, self.wl.remote_store,
                                  self.cfg.feat_dim, self.out, st.stats[b], miss_stream=self.side)
+        if self.consumer:
+            self.ready[q].record(main)
+            cs = self.consumer_stream
+            cs.wait_event(self.ready[q])
+            self.ctx.mean_aggregate(st.blk_indptr[b], st.blk_nbr_local[b], self.bufs.frontier_ub[self.H - 1], self.out,
+                                    self.cfg.feat_dim, self.agg, n_dst_dev=st.tier_offs[b, self.H:], stream=cs)
+            self.consumed[q].record(cs)
         return n
 
     def prefetch_rows(self, b, stream=None, st=None):
@@ -242,6 +281,8 @@ class EpochPipeline:
                 on_batch(self, b)
         if self.prefetch:
             st.pulls_queued = True
+        if self.consumer:
+            main.wait_stream(self.consumer_stream)      # the epoch is served when its last batch has been consumed
         st.served.record(main)
 
     def run_epoch(self, epoch, n_batches, on_batch=None):

@@ -596,6 +596,41 @@ def test_mean_aggregate_over_sampled_block(B, ctx):
     assert np.allclose(got[i], X[nb].astype(np.float64).mean(0), rtol=1e-5, atol=1e-6)
 
 
+def test_pipeline_with_mean_consumer_and_output_ring(B):
+    """Gathers run up to three batches ahead of the consumer (mean aggregation of the outermost block on its own
+    stream) through a ring of output buffers; every batch's aggregate is checked against the oracle."""
+    from paper_2505_10806_amd.pipeline import EpochPipeline
+    wl = synth.build_workload("tiny", seed=9, device=DEV)
+    cfg = wl.cfg
+    H = len(cfg.fanouts)
+    rp, ci = host_graph(wl)
+    X = wl.features.cpu().numpy()
+    train_np = wl.train_ids.cpu().numpy()
+    pipe = EpochPipeline(wl, device=DEV, consumer="mean", queue_depth=3, double_buffer=True)
+    nb = pipe.batches_per_epoch
+    blocks = {}
+
+    def epoch_start(p, k):
+        p._epoch = k
+        for b, seeds in enumerate(oracle.epoch_batches(train_np, cfg.batch_size, wl.seed, k, cfg.max_batches)):
+            blocks[(k, b)] = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, k)
+
+    seen = []
+
+    def batch_done(p, b):
+        torch.cuda.synchronize()
+        blk = blocks[(p._epoch, b)]
+        want, tol = _agg_tolerance(blk.indptr[H - 1], blk.nbr_local[H - 1], X[blk.input_nodes])
+        got = p.agg[:want.shape[0], :cfg.feat_dim].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - want) <= tol), f"epoch {p._epoch} batch {b}"
+        assert np.array_equal(p.out[:blk.input_nodes.size, :cfg.feat_dim].cpu().numpy(), X[blk.input_nodes])
+        seen.append(p.out.data_ptr())
+
+    pipe.run_epochs(0, 2, nb, on_batch=batch_done, on_epoch_start=epoch_start)
+    torch.cuda.synchronize()
+    assert len(seen) == 2 * nb and len(set(seen)) == 3                      # the ring's three buffers were cycled
+
+
 # ------------------------------------------------------------------------------ argument errors
 def test_argument_errors_are_reported_not_launched(B, ctx):
     rp = torch.tensor([0, 1, 2], dtype=torch.int32, device=DEV)
