@@ -197,6 +197,19 @@ RG_API rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32
                          const float* remote_store, int64_t remote_stride, int32_t dim,
                          const rg_cache* cache, void* stream);
 
+/* ---- remote fetches against cache size (the relation of Section V, "impact of cache size on
+ * remote-fetch volume") without building any cache: for each capacity K_j,
+ *   hits[j] = sum of the counts of the K_j best candidates in TopHot order
+ * = the number of row requests a cache of that capacity serves over the period the counts cover
+ * (ties at the threshold all have the threshold's count, so the sum does not depend on the
+ * tie-break); *remote_total = sum of the counts of all candidates = all requests for remote
+ * rows.  Remote fetches = remote_total - hits[j]; hit % = hits[j] / remote_total.
+ * capacities: host int64[num_capacities], each >= 0; hits: device uint64[num_capacities];
+ * remote_total: device uint64[1] or NULL. */
+RG_API rg_status rg_cache_hit_curve(rg_ctx* ctx, const uint32_t* counts, const int32_t* home, int64_t num_nodes,
+                                    const int64_t* capacities, int32_t num_capacities, uint64_t* hits,
+                                    uint64_t* remote_total, void* stream);
+
 /* ---- prefetcher (Section III: features of upcoming batches are prepared ahead of their use) ----
  * Pulls, over the host link, the rows of those cached nodes among input_nodes[0..n) whose slot is
  * not yet resident, and marks them resident.  Called batch by batch ahead of rg_gather_features

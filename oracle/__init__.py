@@ -74,6 +74,8 @@ def lib():
     L.orc_fill_cache.restype = None
     L.orc_gather_features.argtypes = [P, c_i64, P, c_i64, P, P, c_i64, P]
     L.orc_gather_features.restype = None
+    L.orc_cache_hit_curve.argtypes = [P, P, c_i64, P, c_i64, P]
+    L.orc_cache_hit_curve.restype = c_u64
     L.orc_mean_aggregate.argtypes = [P, P, c_i64, P, c_i64, c_i64, P]
     L.orc_mean_aggregate.restype = None
     _lib = L
@@ -216,3 +218,13 @@ def mean_aggregate(indptr, nbr_local, feat):
     out = np.zeros((max(n_dst, 1), F.shape[1]), dtype=np.float64)
     lib().orc_mean_aggregate(_p(ip), _p(nl), n_dst, _p(F), F.shape[1], F.shape[1], _p(out))
     return out[:n_dst]
+
+
+def cache_hit_curve(counts, home, capacities):
+    """(hits uint64 [len(capacities)], total requests for remote rows)."""
+    c = _arr(counts, np.uint32)
+    hm = _arr(home, np.int32)
+    caps = _arr(capacities, np.int64)
+    hits = np.zeros(max(caps.size, 1), dtype=np.uint64)
+    total = lib().orc_cache_hit_curve(_p(c), _p(hm), c.size, _p(caps), caps.size, _p(hits))
+    return hits[:caps.size], int(total)

@@ -293,3 +293,26 @@ void orc_mean_aggregate(const int64_t* indptr, const int32_t* nbr_local, int64_t
         }
     }
 }
+
+/* ---- requests served against cache capacity: prefix sums of the counts in TopHot order */
+uint64_t orc_cache_hit_curve(const uint32_t* counts, const int32_t* home, int64_t num_nodes,
+                             const int64_t* capacities, int64_t num_capacities, uint64_t* hits) {
+    orc_cand* cand = (orc_cand*)malloc((size_t)(num_nodes > 0 ? num_nodes : 1) * sizeof(orc_cand));
+    int64_t n_cand = 0;
+    for (int64_t v = 0; v < num_nodes; ++v)
+        if (((uint32_t)home[v] >> ORC_TAG_SHIFT) == ORC_TAG_REMOTE && counts[v] >= 1u) {
+            cand[n_cand].count = counts[v];
+            cand[n_cand].id = (int32_t)v;
+            ++n_cand;
+        }
+    qsort(cand, (size_t)n_cand, sizeof(orc_cand), orc_cand_cmp);
+    uint64_t total = 0;
+    for (int64_t s = 0; s < n_cand; ++s) total += cand[s].count;
+    for (int64_t j = 0; j < num_capacities; ++j) {
+        uint64_t sum = 0;
+        for (int64_t s = 0; s < n_cand && s < capacities[j]; ++s) sum += cand[s].count;
+        hits[j] = sum;
+    }
+    free(cand);
+    return total;
+}

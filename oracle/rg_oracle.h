@@ -80,6 +80,12 @@ void orc_fill_cache(const float* X, int64_t dim, const int32_t* cache_ids, int64
 void orc_gather_features(const float* X, int64_t dim, const int32_t* input_nodes, int64_t n,
                          const int32_t* loc, float* out, int64_t out_stride, int64_t stats[3]);
 
+/* Requests served by a cache of each capacity (Section V, remote fetches against cache size):
+ * hits[j] = sum of the counts of the first capacities[j] candidates in TopHot order; returns the sum over
+ * all candidates. */
+uint64_t orc_cache_hit_curve(const uint32_t* counts, const int32_t* home, int64_t num_nodes,
+                             const int64_t* capacities, int64_t num_capacities, uint64_t* hits);
+
 /* Eq. 1 with AGG = mean (GraphSAGE, Section II-A) over one sampled block, in fp64:
  * agg[i] = (1/m_i) sum_{e in [indptr[i], indptr[i+1])} feat[nbr_local[e]], zero row when m_i = 0. */
 void orc_mean_aggregate(const int64_t* indptr, const int32_t* nbr_local, int64_t n_dst,

@@ -74,6 +74,7 @@ def _load():
     L.rg_access_histogram.argtypes = [c_p, c_p, c_i64, c_p, c_p, c_i64, c_p]
     L.rg_access_histogram_epoch.argtypes = [c_p, c_p, c_i64, c_p, c_i32, c_i32, c_i32, c_p, c_i64, c_p]
     L.rg_build_cache.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i64, c_i32, ctypes.POINTER(rg_cache), c_p]
+    L.rg_cache_hit_curve.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i32, c_p, c_p, c_p]
     L.rg_prefetch_cache_rows.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_p, c_i64, c_i32, c_p]
     L.rg_stage_rows.argtypes = [c_p, c_p, c_i64, c_p, c_p, ctypes.POINTER(rg_stage), c_i32, c_p, c_i64, c_i32, c_p]
     L.rg_commit_staged_rows.argtypes = [c_p, c_p, c_i64, c_p, c_p, ctypes.POINTER(rg_stage), c_i32,
@@ -85,8 +86,8 @@ def _load():
     L.rg_profile_reset.argtypes = [c_p]
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks",
-                 "rg_access_histogram", "rg_access_histogram_epoch", "rg_build_cache", "rg_prefetch_cache_rows",
-                 "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
+                 "rg_access_histogram", "rg_access_histogram_epoch", "rg_build_cache", "rg_cache_hit_curve",
+                 "rg_prefetch_cache_rows", "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -95,7 +96,7 @@ _lib = _load()
 
 EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "rg_reserve", "rg_epoch_schedule",
                     "rg_blocks_bounds", "rg_sample_blocks", "rg_access_histogram", "rg_access_histogram_epoch",
-                    "rg_build_cache", "rg_prefetch_cache_rows", "rg_stage_rows", "rg_commit_staged_rows",
+                    "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_stage_rows", "rg_commit_staged_rows",
                     "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
 
 
@@ -197,6 +198,17 @@ class Context:
                                         _ptr(home, torch.int32, "cuda", "home"), home.numel(),
                                         _ptr(remote_store, torch.float32, "mapped", "remote_store"), rs, int(dim),
                                         ctypes.byref(cache.c_struct), _stream_handle(stream)))
+
+    # -- rg_cache_hit_curve
+    def cache_hit_curve(self, counts, home, capacities, stream=None):
+        """Returns (hits int64 cuda tensor [len(capacities)], remote_total int64 cuda tensor [1])."""
+        caps = (c_i64 * len(capacities))(*[int(c) for c in capacities])
+        hits = torch.zeros(max(len(capacities), 1), dtype=torch.int64, device=counts.device)
+        total = torch.zeros(1, dtype=torch.int64, device=counts.device)
+        self._check(_lib.rg_cache_hit_curve(self._h, _ptr(counts, torch.int32, "cuda", "counts"),
+                                            _ptr(home, torch.int32, "cuda", "home"), home.numel(), caps, len(capacities),
+                                            hits.data_ptr(), total.data_ptr(), _stream_handle(stream)))
+        return hits[:len(capacities)], total
 
     # -- rg_prefetch_cache_rows
     def prefetch_cache_rows(self, input_nodes, n, cache, home, remote_store, dim, n_dev=None, stream=None):

@@ -136,7 +136,7 @@ __global__ void __launch_bounds__(256) k_topk_pick(TopkCtl* __restrict__ ctl, in
             const uint64_t k = (uint64_t)capacity < (uint64_t)run ? (uint64_t)capacity : (uint64_t)run;
             ctl->k_eff = (uint32_t)k;
             ctl->need = (uint32_t)k;
-            *num_cached = (int64_t)k;
+            if (num_cached) *num_cached = (int64_t)k;
             need0 = (uint32_t)k;
         }
         need_s = need0;
@@ -254,6 +254,41 @@ __global__ void __launch_bounds__(256) k_topk_emit(const uint32_t* __restrict__ 
             loc[v] = (int32_t)hw[q];
         }
     }
+}
+
+// hits += sum of the counts above the threshold plus (ties taken) x threshold: the accesses a cache holding the
+// selected set would serve.  total += sum of the counts of all candidates (written when total != NULL).
+__global__ void __launch_bounds__(256) k_hit_sum(const uint32_t* __restrict__ counts, const int32_t* __restrict__ home, int64_t n,
+                                                 const TopkCtl* __restrict__ ctl, unsigned long long* __restrict__ hits,
+                                                 unsigned long long* __restrict__ total) {
+    const uint32_t T = ctl->prefix;
+    unsigned long long above = 0ull, all = 0ull;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += (int64_t)gridDim.x * blockDim.x) {
+        const uint32_t c = counts[v];
+        if (!rg_is_candidate((uint32_t)home[v], c)) continue;
+        all += c;
+        if (c > T) above += c;
+    }
+#pragma unroll
+    for (int off = RG_WAVE / 2; off > 0; off >>= 1) {
+        above += __shfl_xor(above, off, RG_WAVE);
+        all += __shfl_xor(all, off, RG_WAVE);
+    }
+    __shared__ unsigned long long pa[4], pt[4];
+    if (rg_lane() == 0) { pa[threadIdx.x >> 6] = above; pt[threadIdx.x >> 6] = all; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long a = pa[0] + pa[1] + pa[2] + pa[3];
+        if (blockIdx.x == 0) a += (unsigned long long)ctl->need * (unsigned long long)T;   // need == 0 when nothing is selected
+        if (a) atomicAdd(hits, a);
+        const unsigned long long t = pt[0] + pt[1] + pt[2] + pt[3];
+        if (total && t) atomicAdd(total, t);
+    }
+}
+
+__global__ void k_zero_u64(unsigned long long* __restrict__ p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0ull;
 }
 
 // ---------------------------------------------------------------------------- VectorPull
@@ -634,6 +669,51 @@ rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32_t* hom
     if (cache->filled && filled_words > 0) {
         k_set_filled<<<(int)rg_div_up(filled_words, 256), 256, 0, s>>>(cache->filled, filled_words, cache->num_cached, remote_store ? 1 : 0);
         RG_LAUNCH_CHECK(ctx, "k_set_filled");
+    }
+    return RG_OK;
+}
+
+rg_status rg_cache_hit_curve(rg_ctx* ctx, const uint32_t* counts, const int32_t* home, int64_t num_nodes,
+                             const int64_t* capacities, int32_t num_capacities, uint64_t* hits, uint64_t* remote_total,
+                             void* stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, num_nodes >= 0 && num_nodes <= (int64_t)RG_ROW_MASK + 1, "rg_cache_hit_curve: num_nodes out of range");
+    RG_REQUIRE(ctx, num_capacities >= 0 && num_capacities <= 4096, "rg_cache_hit_curve: num_capacities not in [0, 4096]");
+    RG_REQUIRE(ctx, num_capacities == 0 || (capacities && hits), "rg_cache_hit_curve: null capacities / hits");
+    RG_REQUIRE(ctx, num_nodes == 0 || (counts && home), "rg_cache_hit_curve: null node array");
+    for (int j = 0; j < num_capacities; ++j)
+        RG_REQUIRE(ctx, capacities[j] >= 0 && capacities[j] <= (int64_t)RG_ROW_MASK + 1, "rg_cache_hit_curve: capacities[%d] out of range", j);
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    rg_status st;
+    if ((st = rg_ensure(ctx, ctx->topk_ctl, sizeof(TopkCtl))) != RG_OK) return st;
+    TopkCtl* ctl = (TopkCtl*)ctx->topk_ctl.p;
+    if (num_capacities > 0) {
+        k_zero_u64<<<(num_capacities + 255) / 256, 256, 0, s>>>((unsigned long long*)hits, num_capacities);
+        RG_LAUNCH_CHECK(ctx, "k_zero_u64");
+    }
+    if (remote_total) {
+        k_zero_u64<<<1, 64, 0, s>>>((unsigned long long*)remote_total, 1);
+        RG_LAUNCH_CHECK(ctx, "k_zero_u64");
+    }
+    const int grid = (int)rg_max64(1, rg_min64(rg_div_up(num_nodes, 256 * 8), (int64_t)ctx->num_cus * 8));
+    bool total_done = remote_total == nullptr;
+    for (int j = 0; j < num_capacities || !total_done; ++j) {
+        const int64_t cap = j < num_capacities ? capacities[j] : 0;
+        k_topk_init<<<1, 256, 0, s>>>(ctl);
+        RG_LAUNCH_CHECK(ctx, "k_topk_init");
+        for (int pass = 0; pass < 4; ++pass) {
+            k_topk_hist<<<grid, 256, 0, s>>>(counts, home, num_nodes, pass, ctl);
+            RG_LAUNCH_CHECK(ctx, "k_topk_hist");
+            k_topk_pick<<<1, 256, 0, s>>>(ctl, pass, cap, nullptr);
+            RG_LAUNCH_CHECK(ctx, "k_topk_pick");
+        }
+        // the first pass over the nodes also accumulates the total; when no capacity is given a throw-away slot
+        // of the control block's histogram area receives the (zero) hit sum
+        unsigned long long* hit_slot = j < num_capacities ? (unsigned long long*)hits + j : (unsigned long long*)&ctl->hist[3][0];
+        k_hit_sum<<<grid, 256, 0, s>>>(counts, home, num_nodes, ctl, hit_slot, total_done ? nullptr : (unsigned long long*)remote_total);
+        RG_LAUNCH_CHECK(ctx, "k_hit_sum");
+        total_done = true;
     }
     return RG_OK;
 }

@@ -425,6 +425,49 @@ def test_build_cache_all_local(B, ctx):
     assert np.array_equal(cache.loc.cpu().numpy(), home.numpy())
 
 
+def test_cache_hit_curve(B, ctx):
+    rng = np.random.default_rng(77)
+    n = 40_000
+    home = synth.stores.make_home(torch.from_numpy(rng.random(n) < 0.25))
+    counts = (rng.zipf(1.6, size=n) % 300).astype(np.uint32)
+    counts[rng.integers(0, n, 4)] = np.uint32(2 ** 31 + 11)
+    counts[rng.integers(0, n, 2000)] = 0
+    caps = [0, 1, 2, 17, 1000, 5000, 20_000, 29_999, 30_000, 10 ** 6]
+    hits, total = ctx.cache_hit_curve(torch.from_numpy(counts.view(np.int32)).to(DEV), home.to(DEV), caps)
+    torch.cuda.synchronize()
+    want, want_total = oracle.cache_hit_curve(counts, home.numpy(), caps)
+    assert hits.cpu().numpy().astype(np.uint64).tolist() == want.tolist()
+    assert int(total.item()) == want_total
+    # no capacities: only the total; no remote nodes: everything zero
+    hits, total = ctx.cache_hit_curve(torch.from_numpy(counts.view(np.int32)).to(DEV), home.to(DEV), [])
+    torch.cuda.synchronize()
+    assert hits.numel() == 0 and int(total.item()) == want_total
+    all_local = synth.stores.make_home(torch.ones(n, dtype=torch.bool))
+    hits, total = ctx.cache_hit_curve(torch.from_numpy(counts.view(np.int32)).to(DEV), all_local.to(DEV), [5, 50])
+    torch.cuda.synchronize()
+    assert hits.cpu().tolist() == [0, 0] and int(total.item()) == 0
+
+
+def test_batch_salted_seed_gives_per_batch_streams(B, ctx):
+    """The draw is keyed by (seed, epoch, node, hop).  A caller that wants the streams to differ between batches
+    as well (the paper's "epochs and batches") folds the batch index into the 64-bit seed; the oracle then
+    reproduces each batch with the same folded seed."""
+    rng = np.random.default_rng(5)
+    rp, ci = _handmade_graph(400, 0.6, 30, 0.02, rng)
+    csr = B.CsrGraph(torch.as_tensor(rp, device=DEV), _i32(ci))
+    seeds = np.arange(0, 30, dtype=np.int32)                 # the dense core: degrees above the fan-out
+    rows = []
+    for batch in range(3):
+        salted = (2025 + (batch << 32)) & (2 ** 64 - 1)
+        hip = _run_blocks(B, ctx, csr, seeds, (5, 3), salted, 1)
+        orc = oracle.sample_blocks(rp, ci, seeds, (5, 3), salted, 1)
+        assert_batch_equal(hip, orc, 2, f"batch {batch}")
+        rows.append(hip.nbr[0].tolist())
+    assert rows[0] != rows[1] and rows[1] != rows[2]
+    again = _run_blocks(B, ctx, csr, seeds, (5, 3), 2025, 1)
+    assert again.nbr[0].tolist() == rows[0]                   # batch 0's salt is zero
+
+
 # ------------------------------------------------------------------------------ gather shapes
 @pytest.mark.parametrize("dim,pad", [(64, True), (100, True), (128, True), (256, True), (602, True), (602, False),
                                      (7, False), (7, True), (257, False), (1, False), (1000, True)])

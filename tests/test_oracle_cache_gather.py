@@ -169,3 +169,31 @@ def test_mean_aggregate_is_normalised_sparse_product():
     # transposed operand / wrong normaliser would fail this: two destinations sharing sources in different order
     two = oracle.mean_aggregate(np.array([0, 2, 5]), np.array([1, 2, 2, 1, 3], dtype=np.int32), X)
     assert np.allclose(two[0], (X[1].astype(np.float64) + X[2]) / 2) and np.allclose(two[1], (X[2].astype(np.float64) + X[1] + X[3]) / 3)
+
+
+def test_hit_curve_equals_hits_of_built_caches():
+    """hits(K) must equal the cache hits actually counted when a cache of capacity K is built and every batch of
+    the period is gathered; it is non-decreasing, concave, and saturates at the total of remote requests."""
+    wl = synth.build_workload("tiny", seed=13)
+    cfg = wl.cfg
+    X = wl.features.numpy()
+    rp, ci = wl.row_ptr.numpy().astype(np.int64), wl.col_idx.numpy()
+    home = wl.home.numpy()
+    counts = np.zeros(cfg.num_nodes, dtype=np.uint32)
+    inputs = []
+    for seeds in oracle.epoch_batches(wl.train_ids.numpy(), cfg.batch_size, wl.seed, 0, 4):
+        blk = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, 0)
+        oracle.access_histogram(blk.input_nodes, counts)
+        inputs.append(blk.input_nodes)
+    caps = [0, 1, 10, 100, 500, 1000, 2500, 5000, 10 ** 6]
+    hits, total = oracle.cache_hit_curve(counts, home, caps)
+    remote = _tag(home) == TAG_REMOTE
+    assert total == int(counts[remote].sum())
+    for k, h in zip(caps, hits):
+        _, loc = oracle.build_cache(counts, home, k)
+        served = sum(oracle.gather_features(X[:, :1].copy(), nodes, loc)[1][1] for nodes in inputs)
+        assert int(h) == served, k
+    assert hits[0] == 0 and int(hits[-1]) == total
+    dense_caps = np.arange(0, 3000)
+    h = oracle.cache_hit_curve(counts, home, dense_caps)[0].astype(np.int64)
+    assert np.all(np.diff(h) >= 0) and np.all(np.diff(h, 2) <= 0)            # sorted counts: concave prefix sums
