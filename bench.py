@@ -228,6 +228,16 @@ def main():
         "kernel_ms": {k: {"total_ms": v[0], "launches": v[1]} for k, v in prof.items()},
     }
 
+    # requests for remote rows a cache of a given size would serve, from the last epoch's histogram (no cache is built)
+    fracs = [0.01, 0.05, 0.10, 0.15, 0.20, 0.50, 1.00]
+    caps = [int(f * wl.n_remote) for f in fracs]
+    hits, total = ctx.cache_hit_curve(pipe.counts, wl.home, caps)
+    torch.cuda.synchronize()
+    total = int(total.item())
+    result["cache_hit_curve"] = {"period": f"{pipe.n_batches} batches (last timed epoch)", "remote_requests": total,
+                                 "points": [{"capacity_frac_of_remote": f, "capacity_rows": c,
+                                             "hit_pct": 100.0 * int(h) / max(total, 1), "remote_fetches": total - int(h)}
+                                            for f, c, h in zip(fracs, caps, hits.cpu().tolist())]}
     a_ms, a_launches = prof["mean_aggregate"]
     if a_launches:
         # per launch: one feature row read per sampled edge of the outermost hop, one row written per destination

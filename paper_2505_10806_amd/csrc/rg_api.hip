@@ -107,7 +107,7 @@ rg_status rg_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int64
     if ((st = rg_ensure(ctx, ctx->chunk_sum, chunks * 4)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->topk_blk, ((size_t)rg_div_up(num_nodes, 1024) + 2) * 8)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->gather_src, (size_t)max_rows * 4)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->miss_list, (size_t)max_rows * 4)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->miss_list, (size_t)max_rows * 8)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->gather_ctl, 64)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->pf_list, (size_t)max_rows * 8)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->pf_ctl, 64)) != RG_OK) return st;

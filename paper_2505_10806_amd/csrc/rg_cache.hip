@@ -550,15 +550,6 @@ rg_status launch_list_copy(rg_ctx* ctx, const int32_t* list, const uint32_t* pct
     return RG_OK;
 }
 
-// The pull waits on the host link, not on the GPU: a few hundred wavefronts keep the link busy, and a small grid
-// leaves the wave slots of every CU to the gathers that run beside it.
-void hostlink_launch_shape(int64_t* blocks, int* threads) {
-    const char* pb = getenv("RG_PULL_BLOCKS");
-    *blocks = (pb && atoi(pb) > 0) ? atoi(pb) : 48;
-    const char* pt = getenv("RG_PULL_THREADS");
-    *threads = (pt && (atoi(pt) == 64 || atoi(pt) == 256 || atoi(pt) == 1024)) ? atoi(pt) : 256;
-}
-
 }  // namespace
 
 extern "C" {
@@ -740,7 +731,7 @@ rg_status rg_prefetch_cache_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_
     RG_LAUNCH_CHECK(ctx, "k_prefetch_select");
     int64_t blocks;
     int threads;
-    hostlink_launch_shape(&blocks, &threads);
+    rg_hostlink_launch_shape(&blocks, &threads);
     return launch_list_copy(ctx, list, pctl, remote_store, remote_stride, cache->cache_rows, cache->row_stride, dim, n, blocks,
                             threads, s);
 }
@@ -771,7 +762,7 @@ rg_status rg_stage_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, cons
     RG_LAUNCH_CHECK(ctx, "k_stage_select");
     int64_t blocks;
     int threads;
-    hostlink_launch_shape(&blocks, &threads);
+    rg_hostlink_launch_shape(&blocks, &threads);
     return launch_list_copy(ctx, list, pctl, remote_store, remote_stride, stage->rows, stage->row_stride, dim, n, blocks, threads, s);
 }
 

@@ -32,9 +32,9 @@ __global__ void __launch_bounds__(256) k_classify(const int32_t* __restrict__ no
     const int64_t n_act = rg_actual_n(n, n_dev);
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if ((int64_t)blockIdx.x * blockDim.x >= n_act) return;       // uniform per workgroup
-    uint32_t tag = 3u;
+    uint32_t tag = 3u, w = 0u;
     if (i < n_act) {
-        const uint32_t w = (uint32_t)loc[nodes[i]];
+        w = (uint32_t)loc[nodes[i]];
         src[i] = w;
         tag = w >> RG_TAG_SHIFT;
     }
@@ -53,7 +53,11 @@ __global__ void __launch_bounds__(256) k_classify(const int32_t* __restrict__ no
     if (total_miss == 0) return;                                   // uniform
     if (threadIdx.x == 0) miss_base = atomicAdd(&gctl[0], (uint32_t)total_miss);
     __syncthreads();
-    if (is_miss) miss_list[miss_base + excl] = (int32_t)i;
+    if (is_miss) {                       // (output row, remote row) pairs: the miss kernel needs no further lookup
+        const int64_t j = (int64_t)miss_base + excl;
+        miss_list[2 * j] = (int32_t)i;
+        miss_list[2 * j + 1] = (int32_t)(w & RG_ROW_MASK);
+    }
 }
 
 // Rows whose source is in HBM.  Each wave step moves 64/L rows of cpr chunks; U steps are unrolled.
@@ -106,7 +110,7 @@ __global__ void __launch_bounds__(256) k_gather_hbm(const uint32_t* __restrict__
 
 // Rows whose source is the remote store: walks the compacted miss list.
 template <int VEC, int U>
-__global__ void __launch_bounds__(256) k_gather_miss(const uint32_t* __restrict__ src, const int32_t* __restrict__ miss_list,
+__global__ void __launch_bounds__(1024) k_gather_miss(const int32_t* __restrict__ miss_list,
                                                      const uint32_t* __restrict__ gctl, const float* __restrict__ remote_store,
                                                      int64_t remote_stride, float* __restrict__ out, int64_t out_stride,
                                                      int cpr, int log2L) {
@@ -128,8 +132,8 @@ __global__ void __launch_bounds__(256) k_gather_miss(const uint32_t* __restrict_
             sp[u] = nullptr;
             dp[u] = nullptr;
             if (j < n_miss) {
-                const int64_t i = miss_list[j];
-                const int64_t row = (int64_t)(src[i] & RG_ROW_MASK);
+                const int64_t i = miss_list[2 * j];
+                const int64_t row = miss_list[2 * j + 1];
                 sp[u] = (const V*)(remote_store + row * remote_stride);
                 dp[u] = (V*)(out + i * out_stride);
             }
@@ -183,7 +187,7 @@ rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n,
     rg_status st;
     if ((st = rg_ensure(ctx, ctx->gather_ctl, 64)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->gather_src, (size_t)rg_max64(n, 1) * 4)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->miss_list, (size_t)rg_max64(n, 1) * 4)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->miss_list, (size_t)rg_max64(n, 1) * 8)) != RG_OK) return st;
     uint32_t* gctl = (uint32_t*)ctx->gather_ctl.p;
     uint32_t* src = (uint32_t*)ctx->gather_src.p;
     int32_t* miss_list = (int32_t*)ctx->miss_list.p;
@@ -231,16 +235,18 @@ rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n,
     rg_prof_end(ctx, tok, sh);
     RG_LAUNCH_CHECK(ctx, "k_gather_hbm");
 
-    const int miss_per_cu = env_int("RG_MISS_BLOCKS_PER_CU", 8);
-    const int miss_rows_per_block = 4 * (RG_WAVE >> shp.log2L) * U;
-    const int miss_grid = (int)rg_max64(1, rg_min64(rg_div_up(n, miss_rows_per_block), (int64_t)ctx->num_cus * miss_per_cu));
+    int64_t miss_blocks;
+    int miss_threads;
+    rg_hostlink_launch_shape(&miss_blocks, &miss_threads, true);
+    const int miss_rows_per_block = (miss_threads / RG_WAVE) * (RG_WAVE >> shp.log2L) * U;
+    const int miss_grid = (int)rg_max64(1, rg_min64(rg_div_up(n, miss_rows_per_block), miss_blocks));
     tok = rg_prof_begin(ctx, RG_K_GATHER_MISS, sm);
     if (vec == 4)
-        k_gather_miss<4, U><<<miss_grid, 256, 0, sm>>>(src, miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
+        k_gather_miss<4, U><<<miss_grid, miss_threads, 0, sm>>>(miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
     else if (vec == 2)
-        k_gather_miss<2, U><<<miss_grid, 256, 0, sm>>>(src, miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
+        k_gather_miss<2, U><<<miss_grid, miss_threads, 0, sm>>>(miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
     else
-        k_gather_miss<1, U><<<miss_grid, 256, 0, sm>>>(src, miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
+        k_gather_miss<1, U><<<miss_grid, miss_threads, 0, sm>>>(miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
     rg_prof_end(ctx, tok, sm);
     RG_LAUNCH_CHECK(ctx, "k_gather_miss");
     if (two_streams) {

@@ -44,7 +44,7 @@ struct rg_ctx {
     RgBuf commit_list, commit_ctl;   // the same for rg_commit_staged_rows
     // gather scratch
     RgBuf gather_src;   // uint32[n] resolved location word per output row
-    RgBuf miss_list;    // int32[n] output rows whose source is the remote store
+    RgBuf miss_list;    // int32[2n]: (output row, remote row) pairs of the rows whose source is the remote store
     RgBuf gather_ctl;   // uint32[4]: [0] = number of misses
     hipEvent_t ev_classified = nullptr, ev_miss_done = nullptr;
 

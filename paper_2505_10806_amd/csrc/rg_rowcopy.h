@@ -6,6 +6,8 @@
 // independent loads in flight before the first store.
 #pragma once
 
+#include <stdlib.h>
+
 #include "rg_internal.h"
 
 template <int VEC> struct RgVec;
@@ -40,4 +42,18 @@ static inline RgRowShape rg_row_shape(int32_t dim, int vec) {
     while ((1 << l) < s.cpr && l < 6) ++l;
     s.log2L = l;
     return s;
+}
+
+// Launch shape of kernels that read rows over the host link (cache pulls, miss rows).  They wait on the link, not on
+// the GPU: a few hundred wavefronts keep it busy (48 x 256 threads, 4 rows in flight per lane group), and a small
+// grid leaves the wave slots of every CU to the HBM kernels that run beside them.  Measured on the pull kernel:
+// 2048 workgroups -> the gathers beside it take 153 ms per epoch, 48 -> 79 ms, link rate unchanged.
+static inline void rg_hostlink_launch_shape(int64_t* blocks, int* threads, bool miss_rows = false) {
+    const char* pb = getenv(miss_rows ? "RG_MISS_BLOCKS" : "RG_PULL_BLOCKS");
+    // Miss rows go through one more dependent lookup per step than the pulls and need more wavefronts to fill the
+    // link (swept on the 602-dim workload: 48 workgroups 46 GB/s, 192 -> 51, 384 -> 53, where the HBM kernel beside
+    // them is starved for as long as the miss kernel runs); 192 keeps both moving.
+    *blocks = (pb && atoi(pb) > 0) ? atoi(pb) : (miss_rows ? 192 : 48);
+    const char* pt = getenv("RG_PULL_THREADS");
+    *threads = (pt && (atoi(pt) == 64 || atoi(pt) == 256 || atoi(pt) == 1024)) ? atoi(pt) : 256;
 }
