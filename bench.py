@@ -106,6 +106,8 @@ def main():
     ap.add_argument("--consumer", choices=["none", "mean"], default="none",
                     help="reduce every batch's gathered rows with the mean aggregator over its outermost block, on its own stream")
     ap.add_argument("--queue-depth", type=int, default=3, help="output buffers the gathers may run ahead of the consumer")
+    ap.add_argument("--no-plan", action="store_true",
+                    help="prefetch with a claim pass over every batch instead of the per-epoch prefetch plan")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -151,7 +153,7 @@ def main():
     with torch.cuda.stream(main_stream):
         pipe = EpochPipeline(wl, device=dev, max_batches=min(max(steps, warmup, 1), bpe), two_streams=not args.one_stream,
                              prefetch=not args.bulk_fill, sampler_streams=args.sampler_streams,
-                             double_buffer=(steps > bpe and not args.no_double_buffer), early_pull=args.early_pull,
+                             double_buffer=(steps > bpe and not args.no_double_buffer), early_pull=args.early_pull, planned_prefetch=not args.no_plan,
                              consumer=None if args.consumer == "none" else args.consumer,
                              queue_depth=args.queue_depth if args.consumer != "none" else 1)
         ctx = pipe.ctx
@@ -207,7 +209,7 @@ def main():
                    "cache_fill": "bulk" if args.bulk_fill else "prefetch by first use",
                    "sampler_streams": args.sampler_streams,
                    "double_buffered_cache": bool(steps > bpe and not args.no_double_buffer),
-                   "early_pull": pipe.early_pull, "consumer": args.consumer,
+                   "early_pull": pipe.early_pull, "planned_prefetch": pipe.planned, "consumer": args.consumer,
                    "queue_depth": pipe.queue_depth},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

@@ -165,11 +165,16 @@ RG_API rg_status rg_access_histogram(rg_ctx* ctx, const int32_t* nodes, int64_t 
  * owns an id range, finds its entries in every ascending tier by binary search and adds the range to
  * counts once.  Precondition: tiers 1..num_hops of every batch are ascending by id (as produced by
  * rg_sample_blocks); tier 0 (at most max_seeds seeds per batch) may be in any order.
+ * With first_batch != NULL the same pass also records when each node is first needed:
+ * first_batch[v] = min(first_batch[v], smallest b whose list contains v); the caller sets the array
+ * to 0xFFFFFFFF beforehand (input of rg_plan_prefetch).
  * nodes: device int32; tier_off: device int32[num_batches * (num_hops + 2)]; counts: device
- * uint32[num_nodes], accumulated; 0 <= num_batches <= 65535. */
+ * uint32[num_nodes], accumulated; first_batch: device uint32[num_nodes] or NULL;
+ * 0 <= num_batches <= 65535. */
 RG_API rg_status rg_access_histogram_epoch(rg_ctx* ctx, const int32_t* nodes, int64_t batch_stride,
                                            const int32_t* tier_off, int32_t num_batches, int32_t num_hops,
-                                           int32_t max_seeds, uint32_t* counts, int64_t num_nodes, void* stream);
+                                           int32_t max_seeds, uint32_t* counts, uint32_t* first_batch,
+                                           int64_t num_nodes, void* stream);
 
 /* ---- Alg. 1 lines 3-4: TopHot + VectorPull -----------------------------------------------
  * Candidates = nodes whose home word is remote and whose count >= 1, ranked by
@@ -223,6 +228,31 @@ RG_API rg_status rg_prefetch_cache_rows(rg_ctx* ctx, const int32_t* input_nodes,
                                         const rg_cache* cache, const int32_t* home,
                                         const float* remote_store, int64_t remote_stride, int32_t dim,
                                         void* stream);
+
+/* ---- planned prefetch: the same pulls as rg_prefetch_cache_rows without a pass over each batch ----
+ * The precomputed schedule says in which batch every selected node is first needed
+ * (rg_access_histogram_epoch's first_batch).  rg_plan_prefetch groups the selected slots by that
+ * batch once per epoch: list[offsets[b] .. offsets[b+1]) holds the (slot, remote row) pairs first
+ * needed by batch b, b = 0..num_batches-1; segment num_batches holds the slots no planned batch
+ * uses.  rg_prefetch_planned(b) pulls segment b over the host link and marks its slots resident.
+ * Pulled in batch order ahead of the gathers (one event per batch), every selected row arrives
+ * exactly once and before its first use, and the prefetch stream carries nothing but pulls.
+ * With at most 1023 batches every segment lists its slots in ascending order (ascending remote rows,
+ * which the host link serves faster than scattered ones); beyond that the order inside a segment is
+ * unspecified. */
+typedef struct {
+    int32_t* list;            /* device int32[2 * list_capacity] */
+    int64_t list_capacity;    /* pairs; >= min(cache capacity_rows, num_nodes) */
+    int32_t* offsets;         /* device int32[num_batches + 2] */
+    int32_t num_batches;      /* 0..65535 */
+} rg_prefetch_plan;
+
+/* after rg_build_cache (select only) on the same stream; first_batch: device uint32[num_nodes]. */
+RG_API rg_status rg_plan_prefetch(rg_ctx* ctx, const rg_cache* cache, const int32_t* home, const uint32_t* first_batch,
+                                  int64_t num_nodes, const rg_prefetch_plan* plan, void* stream);
+/* 0 <= batch <= plan->num_batches. */
+RG_API rg_status rg_prefetch_planned(rg_ctx* ctx, const rg_prefetch_plan* plan, int32_t batch, const rg_cache* cache,
+                                     const float* remote_store, int64_t remote_stride, int32_t dim, void* stream);
 
 /* ---- early pull: VectorPull started during the precompute stage ------------------------------
  * When the cache can hold every remote node (capacity_rows >= number of remote nodes), every remote

@@ -49,6 +49,10 @@ class rg_cache(ctypes.Structure):
                 ("row_stride", c_i64), ("loc", c_p), ("num_cached", c_p), ("filled", c_p)]
 
 
+class rg_prefetch_plan(ctypes.Structure):
+    _fields_ = [("list", c_p), ("list_capacity", c_i64), ("offsets", c_p), ("num_batches", c_i32)]
+
+
 class rg_stage(ctypes.Structure):
     _fields_ = [("rows", c_p), ("capacity_rows", c_i64), ("row_stride", c_i64), ("slot_of", c_p),
                 ("owner", c_p), ("touched", c_p), ("cursor", c_p)]
@@ -72,7 +76,9 @@ def _load():
     L.rg_sample_blocks.argtypes = [c_p, ctypes.POINTER(rg_csr), c_p, c_i32, c_p, c_i32, c_u64, c_u32,
                                    ctypes.POINTER(rg_blocks), c_p]
     L.rg_access_histogram.argtypes = [c_p, c_p, c_i64, c_p, c_p, c_i64, c_p]
-    L.rg_access_histogram_epoch.argtypes = [c_p, c_p, c_i64, c_p, c_i32, c_i32, c_i32, c_p, c_i64, c_p]
+    L.rg_access_histogram_epoch.argtypes = [c_p, c_p, c_i64, c_p, c_i32, c_i32, c_i32, c_p, c_p, c_i64, c_p]
+    L.rg_plan_prefetch.argtypes = [c_p, ctypes.POINTER(rg_cache), c_p, c_p, c_i64, ctypes.POINTER(rg_prefetch_plan), c_p]
+    L.rg_prefetch_planned.argtypes = [c_p, ctypes.POINTER(rg_prefetch_plan), c_i32, ctypes.POINTER(rg_cache), c_p, c_i64, c_i32, c_p]
     L.rg_build_cache.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i64, c_i32, ctypes.POINTER(rg_cache), c_p]
     L.rg_cache_hit_curve.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i32, c_p, c_p, c_p]
     L.rg_prefetch_cache_rows.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_p, c_i64, c_i32, c_p]
@@ -87,7 +93,7 @@ def _load():
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks",
                  "rg_access_histogram", "rg_access_histogram_epoch", "rg_build_cache", "rg_cache_hit_curve",
-                 "rg_prefetch_cache_rows", "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
+                 "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_prefetch_planned", "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -96,7 +102,8 @@ _lib = _load()
 
 EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "rg_reserve", "rg_epoch_schedule",
                     "rg_blocks_bounds", "rg_sample_blocks", "rg_access_histogram", "rg_access_histogram_epoch",
-                    "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_stage_rows", "rg_commit_staged_rows",
+                    "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_plan_prefetch",
+                    "rg_prefetch_planned", "rg_stage_rows", "rg_commit_staged_rows",
                     "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
 
 
@@ -179,8 +186,10 @@ class Context:
                                              _stream_handle(stream)))
 
     # -- rg_access_histogram_epoch
-    def access_histogram_epoch(self, arena, tier_offs, num_batches, num_hops, max_seeds, counts, stream=None):
-        """arena: int32 [>= num_batches, batch_stride]; tier_offs: int32 [>= num_batches, num_hops + 2]."""
+    def access_histogram_epoch(self, arena, tier_offs, num_batches, num_hops, max_seeds, counts, first_batch=None,
+                               stream=None):
+        """arena: int32 [>= num_batches, batch_stride]; tier_offs: int32 [>= num_batches, num_hops + 2];
+        first_batch: optional int32 [num_nodes] preset to -1 (= 0xFFFFFFFF)."""
         if tier_offs.dim() != 2 or tier_offs.shape[1] != num_hops + 2 or arena.dim() != 2:
             raise ValueError("access_histogram_epoch: arena must be 2-D and tier_offs [batches, num_hops + 2]")
         if num_batches > arena.shape[0] or num_batches > tier_offs.shape[0]:
@@ -188,7 +197,19 @@ class Context:
         self._check(_lib.rg_access_histogram_epoch(
             self._h, _ptr(arena, torch.int32, "cuda", "arena"), arena.stride(0),
             _ptr(tier_offs, torch.int32, "cuda", "tier_offs"), int(num_batches), int(num_hops), int(max_seeds),
-            _ptr(counts, torch.int32, "cuda", "counts"), counts.numel(), _stream_handle(stream)))
+            _ptr(counts, torch.int32, "cuda", "counts"), _ptr(first_batch, torch.int32, "cuda", "first_batch"),
+            counts.numel(), _stream_handle(stream)))
+
+    # -- rg_plan_prefetch / rg_prefetch_planned
+    def plan_prefetch(self, cache, home, first_batch, plan, stream=None):
+        self._check(_lib.rg_plan_prefetch(self._h, ctypes.byref(cache.c_struct), _ptr(home, torch.int32, "cuda", "home"),
+                                          _ptr(first_batch, torch.int32, "cuda", "first_batch"), home.numel(),
+                                          ctypes.byref(plan.c_struct), _stream_handle(stream)))
+
+    def prefetch_planned(self, plan, batch, cache, remote_store, dim, stream=None):
+        self._check(_lib.rg_prefetch_planned(self._h, ctypes.byref(plan.c_struct), int(batch), ctypes.byref(cache.c_struct),
+                                             _ptr(remote_store, torch.float32, "mapped", "remote_store"),
+                                             remote_store.stride(0), int(dim), _stream_handle(stream)))
 
     # -- rg_build_cache
     def build_cache(self, counts, home, remote_store, dim, cache, stream=None):
@@ -394,3 +415,18 @@ class StagingArea:
         """Start a new period (queued on the current stream)."""
         self.touched.zero_()
         self.cursor.zero_()
+
+
+class PrefetchPlan:
+    """rg_prefetch_plan over caller-owned cuda tensors."""
+
+    def __init__(self, list_capacity, max_batches, device):
+        self.list = torch.empty(2 * max(int(list_capacity), 1), dtype=torch.int32, device=device)
+        self.offsets = torch.zeros(int(max_batches) + 2, dtype=torch.int32, device=device)
+        self.max_batches = int(max_batches)
+        self.c_struct = rg_prefetch_plan(self.list.data_ptr(), int(list_capacity), self.offsets.data_ptr(), int(max_batches))
+
+    def set_num_batches(self, n):
+        if not 0 <= n <= self.max_batches:
+            raise ValueError("PrefetchPlan: num_batches exceeds the offsets buffer")
+        self.c_struct.num_batches = int(n)

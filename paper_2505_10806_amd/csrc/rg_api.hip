@@ -79,7 +79,7 @@ void rg_destroy(rg_ctx* ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
     RgBuf* bufs[] = {&ctx->visited, &ctx->fresh, &ctx->pos, &ctx->chunk_sum, &ctx->sched_keys, &ctx->sched_ids,
-                     &ctx->topk_ctl, &ctx->topk_blk, &ctx->pf_list, &ctx->pf_ctl, &ctx->stage_list, &ctx->stage_ctl, &ctx->commit_list, &ctx->commit_ctl, &ctx->gather_src, &ctx->miss_list, &ctx->gather_ctl};
+                     &ctx->topk_ctl, &ctx->topk_blk, &ctx->pf_list, &ctx->pf_ctl, &ctx->stage_list, &ctx->stage_ctl, &ctx->commit_list, &ctx->commit_ctl, &ctx->plan_cursor, &ctx->gather_src, &ctx->miss_list, &ctx->gather_ctl};
     for (RgBuf* b : bufs)
         if (b->p) (void)hipFree(b->p);
     for (auto& s : ctx->spans) { (void)hipEventDestroy(s.start); (void)hipEventDestroy(s.stop); }

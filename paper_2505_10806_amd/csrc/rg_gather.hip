@@ -128,8 +128,10 @@ __global__ void __launch_bounds__(1024) k_gather_miss(const int32_t* __restrict_
         V* dp[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            // loads are unconditional (a lane group without a row reads output row 0, which is in HBM; the value is
+            // discarded) so that every wavefront keeps U row loads in flight on the link; only the stores are predicated
             const int64_t j = j0 + u * R + sub;
-            sp[u] = nullptr;
+            sp[u] = (const V*)out;
             dp[u] = nullptr;
             if (j < n_miss) {
                 const int64_t i = miss_list[2 * j];
@@ -141,8 +143,7 @@ __global__ void __launch_bounds__(1024) k_gather_miss(const int32_t* __restrict_
         for (int c = c0; c < cpr; c += L) {
             V val[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (sp[u]) val[u] = sp[u][c];
+            for (int u = 0; u < U; ++u) val[u] = sp[u][c];
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (dp[u]) __builtin_nontemporal_store(val[u], &dp[u][c]);

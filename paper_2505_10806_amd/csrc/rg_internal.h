@@ -41,6 +41,7 @@ struct rg_ctx {
     RgBuf pf_list;      // int32[2 * n]: (slot, remote row) pairs still to pull
     RgBuf pf_ctl;       // uint32[4]: [0] = number of pairs
     RgBuf stage_list, stage_ctl;     // the same for rg_stage_rows
+    RgBuf plan_cursor;               // rg_plan_prefetch: per-chunk per-batch counts (ordered plan) or scatter cursors
     RgBuf commit_list, commit_ctl;   // the same for rg_commit_staged_rows
     // gather scratch
     RgBuf gather_src;   // uint32[n] resolved location word per output row

@@ -39,6 +39,8 @@ class _EpochState:
         self.pf_events = [torch.cuda.Event() for _ in range(max_batches)]
         self.sampled = [torch.cuda.Event() for _ in range(max_batches)]
         self.stage = None                      # StagingArea when rows are pulled during the offline stage
+        self.first_batch = None                # per node: first batch of the epoch that needs it (planned prefetch)
+        self.plan = None
         self.built = torch.cuda.Event()        # offline stage of this state finished
         self.served = torch.cuda.Event()       # online stage of this state finished
         self.sizes = None
@@ -49,7 +51,7 @@ class _EpochState:
 class EpochPipeline:
     def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True,
                  epoch_histogram=True, sampler_streams=3, double_buffer=False, early_pull=False,
-                 queue_depth=1, consumer=None):
+                 queue_depth=1, consumer=None, planned_prefetch=True):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -104,6 +106,13 @@ class EpochPipeline:
         if self.early_pull:
             for st in self.states:
                 st.stage = B.StagingArea(cfg.num_nodes, wl.n_remote, wl.stride, device)
+        # planned prefetch: the epoch histogram also records the first batch that needs each node, the selected
+        # slots are grouped by that batch once, and the prefetch stream then carries nothing but pulls
+        self.planned = bool(prefetch and planned_prefetch and epoch_histogram and not self.early_pull)
+        if self.planned:
+            for st in self.states:
+                st.first_batch = torch.empty(cfg.num_nodes, dtype=torch.int32, device=device)
+                st.plan = B.PrefetchPlan(min(wl.capacity_rows, wl.n_remote), self.max_batches, device)
         # The sampler lanes reuse the streams that are idle during the offline stage (miss and prefetch streams);
         # only lanes beyond those get streams of their own.  The device exposes few hardware queues, and streams
         # that end up sharing one would serialise work that is meant to overlap.
@@ -187,9 +196,15 @@ class EpochPipeline:
             for _, _, s in lanes[1:]:
                 head.wait_stream(s)
             if self.epoch_histogram:
-                head_ctx.access_histogram_epoch(st.arena, st.tier_offs, len(ids), self.H, cfg.batch_size, st.counts, stream=head)
+                if self.planned:
+                    st.first_batch.fill_(-1)
+                head_ctx.access_histogram_epoch(st.arena, st.tier_offs, len(ids), self.H, cfg.batch_size, st.counts,
+                                                first_batch=st.first_batch, stream=head)
             head_ctx.build_cache(st.counts, self.wl.home, None if self.prefetch else self.wl.remote_store, cfg.feat_dim,
                                  st.cache, stream=head)
+            if self.planned:
+                st.plan.set_num_batches(len(ids))
+                head_ctx.plan_prefetch(st.cache, self.wl.home, st.first_batch, st.plan, stream=head)
             st.built.record(head)
         st.n_batches = len(ids)
         st.sizes = None
@@ -240,6 +255,9 @@ class EpochPipeline:
         """Pull the not-yet-resident cached rows batch b needs (asynchronous on `stream`).  The row count is
         read on the device, so the pulls of an epoch can be queued before the host knows its batch sizes."""
         st = st or self.state
+        if self.planned:
+            self.ctx.prefetch_planned(st.plan, b, st.cache, self.wl.remote_store, self.cfg.feat_dim, stream=stream)
+            return
         self.ctx.prefetch_cache_rows(st.arena[b], self.slot, st.cache, self.wl.home, self.wl.remote_store,
                                      self.cfg.feat_dim, n_dev=st.tier_offs[b, self.H + 1:], stream=stream)
 

@@ -196,7 +196,8 @@ def test_full_path_small(B, ctx):
     _full_path(B, ctx, "small", two_streams=True, device_counts=True)
 
 
-def test_prefetch_by_first_use_matches_bulk_fill(B, ctx):
+@pytest.mark.parametrize("planned", [False, True])
+def test_prefetch_by_first_use_matches_bulk_fill(B, ctx, planned):
     """Select-only TopHot followed by per-batch prefetch pulls each selected row exactly when a batch first
     needs it; gathers and the final cache contents equal those of the bulk pull."""
     wl = synth.build_workload("tiny", seed=11, device=DEV)
@@ -238,9 +239,30 @@ def test_prefetch_by_first_use_matches_bulk_fill(B, ctx):
     out = torch.empty(bufs.frontier_ub[H], wl.stride, device=DEV)
     stats = torch.zeros(3, dtype=torch.int64, device=DEV)
     side = torch.cuda.Stream()
+    if planned:
+        # per-epoch plan: first batch of every node from the epoch histogram, slots grouped by it
+        arena = torch.zeros(4, bufs.frontier_ub[H], dtype=torch.int32, device=DEV)
+        tier_offs = torch.zeros(4, H + 2, dtype=torch.int32, device=DEV)
+        for b in range(4):
+            blk = oracle.sample_blocks(rp, ci, orc_batches[b], cfg.fanouts, wl.seed, 0)
+            assert np.array_equal(inputs_dev[b].cpu().numpy(), blk.input_nodes)
+            arena[b, :inputs_dev[b].numel()] = inputs_dev[b]
+            tier_offs[b] = torch.as_tensor(blk.tier_off.astype(np.int32))
+        first = torch.full((cfg.num_nodes,), -1, dtype=torch.int32, device=DEV)
+        scratch_counts = torch.zeros_like(counts)
+        ctx.access_histogram_epoch(arena, tier_offs, 4, H, cfg.batch_size, scratch_counts, first_batch=first)
+        plan = B.PrefetchPlan(wl.capacity_rows, 4, DEV)
+        ctx.plan_prefetch(cache, wl.home, first, plan)
+        torch.cuda.synchronize()
+        assert np.array_equal(scratch_counts.cpu().numpy().view(np.uint32), counts_orc)
+        offs = plan.offsets.cpu().numpy()
+        assert offs[0] == 0 and offs[5] == k and np.all(np.diff(offs[:6]) >= 0) and offs[4] == k   # every slot is used by some batch
     for b in range(4):
         n = inputs_dev[b].numel()
-        ctx.prefetch_cache_rows(inputs_dev[b], n, cache, wl.home, wl.remote_store, cfg.feat_dim, stream=side)
+        if planned:
+            ctx.prefetch_planned(plan, b, cache, wl.remote_store, cfg.feat_dim, stream=side)
+        else:
+            ctx.prefetch_cache_rows(inputs_dev[b], n, cache, wl.home, wl.remote_store, cfg.feat_dim, stream=side)
         side.synchronize()
         for v in inputs_orc[b]:
             if int(v) in slot_of:
@@ -384,6 +406,40 @@ def test_stage_and_commit_match_bulk_fill(B, ctx, stage_cap, cache_cap):
     k = ids_orc.size
     assert int(cache.num_cached.item()) == k
     assert np.array_equal(cache.cache_rows[:k, :cfg.feat_dim].cpu().numpy(), X[ids_orc])
+
+
+@pytest.mark.parametrize("num_batches", [0, 1, 7, 1023, 1500])
+def test_prefetch_plan_groups_slots_by_first_batch(B, ctx, num_batches):
+    """rg_plan_prefetch on a synthetic first-use array: segment b holds exactly the slots whose node is first
+    needed by batch b (ascending for up to 1023 batches), segment num_batches the slots no batch uses."""
+    log(f"[prefetch plan] num_batches={num_batches}")
+    rng = np.random.default_rng(num_batches)
+    n, dim = 20_000, 8
+    is_local = torch.from_numpy(rng.random(n) < 0.3)
+    home = synth.stores.make_home(is_local)
+    home_np = home.numpy()
+    counts = rng.integers(0, 3, size=n).astype(np.uint32)
+    first = rng.integers(0, max(num_batches, 1) + 3, size=n).astype(np.uint32)      # some beyond the planned batches
+    first[rng.integers(0, n, 50)] = 0xFFFFFFFF
+    cache = B.FeatureCache(n, 6000, dim, DEV)
+    ctx.build_cache(torch.from_numpy(counts.view(np.int32)).to(DEV), home.to(DEV), None, dim, cache)
+    plan = B.PrefetchPlan(6000, num_batches, DEV)
+    ctx.plan_prefetch(cache, home.to(DEV), torch.from_numpy(first.view(np.int32)).to(DEV), plan)
+    torch.cuda.synchronize()
+    ids_orc, _ = oracle.build_cache(counts, home_np, 6000)
+    k = ids_orc.size
+    key = np.minimum(first[ids_orc].astype(np.int64), num_batches)
+    offs = plan.offsets.cpu().numpy()
+    pairs = plan.list.cpu().numpy().reshape(-1, 2)
+    assert offs[0] == 0 and offs[num_batches + 1] == k
+    for b in range(num_batches + 1):
+        seg = pairs[offs[b]:offs[b + 1]]
+        want_slots = np.flatnonzero(key == b)
+        if num_batches + 1 <= 1024:
+            assert np.array_equal(seg[:, 0], want_slots), b
+        else:
+            assert np.array_equal(np.sort(seg[:, 0]), want_slots), b
+        assert np.array_equal(seg[:, 1], (home_np[ids_orc[seg[:, 0]]].astype(np.int64) & 0x3FFFFFFF)), b
 
 
 # ------------------------------------------------------------------------------ TopHot edge cases
@@ -561,6 +617,21 @@ def test_epoch_histogram_matches_per_batch_definition(B, ctx, n_nodes, n_batches
                                max_seeds, counts)
     torch.cuda.synchronize()
     assert np.array_equal(counts.cpu().numpy().view(np.uint32), want)
+    # the same call with first-use tracking: counts once more, and the first batch whose list holds each id
+    first = torch.full((n_nodes,), -1, dtype=torch.int32, device=DEV)
+    first[5] = 0                                             # an earlier period already saw node 5 in batch 0
+    ctx.access_histogram_epoch(torch.from_numpy(arena).to(DEV), torch.from_numpy(tier_offs).to(DEV), n_batches, H,
+                               max_seeds, counts, first_batch=first)
+    torch.cuda.synchronize()
+    want2 = want.copy()
+    want_first = np.full(n_nodes, 0xFFFFFFFF, dtype=np.uint64)
+    want_first[5] = 0
+    for b in range(n_batches):
+        ids = arena[b, :tier_offs[b, H + 1]]
+        oracle.access_histogram(ids, want2)
+        want_first[ids] = np.minimum(want_first[ids], b)
+    assert np.array_equal(counts.cpu().numpy().view(np.uint32), want2)
+    assert np.array_equal(first.cpu().numpy().view(np.uint32).astype(np.uint64), want_first)
 
 
 # ------------------------------------------------------------------------------ mean aggregation (consumer)
