@@ -19,8 +19,9 @@
  *    stream).  Device-resident outputs are valid once that stream has been synchronised.
  *  - Every call validates its arguments on the host before launching anything and returns
  *    RG_ERR_INVALID_ARG / RG_ERR_CAPACITY without side effects when they are wrong;
- *    rg_last_error() then holds a message.  Node ids out of [0, num_nodes) inside device
- *    arrays are a precondition violation and are not checked.
+ *    rg_last_error() then holds a message.  A remote store that is neither device memory nor
+ *    pinned / registered host memory is refused (RG_ERR_INVALID_ARG).  Node ids out of
+ *    [0, num_nodes) inside device arrays are a precondition violation and are not checked.
  *  - One rg_ctx serves one host thread.  Calls of the same kind (two samplers, two gathers)
  *    share scratch and must be ordered on the stream(s) they use; calls of different kinds
  *    use disjoint scratch.

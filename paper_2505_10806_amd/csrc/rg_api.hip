@@ -42,6 +42,21 @@ rg_status rg_ensure(rg_ctx* ctx, RgBuf& buf, size_t bytes, bool zero_new) {
     return RG_OK;
 }
 
+rg_status rg_check_device_readable(rg_ctx* ctx, const void* p, const char* what) {
+    hipPointerAttribute_t attr;
+    const hipError_t e = hipPointerGetAttributes(&attr, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();          // an ordinary (pageable) host pointer is reported as an error
+        return rg_set_error(ctx, RG_ERR_INVALID_ARG,
+                            "%s = %p is not device-accessible memory (allocate it on the device or as pinned host memory)", what, p);
+    }
+    if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeHost && attr.type != hipMemoryTypeManaged &&
+        attr.type != hipMemoryTypeArray)
+        return rg_set_error(ctx, RG_ERR_INVALID_ARG,
+                            "%s = %p is not device-accessible memory (allocate it on the device or as pinned host memory)", what, p);
+    return RG_OK;
+}
+
 extern "C" {
 
 const char* rg_version(void) { return "rapidgnn-mi355x 0.1 (gfx950)"; }

@@ -780,6 +780,10 @@ rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32_t* hom
     const bool may_select = cache->capacity_rows > 0 && num_nodes > 0;
     RG_REQUIRE(ctx, !may_select || (cache->cache_ids && cache->cache_rows), "rg_build_cache: null cache buffer");
     RG_HIP(ctx, hipSetDevice(ctx->device));
+    if (may_select && remote_store) {
+        const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_build_cache: remote_store");
+        if (chk != RG_OK) return chk;
+    }
     hipStream_t s = (hipStream_t)stream;
 
     const int64_t nblocks = rg_max64(1, rg_div_up(num_nodes, kNodesPerBlock));
@@ -887,6 +891,7 @@ rg_status rg_prefetch_cache_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_
     RG_REQUIRE(ctx, input_nodes && home && remote_store, "rg_prefetch_cache_rows: null pointer");
     RG_REQUIRE(ctx, dim >= 1 && cache->row_stride >= dim && remote_stride >= dim, "rg_prefetch_cache_rows: bad dim / stride");
     RG_HIP(ctx, hipSetDevice(ctx->device));
+    { const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_prefetch_cache_rows: remote_store"); if (chk != RG_OK) return chk; }
     hipStream_t s = (hipStream_t)stream;
     rg_status st;
     if ((st = rg_ensure(ctx, ctx->pf_ctl, 64)) != RG_OK) return st;
@@ -965,6 +970,7 @@ rg_status rg_prefetch_planned(rg_ctx* ctx, const rg_prefetch_plan* plan, int32_t
     RG_REQUIRE(ctx, cache && cache->cache_rows && cache->filled && remote_store, "rg_prefetch_planned: null cache rows / filled / store");
     RG_REQUIRE(ctx, dim >= 1 && cache->row_stride >= dim && remote_stride >= dim, "rg_prefetch_planned: bad dim / stride");
     RG_HIP(ctx, hipSetDevice(ctx->device));
+    { const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_prefetch_planned: remote_store"); if (chk != RG_OK) return chk; }
     int64_t blocks;
     int threads;
     rg_hostlink_launch_shape(&blocks, &threads);
@@ -991,6 +997,7 @@ rg_status rg_stage_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, cons
     RG_REQUIRE(ctx, input_nodes && home && remote_store, "rg_stage_rows: null pointer");
     RG_REQUIRE(ctx, dim >= 1 && stage->row_stride >= dim && remote_stride >= dim, "rg_stage_rows: bad dim / stride");
     RG_HIP(ctx, hipSetDevice(ctx->device));
+    { const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_stage_rows: remote_store"); if (chk != RG_OK) return chk; }
     hipStream_t s = (hipStream_t)stream;
     rg_status st;
     if ((st = rg_ensure(ctx, ctx->stage_ctl, 64)) != RG_OK) return st;

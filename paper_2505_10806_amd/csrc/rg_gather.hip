@@ -181,6 +181,10 @@ rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n,
     RG_REQUIRE(ctx, n == 0 || (local_store && remote_store), "rg_gather_features: null feature store");
     RG_REQUIRE(ctx, n == 0 || cache->cache_rows || cache->capacity_rows == 0, "rg_gather_features: cache_rows is NULL");
     RG_HIP(ctx, hipSetDevice(ctx->device));
+    if (n > 0) {
+        const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_gather_features: remote_store");
+        if (chk != RG_OK) return chk;
+    }
     hipStream_t sh = (hipStream_t)hit_stream;
     hipStream_t sm = miss_stream ? (hipStream_t)miss_stream : sh;
     const bool two_streams = sm != sh;

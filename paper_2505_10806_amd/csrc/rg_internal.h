@@ -30,6 +30,7 @@ struct rg_ctx {
     RgBuf fresh;        // uint32[ceil(N/32)] bitmap of ids first seen in the current hop (kept all-zero between hops)
     RgBuf pos;          // int32[N] position of a node in the cumulative frontier (valid for members only)
     RgBuf chunk_sum;    // int32[] per-256-node chunk edge counts / bitmap block counts
+    bool sampler_dirty = false;   // a sampling call was cut short by an error: `fresh` may hold stale bits
     int64_t fresh_words_clean = 0;   // number of leading words of `fresh` known to be zero
     // schedule scratch
     RgBuf sched_keys;   // uint64[npad]
@@ -59,6 +60,8 @@ struct rg_ctx {
 
 rg_status rg_set_error(rg_ctx* ctx, rg_status code, const char* fmt, ...);
 rg_status rg_ensure(rg_ctx* ctx, RgBuf& buf, size_t bytes, bool zero_new = false);
+// RG_OK if kernels on the ctx's device may dereference p (device, managed or pinned/registered host memory).
+rg_status rg_check_device_readable(rg_ctx* ctx, const void* p, const char* what);
 // Profiling brackets (no-ops unless profiling is enabled).
 int rg_prof_begin(rg_ctx* ctx, int kernel, hipStream_t s);
 void rg_prof_end(rg_ctx* ctx, int token, hipStream_t s);

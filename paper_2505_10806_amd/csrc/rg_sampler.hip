@@ -459,6 +459,11 @@ rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds,
     const bool rp64 = csr->row_ptr_bits == 64;
 
     if (words > 0) {
+        if (ctx->sampler_dirty) {        // an earlier call stopped between a draw kernel and its tier emit
+            k_clear_words<<<(int)rg_div_up(words, 256), 256, 0, s>>>(fresh, words);
+            RG_LAUNCH_CHECK(ctx, "k_clear_words");
+        }
+        ctx->sampler_dirty = true;       // cleared again when every launch of this call has been queued
         k_clear_words<<<(int)rg_div_up(words, 256), 256, 0, s>>>(visited, words);
         RG_LAUNCH_CHECK(ctx, "k_clear_words");
     }
@@ -522,6 +527,7 @@ rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds,
             RG_LAUNCH_CHECK(ctx, "k_relabel");
         }
     }
+    ctx->sampler_dirty = false;
     return RG_OK;
 }
 

@@ -779,6 +779,15 @@ def test_argument_errors_are_reported_not_launched(B, ctx):
     with pytest.raises(B.RgError) as e:
         ctx.build_cache(torch.zeros(2, dtype=torch.int32, device=DEV), seeds, pinned, 0, cache)
     assert e.value.status == B.RG_ERR_INVALID_ARG
+    # a pageable host pointer as the remote store is refused on the host instead of faulting a kernel
+    import ctypes
+    pageable = torch.zeros(2, 4)
+    st = B._lib.rg_gather_features(ctx._h, seeds.data_ptr(), 2, None, ctypes.byref(cache.c_struct), store.data_ptr(), 4,
+                                   pageable.data_ptr(), 4, 4, out.data_ptr(), 4, stats.data_ptr(), None, None)
+    assert st == B.RG_ERR_INVALID_ARG and b"not device-accessible" in B._lib.rg_last_error(ctx._h)
+    st = B._lib.rg_build_cache(ctx._h, torch.zeros(2, dtype=torch.int32, device=DEV).data_ptr(), seeds.data_ptr(), 2,
+                               pageable.data_ptr(), 4, 4, ctypes.byref(cache.c_struct), None)
+    assert st == B.RG_ERR_INVALID_ARG
     # the context still works after the rejected calls
     ctx.sample_blocks(csr, seeds, 2, (2,), 1, 0, bufs)
     torch.cuda.synchronize()
