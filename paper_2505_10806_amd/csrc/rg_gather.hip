@@ -60,51 +60,53 @@ __global__ void __launch_bounds__(256) k_classify(const int32_t* __restrict__ no
     }
 }
 
-// Rows whose source is in HBM.  Each wave step moves 64/L rows of cpr chunks; U steps are unrolled.
-template <int VEC, int U, bool NT>
+// Rows whose source is in HBM, with a flat work split: the batch is one stream of 16-byte chunks (row-major over
+// the output), every wavefront takes 64*T consecutive chunks and every lane T of them, whatever the row length,
+// so all lanes carry T loads in flight for 400-byte and 2408-byte rows as well as for power-of-two ones, and
+// the stores of a wavefront are contiguous when the output stride equals the padded row length.
+template <int VEC, int T>
 __global__ void __launch_bounds__(256) k_gather_hbm(const uint32_t* __restrict__ src, int64_t n, const int32_t* __restrict__ n_dev,
-                                                    const float* __restrict__ local_store, int64_t local_stride,
-                                                    const float* __restrict__ cache_rows, int64_t cache_stride,
-                                                    float* __restrict__ out, int64_t out_stride, int cpr, int log2L) {
+                                                         const float* __restrict__ local_store, int64_t local_stride,
+                                                         const float* __restrict__ cache_rows, int64_t cache_stride,
+                                                         float* __restrict__ out, int64_t out_stride, int cpr, float inv_cpr) {
     typedef typename RgVec<VEC>::type V;
     const int64_t n_act = rg_actual_n(n, n_dev);
     const int lane = rg_lane();
-    const int L = 1 << log2L;
-    const int R = RG_WAVE >> log2L;
-    const int sub = lane >> log2L;
-    const int c0 = lane & (L - 1);
+    constexpr int CW = RG_WAVE * T;                    // chunks per wavefront step
+    const int64_t total = n_act * cpr;
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-    for (int64_t row0 = wave * (R * U); row0 < n_act; row0 += nwaves * (R * U)) {
-        const V* sp[U];
-        V* dp[U];
+    for (int64_t q0 = wave * CW; q0 < total; q0 += nwaves * CW) {
+        const int64_t row0 = q0 / cpr;
+        const int off0 = (int)(q0 - row0 * cpr);
+        const V* sp[T];
+        V* dp[T];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = row0 + u * R + sub;
-            sp[u] = nullptr;
-            dp[u] = nullptr;
+        for (int t = 0; t < T; ++t) {
+            const int ql = off0 + lane + RG_WAVE * t;           // < cpr + 64*T: exact in fp32
+            int r = (int)((float)ql * inv_cpr);
+            if (r * cpr > ql) --r; else if ((r + 1) * cpr <= ql) ++r;
+            const int c = ql - r * cpr;
+            const int64_t i = row0 + r;
+            sp[t] = nullptr;
+            dp[t] = nullptr;
             if (i < n_act) {
                 const uint32_t w = src[i];
                 const uint32_t tag = w >> RG_TAG_SHIFT;
                 const int64_t row = (int64_t)(w & RG_ROW_MASK);
                 if (tag != RG_TAG_REMOTE) {
-                    sp[u] = (const V*)(tag == RG_TAG_LOCAL ? local_store + row * local_stride : cache_rows + row * cache_stride);
-                    dp[u] = (V*)(out + i * out_stride);
+                    sp[t] = (const V*)(tag == RG_TAG_LOCAL ? local_store + row * local_stride : cache_rows + row * cache_stride) + c;
+                    dp[t] = (V*)(out + i * out_stride) + c;
                 }
             }
         }
-        for (int c = c0; c < cpr; c += L) {
-            V val[U];
+        V val[T];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (sp[u]) val[u] = sp[u][c];
+        for (int t = 0; t < T; ++t)
+            if (sp[t]) val[t] = *sp[t];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (dp[u]) {
-                    if (NT) __builtin_nontemporal_store(val[u], &dp[u][c]);
-                    else dp[u][c] = val[u];
-                }
-        }
+        for (int t = 0; t < T; ++t)
+            if (dp[t]) __builtin_nontemporal_store(val[t], dp[t]);
     }
 }
 
@@ -213,29 +215,24 @@ rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n,
     const int64_t strides[4] = {local_stride, remote_stride, cache->cache_rows ? cache->row_stride : 0, out_stride};
     const int vec = rg_pick_vec(dim, ptrs, 4, strides, 4);
     const RgRowShape shp = rg_row_shape(dim, vec);
-    constexpr int U = 4;
-    int unroll = env_int("RG_GATHER_UNROLL", 2);
-    if (vec != 4) unroll = 4;
-    else if (unroll != 2 && unroll != 4 && unroll != 8) unroll = 2;
-    const bool nt = env_int("RG_GATHER_NT", 1) == 1;
-    const int rows_per_block = 4 * (RG_WAVE >> shp.log2L) * unroll;
+    constexpr int U = 4;                                    // rows in flight per lane group in the miss kernel
+    // T chunks in flight per lane; swept on the box: 2 is best (T = 4: -2 %, T = 8: -12 %), an uncapped grid
+    // (one step per wavefront) beats a persistent one, and non-temporal stores make no difference.
+    int T = env_int("RG_GATHER_UNROLL", 2);
+    if (vec != 4 || (T != 2 && T != 4 && T != 8)) T = (vec == 4) ? 2 : 4;
     const int per_cu = env_int("RG_GATHER_BLOCKS_PER_CU", 4096);
-    const int grid = (int)rg_max64(1, rg_min64(rg_div_up(n, rows_per_block), (int64_t)ctx->num_cus * per_cu));
+    const int64_t chunks_per_block = 4ll * RG_WAVE * T;
+    const int grid = (int)rg_max64(1, rg_min64(rg_div_up(n * (int64_t)shp.cpr, chunks_per_block), (int64_t)ctx->num_cus * per_cu));
+    const float inv_cpr = 1.0f / (float)shp.cpr;
     const float* cache_rows = cache->cache_rows ? cache->cache_rows : local_store;   // never dereferenced without cache words
 
     int tok = rg_prof_begin(ctx, RG_K_GATHER_HBM, sh);
-#define RG_LAUNCH_HBM(V, UU, NTT)                                                                                  \
-    k_gather_hbm<V, UU, NTT><<<grid, 256, 0, sh>>>(src, n, n_dev, local_store, local_stride, cache_rows,          \
-                                                   cache->row_stride, out, out_stride, shp.cpr, shp.log2L)
-    if (vec == 4) {
-        if (unroll == 2) { if (nt) RG_LAUNCH_HBM(4, 2, true); else RG_LAUNCH_HBM(4, 2, false); }
-        else if (unroll == 8) { if (nt) RG_LAUNCH_HBM(4, 8, true); else RG_LAUNCH_HBM(4, 8, false); }
-        else { if (nt) RG_LAUNCH_HBM(4, 4, true); else RG_LAUNCH_HBM(4, 4, false); }
-    } else if (vec == 2) {
-        RG_LAUNCH_HBM(2, 4, true);
-    } else {
-        RG_LAUNCH_HBM(1, 4, true);
-    }
+#define RG_LAUNCH_HBM(V, TT)                                                                                     \
+    k_gather_hbm<V, TT><<<grid, 256, 0, sh>>>(src, n, n_dev, local_store, local_stride, cache_rows, cache->row_stride, \
+                                              out, out_stride, shp.cpr, inv_cpr)
+    if (vec == 4) { if (T == 2) RG_LAUNCH_HBM(4, 2); else if (T == 8) RG_LAUNCH_HBM(4, 8); else RG_LAUNCH_HBM(4, 4); }
+    else if (vec == 2) RG_LAUNCH_HBM(2, 4);
+    else RG_LAUNCH_HBM(1, 4);
 #undef RG_LAUNCH_HBM
     rg_prof_end(ctx, tok, sh);
     RG_LAUNCH_CHECK(ctx, "k_gather_hbm");
