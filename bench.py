@@ -56,8 +56,9 @@ def run_steps(pipe, steps, totals=None):
     torch.cuda.current_stream().synchronize()
 
 
-def cpu_baseline(wl, n_batches):
-    """The CPU oracle, as it stands, on the first n_batches batches of epoch 0 (single thread)."""
+def cpu_baseline(wl, n_batches=None, target_s=12.0):
+    """The CPU oracle, as it stands, on the first batches of epoch 0 (single thread).  With n_batches None the
+    sample is sized for about target_s seconds of CPU work from a two-batch trial run."""
     import numpy as np
     import oracle
     cfg = wl.cfg
@@ -66,23 +67,31 @@ def cpu_baseline(wl, n_batches):
     X = wl.features.cpu().numpy()
     home = wl.home.cpu().numpy()
     train = wl.train_ids.cpu().numpy()
-    t0 = time.perf_counter()
-    batches = oracle.epoch_batches(train, cfg.batch_size, wl.seed, 0)[:n_batches]
-    counts = np.zeros(cfg.num_nodes, dtype=np.uint32)
-    inputs = []
-    for seeds in batches:
-        blk = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, 0)
-        oracle.access_histogram(blk.input_nodes, counts)
-        inputs.append(blk.input_nodes)
-    ids, loc = oracle.build_cache(counts, home, wl.capacity_rows)
-    oracle.fill_cache(X, ids, wl.stride)
-    rows = 0
-    for nodes in inputs:
-        oracle.gather_features(X, nodes, loc, wl.stride)
-        rows += nodes.size
-    dt = time.perf_counter() - t0
-    return {"value": len(batches) / dt, "unit": "batches/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {len(batches)} batches of epoch 0 of '{cfg.name}' through the whole path "
+    bpe = wl.batches_per_epoch()
+
+    def whole_path(n):
+        t0 = time.perf_counter()
+        batches = oracle.epoch_batches(train, cfg.batch_size, wl.seed, 0)[:n]
+        counts = np.zeros(cfg.num_nodes, dtype=np.uint32)
+        inputs = []
+        for seeds in batches:
+            blk = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, 0)
+            oracle.access_histogram(blk.input_nodes, counts)
+            inputs.append(blk.input_nodes)
+        ids, loc = oracle.build_cache(counts, home, wl.capacity_rows)
+        oracle.fill_cache(X, ids, wl.stride)
+        rows = 0
+        for nodes in inputs:
+            oracle.gather_features(X, nodes, loc, wl.stride)
+            rows += nodes.size
+        return len(batches), rows, time.perf_counter() - t0
+
+    if n_batches is None:
+        n, _, dt = whole_path(min(2, bpe))
+        n_batches = max(2, min(bpe, int(target_s / max(dt / n, 1e-6))))
+    n, rows, dt = whole_path(min(n_batches, bpe))
+    return {"value": n / dt, "unit": "batches/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {n} batches of epoch 0 of '{cfg.name}' through the whole path "
                       f"(schedule, sample, histogram, TopHot+fill, gather of {rows} rows); {dt:.1f} s on one thread",
             "host_cpus": os.cpu_count()}
 
@@ -94,7 +103,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="stress")
     ap.add_argument("--seed", type=int, default=2025)
-    ap.add_argument("--cpu-batches", type=int, default=None, help="batches the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-batches", type=int, default=None,
+                    help="batches the CPU oracle is timed on (0 = skip; default: about 12 s of CPU work)")
     ap.add_argument("--one-stream", action="store_true", help="copy miss rows on the same stream as the HBM rows")
     ap.add_argument("--bulk-fill", action="store_true",
                     help="pull all cached rows in one go after TopHot instead of batch by batch ahead of the gathers")
@@ -250,12 +260,10 @@ def main():
                               "algorithmic_GBps": (row_bytes * (e_last + sum(int(x) for x in pipe.state.tier_offs[:pipe.n_batches, pipe.H].cpu().tolist()))
                                                    / (a_ms * 1e-3) / 1e9) if e_last else None}
     n_cpu = args.cpu_batches
-    if n_cpu is None:
-        n_cpu = 2 if cfg.num_nodes >= 1_000_000 else min(8, bpe)
-    if n_cpu > 0:
+    if n_cpu is None or n_cpu > 0:
         del pipe
         torch.cuda.empty_cache()
-        log(f"[bench] timing the CPU oracle on {n_cpu} batches ...")
+        log("[bench] timing the CPU oracle on a bounded sample ...")
         result["cpu_baseline"] = cpu_baseline(wl, n_cpu)
     print(json.dumps(result), flush=True)
 
