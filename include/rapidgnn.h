@@ -3,10 +3,16 @@
  *
  * The library implements the steps of the paper's Algorithm 1 that move data:
  *   line 1     precompute the mini-batches of an epoch with a seeded sampler  -> rg_epoch_schedule, rg_sample_blocks
- *   line 2-3   access frequencies of the precomputed input nodes, TopHot      -> rg_access_histogram, rg_build_cache
- *   line 4     VectorPull of the hot rows into the steady cache C_s           -> rg_build_cache (bulk) or rg_prefetch_cache_rows (by first use)
+ *   line 2-3   access frequencies of the precomputed input nodes, TopHot      -> rg_access_histogram[_epoch], rg_build_cache
+ *   line 4     VectorPull of the hot rows into the steady cache C_s           -> rg_build_cache (bulk pull), or pulls in order
+ *              (and the prefetcher of Section III, Fig. 4)                       of first use ahead of the gathers:
+ *                                                                                rg_plan_prefetch + rg_prefetch_planned,
+ *                                                                                rg_prefetch_cache_rows, rg_stage_rows +
+ *                                                                                rg_commit_staged_rows
  *   line 12-14 per-batch feature assembly from local store, cache and         -> rg_gather_features
  *              fallback pull of the misses from the remote store
+ * and two companions: rg_mean_aggregate (Eq. 1 with AGG = mean over a sampled block, the consumer of the
+ * gathered rows) and rg_cache_hit_curve (Section V: remote fetches against cache size).
  * Every step runs in HIP kernels on the device; there is no CPU fallback.
  *
  * Conventions
@@ -56,7 +62,7 @@ typedef enum {
     RG_ERR_CAPACITY = 2,      /* an output buffer is smaller than the static bound (see rg_blocks_bounds) */
     RG_ERR_OOM = 3,           /* scratch allocation failed */
     RG_ERR_HIP = 4,           /* a HIP runtime call failed; message in rg_last_error */
-    RG_ERR_STATE = 5          /* call not valid in the ctx's current state */
+    RG_ERR_STATE = 5          /* call not valid in the ctx's current state (reserved; no call returns it yet) */
 } rg_status;
 
 #define RG_TAG_LOCAL 0u
