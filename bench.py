@@ -38,6 +38,13 @@ def log(msg):
 def run_steps(pipe, steps, totals=None):
     """Run `steps` batches through the whole path, epoch after epoch (the last epoch may be partial)."""
     import torch
+    marks = {"t": time.perf_counter()}
+
+    def started(p, _k):                      # called once the epoch's offline stage has finished (host has its sizes)
+        if totals is not None:
+            now = time.perf_counter()
+            totals["offline_s"] += now - marks["t"]
+            marks["t"] = now
 
     def account(p, _k):
         if totals is not None:
@@ -49,10 +56,9 @@ def run_steps(pipe, steps, totals=None):
             totals["epochs"] += 1
     full, rem = divmod(steps, pipe.max_batches)
     if full:
-        pipe.run_epochs(0, full, pipe.max_batches, on_epoch_done=account)
+        pipe.run_epochs(0, full, pipe.max_batches, on_epoch_done=account, on_epoch_start=started)
     if rem:
-        pipe.run_epoch(full, rem)
-        account(pipe, full)
+        pipe.run_epochs(full, 1, rem, on_epoch_done=account, on_epoch_start=started)
     torch.cuda.current_stream().synchronize()
 
 
@@ -70,30 +76,41 @@ def cpu_baseline(wl, n_batches=None, target_s=12.0):
     bpe = wl.batches_per_epoch()
 
     def whole_path(n):
-        t0 = time.perf_counter()
+        phases = {"schedule": 0.0, "sample": 0.0, "histogram": 0.0, "tophot_fill": 0.0, "gather": 0.0}
+        clock = time.perf_counter
+        t0 = t = clock()
         batches = oracle.epoch_batches(train, cfg.batch_size, wl.seed, 0)[:n]
+        phases["schedule"] = clock() - t
         counts = np.zeros(cfg.num_nodes, dtype=np.uint32)
         inputs = []
         for seeds in batches:
+            t = clock()
             blk = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, 0)
+            phases["sample"] += clock() - t
+            t = clock()
             oracle.access_histogram(blk.input_nodes, counts)
+            phases["histogram"] += clock() - t
             inputs.append(blk.input_nodes)
+        t = clock()
         ids, loc = oracle.build_cache(counts, home, wl.capacity_rows)
         oracle.fill_cache(X, ids, wl.stride)
+        phases["tophot_fill"] = clock() - t
         rows = 0
+        t = clock()
         for nodes in inputs:
             oracle.gather_features(X, nodes, loc, wl.stride)
             rows += nodes.size
-        return len(batches), rows, time.perf_counter() - t0
+        phases["gather"] = clock() - t
+        return len(batches), rows, clock() - t0, phases
 
     if n_batches is None:
-        n, _, dt = whole_path(min(2, bpe))
+        n, _, dt, _ = whole_path(min(2, bpe))
         n_batches = max(2, min(bpe, int(target_s / max(dt / n, 1e-6))))
-    n, rows, dt = whole_path(min(n_batches, bpe))
+    n, rows, dt, phases = whole_path(min(n_batches, bpe))
     return {"value": n / dt, "unit": "batches/s", "cores": 1, "kind": "oracle",
             "sample": f"first {n} batches of epoch 0 of '{cfg.name}' through the whole path "
                       f"(schedule, sample, histogram, TopHot+fill, gather of {rows} rows); {dt:.1f} s on one thread",
-            "host_cpus": os.cpu_count()}
+            "phase_seconds": {k: round(v, 4) for k, v in phases.items()}, "host_cpus": os.cpu_count()}
 
 
 def main():
@@ -171,7 +188,7 @@ def main():
             run_steps(pipe, warmup)
         totals = {"stats": torch.zeros(3, dtype=torch.int64, device=dev), "rows": 0,
                   "edges": torch.zeros((), dtype=torch.int64, device=dev),
-                  "cached": torch.zeros(1, dtype=torch.int64, device=dev), "epochs": 0}
+                  "cached": torch.zeros(1, dtype=torch.int64, device=dev), "epochs": 0, "offline_s": 0.0}
         pipe.profile_enable(True)
         pipe.profile_reset()
         torch.cuda.synchronize()
@@ -238,6 +255,9 @@ def main():
                      "achieved": row_bytes * cached_rows / (f_ms * 1e-3) / 1e9 if f_ms > 0 and cached_rows else None,
                      "note": "sum of pull-kernel durations; the pulls run beside the gathers on their own stream"},
         "kernel_ms": {k: {"total_ms": v[0], "launches": v[1]} for k, v in prof.items()},
+        # host clock: time until each epoch's offline stage (schedule, sampling, histogram, TopHot, plan) had finished,
+        # and the rest (pulls and gathers); with double buffering the next epoch's offline stage hides in "online"
+        "phase_ms": {"offline_until_sizes_known": totals["offline_s"] * 1e3, "online": (dt - totals["offline_s"]) * 1e3},
     }
 
     # requests for remote rows a cache of a given size would serve, from the last epoch's histogram (no cache is built)
