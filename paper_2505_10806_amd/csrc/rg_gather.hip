@@ -22,6 +22,10 @@ __global__ void k_gather_reset(uint32_t* __restrict__ gctl, unsigned long long* 
     if (threadIdx.x < 3) stats[threadIdx.x] = 0ull;
 }
 
+// Four rows per thread (row i0 + k*256 + threadIdx.x, k = 0..3) so that each thread has four independent
+// loc[] lookups in flight; the miss pairs of a workgroup are appended in that visiting order (any order is valid).
+constexpr int kClassifyRows = 4;
+
 __global__ void __launch_bounds__(256) k_classify(const int32_t* __restrict__ nodes, int64_t n, const int32_t* __restrict__ n_dev,
                                                   const int32_t* __restrict__ loc, uint32_t* __restrict__ src,
                                                   int32_t* __restrict__ miss_list, uint32_t* __restrict__ gctl,
@@ -30,22 +34,34 @@ __global__ void __launch_bounds__(256) k_classify(const int32_t* __restrict__ no
     __shared__ int cls[3][4];
     __shared__ uint32_t miss_base;
     const int64_t n_act = rg_actual_n(n, n_dev);
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if ((int64_t)blockIdx.x * blockDim.x >= n_act) return;       // uniform per workgroup
-    uint32_t tag = 3u, w = 0u;
-    if (i < n_act) {
-        w = (uint32_t)loc[nodes[i]];
-        src[i] = w;
-        tag = w >> RG_TAG_SHIFT;
+    const int64_t i0 = (int64_t)blockIdx.x * (256 * kClassifyRows);
+    if (i0 >= n_act) return;                                       // uniform per workgroup
+    uint32_t w[kClassifyRows];
+    int32_t v[kClassifyRows];
+#pragma unroll
+    for (int k = 0; k < kClassifyRows; ++k) {
+        const int64_t i = i0 + k * 256 + threadIdx.x;
+        v[k] = i < n_act ? nodes[i] : -1;
     }
-    const int is_miss = tag == RG_TAG_REMOTE;
+#pragma unroll
+    for (int k = 0; k < kClassifyRows; ++k) w[k] = v[k] >= 0 ? (uint32_t)loc[v[k]] : 0xFFFFFFFFu;   // tag 3 = no row
+    int c_local = 0, c_hit = 0, n_miss = 0;
+#pragma unroll
+    for (int k = 0; k < kClassifyRows; ++k) {
+        const int64_t i = i0 + k * 256 + threadIdx.x;
+        const uint32_t tag = w[k] >> RG_TAG_SHIFT;
+        if (i < n_act) src[i] = w[k];
+        c_local += tag == RG_TAG_LOCAL;
+        c_hit += tag == RG_TAG_CACHE;
+        n_miss += tag == RG_TAG_REMOTE;
+    }
     const int wave = threadIdx.x >> 6;
-    const int c_local = __popcll(__ballot(tag == RG_TAG_LOCAL));
-    const int c_hit = __popcll(__ballot(tag == RG_TAG_CACHE));
-    const int c_miss = __popcll(__ballot(is_miss));
+    c_local = rg_wave_sum(c_local);
+    c_hit = rg_wave_sum(c_hit);
+    const int c_miss = rg_wave_sum(n_miss);
     if (rg_lane() == 0) { cls[0][wave] = c_local; cls[1][wave] = c_hit; cls[2][wave] = c_miss; }
     int total_miss;
-    const int excl = rg_block_excl_scan<256 / RG_WAVE>(is_miss, smem, &total_miss);   // barriers inside publish cls[]
+    int excl = rg_block_excl_scan<256 / RG_WAVE>(n_miss, smem, &total_miss);          // barriers inside publish cls[]
     if (threadIdx.x < 3) {
         const int t = cls[threadIdx.x][0] + cls[threadIdx.x][1] + cls[threadIdx.x][2] + cls[threadIdx.x][3];
         if (t) atomicAdd(&stats[threadIdx.x], (unsigned long long)t);
@@ -53,11 +69,13 @@ __global__ void __launch_bounds__(256) k_classify(const int32_t* __restrict__ no
     if (total_miss == 0) return;                                   // uniform
     if (threadIdx.x == 0) miss_base = atomicAdd(&gctl[0], (uint32_t)total_miss);
     __syncthreads();
-    if (is_miss) {                       // (output row, remote row) pairs: the miss kernel needs no further lookup
-        const int64_t j = (int64_t)miss_base + excl;
-        miss_list[2 * j] = (int32_t)i;
-        miss_list[2 * j + 1] = (int32_t)(w & RG_ROW_MASK);
-    }
+#pragma unroll
+    for (int k = 0; k < kClassifyRows; ++k)
+        if ((w[k] >> RG_TAG_SHIFT) == RG_TAG_REMOTE) {   // (output row, remote row) pairs: the miss kernel needs no further lookup
+            const int64_t j = (int64_t)miss_base + excl++;
+            miss_list[2 * j] = (int32_t)(i0 + k * 256 + threadIdx.x);
+            miss_list[2 * j + 1] = (int32_t)(w[k] & RG_ROW_MASK);
+        }
 }
 
 // Rows whose source is in HBM, with a flat work split: the batch is one stream of 16-byte chunks (row-major over
@@ -204,7 +222,7 @@ rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n,
     RG_LAUNCH_CHECK(ctx, "k_gather_reset");
     if (n == 0) return RG_OK;
 
-    k_classify<<<(int)rg_div_up(n, 256), 256, 0, sh>>>(input_nodes, n, n_dev, cache->loc, src, miss_list, gctl, dstats);
+    k_classify<<<(int)rg_div_up(n, 256 * kClassifyRows), 256, 0, sh>>>(input_nodes, n, n_dev, cache->loc, src, miss_list, gctl, dstats);
     RG_LAUNCH_CHECK(ctx, "k_classify");
     if (two_streams) {
         RG_HIP(ctx, hipEventRecord(ctx->ev_classified, sh));
