@@ -1,5 +1,7 @@
-// Access-frequency histogram (Section IV, offline stage), TopHot selection (Alg. 1 line 3) and the
-// bulk pull of the selected rows into the HBM cache (VectorPull, Alg. 1 line 4).
+// Access-frequency histogram (Section IV, offline stage), TopHot selection (Alg. 1 line 3), the hit curve
+// against cache size (Section V), and VectorPull (Alg. 1 line 4) in its three forms: one bulk pull, pulls by
+// first use ahead of the gathers (the prefetcher of Section III: with a per-batch claim pass or from a
+// per-epoch plan), and early pulls into a staging area during the offline stage.
 #include <stdlib.h>
 
 #include "rg_rowcopy.h"

@@ -1,9 +1,10 @@
-// Row-copy building blocks shared by the cache fill and the per-batch gather.
+// Row-copy building blocks shared by the cache pulls, the gather and the mean aggregation.
 //
-// A feature row is moved as `cpr` chunks of VEC floats (VEC = 4 -> 16-byte accesses).  A wavefront is
-// split into groups of L = 2^log2L lanes, one group per row, so 64/L rows move per wave step and short
-// rows (256 B, 400 B, 512 B) still fill all lanes.  U row groups are unrolled so every lane has U
-// independent loads in flight before the first store.
+// A feature row is moved as `cpr` chunks of VEC floats (VEC = 4 -> 16-byte accesses).  In the link kernels
+// and the aggregation a wavefront is split into groups of L = 2^log2L lanes, one group per row, so 64/L rows
+// move per wave step and short rows (256 B, 400 B, 512 B) still fill most lanes; U row groups are unrolled
+// so every lane has U independent loads in flight before the first store.  (The HBM gather kernel splits
+// the work by chunks instead of rows.)
 #pragma once
 
 #include <stdlib.h>
