@@ -788,6 +788,29 @@ def test_argument_errors_are_reported_not_launched(B, ctx):
     st = B._lib.rg_build_cache(ctx._h, torch.zeros(2, dtype=torch.int32, device=DEV).data_ptr(), seeds.data_ptr(), 2,
                                pageable.data_ptr(), 4, 4, ctypes.byref(cache.c_struct), None)
     assert st == B.RG_ERR_INVALID_ARG
+    # the later entry points validate on the host as well
+    with pytest.raises(B.RgError) as e:
+        ctx.cache_hit_curve(torch.zeros(2, dtype=torch.int32, device=DEV), seeds, [-1])
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    plan = B.PrefetchPlan(0, 2, DEV)                       # list too small for the cache's capacity
+    with pytest.raises(B.RgError) as e:
+        ctx.plan_prefetch(cache, seeds, torch.zeros(2, dtype=torch.int32, device=DEV), plan)
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    good_plan = B.PrefetchPlan(1, 2, DEV)
+    with pytest.raises(B.RgError) as e:
+        ctx.prefetch_planned(good_plan, 4, cache, pinned, 4)   # batch beyond the plan
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    stage = B.StagingArea(2, 2, 4, DEV)
+    with pytest.raises(B.RgError) as e:
+        ctx.stage_rows(seeds, 2, seeds, stage, -1, pinned, 4)
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    with pytest.raises(B.RgError) as e:
+        ctx.mean_aggregate(seeds, seeds, 1, store, 8, out)     # dim larger than the strides
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    with pytest.raises(B.RgError) as e:
+        ctx.access_histogram_epoch(torch.zeros(1, 4, dtype=torch.int32, device=DEV), torch.zeros(1, 11, dtype=torch.int32, device=DEV),
+                                   1, 9, 1, torch.zeros(2, dtype=torch.int32, device=DEV))
+    assert e.value.status == B.RG_ERR_INVALID_ARG          # more hops than RG_MAX_HOPS
     # the context still works after the rejected calls
     ctx.sample_blocks(csr, seeds, 2, (2,), 1, 0, bufs)
     torch.cuda.synchronize()
