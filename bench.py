@@ -27,7 +27,7 @@ HOSTLINK_PEAK_GBS = 64.0   # PCIe Gen5 x16, one direction
 # HBM bytes moved by one k_gather_hbm launch on the stress workload, measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE, one counter per run, each scaled by what the same counter reads for a plain 1 GiB copy: x2.000 and
 # x1.000).  The figures and the commands are in profiles/stress_gather_hbm_pmc_traffic.txt.
-PMC_TRAFFIC = {"stress": {"fetch_kib": 404240.0, "fetch_scale": 2.0, "write_kib": 796000.1, "write_scale": 1.0,
+PMC_TRAFFIC = {"stress": {"fetch_kib": 404251.2, "fetch_scale": 2.0, "write_kib": 795996.3, "write_scale": 1.0,
                           "rows_per_launch": 795995}}
 
 
