@@ -93,7 +93,7 @@ void rg_destroy(rg_ctx* ctx) {
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
-    RgBuf* bufs[] = {&ctx->visited, &ctx->fresh, &ctx->pos, &ctx->chunk_sum, &ctx->sched_keys, &ctx->sched_ids,
+    RgBuf* bufs[] = {&ctx->visited, &ctx->fresh, &ctx->pos, &ctx->chunk_sum, &ctx->row_start, &ctx->row_deg, &ctx->sched_keys, &ctx->sched_ids,
                      &ctx->topk_ctl, &ctx->topk_blk, &ctx->pf_list, &ctx->pf_ctl, &ctx->stage_list, &ctx->stage_ctl, &ctx->commit_list, &ctx->commit_ctl, &ctx->plan_cursor, &ctx->gather_src, &ctx->miss_list, &ctx->gather_ctl};
     for (RgBuf* b : bufs)
         if (b->p) (void)hipFree(b->p);
@@ -120,6 +120,8 @@ rg_status rg_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int64
     if ((st = rg_ensure(ctx, ctx->pos, (size_t)num_nodes * 4)) != RG_OK) return st;
     const size_t chunks = (size_t)rg_max64(rg_div_up(max_frontier, 256), rg_div_up((int64_t)words, 1024)) + 2;
     if ((st = rg_ensure(ctx, ctx->chunk_sum, chunks * 4)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->row_start, (size_t)max_frontier * 8)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->row_deg, (size_t)max_frontier * 4)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->topk_blk, ((size_t)rg_div_up(num_nodes, 1024) + 2) * 8)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->gather_src, (size_t)max_rows * 4)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->miss_list, (size_t)max_rows * 8)) != RG_OK) return st;

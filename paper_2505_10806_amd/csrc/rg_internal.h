@@ -30,6 +30,8 @@ struct rg_ctx {
     RgBuf fresh;        // uint32[ceil(N/32)] bitmap of ids first seen in the current hop (kept all-zero between hops)
     RgBuf pos;          // int32[N] position of a node in the cumulative frontier (valid for members only)
     RgBuf chunk_sum;    // int32[] per-256-node chunk edge counts / bitmap block counts
+    RgBuf row_start;    // int64[max_frontier] adjacency row start of every frontier node (current hop)
+    RgBuf row_deg;      // int32[max_frontier] its degree
     bool sampler_dirty = false;   // a sampling call was cut short by an error: `fresh` may hold stale bits
     int64_t fresh_words_clean = 0;   // number of leading words of `fresh` known to be zero
     // schedule scratch

@@ -118,11 +118,13 @@ __global__ void __launch_bounds__(256) k_mark_seeds(const int32_t* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------- per hop: sizes
-// indptr[i] = exclusive prefix of m within the node's 256-node chunk; chunk_sum[b] = chunk total.
+// indptr[i] = exclusive prefix of m within the node's 256-node chunk; chunk_sum[b] = chunk total;
+// row_start[i], row_deg[i] = the node's adjacency row.
 template <typename RP>
 __global__ void __launch_bounds__(kChunk) k_hop_count(const RP* __restrict__ row_ptr, const int32_t* __restrict__ nodes,
                                                       const int32_t* __restrict__ n_frontier_ptr, int fanout,
-                                                      int32_t* __restrict__ indptr, int32_t* __restrict__ chunk_sum) {
+                                                      int32_t* __restrict__ indptr, int32_t* __restrict__ chunk_sum,
+                                                      int64_t* __restrict__ row_start, int32_t* __restrict__ row_deg) {
     __shared__ int smem[kChunk / RG_WAVE + 1];
     const int n_h = *n_frontier_ptr;
     const int64_t first = (int64_t)blockIdx.x * kChunk;
@@ -133,6 +135,8 @@ __global__ void __launch_bounds__(kChunk) k_hop_count(const RP* __restrict__ row
         int64_t start, deg;
         rg_row_extent(row_ptr, nodes[i], start, deg);
         m = (fanout < 0 || deg <= fanout) ? (int)deg : fanout;
+        row_start[i] = start;             // kept for the draw kernel: one coalesced read there instead of a second
+        row_deg[i] = (int32_t)deg;        // random lookup of row_ptr
     }
     int total;
     const int excl = rg_block_excl_scan<kChunk / RG_WAVE>(m, smem, &total);
@@ -183,9 +187,8 @@ __device__ __forceinline__ void rg_mark_fresh(int32_t u, const uint32_t* __restr
 
 // General sampler: one wavefront (= one 64-thread workgroup) per frontier node, any fan-out up to
 // RG_MAX_FANOUT.  The Floyd set lives in LDS; step i tests membership of t with all lanes.
-template <typename RP>
-__global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const RP* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-                                                            const int32_t* __restrict__ nodes,
+__global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int64_t* __restrict__ row_start, const int32_t* __restrict__ row_deg,
+                                                            const int32_t* __restrict__ col_idx, const int32_t* __restrict__ nodes,
                                                             const int32_t* __restrict__ n_frontier_ptr, int fanout, uint32_t hop,
                                                             uint32_t k0, uint32_t k1, uint32_t epoch,
                                                             int32_t* __restrict__ indptr, const int32_t* __restrict__ chunk_sum,
@@ -197,8 +200,7 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const RP* __restric
     const int lane = threadIdx.x;
     for (int64_t i = blockIdx.x; i < n_h; i += gridDim.x) {
         const int32_t v = nodes[i];
-        int64_t start, deg;
-        rg_row_extent(row_ptr, v, start, deg);
+        const int64_t start = row_start[i], deg = row_deg[i];
         const int base = indptr[i] + chunk_sum[i / kChunk];
         __syncthreads();                               // every lane has read indptr[i] before it is rewritten
         if (lane == 0) indptr[i] = base;
@@ -241,9 +243,9 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const RP* __restric
 // draws (Philox + Floyd entirely in registers), the 256 nodes of a workgroup stage the col_idx offsets
 // of their picks in LDS in output order, then the whole workgroup reads col_idx and writes nbr with
 // consecutive lanes on consecutive output slots.
-template <typename RP, int KMAX>
-__global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const RP* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-                                                              const int32_t* __restrict__ nodes,
+template <int KMAX>
+__global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const int64_t* __restrict__ row_start, const int32_t* __restrict__ row_deg,
+                                                              const int32_t* __restrict__ col_idx, const int32_t* __restrict__ nodes,
                                                               const int32_t* __restrict__ n_frontier_ptr, int fanout, uint32_t hop,
                                                               uint32_t k0, uint32_t k1, uint32_t epoch,
                                                               int32_t* __restrict__ indptr, const int32_t* __restrict__ chunk_sum,
@@ -262,8 +264,7 @@ __global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const RP* __restri
     const int chunk_edges = (last_chunk ? indptr[n_h] : chunk_sum[blockIdx.x + 1]) - base;
     if (i < n_h) {
         const int32_t v = nodes[i];
-        int64_t start, deg;
-        rg_row_extent(row_ptr, v, start, deg);
+        const int64_t start = row_start[i], deg = row_deg[i];
         const int off = indptr[i];                       // chunk-local exclusive prefix from k_hop_count
         indptr[i] = base + off;
         if (deg <= k) {                                  // whole row, CSR order
@@ -455,6 +456,8 @@ rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds,
     uint32_t* fresh = (uint32_t*)ctx->fresh.p;
     int32_t* pos = (int32_t*)ctx->pos.p;
     int32_t* chunk_sum = (int32_t*)ctx->chunk_sum.p;
+    int64_t* row_start = (int64_t*)ctx->row_start.p;
+    int32_t* row_deg = (int32_t*)ctx->row_deg.p;
     const uint32_t k0 = (uint32_t)(seed & 0xffffffffu), k1 = (uint32_t)(seed >> 32);
     const bool rp64 = csr->row_ptr_bits == 64;
 
@@ -476,9 +479,9 @@ rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds,
         const int count_blocks = grid_for(fub[h], kChunk, 1ll << 30);
         int32_t* indptr = out->indptr[h];
         if (rp64)
-            k_hop_count<int64_t><<<count_blocks, kChunk, 0, s>>>((const int64_t*)csr->row_ptr, out->nodes, n_frontier, fanouts[h], indptr, chunk_sum);
+            k_hop_count<int64_t><<<count_blocks, kChunk, 0, s>>>((const int64_t*)csr->row_ptr, out->nodes, n_frontier, fanouts[h], indptr, chunk_sum, row_start, row_deg);
         else
-            k_hop_count<int32_t><<<count_blocks, kChunk, 0, s>>>((const int32_t*)csr->row_ptr, out->nodes, n_frontier, fanouts[h], indptr, chunk_sum);
+            k_hop_count<int32_t><<<count_blocks, kChunk, 0, s>>>((const int32_t*)csr->row_ptr, out->nodes, n_frontier, fanouts[h], indptr, chunk_sum, row_start, row_deg);
         RG_LAUNCH_CHECK(ctx, "k_hop_count");
         // chunk sums -> exclusive offsets; total edge count -> indptr[n_h]
         k_scan_sums<<<1, 1024, 0, s>>>(chunk_sum, n_frontier, 0, kChunk, nullptr, indptr, 1, out->num_edges ? out->num_edges + h : nullptr);
@@ -489,26 +492,16 @@ rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds,
         if (F >= 1 && F <= 32 && csr->num_edges < (1ll << 32)) {
             const int kmax = F <= 8 ? 8 : (F <= 16 ? 16 : 32);
             const size_t lds = (size_t)kChunk * F * sizeof(uint32_t);
-#define RG_LAUNCH_FAST(RPT, KM)                                                                                       \
-    k_hop_sample_thread<RPT, KM><<<count_blocks, kChunk, lds, s>>>((const RPT*)csr->row_ptr, csr->col_idx, out->nodes,    \
-                                                                   n_frontier, F, (uint32_t)h, k0, k1, epoch, indptr,    \
-                                                                   chunk_sum, out->nbr[h], visited, fresh)
-            if (rp64) {
-                if (kmax == 8) RG_LAUNCH_FAST(int64_t, 8); else if (kmax == 16) RG_LAUNCH_FAST(int64_t, 16); else RG_LAUNCH_FAST(int64_t, 32);
-            } else {
-                if (kmax == 8) RG_LAUNCH_FAST(int32_t, 8); else if (kmax == 16) RG_LAUNCH_FAST(int32_t, 16); else RG_LAUNCH_FAST(int32_t, 32);
-            }
+#define RG_LAUNCH_FAST(KM)                                                                                            \
+    k_hop_sample_thread<KM><<<count_blocks, kChunk, lds, s>>>(row_start, row_deg, csr->col_idx, out->nodes, n_frontier, F,   \
+                                                              (uint32_t)h, k0, k1, epoch, indptr, chunk_sum, out->nbr[h],  \
+                                                              visited, fresh)
+            if (kmax == 8) RG_LAUNCH_FAST(8); else if (kmax == 16) RG_LAUNCH_FAST(16); else RG_LAUNCH_FAST(32);
 #undef RG_LAUNCH_FAST
         } else {
             const int sample_blocks = grid_for(fub[h], 1, (int64_t)ctx->num_cus * 64);
-            if (rp64)
-                k_hop_sample_wave<int64_t><<<sample_blocks, RG_WAVE, 0, s>>>((const int64_t*)csr->row_ptr, csr->col_idx, out->nodes, n_frontier,
-                                                                            F, (uint32_t)h, k0, k1, epoch, indptr, chunk_sum,
-                                                                            out->nbr[h], visited, fresh);
-            else
-                k_hop_sample_wave<int32_t><<<sample_blocks, RG_WAVE, 0, s>>>((const int32_t*)csr->row_ptr, csr->col_idx, out->nodes, n_frontier,
-                                                                            F, (uint32_t)h, k0, k1, epoch, indptr, chunk_sum,
-                                                                            out->nbr[h], visited, fresh);
+            k_hop_sample_wave<<<sample_blocks, RG_WAVE, 0, s>>>(row_start, row_deg, csr->col_idx, out->nodes, n_frontier, F, (uint32_t)h,
+                                                                k0, k1, epoch, indptr, chunk_sum, out->nbr[h], visited, fresh);
         }
         rg_prof_end(ctx, tok, s);
         RG_LAUNCH_CHECK(ctx, "k_hop_sample");
