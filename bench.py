@@ -262,10 +262,15 @@ def main():
 
     # requests for remote rows a cache of a given size would serve, from the last epoch's histogram (no cache is built)
     fracs = [0.01, 0.05, 0.10, 0.15, 0.20, 0.50, 1.00]
-    caps = [int(f * wl.n_remote) for f in fracs]
+    caps = [int(f * wl.n_remote) for f in fracs] + [wl.capacity_rows]
     hits, total = ctx.cache_hit_curve(pipe.counts, wl.home, caps)
     torch.cuda.synchronize()
     total = int(total.item())
+    predicted = int(hits[-1].item())
+    hits, caps = hits[:-1], caps[:-1]
+    result["gather"]["cache_hit_pct_predicted_from_histogram"] = 100.0 * predicted / max(total, 1)
+    if totals["epochs"] == 1:      # one epoch: the hits counted by the gathers are exactly those the histogram predicts
+        assert predicted == n_hit and total == n_hit + n_miss, "cache hits differ from the histogram's prediction"
     result["cache_hit_curve"] = {"period": f"{pipe.n_batches} batches (last timed epoch)", "remote_requests": total,
                                  "points": [{"capacity_frac_of_remote": f, "capacity_rows": c,
                                              "hit_pct": 100.0 * int(h) / max(total, 1), "remote_fetches": total - int(h)}
