@@ -575,6 +575,44 @@ def test_gather_shapes_and_tags(B, ctx, dim, pad, two_streams):
     assert tuple(stats.cpu().tolist()) == st
 
 
+def test_gather_with_stale_cache_and_misaligned_buffers(B, ctx):
+    """A cache selected for another epoch changes the hit rate, never the rows; buffers that are only 4-byte aligned
+    fall back to scalar accesses and still copy exactly dim floats."""
+    wl = synth.build_workload("tiny", seed=41, device=DEV)
+    cfg = wl.cfg
+    H = len(cfg.fanouts)
+    rp, ci = host_graph(wl)
+    X = wl.features.cpu().numpy()
+    home_np, train_np = wl.home.cpu().numpy(), wl.train_ids.cpu().numpy()
+    counts0 = np.zeros(cfg.num_nodes, dtype=np.uint32)
+    for seeds in oracle.epoch_batches(train_np, cfg.batch_size, wl.seed, 0, 4):
+        oracle.access_histogram(oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, 0).input_nodes, counts0)
+    cache = B.FeatureCache(cfg.num_nodes, wl.capacity_rows, wl.stride, DEV)
+    ctx.build_cache(torch.from_numpy(counts0.view(np.int32)).to(DEV), wl.home, wl.remote_store, cfg.feat_dim, cache)
+    _, loc0 = oracle.build_cache(counts0, home_np, wl.capacity_rows)
+    seeds1 = oracle.epoch_batches(train_np, cfg.batch_size, wl.seed, 1, 4)[2]          # a batch of the next epoch
+    blk = oracle.sample_blocks(rp, ci, seeds1, cfg.fanouts, wl.seed, 1)
+    nodes = torch.as_tensor(blk.input_nodes, device=DEV)
+    n = blk.input_nodes.size
+    stats = torch.zeros(3, dtype=torch.int64, device=DEV)
+    want, st = oracle.gather_features(X, blk.input_nodes, loc0)
+    # aligned, padded output
+    out = torch.full((n, wl.stride), float("nan"), device=DEV)
+    ctx.gather_features(nodes, n, cache, wl.local_store, wl.remote_store, cfg.feat_dim, out, stats)
+    torch.cuda.synchronize()
+    assert np.array_equal(out[:, :cfg.feat_dim].cpu().numpy(), want) and tuple(stats.cpu().tolist()) == st
+    assert 0 < st[1] and 0 < st[2]                                                    # still some hits, more misses
+    # output that starts 4 bytes into an allocation, row stride = dim + 1: scalar path, neighbours untouched
+    flat = torch.full((n * (cfg.feat_dim + 1) + 1,), float("nan"), device=DEV)
+    out2 = flat[1:].view(n, cfg.feat_dim + 1)
+    assert out2.data_ptr() % 16 == 4
+    ctx.gather_features(nodes, n, cache, wl.local_store, wl.remote_store, cfg.feat_dim, out2, stats)
+    torch.cuda.synchronize()
+    assert np.array_equal(out2[:, :cfg.feat_dim].cpu().numpy(), want)
+    assert torch.isnan(out2[:, cfg.feat_dim]).all() and torch.isnan(flat[0])
+    assert tuple(stats.cpu().tolist()) == st
+
+
 # ------------------------------------------------------------------------------ histogram
 def test_histogram_with_repeats_and_device_count(B, ctx):
     rng = np.random.default_rng(4)
