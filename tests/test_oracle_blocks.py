@@ -195,3 +195,42 @@ def test_empty_and_isolated_inputs():
     assert e.nodes.size == 0 and e.tier_off.tolist() == [0, 0, 0]
     c = oracle.sample_blocks(rp, ci, np.array([1], dtype=np.int32), (4, 4), 1, 0)
     assert c.nodes.tolist() == [1, 2] and c.nbr[1].tolist() == [2, 1] and c.nbr_local[1].tolist() == [1, 0]
+
+
+# ---- randomised: the C oracle against the dictionary-and-bigint reimplementation on generated graphs
+from hypothesis import given, settings, strategies as st  # noqa: E402
+
+
+@st.composite
+def _graph_and_query(draw):
+    n = draw(st.integers(2, 40))
+    edges = draw(st.sets(st.tuples(st.integers(0, n - 1), st.integers(0, n - 1)), max_size=4 * n))
+    adj = {v: set() for v in range(n)}
+    for u, v in edges:
+        if u != v:
+            adj[u].add(v)
+            adj[v].add(u)
+    adj = {v: sorted(a) for v, a in adj.items()}
+    seeds = draw(st.lists(st.integers(0, n - 1), min_size=0, max_size=min(n, 8), unique=True))
+    fanouts = tuple(draw(st.lists(st.integers(0, 6), min_size=1, max_size=3)))
+    seed = draw(st.integers(0, 2 ** 64 - 1))
+    epoch = draw(st.integers(0, 2 ** 32 - 1))
+    return n, adj, seeds, fanouts, seed, epoch
+
+
+@settings(max_examples=150, deadline=None)
+@given(_graph_and_query())
+def test_blocks_against_bruteforce_on_generated_graphs(case):
+    n, adj, seeds, fanouts, seed, epoch = case
+    rp = np.zeros(n + 1, dtype=np.int64)
+    rp[1:] = np.cumsum([len(adj[v]) for v in range(n)])
+    ci = np.array([u for v in range(n) for u in adj[v]], dtype=np.int32)
+    frontier, tiers, hops = _blocks_py(adj, seeds, fanouts, seed, epoch)
+    b = oracle.sample_blocks(rp, ci, np.array(seeds, dtype=np.int32), fanouts, seed, epoch)
+    assert b.nodes.tolist() == frontier
+    assert b.tier_off.tolist() == np.concatenate([[0], np.cumsum([len(t) for t in tiers])]).tolist()
+    for h, rows in enumerate(hops):
+        assert b.nbr[h].tolist() == [u for r in rows for u in r]
+        assert b.indptr[h].tolist() == np.concatenate([[0], np.cumsum([len(r) for r in rows])]).tolist()
+        pos = {v: i for i, v in enumerate(b.nodes.tolist())}
+        assert b.nbr_local[h].tolist() == [pos[u] for r in rows for u in r]
