@@ -84,6 +84,35 @@ def test_blocks_handmade_graph(B, ctx, fanouts, rp_dtype):
         assert_batch_equal(hip, orc, len(fanouts), f"seed={seed} epoch={epoch}")
 
 
+def test_blocks_on_generated_csr(B, ctx):
+    """Randomised: arbitrary CSR rows (repeated neighbours, self loops, empty rows), random distinct seeds, fan-outs
+    that exercise the whole-row branch, both draw kernels and "all neighbours", both offset widths."""
+    from hypothesis import given, settings, strategies as st
+
+    @st.composite
+    def case(draw):
+        n = draw(st.integers(1, 60))
+        rows = [draw(st.lists(st.integers(0, n - 1), max_size=draw(st.sampled_from([0, 3, 8, 45])))) for _ in range(n)]
+        seeds = draw(st.lists(st.integers(0, n - 1), max_size=min(n, 12), unique=True))
+        fanouts = tuple(draw(st.lists(st.sampled_from([-1, 0, 1, 2, 5, 8, 9, 16, 17, 32, 33, 40]), min_size=1, max_size=3)))
+        return rows, seeds, fanouts, draw(st.integers(0, 2 ** 64 - 1)), draw(st.integers(0, 2 ** 32 - 1)), draw(st.booleans())
+
+    @settings(max_examples=120, deadline=None)
+    @given(case())
+    def run(c):
+        rows, seeds, fanouts, seed, epoch, wide = c
+        rp = np.zeros(len(rows) + 1, dtype=np.int64)
+        rp[1:] = np.cumsum([len(r) for r in rows])
+        ci = np.array([u for r in rows for u in r], dtype=np.int32)
+        csr = B.CsrGraph(torch.as_tensor(rp, device=DEV).to(torch.int64 if wide else torch.int32),
+                         _i32(ci) if ci.size else torch.empty(0, dtype=torch.int32, device=DEV))
+        hip = _run_blocks(B, ctx, csr, np.array(seeds, dtype=np.int32), fanouts, seed, epoch)
+        orc = oracle.sample_blocks(rp, ci, np.array(seeds, dtype=np.int32), fanouts, seed, epoch)
+        assert_batch_equal(hip, orc, len(fanouts), f"fanouts={fanouts} seeds={seeds}")
+
+    run()
+
+
 def test_blocks_degenerate_inputs(B, ctx):
     log("[blocks degenerate]")
     rp = np.array([0, 0, 1, 2, 2], dtype=np.int64)          # 0 and 3 isolated, 1 <-> 2
