@@ -198,7 +198,7 @@ def test_empty_and_isolated_inputs():
 
 
 # ---- randomised: the C oracle against the dictionary-and-bigint reimplementation on generated graphs
-from hypothesis import given, settings, strategies as st  # noqa: E402
+from hypothesis import HealthCheck, given, settings, strategies as st  # noqa: E402
 
 
 @st.composite
@@ -218,7 +218,7 @@ def _graph_and_query(draw):
     return n, adj, seeds, fanouts, seed, epoch
 
 
-@settings(max_examples=150, deadline=None)
+@settings(max_examples=150, deadline=None, derandomize=True, suppress_health_check=list(HealthCheck))
 @given(_graph_and_query())
 def test_blocks_against_bruteforce_on_generated_graphs(case):
     n, adj, seeds, fanouts, seed, epoch = case
