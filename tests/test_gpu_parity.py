@@ -498,6 +498,44 @@ def test_build_cache_edge_cases(B, ctx, capacity):
     assert np.array_equal(cache.cache_rows[:k, :dim].cpu().numpy(), X[ids_orc])
 
 
+def test_build_cache_on_generated_counts(B, ctx):
+    """Randomised TopHot: counts with heavy ties, zeros and values on every byte boundary of the radix select."""
+    from hypothesis import HealthCheck, given, settings, strategies as st
+    special = [0, 1, 2, 255, 256, 257, 65535, 65536, 2 ** 24 - 1, 2 ** 24, 2 ** 31, 2 ** 32 - 1]
+
+    @st.composite
+    def case(draw):
+        n = draw(st.integers(1, 2500))
+        pool = draw(st.lists(st.sampled_from(special) | st.integers(0, 5), min_size=1, max_size=6))
+        seed = draw(st.integers(0, 2 ** 31))
+        cap = draw(st.sampled_from([0, 1, 2, 7, 64, 500, 2499, 2500, 10 ** 6]))
+        p_local = draw(st.sampled_from([0.0, 0.3, 1.0]))
+        return n, pool, seed, cap, p_local
+
+    @settings(max_examples=80, deadline=None, derandomize=True, suppress_health_check=list(HealthCheck))
+    @given(case())
+    def run(c):
+        n, pool, seed, cap, p_local = c
+        rng = np.random.default_rng(seed)
+        counts = np.array(pool, dtype=np.uint64)[rng.integers(0, len(pool), size=n)].astype(np.uint32)
+        home = synth.stores.make_home(torch.from_numpy(rng.random(n) < p_local))
+        cache = B.FeatureCache(n, min(cap, n), 4, DEV)
+        cache.c_struct.capacity_rows = cap
+        ctx.build_cache(torch.from_numpy(counts.view(np.int32)).to(DEV), home.to(DEV), None, 4, cache)
+        torch.cuda.synchronize()
+        ids_orc, loc_orc = oracle.build_cache(counts, home.numpy(), cap)
+        k = int(cache.num_cached.item())
+        assert k == ids_orc.size
+        assert np.array_equal(cache.cache_ids[:k].cpu().numpy(), ids_orc)
+        assert np.array_equal(cache.loc.cpu().numpy(), loc_orc)
+        hits, total = ctx.cache_hit_curve(torch.from_numpy(counts.view(np.int32)).to(DEV), home.to(DEV), [cap])
+        torch.cuda.synchronize()
+        want_hits, want_total = oracle.cache_hit_curve(counts, home.numpy(), [cap])
+        assert int(hits[0].item()) == int(want_hits[0]) and int(total.item()) == want_total
+
+    run()
+
+
 def test_build_cache_all_local(B, ctx):
     n = 300
     home = synth.stores.make_home(torch.ones(n, dtype=torch.bool))
