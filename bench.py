@@ -125,7 +125,7 @@ def main():
     ap.add_argument("--one-stream", action="store_true", help="copy miss rows on the same stream as the HBM rows")
     ap.add_argument("--bulk-fill", action="store_true",
                     help="pull all cached rows in one go after TopHot instead of batch by batch ahead of the gathers")
-    ap.add_argument("--sampler-streams", type=int, default=3, help="batches sampled side by side during the offline stage")
+    ap.add_argument("--sampler-streams", type=int, default=2, help="batches sampled side by side during the offline stage")
     ap.add_argument("--no-double-buffer", action="store_true",
                     help="with more than one epoch of steps: do not precompute epoch e+1 while epoch e is served")
     ap.add_argument("--early-pull", action="store_true",
@@ -135,6 +135,8 @@ def main():
     ap.add_argument("--queue-depth", type=int, default=3, help="output buffers the gathers may run ahead of the consumer")
     ap.add_argument("--no-plan", action="store_true",
                     help="prefetch with a claim pass over every batch instead of the per-epoch prefetch plan")
+    ap.add_argument("--sample-group", type=int, default=8,
+                    help="batches sampled by one rg_sample_blocks_group call")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -180,7 +182,7 @@ def main():
     with torch.cuda.stream(main_stream):
         pipe = EpochPipeline(wl, device=dev, max_batches=min(max(steps, warmup, 1), bpe), two_streams=not args.one_stream,
                              prefetch=not args.bulk_fill, sampler_streams=args.sampler_streams,
-                             double_buffer=(steps > bpe and not args.no_double_buffer), early_pull=args.early_pull, planned_prefetch=not args.no_plan,
+                             double_buffer=(steps > bpe and not args.no_double_buffer), early_pull=args.early_pull, planned_prefetch=not args.no_plan, sample_group=args.sample_group,
                              consumer=None if args.consumer == "none" else args.consumer,
                              queue_depth=args.queue_depth if args.consumer != "none" else 1)
         ctx = pipe.ctx
@@ -234,7 +236,7 @@ def main():
                    "fanouts": list(cfg.fanouts), "batch_size": cfg.batch_size, "epochs_timed": totals["epochs"],
                    "cache_capacity_rows": wl.capacity_rows, "miss_stream": "shared" if args.one_stream else "separate",
                    "cache_fill": "bulk" if args.bulk_fill else "prefetch by first use",
-                   "sampler_streams": args.sampler_streams,
+                   "sampler_streams": args.sampler_streams, "sample_group": args.sample_group,
                    "double_buffered_cache": bool(steps > bpe and not args.no_double_buffer),
                    "early_pull": pipe.early_pull, "planned_prefetch": pipe.planned, "consumer": args.consumer,
                    "queue_depth": pipe.queue_depth},

@@ -75,6 +75,8 @@ typedef enum {
 #define RG_MAX_FANOUT 1024
 #define RG_FANOUT_ALL (-1)
 #define RG_MAX_HOPS 8
+/* Most batches one rg_sample_blocks_group call samples side by side. */
+#define RG_MAX_GROUP 8
 
 typedef struct rg_ctx rg_ctx;
 
@@ -153,6 +155,15 @@ RG_API rg_status rg_blocks_bounds(int64_t num_nodes, int64_t num_edges, int64_t 
 RG_API rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds, int32_t num_seeds,
                            const int32_t* fanouts, int32_t num_hops, uint64_t seed, uint32_t epoch,
                            const rg_blocks* out, void* stream);
+
+/* The same for `group` batches at once (1 <= group <= RG_MAX_GROUP): batch g has seeds[g]
+ * (num_seeds[g] of them) and writes out[g]; fan-outs, seed and epoch are shared.  The results are
+ * exactly those of `group` separate calls; the kernels of a hop take all the batches in one launch
+ * (most per-batch kernels are far smaller than the device).  seeds: host array[group] of device
+ * pointers; num_seeds: host int32[group]; out: host array[group]. */
+RG_API rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, const int32_t* const* seeds,
+                                        const int32_t* num_seeds, const int32_t* fanouts, int32_t num_hops,
+                                        uint64_t seed, uint32_t epoch, const rg_blocks* out, void* stream);
 
 /* ---- Alg. 1 line 2 / Section IV: access frequency freq(n) -------------------------------
  * counts[v] += number of occurrences of v in nodes[0..n).  counts accumulates over calls

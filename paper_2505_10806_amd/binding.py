@@ -17,6 +17,7 @@ RG_OK, RG_ERR_INVALID_ARG, RG_ERR_CAPACITY, RG_ERR_OOM, RG_ERR_HIP, RG_ERR_STATE
 RG_MAX_FANOUT = 1024
 RG_FANOUT_ALL = -1
 RG_MAX_HOPS = 8
+RG_MAX_GROUP = 8
 RG_K_GATHER_HBM, RG_K_GATHER_MISS, RG_K_SAMPLE, RG_K_HISTOGRAM, RG_K_CACHE_FILL, RG_K_AGGREGATE = range(6)
 
 _STATUS_NAMES = {0: "RG_OK", 1: "RG_ERR_INVALID_ARG", 2: "RG_ERR_CAPACITY", 3: "RG_ERR_OOM",
@@ -75,6 +76,8 @@ def _load():
     L.rg_blocks_bounds.argtypes = [c_i64, c_i64, c_i64, c_p, c_i32, c_p, c_p]
     L.rg_sample_blocks.argtypes = [c_p, ctypes.POINTER(rg_csr), c_p, c_i32, c_p, c_i32, c_u64, c_u32,
                                    ctypes.POINTER(rg_blocks), c_p]
+    L.rg_sample_blocks_group.argtypes = [c_p, ctypes.POINTER(rg_csr), c_i32, ctypes.POINTER(c_p), ctypes.POINTER(c_i32), c_p,
+                                         c_i32, c_u64, c_u32, ctypes.POINTER(rg_blocks), c_p]
     L.rg_access_histogram.argtypes = [c_p, c_p, c_i64, c_p, c_p, c_i64, c_p]
     L.rg_access_histogram_epoch.argtypes = [c_p, c_p, c_i64, c_p, c_i32, c_i32, c_i32, c_p, c_p, c_i64, c_p]
     L.rg_plan_prefetch.argtypes = [c_p, ctypes.POINTER(rg_cache), c_p, c_p, c_i64, ctypes.POINTER(rg_prefetch_plan), c_p]
@@ -91,7 +94,7 @@ def _load():
     L.rg_profile_enable.argtypes = [c_p, ctypes.c_int]
     L.rg_profile_reset.argtypes = [c_p]
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
-    for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks",
+    for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group",
                  "rg_access_histogram", "rg_access_histogram_epoch", "rg_build_cache", "rg_cache_hit_curve",
                  "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_prefetch_planned", "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
         getattr(L, name).restype = ctypes.c_int
@@ -101,7 +104,8 @@ def _load():
 _lib = _load()
 
 EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "rg_reserve", "rg_epoch_schedule",
-                    "rg_blocks_bounds", "rg_sample_blocks", "rg_access_histogram", "rg_access_histogram_epoch",
+                    "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group", "rg_access_histogram",
+                    "rg_access_histogram_epoch",
                     "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_plan_prefetch",
                     "rg_prefetch_planned", "rg_stage_rows", "rg_commit_staged_rows",
                     "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
@@ -177,6 +181,19 @@ class Context:
         self._check(_lib.rg_sample_blocks(self._h, ctypes.byref(csr.c_struct), _ptr(seeds, torch.int32, "cuda", "seeds"),
                                           int(num_seeds), fo, len(fanouts), int(seed), int(epoch),
                                           ctypes.byref(out.c_struct), _stream_handle(stream)))
+
+    # -- rg_sample_blocks_group
+    def sample_blocks_group(self, csr, seeds, fanouts, seed, epoch, outs, stream=None):
+        """seeds: list of int32 cuda tensors (one per batch); outs: list of BlockBuffers of the same length."""
+        g = len(seeds)
+        if g != len(outs) or not 1 <= g <= RG_MAX_GROUP:
+            raise ValueError(f"sample_blocks_group: between 1 and {RG_MAX_GROUP} batches with one BlockBuffers each")
+        ptrs = (c_p * g)(*[_ptr(t, torch.int32, "cuda", "seeds") for t in seeds])
+        nums = (c_i32 * g)(*[t.numel() for t in seeds])
+        structs = (rg_blocks * g)(*[o.c_struct for o in outs])
+        fo = (c_i32 * len(fanouts))(*[int(f) for f in fanouts])
+        self._check(_lib.rg_sample_blocks_group(self._h, ctypes.byref(csr.c_struct), g, ptrs, nums, fo, len(fanouts),
+                                                int(seed), int(epoch), structs, _stream_handle(stream)))
 
     # -- rg_access_histogram
     def access_histogram(self, nodes, n, counts, n_dev=None, stream=None):

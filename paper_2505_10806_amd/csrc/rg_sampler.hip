@@ -99,63 +99,82 @@ __global__ void __launch_bounds__(256) k_sched_out(const int32_t* __restrict__ i
     if (i < n) out[i] = ids[i];
 }
 
+// ---------------------------------------------------------------------------- batches of a group
+// Several batches are sampled by the same launches: blockIdx.y selects the batch, which brings its own outputs
+// (SampleGroup, passed by value) and its own slice of the scratch (SampleScratch).  Most kernels of one batch are
+// far smaller than the device (hop 0 of a 4096-seed batch is 16 workgroups), so a group fills it better and pays
+// every launch once.
+constexpr int kMaxGroup = RG_MAX_GROUP;
+
+struct SampleGroup {
+    const int32_t* seeds[kMaxGroup];
+    int32_t num_seeds[kMaxGroup];
+    int32_t* nodes[kMaxGroup];
+    int32_t* tier_off[kMaxGroup];
+    int32_t* indptr[kMaxGroup];       // of the current hop
+    int32_t* nbr[kMaxGroup];
+    int32_t* nbr_local[kMaxGroup];    // may be NULL
+    int32_t* edges_out[kMaxGroup];    // may be NULL
+};
+
+struct SampleScratch {
+    uint32_t* visited;                // [group][words]
+    uint32_t* fresh;                  // [group][words]
+    int32_t* pos;                     // [group][num_nodes]
+    int32_t* chunk_sum;               // [group][chunk_stride]
+    int64_t* row_start;               // [group][frontier_stride]
+    int32_t* row_deg;                 // [group][frontier_stride]
+    int64_t words, num_nodes, chunk_stride, frontier_stride;
+};
+
 // ---------------------------------------------------------------------------- batch start
 __global__ void __launch_bounds__(256) k_clear_words(uint32_t* __restrict__ w, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) w[i] = 0u;
 }
 
-__global__ void __launch_bounds__(256) k_mark_seeds(const int32_t* __restrict__ seeds, int32_t num_seeds,
-                                                    int32_t* __restrict__ nodes, int32_t* __restrict__ pos,
-                                                    uint32_t* __restrict__ visited, int32_t* __restrict__ tier_off) {
+__global__ void __launch_bounds__(256) k_mark_seeds(const SampleGroup G, const SampleScratch S) {
+    const int g = blockIdx.y;
+    const int num_seeds = G.num_seeds[g];
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) { tier_off[0] = 0; tier_off[1] = num_seeds; }
+    if (i == 0) { G.tier_off[g][0] = 0; G.tier_off[g][1] = num_seeds; }
     if (i >= num_seeds) return;
-    const int32_t v = seeds[i];
-    nodes[i] = v;
-    pos[v] = i;
-    atomicOr(&visited[(uint32_t)v >> 5], 1u << (v & 31));
+    const int32_t v = G.seeds[g][i];
+    G.nodes[g][i] = v;
+    S.pos[g * S.num_nodes + v] = i;
+    atomicOr(&S.visited[g * S.words + ((uint32_t)v >> 5)], 1u << (v & 31));
 }
 
 // ---------------------------------------------------------------------------- per hop: sizes
 // indptr[i] = exclusive prefix of m within the node's 256-node chunk; chunk_sum[b] = chunk total;
 // row_start[i], row_deg[i] = the node's adjacency row.
 template <typename RP>
-__global__ void __launch_bounds__(kChunk) k_hop_count(const RP* __restrict__ row_ptr, const int32_t* __restrict__ nodes,
-                                                      const int32_t* __restrict__ n_frontier_ptr, int fanout,
-                                                      int32_t* __restrict__ indptr, int32_t* __restrict__ chunk_sum,
-                                                      int64_t* __restrict__ row_start, int32_t* __restrict__ row_deg) {
+__global__ void __launch_bounds__(kChunk) k_hop_count(const RP* __restrict__ row_ptr, const SampleGroup G, const SampleScratch S,
+                                                      int hop, int fanout) {
     __shared__ int smem[kChunk / RG_WAVE + 1];
-    const int n_h = *n_frontier_ptr;
+    const int g = blockIdx.y;
+    const int n_h = G.tier_off[g][hop + 1];
     const int64_t first = (int64_t)blockIdx.x * kChunk;
     if (first >= n_h) return;                       // uniform per workgroup
     const int64_t i = first + threadIdx.x;
     int m = 0;
     if (i < n_h) {
         int64_t start, deg;
-        rg_row_extent(row_ptr, nodes[i], start, deg);
+        rg_row_extent(row_ptr, G.nodes[g][i], start, deg);
         m = (fanout < 0 || deg <= fanout) ? (int)deg : fanout;
-        row_start[i] = start;             // kept for the draw kernel: one coalesced read there instead of a second
-        row_deg[i] = (int32_t)deg;        // random lookup of row_ptr
+        S.row_start[g * S.frontier_stride + i] = start;   // kept for the draw kernel: one coalesced read there instead
+        S.row_deg[g * S.frontier_stride + i] = (int32_t)deg;   // of a second random lookup of row_ptr
     }
     int total;
     const int excl = rg_block_excl_scan<kChunk / RG_WAVE>(m, smem, &total);
-    if (i < n_h) indptr[i] = excl;
-    if (threadIdx.x == 0) chunk_sum[blockIdx.x] = total;
+    if (i < n_h) G.indptr[g][i] = excl;
+    if (threadIdx.x == 0) S.chunk_sum[g * S.chunk_stride + blockIdx.x] = total;
 }
 
-// In-place exclusive scan of data[0..n) by one workgroup, n = ceil(count / per) with count = *count_ptr
-// (or fixed_count when count_ptr is NULL).  The grand total plus *base_ptr (or 0) is stored to
-// total_out[count] when total_at_count is set (the edge total behind the last indptr entry), else to
-// total_out[0].
-__global__ void __launch_bounds__(1024) k_scan_sums(int32_t* __restrict__ data, const int32_t* __restrict__ count_ptr,
-                                                    int64_t fixed_count, int per, const int32_t* __restrict__ base_ptr,
-                                                    int32_t* __restrict__ total_out, int total_at_count,
-                                                    int32_t* __restrict__ total_copy) {
+// In-place exclusive scan of data[0..n) by one workgroup; returns (to thread 0) the grand total.
+__device__ __forceinline__ int rg_scan_in_place(int32_t* __restrict__ data, int64_t n) {
     __shared__ int smem[1024 / RG_WAVE + 1];
     __shared__ int carry_s;
-    const int64_t count = count_ptr ? (int64_t)*count_ptr : fixed_count;
-    const int64_t n = (count + per - 1) / per;
     if (threadIdx.x == 0) carry_s = 0;
     __syncthreads();
     for (int64_t base = 0; base < n; base += 1024) {
@@ -169,12 +188,25 @@ __global__ void __launch_bounds__(1024) k_scan_sums(int32_t* __restrict__ data, 
         if (threadIdx.x == 0) carry_s = carry + total;
         __syncthreads();
     }
+    return carry_s;
+}
+
+// Chunk totals of a hop -> exclusive offsets; the hop's edge total goes behind the last indptr entry.
+__global__ void __launch_bounds__(1024) k_scan_hop(const SampleGroup G, const SampleScratch S, int hop) {
+    const int g = blockIdx.y;
+    const int n_h = G.tier_off[g][hop + 1];
+    const int total = rg_scan_in_place(S.chunk_sum + g * S.chunk_stride, ((int64_t)n_h + kChunk - 1) / kChunk);
     if (threadIdx.x == 0) {
-        const int b = base_ptr ? *base_ptr : 0;
-        const int64_t slot = total_at_count ? count : 0;
-        total_out[slot] = b + carry_s;
-        if (total_copy) *total_copy = b + carry_s;
+        G.indptr[g][n_h] = total;
+        if (G.edges_out[g]) *G.edges_out[g] = total;
     }
+}
+
+// Per-block counts of fresh ids -> exclusive offsets; the end of the new tier goes to tier_off[hop + 2].
+__global__ void __launch_bounds__(1024) k_scan_tier(const SampleGroup G, const SampleScratch S, int hop, int tier_blocks) {
+    const int g = blockIdx.y;
+    const int total = rg_scan_in_place(S.chunk_sum + g * S.chunk_stride, tier_blocks);
+    if (threadIdx.x == 0) G.tier_off[g][hop + 2] = G.tier_off[g][hop + 1] + total;
 }
 
 // ---------------------------------------------------------------------------- per hop: draw + read
@@ -187,16 +219,21 @@ __device__ __forceinline__ void rg_mark_fresh(int32_t u, const uint32_t* __restr
 
 // General sampler: one wavefront (= one 64-thread workgroup) per frontier node, any fan-out up to
 // RG_MAX_FANOUT.  The Floyd set lives in LDS; step i tests membership of t with all lanes.
-__global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int64_t* __restrict__ row_start, const int32_t* __restrict__ row_deg,
-                                                            const int32_t* __restrict__ col_idx, const int32_t* __restrict__ nodes,
-                                                            const int32_t* __restrict__ n_frontier_ptr, int fanout, uint32_t hop,
-                                                            uint32_t k0, uint32_t k1, uint32_t epoch,
-                                                            int32_t* __restrict__ indptr, const int32_t* __restrict__ chunk_sum,
-                                                            int32_t* __restrict__ nbr, const uint32_t* __restrict__ visited,
-                                                            uint32_t* __restrict__ fresh) {
+__global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int32_t* __restrict__ col_idx, const SampleGroup G,
+                                                            const SampleScratch S, int fanout, uint32_t hop, uint32_t k0,
+                                                            uint32_t k1, uint32_t epoch) {
     __shared__ uint32_t draws[RG_MAX_FANOUT];
     __shared__ uint32_t chosen[RG_MAX_FANOUT];
-    const int n_h = *n_frontier_ptr;
+    const int g = blockIdx.y;
+    const int n_h = G.tier_off[g][hop + 1];
+    const int32_t* __restrict__ nodes = G.nodes[g];
+    int32_t* __restrict__ indptr = G.indptr[g];
+    int32_t* __restrict__ nbr = G.nbr[g];
+    const int32_t* __restrict__ chunk_sum = S.chunk_sum + g * S.chunk_stride;
+    const int64_t* __restrict__ row_start = S.row_start + g * S.frontier_stride;
+    const int32_t* __restrict__ row_deg = S.row_deg + g * S.frontier_stride;
+    const uint32_t* __restrict__ visited = S.visited + g * S.words;
+    uint32_t* __restrict__ fresh = S.fresh + g * S.words;
     const int lane = threadIdx.x;
     for (int64_t i = blockIdx.x; i < n_h; i += gridDim.x) {
         const int32_t v = nodes[i];
@@ -244,17 +281,19 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int64_t* __re
 // of their picks in LDS in output order, then the whole workgroup reads col_idx and writes nbr with
 // consecutive lanes on consecutive output slots.
 template <int KMAX>
-__global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const int64_t* __restrict__ row_start, const int32_t* __restrict__ row_deg,
-                                                              const int32_t* __restrict__ col_idx, const int32_t* __restrict__ nodes,
-                                                              const int32_t* __restrict__ n_frontier_ptr, int fanout, uint32_t hop,
-                                                              uint32_t k0, uint32_t k1, uint32_t epoch,
-                                                              int32_t* __restrict__ indptr, const int32_t* __restrict__ chunk_sum,
-                                                              int32_t* __restrict__ nbr, const uint32_t* __restrict__ visited,
-                                                              uint32_t* __restrict__ fresh) {
+__global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const int32_t* __restrict__ col_idx, const SampleGroup G,
+                                                              const SampleScratch S, int fanout, uint32_t hop, uint32_t k0,
+                                                              uint32_t k1, uint32_t epoch) {
     extern __shared__ uint32_t staged[];                 // kChunk * fanout col_idx offsets
-    const int n_h = *n_frontier_ptr;
+    const int g = blockIdx.y;
+    const int n_h = G.tier_off[g][hop + 1];
     const int64_t first = (int64_t)blockIdx.x * kChunk;
     if (first >= n_h) return;                            // uniform per workgroup
+    int32_t* __restrict__ indptr = G.indptr[g];
+    int32_t* __restrict__ nbr = G.nbr[g];
+    const int32_t* __restrict__ chunk_sum = S.chunk_sum + g * S.chunk_stride;
+    const uint32_t* __restrict__ visited = S.visited + g * S.words;
+    uint32_t* __restrict__ fresh = S.fresh + g * S.words;
     const int64_t i = first + threadIdx.x;
     const int k = fanout;
     // chunk_sum[b] is the exclusive offset of chunk b; the chunk's edge count follows from its successor
@@ -263,8 +302,8 @@ __global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const int64_t* __r
     const bool last_chunk = first + kChunk >= n_h;
     const int chunk_edges = (last_chunk ? indptr[n_h] : chunk_sum[blockIdx.x + 1]) - base;
     if (i < n_h) {
-        const int32_t v = nodes[i];
-        const int64_t start = row_start[i], deg = row_deg[i];
+        const int32_t v = G.nodes[g][i];
+        const int64_t start = S.row_start[g * S.frontier_stride + i], deg = S.row_deg[g * S.frontier_stride + i];
         const int off = indptr[i];                       // chunk-local exclusive prefix from k_hop_count
         indptr[i] = base + off;
         if (deg <= k) {                                  // whole row, CSR order
@@ -304,38 +343,42 @@ __global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const int64_t* __r
 }
 
 // ---------------------------------------------------------------------------- per hop: new tier
-__global__ void __launch_bounds__(256) k_tier_count(const uint32_t* __restrict__ fresh, int64_t words,
-                                                    int32_t* __restrict__ blk_sum) {
+__global__ void __launch_bounds__(256) k_tier_count(const SampleScratch S) {
+    const int g = blockIdx.y;
+    const uint32_t* __restrict__ fresh = S.fresh + g * S.words;
     const int64_t w0 = (int64_t)blockIdx.x * kWordsPerBlock + threadIdx.x * 4;
     int c = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-        if (w0 + q < words) c += __popc(fresh[w0 + q]);
+        if (w0 + q < S.words) c += __popc(fresh[w0 + q]);
     c = rg_wave_sum(c);
     __shared__ int part[4];
     if (rg_lane() == 0) part[threadIdx.x >> 6] = c;
     __syncthreads();
-    if (threadIdx.x == 0) blk_sum[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+    if (threadIdx.x == 0) S.chunk_sum[g * S.chunk_stride + blockIdx.x] = part[0] + part[1] + part[2] + part[3];
 }
 
 // Emit the ids of `fresh` in ascending order behind the current frontier, record their positions,
-// fold `fresh` into `visited` and leave `fresh` all-zero.  blk_sum holds exclusive block offsets.
-__global__ void __launch_bounds__(256) k_tier_emit(uint32_t* __restrict__ fresh, uint32_t* __restrict__ visited, int64_t words,
-                                                   const int32_t* __restrict__ blk_sum, const int32_t* __restrict__ tier_start_ptr,
-                                                   int32_t* __restrict__ nodes, int32_t* __restrict__ pos) {
+// fold `fresh` into `visited` and leave `fresh` all-zero.  chunk_sum holds exclusive block offsets.
+__global__ void __launch_bounds__(256) k_tier_emit(const SampleGroup G, const SampleScratch S, int hop) {
     __shared__ int smem[256 / RG_WAVE + 1];
+    const int g = blockIdx.y;
+    uint32_t* __restrict__ fresh = S.fresh + g * S.words;
+    uint32_t* __restrict__ visited = S.visited + g * S.words;
+    int32_t* __restrict__ nodes = G.nodes[g];
+    int32_t* __restrict__ pos = S.pos + g * S.num_nodes;
     const int64_t w0 = (int64_t)blockIdx.x * kWordsPerBlock + threadIdx.x * 4;
     uint32_t bits[4];
     int c = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        bits[q] = (w0 + q < words) ? fresh[w0 + q] : 0u;
+        bits[q] = (w0 + q < S.words) ? fresh[w0 + q] : 0u;
         c += __popc(bits[q]);
     }
     int total;
     const int excl = rg_block_excl_scan<256 / RG_WAVE>(c, smem, &total);
     if (total == 0) return;                          // uniform: nothing fresh in this block
-    int out = *tier_start_ptr + blk_sum[blockIdx.x] + excl;
+    int out = G.tier_off[g][hop + 1] + S.chunk_sum[g * S.chunk_stride + blockIdx.x] + excl;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         uint32_t b = bits[q];
@@ -355,10 +398,13 @@ __global__ void __launch_bounds__(256) k_tier_emit(uint32_t* __restrict__ fresh,
 }
 
 // nbr_local[e] = position of nbr[e] in the extended frontier; the hop's edge count is indptr[n_h].
-__global__ void __launch_bounds__(256) k_relabel(const int32_t* __restrict__ nbr, const int32_t* __restrict__ indptr,
-                                                 const int32_t* __restrict__ n_frontier_ptr, const int32_t* __restrict__ pos,
-                                                 int32_t* __restrict__ nbr_local) {
-    const int n = indptr[*n_frontier_ptr];
+__global__ void __launch_bounds__(256) k_relabel(const SampleGroup G, const SampleScratch S, int hop) {
+    const int g = blockIdx.y;
+    int32_t* __restrict__ nbr_local = G.nbr_local[g];
+    if (!nbr_local) return;
+    const int32_t* __restrict__ nbr = G.nbr[g];
+    const int32_t* __restrict__ pos = S.pos + g * S.num_nodes;
+    const int n = G.indptr[g][G.tier_off[g][hop + 1]];
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x)
         nbr_local[e] = pos[nbr[e]];
 }
@@ -410,82 +456,122 @@ rg_status rg_epoch_schedule(rg_ctx* ctx, const int32_t* train_ids, int64_t n, ui
     return RG_OK;
 }
 
-rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds, int32_t num_seeds,
-                           const int32_t* fanouts, int32_t num_hops, uint64_t seed, uint32_t epoch,
-                           const rg_blocks* out, void* stream) {
+rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, const int32_t* const* seeds,
+                                 const int32_t* num_seeds, const int32_t* fanouts, int32_t num_hops, uint64_t seed,
+                                 uint32_t epoch, const rg_blocks* out, void* stream) {
     if (!ctx) return RG_ERR_INVALID_ARG;
-    RG_REQUIRE(ctx, csr && out && fanouts, "rg_sample_blocks: null argument");
+    RG_REQUIRE(ctx, group >= 1 && group <= RG_MAX_GROUP, "rg_sample_blocks: group = %d not in [1,%d]", group, RG_MAX_GROUP);
+    RG_REQUIRE(ctx, csr && out && fanouts && seeds && num_seeds, "rg_sample_blocks: null argument");
     RG_REQUIRE(ctx, num_hops >= 1 && num_hops <= RG_MAX_HOPS, "rg_sample_blocks: num_hops = %d not in [1,%d]", num_hops, RG_MAX_HOPS);
-    RG_REQUIRE(ctx, num_seeds >= 0, "rg_sample_blocks: num_seeds is negative");
     RG_REQUIRE(ctx, csr->num_nodes >= 0 && csr->num_nodes <= (int64_t)RG_ROW_MASK + 1, "rg_sample_blocks: num_nodes out of range");
     RG_REQUIRE(ctx, csr->num_edges >= 0, "rg_sample_blocks: num_edges is negative");
     RG_REQUIRE(ctx, csr->row_ptr_bits == 32 || csr->row_ptr_bits == 64, "rg_sample_blocks: row_ptr_bits must be 32 or 64");
     RG_REQUIRE(ctx, csr->row_ptr_bits == 64 || csr->num_edges < (1ll << 31), "rg_sample_blocks: 32-bit row_ptr with >= 2^31 edges");
     RG_REQUIRE(ctx, csr->row_ptr && (csr->col_idx || csr->num_edges == 0), "rg_sample_blocks: null CSR array");
-    RG_REQUIRE(ctx, num_seeds <= csr->num_nodes, "rg_sample_blocks: more seeds than nodes (seeds must be distinct)");
-    RG_REQUIRE(ctx, seeds || num_seeds == 0, "rg_sample_blocks: seeds is NULL");
-    RG_REQUIRE(ctx, out->nodes && out->tier_off && out->indptr && out->indptr_cap && out->nbr && out->nbr_cap,
-               "rg_sample_blocks: null output pointer");
     for (int h = 0; h < num_hops; ++h)
         RG_REQUIRE(ctx, fanouts[h] == RG_FANOUT_ALL || (fanouts[h] >= 0 && fanouts[h] <= RG_MAX_FANOUT),
                    "rg_sample_blocks: fanouts[%d] = %d not in [0,%d] and not RG_FANOUT_ALL", h, fanouts[h], RG_MAX_FANOUT);
-    int64_t fub[RG_MAX_HOPS + 1], eub[RG_MAX_HOPS];
-    rg_blocks_bounds(csr->num_nodes, csr->num_edges, num_seeds, fanouts, num_hops, fub, eub);
-    for (int h = 0; h < num_hops; ++h) {
-        RG_REQUIRE(ctx, eub[h] < (1ll << 31), "rg_sample_blocks: hop %d may produce >= 2^31 edges", h);
-        RG_REQUIRE(ctx, out->indptr[h] && (out->nbr[h] || eub[h] == 0), "rg_sample_blocks: null buffer for hop %d", h);
-        if (out->indptr_cap[h] < fub[h] + 1)
-            return rg_set_error(ctx, RG_ERR_CAPACITY, "rg_sample_blocks: indptr_cap[%d] = %lld < %lld", h,
-                                (long long)out->indptr_cap[h], (long long)(fub[h] + 1));
-        if (out->nbr_cap[h] < eub[h])
-            return rg_set_error(ctx, RG_ERR_CAPACITY, "rg_sample_blocks: nbr_cap[%d] = %lld < %lld", h,
-                                (long long)out->nbr_cap[h], (long long)eub[h]);
-        RG_REQUIRE(ctx, !out->nbr_local || out->nbr_local[h] || eub[h] == 0, "rg_sample_blocks: nbr_local[%d] is NULL", h);
+    // static bounds: per batch for the capacity checks, their maximum for the launch shapes
+    int64_t fub_max[RG_MAX_HOPS + 1] = {0}, eub_max[RG_MAX_HOPS] = {0};
+    int32_t seeds_max = 0;
+    for (int g = 0; g < group; ++g) {
+        const rg_blocks* o = out + g;
+        RG_REQUIRE(ctx, num_seeds[g] >= 0, "rg_sample_blocks: num_seeds is negative (batch %d)", g);
+        RG_REQUIRE(ctx, num_seeds[g] <= csr->num_nodes, "rg_sample_blocks: more seeds than nodes (seeds must be distinct; batch %d)", g);
+        RG_REQUIRE(ctx, seeds[g] || num_seeds[g] == 0, "rg_sample_blocks: seeds is NULL (batch %d)", g);
+        RG_REQUIRE(ctx, o->nodes && o->tier_off && o->indptr && o->indptr_cap && o->nbr && o->nbr_cap,
+                   "rg_sample_blocks: null output pointer (batch %d)", g);
+        int64_t fub[RG_MAX_HOPS + 1], eub[RG_MAX_HOPS];
+        rg_blocks_bounds(csr->num_nodes, csr->num_edges, num_seeds[g], fanouts, num_hops, fub, eub);
+        for (int h = 0; h < num_hops; ++h) {
+            RG_REQUIRE(ctx, eub[h] < (1ll << 31), "rg_sample_blocks: hop %d may produce >= 2^31 edges", h);
+            RG_REQUIRE(ctx, o->indptr[h] && (o->nbr[h] || eub[h] == 0), "rg_sample_blocks: null buffer for hop %d (batch %d)", h, g);
+            if (o->indptr_cap[h] < fub[h] + 1)
+                return rg_set_error(ctx, RG_ERR_CAPACITY, "rg_sample_blocks: indptr_cap[%d] = %lld < %lld (batch %d)", h,
+                                    (long long)o->indptr_cap[h], (long long)(fub[h] + 1), g);
+            if (o->nbr_cap[h] < eub[h])
+                return rg_set_error(ctx, RG_ERR_CAPACITY, "rg_sample_blocks: nbr_cap[%d] = %lld < %lld (batch %d)", h,
+                                    (long long)o->nbr_cap[h], (long long)eub[h], g);
+            RG_REQUIRE(ctx, !o->nbr_local || o->nbr_local[h] || eub[h] == 0, "rg_sample_blocks: nbr_local[%d] is NULL (batch %d)", h, g);
+            eub_max[h] = rg_max64(eub_max[h], eub[h]);
+        }
+        if (o->nodes_cap < fub[num_hops])
+            return rg_set_error(ctx, RG_ERR_CAPACITY, "rg_sample_blocks: nodes_cap = %lld < %lld (batch %d)", (long long)o->nodes_cap,
+                                (long long)fub[num_hops], g);
+        for (int h = 0; h <= num_hops; ++h) fub_max[h] = rg_max64(fub_max[h], fub[h]);
+        seeds_max = num_seeds[g] > seeds_max ? num_seeds[g] : seeds_max;
     }
-    if (out->nodes_cap < fub[num_hops])
-        return rg_set_error(ctx, RG_ERR_CAPACITY, "rg_sample_blocks: nodes_cap = %lld < %lld", (long long)out->nodes_cap,
-                            (long long)fub[num_hops]);
 
     RG_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t s = (hipStream_t)stream;
     const int64_t N = csr->num_nodes;
     const int64_t words = rg_div_up(N, 32);
-    rg_status st = rg_reserve(ctx, N, fub[num_hops], 0);
-    if (st != RG_OK) return st;
-    uint32_t* visited = (uint32_t*)ctx->visited.p;
-    uint32_t* fresh = (uint32_t*)ctx->fresh.p;
-    int32_t* pos = (int32_t*)ctx->pos.p;
-    int32_t* chunk_sum = (int32_t*)ctx->chunk_sum.p;
-    int64_t* row_start = (int64_t*)ctx->row_start.p;
-    int32_t* row_deg = (int32_t*)ctx->row_deg.p;
+    const int tier_blocks = (int)rg_max64(1, rg_div_up(words, kWordsPerBlock));
+    SampleScratch S;
+    S.words = words;
+    S.num_nodes = N;
+    S.frontier_stride = rg_max64(fub_max[num_hops], 1);
+    S.chunk_stride = rg_max64(rg_div_up(S.frontier_stride, kChunk), tier_blocks) + 2;
+    rg_status st;
+    if ((st = rg_ensure(ctx, ctx->visited, (size_t)group * words * 4)) != RG_OK) return st;
+    // `fresh` must be all-zero between hops: a new allocation starts zeroed and every hop leaves it zeroed
+    if ((st = rg_ensure(ctx, ctx->fresh, (size_t)group * words * 4, true)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->pos, (size_t)group * N * 4)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->chunk_sum, (size_t)group * S.chunk_stride * 4)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->row_start, (size_t)group * S.frontier_stride * 8)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->row_deg, (size_t)group * S.frontier_stride * 4)) != RG_OK) return st;
+    S.visited = (uint32_t*)ctx->visited.p;
+    S.fresh = (uint32_t*)ctx->fresh.p;
+    S.pos = (int32_t*)ctx->pos.p;
+    S.chunk_sum = (int32_t*)ctx->chunk_sum.p;
+    S.row_start = (int64_t*)ctx->row_start.p;
+    S.row_deg = (int32_t*)ctx->row_deg.p;
     const uint32_t k0 = (uint32_t)(seed & 0xffffffffu), k1 = (uint32_t)(seed >> 32);
     const bool rp64 = csr->row_ptr_bits == 64;
 
+    SampleGroup G;
+    for (int g = 0; g < kMaxGroup; ++g) {
+        const bool live = g < group;
+        G.seeds[g] = live ? seeds[g] : nullptr;
+        G.num_seeds[g] = live ? num_seeds[g] : 0;
+        G.nodes[g] = live ? out[g].nodes : nullptr;
+        G.tier_off[g] = live ? out[g].tier_off : nullptr;
+        G.indptr[g] = G.nbr[g] = G.nbr_local[g] = G.edges_out[g] = nullptr;
+    }
+    const unsigned ug = (unsigned)group;
+
     if (words > 0) {
+        // the whole allocation is cleared: a smaller group after a larger one must not find stale bits
+        const int64_t fresh_words = (int64_t)(ctx->fresh.bytes / 4), visited_words = (int64_t)group * words;
         if (ctx->sampler_dirty) {        // an earlier call stopped between a draw kernel and its tier emit
-            k_clear_words<<<(int)rg_div_up(words, 256), 256, 0, s>>>(fresh, words);
+            k_clear_words<<<(int)rg_div_up(fresh_words, 256), 256, 0, s>>>(S.fresh, fresh_words);
             RG_LAUNCH_CHECK(ctx, "k_clear_words");
         }
         ctx->sampler_dirty = true;       // cleared again when every launch of this call has been queued
-        k_clear_words<<<(int)rg_div_up(words, 256), 256, 0, s>>>(visited, words);
+        k_clear_words<<<(int)rg_div_up(visited_words, 256), 256, 0, s>>>(S.visited, visited_words);
         RG_LAUNCH_CHECK(ctx, "k_clear_words");
     }
-    k_mark_seeds<<<grid_for(num_seeds, 256, 1 << 30), 256, 0, s>>>(seeds, num_seeds, out->nodes, pos, visited, out->tier_off);
+    k_mark_seeds<<<dim3((unsigned)grid_for(seeds_max, 256, 1 << 30), ug), 256, 0, s>>>(G, S);
     RG_LAUNCH_CHECK(ctx, "k_mark_seeds");
 
-    const int tier_blocks = (int)rg_max64(1, rg_div_up(words, kWordsPerBlock));
     for (int h = 0; h < num_hops; ++h) {
-        const int32_t* n_frontier = out->tier_off + h + 1;
-        const int count_blocks = grid_for(fub[h], kChunk, 1ll << 30);
-        int32_t* indptr = out->indptr[h];
+        bool any_local = false;
+        for (int g = 0; g < group; ++g) {
+            G.indptr[g] = out[g].indptr[h];
+            G.nbr[g] = out[g].nbr[h];
+            G.nbr_local[g] = out[g].nbr_local ? out[g].nbr_local[h] : nullptr;
+            G.edges_out[g] = out[g].num_edges ? out[g].num_edges + h : nullptr;
+            any_local = any_local || G.nbr_local[g];
+        }
+        const unsigned count_blocks = (unsigned)grid_for(fub_max[h], kChunk, 1ll << 30);
         if (rp64)
-            k_hop_count<int64_t><<<count_blocks, kChunk, 0, s>>>((const int64_t*)csr->row_ptr, out->nodes, n_frontier, fanouts[h], indptr, chunk_sum, row_start, row_deg);
+            k_hop_count<int64_t><<<dim3(count_blocks, ug), kChunk, 0, s>>>((const int64_t*)csr->row_ptr, G, S, h, fanouts[h]);
         else
-            k_hop_count<int32_t><<<count_blocks, kChunk, 0, s>>>((const int32_t*)csr->row_ptr, out->nodes, n_frontier, fanouts[h], indptr, chunk_sum, row_start, row_deg);
+            k_hop_count<int32_t><<<dim3(count_blocks, ug), kChunk, 0, s>>>((const int32_t*)csr->row_ptr, G, S, h, fanouts[h]);
         RG_LAUNCH_CHECK(ctx, "k_hop_count");
         // chunk sums -> exclusive offsets; total edge count -> indptr[n_h]
-        k_scan_sums<<<1, 1024, 0, s>>>(chunk_sum, n_frontier, 0, kChunk, nullptr, indptr, 1, out->num_edges ? out->num_edges + h : nullptr);
-        RG_LAUNCH_CHECK(ctx, "k_scan_sums");
+        k_scan_hop<<<dim3(1, ug), 1024, 0, s>>>(G, S, h);
+        RG_LAUNCH_CHECK(ctx, "k_scan_hop");
 
         const int tok = rg_prof_begin(ctx, RG_K_SAMPLE, s);
         const int F = fanouts[h];
@@ -493,35 +579,37 @@ rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds,
             const int kmax = F <= 8 ? 8 : (F <= 16 ? 16 : 32);
             const size_t lds = (size_t)kChunk * F * sizeof(uint32_t);
 #define RG_LAUNCH_FAST(KM)                                                                                            \
-    k_hop_sample_thread<KM><<<count_blocks, kChunk, lds, s>>>(row_start, row_deg, csr->col_idx, out->nodes, n_frontier, F,   \
-                                                              (uint32_t)h, k0, k1, epoch, indptr, chunk_sum, out->nbr[h],  \
-                                                              visited, fresh)
+    k_hop_sample_thread<KM><<<dim3(count_blocks, ug), kChunk, lds, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch)
             if (kmax == 8) RG_LAUNCH_FAST(8); else if (kmax == 16) RG_LAUNCH_FAST(16); else RG_LAUNCH_FAST(32);
 #undef RG_LAUNCH_FAST
         } else {
-            const int sample_blocks = grid_for(fub[h], 1, (int64_t)ctx->num_cus * 64);
-            k_hop_sample_wave<<<sample_blocks, RG_WAVE, 0, s>>>(row_start, row_deg, csr->col_idx, out->nodes, n_frontier, F, (uint32_t)h,
-                                                                k0, k1, epoch, indptr, chunk_sum, out->nbr[h], visited, fresh);
+            const unsigned sample_blocks = (unsigned)grid_for(fub_max[h], 1, (int64_t)ctx->num_cus * 64);
+            k_hop_sample_wave<<<dim3(sample_blocks, ug), RG_WAVE, 0, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch);
         }
         rg_prof_end(ctx, tok, s);
         RG_LAUNCH_CHECK(ctx, "k_hop_sample");
 
         // new tier: count fresh bits per block, scan, emit ascending
-        k_tier_count<<<tier_blocks, 256, 0, s>>>(fresh, words, chunk_sum);
+        k_tier_count<<<dim3((unsigned)tier_blocks, ug), 256, 0, s>>>(S);
         RG_LAUNCH_CHECK(ctx, "k_tier_count");
-        k_scan_sums<<<1, 1024, 0, s>>>(chunk_sum, nullptr, tier_blocks, 1, n_frontier, out->tier_off + h + 2, 0, nullptr);
-        RG_LAUNCH_CHECK(ctx, "k_scan_sums");
-        k_tier_emit<<<tier_blocks, 256, 0, s>>>(fresh, visited, words, chunk_sum, n_frontier, out->nodes, pos);
+        k_scan_tier<<<dim3(1, ug), 1024, 0, s>>>(G, S, h, tier_blocks);
+        RG_LAUNCH_CHECK(ctx, "k_scan_tier");
+        k_tier_emit<<<dim3((unsigned)tier_blocks, ug), 256, 0, s>>>(G, S, h);
         RG_LAUNCH_CHECK(ctx, "k_tier_emit");
 
-        if (out->nbr_local && eub[h] > 0) {
-            k_relabel<<<grid_for(eub[h], 256, (int64_t)ctx->num_cus * 16), 256, 0, s>>>(out->nbr[h], indptr, n_frontier, pos,
-                                                                                       out->nbr_local[h]);
+        if (any_local && eub_max[h] > 0) {
+            k_relabel<<<dim3((unsigned)grid_for(eub_max[h], 256, (int64_t)ctx->num_cus * 16), ug), 256, 0, s>>>(G, S, h);
             RG_LAUNCH_CHECK(ctx, "k_relabel");
         }
     }
     ctx->sampler_dirty = false;
     return RG_OK;
+}
+
+rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds, int32_t num_seeds,
+                           const int32_t* fanouts, int32_t num_hops, uint64_t seed, uint32_t epoch,
+                           const rg_blocks* out, void* stream) {
+    return rg_sample_blocks_group(ctx, csr, 1, &seeds, &num_seeds, fanouts, num_hops, seed, epoch, out, stream);
 }
 
 }  // extern "C"

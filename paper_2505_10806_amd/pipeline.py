@@ -50,8 +50,8 @@ class _EpochState:
 
 class EpochPipeline:
     def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True,
-                 epoch_histogram=True, sampler_streams=3, double_buffer=False, early_pull=False,
-                 queue_depth=1, consumer=None, planned_prefetch=True):
+                 epoch_histogram=True, sampler_streams=2, double_buffer=False, early_pull=False,
+                 queue_depth=1, consumer=None, planned_prefetch=True, sample_group=8):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -66,8 +66,11 @@ class EpochPipeline:
             n_lanes = max(n_lanes, 2)
         self.n_lanes = n_lanes
         self.lane_ctx = [self.ctx] + [B.Context(self.ctx.device) for _ in range(n_lanes - 1)]
-        self.lane_bufs = [B.BlockBuffers(cfg.num_nodes, wl.nnz, cfg.batch_size, cfg.fanouts, device) for _ in range(n_lanes)]
-        self.bufs = self.lane_bufs[0]
+        # every lane samples sample_group batches per call (one launch per kernel for the whole group)
+        self.sample_group = max(1, min(int(sample_group), B.RG_MAX_GROUP))
+        self.lane_bufs = [[B.BlockBuffers(cfg.num_nodes, wl.nnz, cfg.batch_size, cfg.fanouts, device)
+                           for _ in range(self.sample_group)] for _ in range(n_lanes)]
+        self.bufs = self.lane_bufs[0][0]
         self.slot = self.bufs.frontier_ub[self.H]
         self.double_buffer = double_buffer
         # consumer = "mean": the gathered rows of every batch are reduced by the mean aggregator over the batch's
@@ -178,21 +181,28 @@ class EpochPipeline:
             for _, _, s in lanes[1:]:
                 s.wait_stream(head)
             n_train = self.order.numel()
-            for i, b in enumerate(ids):
-                seeds = self.order[b * cfg.batch_size:min((b + 1) * cfg.batch_size, n_train)]
-                c, bufs, s = lanes[i % len(lanes)]
-                bufs.set_outputs(st.arena[i], st.tier_offs[i], st.edge_counts[i])
-                if st.blk_indptr is not None:
-                    bufs.set_hop(self.H - 1, st.blk_indptr[i], st.blk_nbr[i], st.blk_nbr_local[i])
-                c.sample_blocks(self.csr, seeds, seeds.numel(), cfg.fanouts, self.wl.seed, epoch, bufs, stream=s or head)
-                if self.early_pull:
-                    st.sampled[i].record(s or head)
-                    self.pf_stream.wait_event(st.sampled[i])
-                    self.ctx.stage_rows(st.arena[i], self.slot, self.wl.home, st.stage, i, self.wl.remote_store, cfg.feat_dim,
-                                        n_dev=st.tier_offs[i, self.H + 1:], stream=self.pf_stream)
-                    st.pf_events[i].record(self.pf_stream)
-                if not self.epoch_histogram:
-                    head_ctx.access_histogram(st.arena[i], self.slot, st.counts, n_dev=st.tier_offs[i, self.H + 1:], stream=head)
+            gsz = self.sample_group
+            for call, i0 in enumerate(range(0, len(ids), gsz)):
+                c, bufs_list, s = lanes[call % len(lanes)]
+                seeds_list, outs = [], []
+                for k, i in enumerate(range(i0, min(i0 + gsz, len(ids)))):
+                    b = ids[i]
+                    seeds_list.append(self.order[b * cfg.batch_size:min((b + 1) * cfg.batch_size, n_train)])
+                    bufs = bufs_list[k]
+                    bufs.set_outputs(st.arena[i], st.tier_offs[i], st.edge_counts[i])
+                    if st.blk_indptr is not None:
+                        bufs.set_hop(self.H - 1, st.blk_indptr[i], st.blk_nbr[i], st.blk_nbr_local[i])
+                    outs.append(bufs)
+                c.sample_blocks_group(self.csr, seeds_list, cfg.fanouts, self.wl.seed, epoch, outs, stream=s or head)
+                for i in range(i0, min(i0 + gsz, len(ids))):
+                    if self.early_pull:
+                        st.sampled[i].record(s or head)
+                        self.pf_stream.wait_event(st.sampled[i])
+                        self.ctx.stage_rows(st.arena[i], self.slot, self.wl.home, st.stage, i, self.wl.remote_store, cfg.feat_dim,
+                                            n_dev=st.tier_offs[i, self.H + 1:], stream=self.pf_stream)
+                        st.pf_events[i].record(self.pf_stream)
+                    if not self.epoch_histogram:
+                        head_ctx.access_histogram(st.arena[i], self.slot, st.counts, n_dev=st.tier_offs[i, self.H + 1:], stream=head)
             for _, _, s in lanes[1:]:
                 head.wait_stream(s)
             if self.epoch_histogram:

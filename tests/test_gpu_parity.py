@@ -113,6 +113,30 @@ def test_blocks_on_generated_csr(B, ctx):
     run()
 
 
+@pytest.mark.parametrize("group", [1, 2, 3, 8])
+@pytest.mark.parametrize("fanouts", [(5, 3), (40, 2), (-1, 4)])
+def test_blocks_group_equals_separate_batches(B, ctx, group, fanouts):
+    """One call for several batches (different seed counts, one of them empty) gives each batch exactly the block
+    of a call of its own; a smaller group after a larger one on the same context is unaffected by the earlier run."""
+    log(f"[blocks group] group={group} fanouts={fanouts}")
+    rng = np.random.default_rng(group * 10 + len(fanouts))
+    rp, ci = _handmade_graph(700, 0.7, 35, 0.015, rng)
+    csr = B.CsrGraph(torch.as_tensor(rp, device=DEV), _i32(ci))
+    sizes = [64, 0, 200, 1, 37, 128, 5, 90][:group]
+    seeds_np = [rng.choice(700, size=n, replace=False).astype(np.int32) for n in sizes]
+    outs = [B.BlockBuffers(700, ci.size, max(n, 1), fanouts, DEV) for n in sizes]
+    ctx.sample_blocks_group(csr, [_i32(x) if x.size else torch.empty(0, dtype=torch.int32, device=DEV) for x in seeds_np],
+                            fanouts, 99, 4, outs)
+    for g in range(group):
+        hip = HipBatch(outs[g], len(fanouts))
+        orc = oracle.sample_blocks(rp, ci, seeds_np[g], fanouts, 99, 4)
+        assert_batch_equal(hip, orc, len(fanouts), f"batch {g} of {group}")
+    # a single batch afterwards on the same context
+    hip = _run_blocks(B, ctx, csr, seeds_np[0], fanouts, 7, 1)
+    orc = oracle.sample_blocks(rp, ci, seeds_np[0], fanouts, 7, 1)
+    assert_batch_equal(hip, orc, len(fanouts), "single batch after the group")
+
+
 def test_blocks_degenerate_inputs(B, ctx):
     log("[blocks degenerate]")
     rp = np.array([0, 0, 1, 2, 2], dtype=np.int64)          # 0 and 3 isolated, 1 <-> 2
