@@ -62,7 +62,7 @@ typedef enum {
     RG_ERR_CAPACITY = 2,      /* an output buffer is smaller than the static bound (see rg_blocks_bounds) */
     RG_ERR_OOM = 3,           /* scratch allocation failed */
     RG_ERR_HIP = 4,           /* a HIP runtime call failed; message in rg_last_error */
-    RG_ERR_STATE = 5          /* call not valid in the ctx's current state (reserved; no call returns it yet) */
+    RG_ERR_STATE = 5          /* call not valid in the ctx's current state (rg_gather_run on an unprepared ticket) */
 } rg_status;
 
 #define RG_TAG_LOCAL 0u
@@ -323,6 +323,27 @@ RG_API rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int
                              const float* remote_store, int64_t remote_stride,
                              int32_t dim, float* out, int64_t out_stride,
                              rg_gather_stats* stats, void* hit_stream, void* miss_stream);
+
+/* The same assembly in two steps.  rg_gather_prepare resolves, for `count` batches in one launch,
+ * every output row to its source (one lookup of loc[] per row), counts the three classes into
+ * stats[k] and lists the miss rows, into the ctx's scratch entries ("tickets") first_ticket ..
+ * first_ticket + count - 1; rg_gather_run copies the rows of one prepared ticket (HBM rows on
+ * hit_stream, miss rows on miss_stream, joined as in rg_gather_features).  Preparing several batches
+ * at once pays the lookup launch once per group and leaves one copy kernel per batch on the stream.
+ * rg_gather_features = prepare (ticket 0, one batch) + run.  A ticket is busy from its prepare until
+ * the work of its run has finished; prepare and run of a ticket are given the same n, n_dev and
+ * cache and are ordered on their streams by the caller (trivially so on one stream).
+ * rg_gather_run returns RG_ERR_STATE if the ticket was not prepared for n rows.
+ * input_nodes, n_dev, stats: host arrays[count] of device pointers (n_dev may be NULL, or hold
+ * NULLs); n: host int64[count]; 0 <= first_ticket, first_ticket + count <= RG_GATHER_TICKETS. */
+#define RG_GATHER_TICKETS 8
+RG_API rg_status rg_gather_prepare(rg_ctx* ctx, int32_t first_ticket, int32_t count, const int32_t* const* input_nodes,
+                                   const int64_t* n, const int32_t* const* n_dev, const rg_cache* cache,
+                                   rg_gather_stats* const* stats, void* stream);
+RG_API rg_status rg_gather_run(rg_ctx* ctx, int32_t ticket, int64_t n, const int32_t* n_dev, const rg_cache* cache,
+                               const float* local_store, int64_t local_stride,
+                               const float* remote_store, int64_t remote_stride,
+                               int32_t dim, float* out, int64_t out_stride, void* hit_stream, void* miss_stream);
 
 /* ---- consumer of the gathered rows: Eq. 1 with AGG = mean (GraphSAGE, Section II-A) -------------
  * For the block of one hop (destination i = position in frontier_h, sources = positions in

@@ -18,6 +18,7 @@ RG_MAX_FANOUT = 1024
 RG_FANOUT_ALL = -1
 RG_MAX_HOPS = 8
 RG_MAX_GROUP = 8
+RG_GATHER_TICKETS = 8
 RG_K_GATHER_HBM, RG_K_GATHER_MISS, RG_K_SAMPLE, RG_K_HISTOGRAM, RG_K_CACHE_FILL, RG_K_AGGREGATE = range(6)
 
 _STATUS_NAMES = {0: "RG_OK", 1: "RG_ERR_INVALID_ARG", 2: "RG_ERR_CAPACITY", 3: "RG_ERR_OOM",
@@ -88,6 +89,10 @@ def _load():
     L.rg_stage_rows.argtypes = [c_p, c_p, c_i64, c_p, c_p, ctypes.POINTER(rg_stage), c_i32, c_p, c_i64, c_i32, c_p]
     L.rg_commit_staged_rows.argtypes = [c_p, c_p, c_i64, c_p, c_p, ctypes.POINTER(rg_stage), c_i32,
                                         ctypes.POINTER(rg_cache), c_i32, c_p]
+    L.rg_gather_prepare.argtypes = [c_p, c_i32, c_i32, ctypes.POINTER(c_p), ctypes.POINTER(c_i64), ctypes.POINTER(c_p),
+                                    ctypes.POINTER(rg_cache), ctypes.POINTER(c_p), c_p]
+    L.rg_gather_run.argtypes = [c_p, c_i32, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_i64, c_p, c_i64, c_i32, c_p, c_i64,
+                                c_p, c_p]
     L.rg_mean_aggregate.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_p, c_i64, c_i32, c_p, c_i64, c_p]
     L.rg_gather_features.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_i64, c_p, c_i64,
                                      c_i32, c_p, c_i64, c_p, c_p, c_p]
@@ -96,7 +101,7 @@ def _load():
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group",
                  "rg_access_histogram", "rg_access_histogram_epoch", "rg_build_cache", "rg_cache_hit_curve",
-                 "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_prefetch_planned", "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
+                 "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_prefetch_planned", "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -108,7 +113,7 @@ EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "r
                     "rg_access_histogram_epoch",
                     "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_plan_prefetch",
                     "rg_prefetch_planned", "rg_stage_rows", "rg_commit_staged_rows",
-                    "rg_gather_features", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
+                    "rg_gather_features", "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
 
 
 def _ptr(t, dtype=None, device_type=None, name="tensor"):
@@ -283,6 +288,26 @@ class Context:
             _ptr(remote_store, torch.float32, "mapped", "remote_store"), remote_store.stride(0),
             int(dim), _ptr(out, torch.float32, "cuda", "out"), out.stride(0),
             _ptr(stats, torch.int64, "cuda", "stats"), _stream_handle(hit_stream),
+            None if miss_stream is None else _stream_handle(miss_stream)))
+
+    # -- rg_gather_prepare / rg_gather_run
+    def gather_prepare(self, first_ticket, input_nodes, n, cache, stats, n_dev=None, stream=None):
+        """input_nodes, stats (and n_dev): lists with one tensor per batch; n: list of row counts."""
+        g = len(input_nodes)
+        nodes = (c_p * g)(*[_ptr(t, torch.int32, "cuda", "input_nodes") for t in input_nodes])
+        rows = (c_i64 * g)(*[int(x) for x in n])
+        sts = (c_p * g)(*[_ptr(t, torch.int64, "cuda", "stats") for t in stats])
+        nd = None if n_dev is None else (c_p * g)(*[_ptr(t, torch.int32, "cuda", "n_dev") for t in n_dev])
+        self._check(_lib.rg_gather_prepare(self._h, int(first_ticket), g, nodes, rows, nd, ctypes.byref(cache.c_struct), sts,
+                                           _stream_handle(stream)))
+
+    def gather_run(self, ticket, n, cache, local_store, remote_store, dim, out, n_dev=None, hit_stream=None,
+                   miss_stream=None):
+        self._check(_lib.rg_gather_run(
+            self._h, int(ticket), int(n), _ptr(n_dev, torch.int32, "cuda", "n_dev"), ctypes.byref(cache.c_struct),
+            _ptr(local_store, torch.float32, "cuda", "local_store"), local_store.stride(0),
+            _ptr(remote_store, torch.float32, "mapped", "remote_store"), remote_store.stride(0),
+            int(dim), _ptr(out, torch.float32, "cuda", "out"), out.stride(0), _stream_handle(hit_stream),
             None if miss_stream is None else _stream_handle(miss_stream)))
 
     # -- rg_mean_aggregate

@@ -57,6 +57,19 @@ rg_status rg_check_device_readable(rg_ctx* ctx, const void* p, const char* what)
     return RG_OK;
 }
 
+rg_status rg_gather_reserve(rg_ctx* ctx, int64_t rows) {
+    rg_status st;
+    if ((st = rg_ensure(ctx, ctx->gather_ctl, (size_t)RG_GATHER_TICKETS * 64)) != RG_OK) return st;
+    if (rows <= ctx->gather_cap) return RG_OK;
+    // a larger per-ticket stride moves every ticket's slice: nothing prepared earlier stays valid
+    for (int t = 0; t < RG_GATHER_TICKETS; ++t) ctx->gather_rows[t] = -1;
+    const int64_t cap = rg_max64(rows, ctx->gather_cap + ctx->gather_cap / 2);
+    if ((st = rg_ensure(ctx, ctx->gather_src, (size_t)RG_GATHER_TICKETS * cap * 4)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->miss_list, (size_t)RG_GATHER_TICKETS * cap * 8)) != RG_OK) return st;
+    ctx->gather_cap = cap;
+    return RG_OK;
+}
+
 extern "C" {
 
 const char* rg_version(void) { return "rapidgnn-mi355x 0.1 (gfx950)"; }
@@ -123,9 +136,7 @@ rg_status rg_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int64
     if ((st = rg_ensure(ctx, ctx->row_start, (size_t)max_frontier * 8)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->row_deg, (size_t)max_frontier * 4)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->topk_blk, ((size_t)rg_div_up(num_nodes, 1024) + 2) * 8)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->gather_src, (size_t)max_rows * 4)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->miss_list, (size_t)max_rows * 8)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->gather_ctl, 64)) != RG_OK) return st;
+    if ((st = rg_gather_reserve(ctx, max_rows)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->pf_list, (size_t)max_rows * 8)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->pf_ctl, 64)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->stage_list, (size_t)max_rows * 8)) != RG_OK) return st;

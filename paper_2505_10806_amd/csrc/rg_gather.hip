@@ -17,23 +17,38 @@ __device__ __forceinline__ int64_t rg_actual_n(int64_t n, const int32_t* __restr
     return d < n ? d : n;
 }
 
-__global__ void k_gather_reset(uint32_t* __restrict__ gctl, unsigned long long* __restrict__ stats) {
-    if (threadIdx.x == 0) gctl[0] = 0u;
-    if (threadIdx.x < 3) stats[threadIdx.x] = 0ull;
+// Batches classified by one launch: blockIdx.y selects the batch (its ticket's scratch slices).
+struct ClassifyGroup {
+    const int32_t* nodes[RG_GATHER_TICKETS];
+    const int32_t* n_dev[RG_GATHER_TICKETS];
+    int64_t n[RG_GATHER_TICKETS];
+    uint32_t* src[RG_GATHER_TICKETS];
+    int32_t* miss_list[RG_GATHER_TICKETS];
+    uint32_t* gctl[RG_GATHER_TICKETS];
+    unsigned long long* stats[RG_GATHER_TICKETS];
+};
+
+__global__ void k_gather_reset(const ClassifyGroup C) {
+    const int k = blockIdx.x;
+    if (threadIdx.x == 0) C.gctl[k][0] = 0u;
+    if (threadIdx.x < 3) C.stats[k][threadIdx.x] = 0ull;
 }
 
 // Four rows per thread (row i0 + k*256 + threadIdx.x, k = 0..3) so that each thread has four independent
 // loc[] lookups in flight; the miss pairs of a workgroup are appended in that visiting order (any order is valid).
 constexpr int kClassifyRows = 4;
 
-__global__ void __launch_bounds__(256) k_classify(const int32_t* __restrict__ nodes, int64_t n, const int32_t* __restrict__ n_dev,
-                                                  const int32_t* __restrict__ loc, uint32_t* __restrict__ src,
-                                                  int32_t* __restrict__ miss_list, uint32_t* __restrict__ gctl,
-                                                  unsigned long long* __restrict__ stats) {
+__global__ void __launch_bounds__(256) k_classify(const ClassifyGroup C, const int32_t* __restrict__ loc) {
     __shared__ int smem[256 / RG_WAVE + 1];
     __shared__ int cls[3][4];
     __shared__ uint32_t miss_base;
-    const int64_t n_act = rg_actual_n(n, n_dev);
+    const int b = blockIdx.y;
+    const int32_t* __restrict__ nodes = C.nodes[b];
+    uint32_t* __restrict__ src = C.src[b];
+    int32_t* __restrict__ miss_list = C.miss_list[b];
+    uint32_t* __restrict__ gctl = C.gctl[b];
+    unsigned long long* __restrict__ stats = C.stats[b];
+    const int64_t n_act = rg_actual_n(C.n[b], C.n_dev[b]);
     const int64_t i0 = (int64_t)blockIdx.x * (256 * kClassifyRows);
     if (i0 >= n_act) return;                                       // uniform per workgroup
     uint32_t w[kClassifyRows];
@@ -182,48 +197,81 @@ int env_int(const char* name, int dflt) {
 
 extern "C" {
 
-rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
-                             const rg_cache* cache, const float* local_store, int64_t local_stride,
-                             const float* remote_store, int64_t remote_stride, int32_t dim, float* out,
-                             int64_t out_stride, rg_gather_stats* stats, void* hit_stream, void* miss_stream) {
+rg_status rg_gather_prepare(rg_ctx* ctx, int32_t first_ticket, int32_t count, const int32_t* const* input_nodes,
+                            const int64_t* n, const int32_t* const* n_dev, const rg_cache* cache,
+                            rg_gather_stats* const* stats, void* stream) {
     if (!ctx) return RG_ERR_INVALID_ARG;
-    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_gather_features: n = %lld out of range", (long long)n);
-    RG_REQUIRE(ctx, stats, "rg_gather_features: stats is NULL");
-    RG_REQUIRE(ctx, dim >= 1, "rg_gather_features: dim = %d must be positive", dim);
-    RG_REQUIRE(ctx, cache && cache->loc, "rg_gather_features: cache / cache->loc is NULL");
-    RG_REQUIRE(ctx, out_stride >= dim, "rg_gather_features: out_stride < dim");
-    RG_REQUIRE(ctx, !local_store || local_stride >= dim, "rg_gather_features: local_stride < dim");
-    RG_REQUIRE(ctx, !remote_store || remote_stride >= dim, "rg_gather_features: remote_stride < dim");
-    RG_REQUIRE(ctx, !cache->cache_rows || cache->row_stride >= dim, "rg_gather_features: cache row_stride < dim");
-    RG_REQUIRE(ctx, n == 0 || (input_nodes && out), "rg_gather_features: null input_nodes / out");
+    RG_REQUIRE(ctx, first_ticket >= 0 && count >= 0 && first_ticket + count <= RG_GATHER_TICKETS,
+               "rg_gather_prepare: tickets %d..%d not in [0,%d)", first_ticket, first_ticket + count - 1, RG_GATHER_TICKETS);
+    if (count == 0) return RG_OK;
+    RG_REQUIRE(ctx, input_nodes && n && stats, "rg_gather_prepare: null argument array");
+    RG_REQUIRE(ctx, cache && cache->loc, "rg_gather_prepare: cache / cache->loc is NULL");
+    int64_t n_max = 0;
+    for (int k = 0; k < count; ++k) {
+        RG_REQUIRE(ctx, n[k] >= 0 && n[k] <= (1ll << 31) - 1, "rg_gather_prepare: n = %lld out of range (batch %d)", (long long)n[k], k);
+        RG_REQUIRE(ctx, stats[k], "rg_gather_prepare: stats is NULL (batch %d)", k);
+        RG_REQUIRE(ctx, n[k] == 0 || input_nodes[k], "rg_gather_prepare: input_nodes is NULL (batch %d)", k);
+        n_max = rg_max64(n_max, n[k]);
+    }
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    rg_status st = rg_gather_reserve(ctx, rg_max64(n_max, 1));
+    if (st != RG_OK) return st;
+    ClassifyGroup C;
+    for (int k = 0; k < RG_GATHER_TICKETS; ++k) {
+        const bool live = k < count;
+        const int t = first_ticket + (live ? k : 0);
+        C.nodes[k] = live ? input_nodes[k] : nullptr;
+        C.n_dev[k] = live && n_dev ? n_dev[k] : nullptr;
+        C.n[k] = live ? n[k] : 0;
+        C.src[k] = (uint32_t*)ctx->gather_src.p + (int64_t)t * ctx->gather_cap;
+        C.miss_list[k] = (int32_t*)ctx->miss_list.p + (int64_t)t * 2 * ctx->gather_cap;
+        C.gctl[k] = (uint32_t*)ctx->gather_ctl.p + t * 16;
+        C.stats[k] = live ? (unsigned long long*)stats[k] : nullptr;
+        if (live) ctx->gather_rows[t] = -1;
+    }
+    k_gather_reset<<<count, 64, 0, s>>>(C);
+    RG_LAUNCH_CHECK(ctx, "k_gather_reset");
+    if (n_max > 0) {
+        k_classify<<<dim3((unsigned)rg_div_up(n_max, 256 * kClassifyRows), (unsigned)count), 256, 0, s>>>(C, cache->loc);
+        RG_LAUNCH_CHECK(ctx, "k_classify");
+    }
+    for (int k = 0; k < count; ++k) ctx->gather_rows[first_ticket + k] = n[k];
+    return RG_OK;
+}
+
+rg_status rg_gather_run(rg_ctx* ctx, int32_t ticket, int64_t n, const int32_t* n_dev, const rg_cache* cache,
+                        const float* local_store, int64_t local_stride, const float* remote_store, int64_t remote_stride,
+                        int32_t dim, float* out, int64_t out_stride, void* hit_stream, void* miss_stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, ticket >= 0 && ticket < RG_GATHER_TICKETS, "rg_gather_run: ticket = %d not in [0,%d)", ticket, RG_GATHER_TICKETS);
+    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_gather_run: n = %lld out of range", (long long)n);
+    RG_REQUIRE(ctx, dim >= 1, "rg_gather_run: dim = %d must be positive", dim);
+    RG_REQUIRE(ctx, cache && cache->loc, "rg_gather_run: cache / cache->loc is NULL");
+    RG_REQUIRE(ctx, out_stride >= dim, "rg_gather_run: out_stride < dim");
+    RG_REQUIRE(ctx, !local_store || local_stride >= dim, "rg_gather_run: local_stride < dim");
+    RG_REQUIRE(ctx, !remote_store || remote_stride >= dim, "rg_gather_run: remote_stride < dim");
+    RG_REQUIRE(ctx, !cache->cache_rows || cache->row_stride >= dim, "rg_gather_run: cache row_stride < dim");
+    RG_REQUIRE(ctx, n == 0 || out, "rg_gather_run: out is NULL");
     // A store may be absent only if no location word can point into it; that cannot be verified on the
     // host, so all three are required whenever rows are requested.
-    RG_REQUIRE(ctx, n == 0 || (local_store && remote_store), "rg_gather_features: null feature store");
-    RG_REQUIRE(ctx, n == 0 || cache->cache_rows || cache->capacity_rows == 0, "rg_gather_features: cache_rows is NULL");
+    RG_REQUIRE(ctx, n == 0 || (local_store && remote_store), "rg_gather_run: null feature store");
+    RG_REQUIRE(ctx, n == 0 || cache->cache_rows || cache->capacity_rows == 0, "rg_gather_run: cache_rows is NULL");
+    if (ctx->gather_rows[ticket] != n)
+        return rg_set_error(ctx, RG_ERR_STATE, "rg_gather_run: ticket %d was prepared for %lld rows, not %lld", ticket,
+                            (long long)ctx->gather_rows[ticket], (long long)n);
+    if (n == 0) return RG_OK;
     RG_HIP(ctx, hipSetDevice(ctx->device));
-    if (n > 0) {
-        const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_gather_features: remote_store");
+    {
+        const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_gather_run: remote_store");
         if (chk != RG_OK) return chk;
     }
     hipStream_t sh = (hipStream_t)hit_stream;
     hipStream_t sm = miss_stream ? (hipStream_t)miss_stream : sh;
     const bool two_streams = sm != sh;
-
-    rg_status st;
-    if ((st = rg_ensure(ctx, ctx->gather_ctl, 64)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->gather_src, (size_t)rg_max64(n, 1) * 4)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->miss_list, (size_t)rg_max64(n, 1) * 8)) != RG_OK) return st;
-    uint32_t* gctl = (uint32_t*)ctx->gather_ctl.p;
-    uint32_t* src = (uint32_t*)ctx->gather_src.p;
-    int32_t* miss_list = (int32_t*)ctx->miss_list.p;
-    unsigned long long* dstats = (unsigned long long*)stats;
-
-    k_gather_reset<<<1, 64, 0, sh>>>(gctl, dstats);
-    RG_LAUNCH_CHECK(ctx, "k_gather_reset");
-    if (n == 0) return RG_OK;
-
-    k_classify<<<(int)rg_div_up(n, 256 * kClassifyRows), 256, 0, sh>>>(input_nodes, n, n_dev, cache->loc, src, miss_list, gctl, dstats);
-    RG_LAUNCH_CHECK(ctx, "k_classify");
+    uint32_t* gctl = (uint32_t*)ctx->gather_ctl.p + ticket * 16;
+    uint32_t* src = (uint32_t*)ctx->gather_src.p + (int64_t)ticket * ctx->gather_cap;
+    int32_t* miss_list = (int32_t*)ctx->miss_list.p + (int64_t)ticket * 2 * ctx->gather_cap;
     if (two_streams) {
         RG_HIP(ctx, hipEventRecord(ctx->ev_classified, sh));
         RG_HIP(ctx, hipStreamWaitEvent(sm, ctx->ev_classified, 0));
@@ -274,6 +322,31 @@ rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n,
         RG_HIP(ctx, hipStreamWaitEvent(sh, ctx->ev_miss_done, 0));
     }
     return RG_OK;
+}
+
+rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
+                             const rg_cache* cache, const float* local_store, int64_t local_stride,
+                             const float* remote_store, int64_t remote_stride, int32_t dim, float* out,
+                             int64_t out_stride, rg_gather_stats* stats, void* hit_stream, void* miss_stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, stats, "rg_gather_features: stats is NULL");
+    // argument errors of the copy step are reported before anything is queued
+    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_gather_features: n = %lld out of range", (long long)n);
+    RG_REQUIRE(ctx, dim >= 1, "rg_gather_features: dim = %d must be positive", dim);
+    RG_REQUIRE(ctx, cache && cache->loc, "rg_gather_features: cache / cache->loc is NULL");
+    RG_REQUIRE(ctx, out_stride >= dim && (!local_store || local_stride >= dim) && (!remote_store || remote_stride >= dim) &&
+                        (!cache->cache_rows || cache->row_stride >= dim), "rg_gather_features: a row stride is smaller than dim");
+    RG_REQUIRE(ctx, n == 0 || (input_nodes && out && local_store && remote_store), "rg_gather_features: null pointer");
+    RG_REQUIRE(ctx, n == 0 || cache->cache_rows || cache->capacity_rows == 0, "rg_gather_features: cache_rows is NULL");
+    if (n > 0) {
+        RG_HIP(ctx, hipSetDevice(ctx->device));
+        const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_gather_features: remote_store");
+        if (chk != RG_OK) return chk;
+    }
+    rg_status st = rg_gather_prepare(ctx, 0, 1, &input_nodes, &n, &n_dev, cache, &stats, hit_stream);
+    if (st != RG_OK) return st;
+    return rg_gather_run(ctx, 0, n, n_dev, cache, local_store, local_stride, remote_store, remote_stride, dim, out, out_stride,
+                         hit_stream, miss_stream);
 }
 
 }  // extern "C"

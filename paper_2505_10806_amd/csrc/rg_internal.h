@@ -47,9 +47,12 @@ struct rg_ctx {
     RgBuf plan_cursor;               // rg_plan_prefetch: per-chunk per-batch counts (ordered plan) or scatter cursors
     RgBuf commit_list, commit_ctl;   // the same for rg_commit_staged_rows
     // gather scratch
-    RgBuf gather_src;   // uint32[n] resolved location word per output row
-    RgBuf miss_list;    // int32[2n]: (output row, remote row) pairs of the rows whose source is the remote store
-    RgBuf gather_ctl;   // uint32[4]: [0] = number of misses
+    // RG_GATHER_TICKETS entries each, so that several batches can be classified by one launch ahead of their copies
+    RgBuf gather_src;   // [ticket][gather_cap] uint32: resolved location word per output row
+    RgBuf miss_list;    // [ticket][2 * gather_cap] int32: (output row, remote row) pairs of the miss rows
+    RgBuf gather_ctl;   // [ticket][16] uint32: [0] = number of misses
+    int64_t gather_cap = 0;                                  // rows per ticket the buffers hold
+    int64_t gather_rows[RG_GATHER_TICKETS] = {-1, -1, -1, -1, -1, -1, -1, -1};   // rows a ticket was prepared for (-1: none)
     hipEvent_t ev_classified = nullptr, ev_miss_done = nullptr;
 
     // profiling
@@ -64,6 +67,8 @@ rg_status rg_set_error(rg_ctx* ctx, rg_status code, const char* fmt, ...);
 rg_status rg_ensure(rg_ctx* ctx, RgBuf& buf, size_t bytes, bool zero_new = false);
 // RG_OK if kernels on the ctx's device may dereference p (device, managed or pinned/registered host memory).
 rg_status rg_check_device_readable(rg_ctx* ctx, const void* p, const char* what);
+// Makes every gather ticket hold at least `rows` rows (a reallocation invalidates prepared tickets).
+rg_status rg_gather_reserve(rg_ctx* ctx, int64_t rows);
 // Profiling brackets (no-ops unless profiling is enabled).
 int rg_prof_begin(rg_ctx* ctx, int kernel, hipStream_t s);
 void rg_prof_end(rg_ctx* ctx, int token, hipStream_t s);

@@ -92,6 +92,7 @@ class EpochPipeline:
         self.agg = (torch.empty(max(self.bufs.frontier_ub[self.H - 1], 1), wl.stride, dtype=torch.float32, device=device)
                     if consumer else None)
         self._gathered = 0
+        self._tickets = {}                         # ticket -> (epoch state, batch) it is prepared for
         self.order = torch.empty_like(wl.train_ids)
         self.side = torch.cuda.Stream(device=device) if two_streams else None
         # prefetch = pull cached rows batch by batch, in order of first use, on a stream of their own so the
@@ -250,8 +251,14 @@ class EpochPipeline:
         self.out = self.out_ring[q]
         if self.consumer:
             main.wait_event(self.consumed[q])           # the ring slot is free once its previous batch was consumed
-        self.ctx.gather_features(st.arena[b], n, st.cache, self.wl.local_store, self.wl.remote_store,
-                                 self.cfg.feat_dim, self.out, st.stats[b], miss_stream=self.side)
+        # the lookups of a whole group of batches are made by one launch (prepare); each batch then costs one copy
+        # kernel on this stream (plus its miss rows on the miss stream)
+        ticket = b % B.RG_GATHER_TICKETS
+        if self._tickets.get(ticket) != (id(st), b):
+            self._prepare(st, [b])
+        self.ctx.gather_run(ticket, n, st.cache, self.wl.local_store, self.wl.remote_store, self.cfg.feat_dim, self.out,
+                            hit_stream=main, miss_stream=self.side)
+        self._tickets.pop(ticket, None)
         if self.consumer:
             self.ready[q].record(main)
             cs = self.consumer_stream
@@ -260,6 +267,14 @@ class EpochPipeline:
                                     self.cfg.feat_dim, self.agg, n_dst_dev=st.tier_offs[b, self.H:], stream=cs)
             self.consumed[q].record(cs)
         return n
+
+    def _prepare(self, st, batches):
+        """Classify the listed batches (consecutive, within one group of tickets) with one launch on the current stream."""
+        first = batches[0] % B.RG_GATHER_TICKETS
+        self.ctx.gather_prepare(first, [st.arena[b] for b in batches], [st.sizes[b] for b in batches], st.cache,
+                                [st.stats[b] for b in batches])
+        for b in batches:
+            self._tickets[b % B.RG_GATHER_TICKETS] = (id(st), b)
 
     def prefetch_rows(self, b, stream=None, st=None):
         """Pull the not-yet-resident cached rows batch b needs (asynchronous on `stream`).  The row count is
@@ -297,6 +312,8 @@ class EpochPipeline:
         if self.early_pull:
             main.wait_event(st.built)                   # the commits need this epoch's TopHot
         for b in range(n_batches):
+            if b % B.RG_GATHER_TICKETS == 0:
+                self._prepare(st, list(range(b, min(b + B.RG_GATHER_TICKETS, n_batches))))
             if self.prefetch:
                 if not st.pulls_queued:
                     self.prefetch_rows(b, stream=self.pf_stream)

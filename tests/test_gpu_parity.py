@@ -704,6 +704,62 @@ def test_gather_with_stale_cache_and_misaligned_buffers(B, ctx):
     assert tuple(stats.cpu().tolist()) == st
 
 
+def test_gather_prepare_group_then_run(B, ctx):
+    """Several batches classified by one launch, copied later ticket by ticket in any order, on another stream;
+    a ticket that was not prepared for the same row count is refused."""
+    rng = np.random.default_rng(12)
+    n_nodes, dim = 4000, 20
+    stride = synth.stores.row_stride(dim)
+    X = rng.standard_normal((n_nodes, dim)).astype(np.float32)
+    is_local = torch.from_numpy(rng.random(n_nodes) < 0.4)
+    home = synth.stores.make_home(is_local)
+    local = torch.zeros(int(is_local.sum()), stride, device=DEV)
+    local[:, :dim] = torch.from_numpy(X)[is_local].to(DEV)
+    remote = torch.zeros(int((~is_local).sum()), stride, pin_memory=True)
+    remote[:, :dim] = torch.from_numpy(X)[~is_local]
+    cache = B.FeatureCache(n_nodes, 0, stride, DEV)
+    cache.loc.copy_(home)
+    prep, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    sizes = (700, 1, 2500, 0, 64, 4097, 33, 1500)
+    batches = [rng.integers(0, n_nodes, size=s).astype(np.int32) for s in sizes]
+    nodes_dev = [torch.as_tensor(b, device=DEV) if b.size else torch.empty(1, dtype=torch.int32, device=DEV) for b in batches]
+    stats = torch.full((8, 3), -1, dtype=torch.int64, device=DEV)
+    outs = [torch.full((max(b.size, 1), stride), float("nan"), device=DEV) for b in batches]
+    torch.cuda.synchronize()
+    ctx.gather_prepare(0, nodes_dev[:5], sizes[:5], cache, [stats[t] for t in range(5)], stream=prep)
+    ctx.gather_prepare(5, nodes_dev[5:], sizes[5:], cache, [stats[t] for t in range(5, 8)], stream=prep,
+                       n_dev=[torch.tensor([s], dtype=torch.int32, device=DEV) for s in sizes[5:]])
+    done = torch.cuda.Event()
+    done.record(prep)
+    copy.wait_event(done)
+    for t in (2, 7, 0, 3, 6, 1, 5, 4):
+        ctx.gather_run(t, sizes[t], cache, local, remote, dim, outs[t], hit_stream=copy)
+    torch.cuda.synchronize()
+    for t in range(8):
+        want, st = oracle.gather_features(X, batches[t], home.numpy())
+        assert np.array_equal(outs[t][:sizes[t], :dim].cpu().numpy(), want), t
+        assert tuple(stats[t].cpu().tolist()) == st, t
+    with pytest.raises(B.RgError) as e:
+        ctx.gather_run(1, 5, cache, local, remote, dim, outs[1], hit_stream=copy)      # prepared for 1 row
+    assert e.value.status == B.RG_ERR_STATE
+    with pytest.raises(B.RgError) as e:
+        ctx.gather_prepare(6, nodes_dev[:3], sizes[:3], cache, [stats[t] for t in range(3)])   # tickets 6..8
+    assert e.value.status == B.RG_ERR_INVALID_ARG
+    # on a fresh context: a batch larger than anything seen so far grows the scratch and drops every earlier preparation
+    c2 = B.Context(0)
+    c2.gather_prepare(2, [nodes_dev[2]], [sizes[2]], cache, [stats[2]])
+    big = rng.integers(0, n_nodes, size=200_000).astype(np.int32)
+    c2.gather_prepare(3, [torch.as_tensor(big, device=DEV)], [big.size], cache, [stats[3]])
+    with pytest.raises(B.RgError) as e:
+        c2.gather_run(2, sizes[2], cache, local, remote, dim, outs[2])
+    assert e.value.status == B.RG_ERR_STATE
+    out_big = torch.empty(big.size, stride, device=DEV)
+    c2.gather_run(3, big.size, cache, local, remote, dim, out_big)
+    torch.cuda.synchronize()
+    assert np.array_equal(out_big[:, :dim].cpu().numpy(), X[big])
+    c2.close()
+
+
 # ------------------------------------------------------------------------------ histogram
 def test_histogram_with_repeats_and_device_count(B, ctx):
     rng = np.random.default_rng(4)
