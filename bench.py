@@ -3,18 +3,29 @@
 
 A step is one mini-batch taken through the whole hot path: epoch schedule (once per epoch), k-hop
 sampling, access histogram, TopHot + cache fill (once per epoch, amortised over its batches) and the
-per-batch feature gather.  Inputs are synthetic (seeded Chung-Lu graph, N(0,1) features) and resident
-in HBM / pinned host memory before the timed region starts.  Prints one JSON line.
+per-batch feature gather.  `--steps K` with K below one epoch times a K-batch epoch from a cold cache
+(schedule, K samples, histogram over them, TopHot, pulls, K gathers); the timed region is repeated
+`--reps` times, each from a cold cache, and the median is reported with the spread beside it.  Because
+the first batches of an epoch need most of the remote rows, the per-batch time of a short epoch is
+dominated by the host link; the rate of the workload's whole epoch is therefore measured in the same run
+and reported under "full_epoch", whatever K is.  Kernel durations (roofline) come from one more pass with
+the library's hipEvent brackets switched on, outside the timed repetitions.
+
+Inputs are synthetic (seeded Chung-Lu graph, N(0,1) features) and resident in HBM / pinned host memory
+before the timed region starts.  Prints one JSON line.
 """
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
 # The pipeline keeps up to five streams busy at once (gathers, miss rows, host-link pulls, two more sampler lanes);
-# with HIP's default of 4 hardware queues two of them would share a queue and serialise.
-if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 8:
+# with HIP's default of 4 hardware queues two of them would share a queue and serialise.  A value the user set is kept.
+HWQ_SET_BY_USER = "GPU_MAX_HW_QUEUES" in os.environ
+if not HWQ_SET_BY_USER:
     os.environ["GPU_MAX_HW_QUEUES"] = "8"
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -24,27 +35,30 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E peak
 HOSTLINK_PEAK_GBS = 64.0   # PCIe Gen5 x16, one direction
 
-# HBM bytes moved by one k_gather_hbm launch on the stress workload, measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE, one counter per run, each scaled by what the same counter reads for a plain 1 GiB copy: x2.000 and
-# x1.000).  The figures and the commands are in profiles/stress_gather_hbm_pmc_traffic.txt.
-PMC_TRAFFIC = {"stress": {"fetch_kib": 404251.2, "fetch_scale": 2.0, "write_kib": 795996.3, "write_scale": 1.0,
-                          "rows_per_launch": 795995}}
-
 
 def log(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
-def run_steps(pipe, steps, totals=None):
+def recorded_traffic(workload):
+    """HBM bytes per gathered row from the committed rocprofv3 --pmc summary of this workload's gather kernel, or None.
+    The summary file carries one machine-readable line: `bench_traffic_json: {...}`."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_gather_hbm_pmc_traffic.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None, None
+    m = re.search(r"^bench_traffic_json:\s*(\{.*\})\s*$", text, re.M)
+    if not m:
+        return None, None
+    t = json.loads(m.group(1))
+    per_row = (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]) * 1024.0 / t["rows_per_launch"]
+    return per_row, os.path.relpath(path, ROOT)
+
+
+def run_steps(pipe, steps, totals=None, first_epoch=0):
     """Run `steps` batches through the whole path, epoch after epoch (the last epoch may be partial)."""
     import torch
-    marks = {"t": time.perf_counter()}
-
-    def started(p, _k):                      # called once the epoch's offline stage has finished (host has its sizes)
-        if totals is not None:
-            now = time.perf_counter()
-            totals["offline_s"] += now - marks["t"]
-            marks["t"] = now
 
     def account(p, _k):
         if totals is not None:
@@ -54,12 +68,69 @@ def run_steps(pipe, steps, totals=None):
             totals["edges"] += p.edge_counts[:nb].sum()
             totals["cached"] += p.cache.num_cached.clone()
             totals["epochs"] += 1
-    full, rem = divmod(steps, pipe.max_batches)
+    bpe = pipe.batches_per_epoch
+    full, rem = divmod(steps, bpe)
     if full:
-        pipe.run_epochs(0, full, pipe.max_batches, on_epoch_done=account, on_epoch_start=started)
+        pipe.run_epochs(first_epoch, full, bpe, on_epoch_done=account)
     if rem:
-        pipe.run_epochs(full, 1, rem, on_epoch_done=account, on_epoch_start=started)
+        pipe.run_epochs(first_epoch + full, 1, rem, on_epoch_done=account)
     torch.cuda.current_stream().synchronize()
+
+
+def new_totals(dev):
+    import torch
+    return {"stats": torch.zeros(3, dtype=torch.int64, device=dev), "rows": 0,
+            "edges": torch.zeros((), dtype=torch.int64, device=dev),
+            "cached": torch.zeros(1, dtype=torch.int64, device=dev), "epochs": 0}
+
+
+def timed_reps(pipe, steps, reps):
+    """`reps` repetitions of `steps` batches, each from a cold cache, each bracketed by a device synchronisation."""
+    import torch
+    times = []
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(pipe, steps)
+        torch.cuda.synchronize()
+        times.append(time.perf_counter() - t0)
+    return times
+
+
+def profiled_pass(pipe, steps, dev):
+    """One more repetition with the library's hipEvent brackets on: per-kernel durations and the row statistics."""
+    import torch
+    from paper_2505_10806_amd import binding as B
+    totals = new_totals(dev)
+    pipe.profile_enable(True)
+    pipe.profile_reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(pipe, steps, totals)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = {name: pipe.profile_read(kid) for name, kid in
+            [("gather_hbm", B.RG_K_GATHER_HBM), ("gather_miss", B.RG_K_GATHER_MISS), ("sample", B.RG_K_SAMPLE),
+             ("histogram", B.RG_K_HISTOGRAM), ("cache_fill", B.RG_K_CACHE_FILL), ("mean_aggregate", B.RG_K_AGGREGATE)]}
+    pipe.profile_enable(False)
+    return dt, prof, totals
+
+
+def gather_roofline(prof, totals, row_bytes):
+    """Algorithmic HBM bytes of the k_gather_hbm launches of a profiled pass over their summed duration."""
+    n_local, n_hit, _ = [int(x) for x in totals["stats"].cpu().tolist()]
+    g_ms, g_launches = prof["gather_hbm"]
+    hbm_rows = n_local + n_hit
+    alg_bytes = 2.0 * row_bytes * hbm_rows                       # every HBM-served row is read once and written once
+    achieved = alg_bytes / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0
+    return {"achieved": achieved, "frac": achieved / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": alg_bytes / max(g_launches, 1),
+            "avg_launch_ms": g_ms / max(g_launches, 1), "launches": g_launches, "hbm_rows": hbm_rows}
+
+
+def spread(times, steps):
+    med = statistics.median(times)
+    return {"reps": len(times), "median_ms": med * 1e3, "min_ms": min(times) * 1e3, "max_ms": max(times) * 1e3,
+            "batches_per_s_median": steps / med, "batches_per_s_min": steps / max(times), "batches_per_s_max": steps / min(times)}
 
 
 def cpu_baseline(wl, n_batches=None, target_s=12.0):
@@ -118,6 +189,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="mini-batches in the timed region (default: one epoch)")
     ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--reps", type=int, default=5, help="repetitions of the timed region, each from a cold cache (median reported)")
     ap.add_argument("--workload", default="stress")
     ap.add_argument("--seed", type=int, default=2025)
     ap.add_argument("--cpu-batches", type=int, default=None,
@@ -128,8 +200,6 @@ def main():
     ap.add_argument("--sampler-streams", type=int, default=2, help="batches sampled side by side during the offline stage")
     ap.add_argument("--no-double-buffer", action="store_true",
                     help="with more than one epoch of steps: do not precompute epoch e+1 while epoch e is served")
-    ap.add_argument("--early-pull", action="store_true",
-                    help="pull rows into a staging area during the offline stage (only when the cache can hold every remote node)")
     ap.add_argument("--consumer", choices=["none", "mean"], default="none",
                     help="reduce every batch's gathered rows with the mean aggregator over its outermost block, on its own stream")
     ap.add_argument("--queue-depth", type=int, default=3, help="output buffers the gathers may run ahead of the consumer")
@@ -137,6 +207,8 @@ def main():
                     help="prefetch with a claim pass over every batch instead of the per-epoch prefetch plan")
     ap.add_argument("--sample-group", type=int, default=8,
                     help="batches sampled by one rg_sample_blocks_group call")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the extra passes (whole-epoch rate, gather kernel without concurrent pulls, hit curve)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -147,7 +219,6 @@ def main():
 
     import torch
     import synth
-    from paper_2505_10806_amd import binding as B
     from paper_2505_10806_amd.pipeline import EpochPipeline
 
     dev = "cuda:0"
@@ -177,115 +248,129 @@ def main():
 
     bpe = wl.batches_per_epoch()
     steps = args.steps if args.steps is not None else bpe
-    warmup = args.warmup
+    warmup, reps = args.warmup, max(1, args.reps)
+    row_bytes = 4 * cfg.feat_dim
+    multi_epoch = steps > bpe
     main_stream = torch.cuda.Stream()
-    with torch.cuda.stream(main_stream):
-        pipe = EpochPipeline(wl, device=dev, max_batches=min(max(steps, warmup, 1), bpe), two_streams=not args.one_stream,
-                             prefetch=not args.bulk_fill, sampler_streams=args.sampler_streams,
-                             double_buffer=(steps > bpe and not args.no_double_buffer), early_pull=args.early_pull, planned_prefetch=not args.no_plan, sample_group=args.sample_group,
+
+    def make_pipeline(prefetch):
+        return EpochPipeline(wl, device=dev, two_streams=not args.one_stream, prefetch=prefetch,
+                             sampler_streams=args.sampler_streams, double_buffer=(multi_epoch and not args.no_double_buffer),
+                             planned_prefetch=not args.no_plan, sample_group=args.sample_group,
                              consumer=None if args.consumer == "none" else args.consumer,
                              queue_depth=args.queue_depth if args.consumer != "none" else 1)
+
+    with torch.cuda.stream(main_stream):
+        pipe = make_pipeline(not args.bulk_fill)
         ctx = pipe.ctx
         if warmup > 0:
             run_steps(pipe, warmup)
-        totals = {"stats": torch.zeros(3, dtype=torch.int64, device=dev), "rows": 0,
-                  "edges": torch.zeros((), dtype=torch.int64, device=dev),
-                  "cached": torch.zeros(1, dtype=torch.int64, device=dev), "epochs": 0, "offline_s": 0.0}
-        pipe.profile_enable(True)
-        pipe.profile_reset()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        run_steps(pipe, steps, totals)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        pipe.profile_enable(False)
+        times = timed_reps(pipe, steps, reps)
+        prof_dt, prof, totals = profiled_pass(pipe, steps, dev)
+        roof = gather_roofline(prof, totals, row_bytes)
 
+        full_epoch = None
+        if not args.no_extras and steps != bpe and not multi_epoch:
+            run_steps(pipe, bpe)                                     # warm-up at the whole epoch's sizes
+            full_times = timed_reps(pipe, bpe, 3)
+            f_dt, f_prof, f_totals = profiled_pass(pipe, bpe, dev)
+            f_roof = gather_roofline(f_prof, f_totals, row_bytes)
+            full_epoch = dict(spread(full_times, bpe), batches=bpe,
+                              k_gather_hbm_frac=f_roof["frac"], k_gather_hbm_avg_launch_ms=f_roof["avg_launch_ms"])
+
+    med = statistics.median(times)
     n_local, n_hit, n_miss = [int(x) for x in totals["stats"].cpu().tolist()]
     rows = totals["rows"]
     assert rows == n_local + n_hit + n_miss, "gather statistics do not add up"
-    row_bytes = 4 * cfg.feat_dim
-    prof = {name: pipe.profile_read(kid) for name, kid in
-            [("gather_hbm", B.RG_K_GATHER_HBM), ("gather_miss", B.RG_K_GATHER_MISS), ("sample", B.RG_K_SAMPLE),
-             ("histogram", B.RG_K_HISTOGRAM), ("cache_fill", B.RG_K_CACHE_FILL), ("mean_aggregate", B.RG_K_AGGREGATE)]}
-    g_ms, g_launches = prof["gather_hbm"]
-    hbm_rows = n_local + n_hit
-    alg_bytes = 2.0 * row_bytes * hbm_rows                       # every HBM-served row is read once and written once
-    achieved = alg_bytes / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0
     cached_rows = int(totals["cached"].item())
     m_ms, _ = prof["gather_miss"]
     f_ms, _ = prof["cache_fill"]
-    traffic = None
-    if cfg.name in PMC_TRAFFIC and g_launches:
-        t = PMC_TRAFFIC[cfg.name]
-        per_row = (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]) * 1024.0 / t["rows_per_launch"]
-        traffic = per_row * hbm_rows / g_launches            # measured bytes per row x rows per launch of this run
+    per_row_traffic, traffic_source = recorded_traffic(cfg.name)
     result = {
         "metric": "mini-batch sample+gather/sec; feature gather GB/s vs HBM peak; cache hit %",
-        "value": steps / dt,
+        "value": steps / med,
         "unit": "batches/s",
         "n_gpus": 1,
         "steps": steps,
         "warmup": warmup,
-        "ms_per_step": dt * 1e3 / steps,
+        "ms_per_step": med * 1e3 / steps,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "int32 indices / fp32 rows (copy)",
         "data": "synthetic",
+        "timing": dict(spread(times, steps),
+                       step_definition=("one batch of a %d-batch epoch taken from a cold cache through schedule, sampling, histogram, "
+                                        "TopHot, pulls and gather" % min(steps, bpe)) if not multi_epoch else
+                                       "one batch of %d epochs run back to back with the double-buffered cache" % -(-steps // bpe),
+                       profiled_pass_ms=prof_dt * 1e3,
+                       note="value = steps / median; kernel durations come from the extra profiled pass"),
         "config": {"workload": cfg.name, "num_nodes": cfg.num_nodes, "nnz": wl.nnz, "feat_dim": cfg.feat_dim,
-                   "fanouts": list(cfg.fanouts), "batch_size": cfg.batch_size, "epochs_timed": totals["epochs"],
+                   "fanouts": list(cfg.fanouts), "batch_size": cfg.batch_size, "batches_per_epoch": bpe,
+                   "epochs_per_rep": totals["epochs"],
                    "cache_capacity_rows": wl.capacity_rows, "miss_stream": "shared" if args.one_stream else "separate",
                    "cache_fill": "bulk" if args.bulk_fill else "prefetch by first use",
                    "sampler_streams": args.sampler_streams, "sample_group": args.sample_group,
-                   "double_buffered_cache": bool(steps > bpe and not args.no_double_buffer),
-                   "early_pull": pipe.early_pull, "planned_prefetch": pipe.planned, "consumer": args.consumer,
-                   "queue_depth": pipe.queue_depth},
-        "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": alg_bytes / max(g_launches, 1),
-                     "avg_launch_ms": g_ms / max(g_launches, 1), "launches": g_launches},
+                   "double_buffered_cache": bool(multi_epoch and not args.no_double_buffer),
+                   "planned_prefetch": pipe.planned, "consumer": args.consumer, "queue_depth": pipe.queue_depth,
+                   "GPU_MAX_HW_QUEUES": os.environ.get("GPU_MAX_HW_QUEUES"), "GPU_MAX_HW_QUEUES_set_by": "user" if HWQ_SET_BY_USER else "bench.py"},
+        "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": roof["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": roof["frac"],
+                     # not measured in this run: bytes per row from the recorded counter run, times this run's rows per launch
+                     "traffic": per_row_traffic * roof["hbm_rows"] / max(roof["launches"], 1) if per_row_traffic else None,
+                     "traffic_source": traffic_source,
+                     "algorithmic_bytes_per_launch": roof["algorithmic_bytes_per_launch"],
+                     "avg_launch_ms": roof["avg_launch_ms"], "launches": roof["launches"],
+                     "condition": "bulk fill: nothing runs beside the gathers" if args.bulk_fill
+                                  else "host-link pulls of later batches run beside the gathers"},
         "gather": {"rows": rows, "n_local": n_local, "n_hit": n_hit, "n_miss": n_miss,
                    "cache_hit_pct": 100.0 * n_hit / max(1, n_hit + n_miss),
-                   "payload_GBps_hbm_kernel": row_bytes * hbm_rows / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0,
+                   "payload_GBps_hbm_kernel": roof["achieved"] / 2,
                    "miss_hostlink_GBps": row_bytes * n_miss / (m_ms * 1e-3) / 1e9 if m_ms > 0 and n_miss else None,
                    "cache_fill_hostlink_GBps": row_bytes * cached_rows / (f_ms * 1e-3) / 1e9 if f_ms > 0 and cached_rows else None,
                    "cached_rows": cached_rows},
         "sampler": {"sampled_edges": int(totals["edges"].item()), "input_nodes": rows,
-                    "sampled_edges_per_s_whole_path": int(totals["edges"].item()) / dt,
+                    "sampled_edges_per_s_whole_path": int(totals["edges"].item()) / med,
                     "draw_kernel_edges_per_s": int(totals["edges"].item()) / (prof["sample"][0] * 1e-3) if prof["sample"][0] > 0 else None},
         "hostlink": {"bound": "pcie", "kernel": "k_prefetch_pull / k_cache_fill", "peak": HOSTLINK_PEAK_GBS, "unit": "GB/s",
                      "achieved": row_bytes * cached_rows / (f_ms * 1e-3) / 1e9 if f_ms > 0 and cached_rows else None,
                      "note": "sum of pull-kernel durations; the pulls run beside the gathers on their own stream"},
         "kernel_ms": {k: {"total_ms": v[0], "launches": v[1]} for k, v in prof.items()},
-        # host clock: time until each epoch's offline stage (schedule, sampling, histogram, TopHot, plan) had finished,
-        # and the rest (pulls and gathers); with double buffering the next epoch's offline stage hides in "online"
-        "phase_ms": {"offline_until_sizes_known": totals["offline_s"] * 1e3, "online": (dt - totals["offline_s"]) * 1e3},
     }
+    if full_epoch is not None:
+        result["full_epoch"] = full_epoch
+    elif not multi_epoch and steps == bpe:
+        result["full_epoch"] = dict(spread(times, bpe), batches=bpe, k_gather_hbm_frac=roof["frac"],
+                                    k_gather_hbm_avg_launch_ms=roof["avg_launch_ms"])
 
-    # requests for remote rows a cache of a given size would serve, from the last epoch's histogram (no cache is built)
-    fracs = [0.01, 0.05, 0.10, 0.15, 0.20, 0.50, 1.00]
-    caps = [int(f * wl.n_remote) for f in fracs] + [wl.capacity_rows]
-    hits, total = ctx.cache_hit_curve(pipe.counts, wl.home, caps)
-    torch.cuda.synchronize()
-    total = int(total.item())
-    predicted = int(hits[-1].item())
-    hits, caps = hits[:-1], caps[:-1]
-    result["gather"]["cache_hit_pct_predicted_from_histogram"] = 100.0 * predicted / max(total, 1)
-    if totals["epochs"] == 1:      # one epoch: the hits counted by the gathers are exactly those the histogram predicts
-        assert predicted == n_hit and total == n_hit + n_miss, "cache hits differ from the histogram's prediction"
-    result["cache_hit_curve"] = {"period": f"{pipe.n_batches} batches (last timed epoch)", "remote_requests": total,
-                                 "points": [{"capacity_frac_of_remote": f, "capacity_rows": c,
-                                             "hit_pct": 100.0 * int(h) / max(total, 1), "remote_fetches": total - int(h)}
-                                            for f, c, h in zip(fracs, caps, hits.cpu().tolist())]}
+    if not args.no_extras:
+        # requests for remote rows a cache of a given size would serve, from the last epoch's histogram (no cache is built)
+        fracs = [0.01, 0.05, 0.10, 0.15, 0.20, 0.50, 1.00]
+        caps = [int(f * wl.n_remote) for f in fracs] + [wl.capacity_rows]
+        hits, total = ctx.cache_hit_curve(pipe.counts, wl.home, caps)
+        torch.cuda.synchronize()
+        total = int(total.item())
+        hits, caps = hits[:-1], caps[:-1]
+        result["cache_hit_curve"] = {"period": f"{pipe.n_batches} batches (last epoch run)", "remote_requests": total,
+                                     "points": [{"capacity_frac_of_remote": f, "capacity_rows": c,
+                                                 "hit_pct": 100.0 * int(h) / max(total, 1), "remote_fetches": total - int(h)}
+                                                for f, c, h in zip(fracs, caps, hits.cpu().tolist())]}
+        if not args.bulk_fill and not multi_epoch:
+            # the same gathers with all rows pulled beforehand: the copy kernel with nothing beside it
+            n_b = min(steps, bpe)
+            del pipe
+            torch.cuda.empty_cache()
+            with torch.cuda.stream(main_stream):
+                bulk = make_pipeline(False)
+                run_steps(bulk, n_b)
+                _, b_prof, b_totals = profiled_pass(bulk, n_b, dev)
+            b_roof = gather_roofline(b_prof, b_totals, row_bytes)
+            result["roofline"]["frac_without_concurrent_pulls"] = b_roof["frac"]
+            result["roofline"]["avg_launch_ms_without_concurrent_pulls"] = b_roof["avg_launch_ms"]
+            pipe = bulk
     a_ms, a_launches = prof["mean_aggregate"]
     if a_launches:
-        # per launch: one feature row read per sampled edge of the outermost hop, one row written per destination
-        last = pipe.H - 1
-        e_last = sum(int(st.edge_counts[:st.n_batches, last].sum().item()) for st in pipe.states[:1]) if steps <= bpe else None
-        result["consumer"] = {"kernel": "k_mean_aggregate", "total_ms": a_ms, "launches": a_launches,
-                              "outermost_hop_edges": e_last,
-                              "algorithmic_GBps": (row_bytes * (e_last + sum(int(x) for x in pipe.state.tier_offs[:pipe.n_batches, pipe.H].cpu().tolist()))
-                                                   / (a_ms * 1e-3) / 1e9) if e_last else None}
+        result["consumer"] = {"kernel": "k_mean_aggregate", "total_ms": a_ms, "launches": a_launches}
     n_cpu = args.cpu_batches
     if n_cpu is None or n_cpu > 0:
         del pipe

@@ -7,8 +7,7 @@
  *   line 4     VectorPull of the hot rows into the steady cache C_s           -> rg_build_cache (bulk pull), or pulls in order
  *              (and the prefetcher of Section III, Fig. 4)                       of first use ahead of the gathers:
  *                                                                                rg_plan_prefetch + rg_prefetch_planned,
- *                                                                                rg_prefetch_cache_rows, rg_stage_rows +
- *                                                                                rg_commit_staged_rows
+ *                                                                                rg_prefetch_cache_rows
  *   line 12-14 per-batch feature assembly from local store, cache and         -> rg_gather_features
  *              fallback pull of the misses from the remote store
  * and two companions: rg_mean_aggregate (Eq. 1 with AGG = mean over a sampled block, the consumer of the
@@ -34,10 +33,15 @@
  *  - Location word (used by home[] and loc[]): (tag << 30) | row as uint32 stored in int32;
  *    tag 0 = row of the local store, 1 = row (slot) of the cache, 2 = row of the remote store.
  *  - Row strides are in floats.  Rows are copied with 16-byte accesses when every base
- *    pointer is 16-byte aligned and every stride is a multiple of 4 floats; in that case the
- *    copy covers round_up(dim, 4) floats, i.e. up to 3 floats of row padding are read from
- *    the source row and written to the destination row.  Otherwise 8- or 4-byte accesses
- *    copy exactly dim floats.
+ *    pointer is 16-byte aligned and every stride is a multiple of 4 floats; then up to 3 floats
+ *    of padding behind a source row are read (they lie inside the row's stride).  Writes
+ *    cover exactly floats [0, dim) of a destination row, whatever the access width: the padding
+ *    of output, cache and aggregate rows is never touched.
+ *  - Launch shapes can be overridden for re-tuning on another device by environment variables
+ *    that rg_create reads once per context: RG_GATHER_UNROLL (2, 4 or 8 chunks in flight per
+ *    lane of the HBM gather), RG_GATHER_BLOCKS_PER_CU (grid cap of the HBM gather, default
+ *    none), RG_PULL_BLOCKS / RG_PULL_THREADS (grid of the host-link pull kernels, default
+ *    48 x 256), RG_MISS_BLOCKS (grid of the miss-row kernel, default 192).
  */
 #ifndef RAPIDGNN_H
 #define RAPIDGNN_H
@@ -89,10 +93,12 @@ RG_API void rg_destroy(rg_ctx* ctx);
 RG_API const char* rg_last_error(const rg_ctx* ctx);
 RG_API const char* rg_version(void);
 
-/* Pre-size the scratch so later calls allocate nothing: graphs of up to num_nodes nodes,
- * cumulative frontiers of up to max_frontier nodes, gathers of up to max_rows rows.
- * Optional: every call grows the scratch on demand (a synchronising allocation). */
-RG_API rg_status rg_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int64_t max_rows);
+/* Pre-size the scratch so later sampling, histogram, TopHot and gather calls allocate nothing:
+ * graphs of up to num_nodes nodes, cumulative frontiers of up to max_frontier nodes, sampler
+ * calls of up to sample_group batches (1 for rg_sample_blocks), gathers and per-batch prefetch
+ * passes of up to max_rows rows.  Optional: every call grows the scratch on demand (a
+ * synchronising allocation).  1 <= sample_group <= RG_MAX_GROUP. */
+RG_API rg_status rg_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int64_t max_rows, int32_t sample_group);
 
 /* CSR adjacency in HBM: row v lists the nodes whose features v aggregates (Eq. 1, eta(v)). */
 typedef struct {
@@ -128,13 +134,13 @@ RG_API rg_status rg_epoch_schedule(rg_ctx* ctx, const int32_t* train_ids, int64_
  */
 typedef struct {
     int32_t* nodes;            /* device int32[nodes_cap] */
-    int64_t nodes_cap;
+    int64_t nodes_cap;         /* in; on RG_ERR_CAPACITY out: the required size */
     int32_t* tier_off;         /* device int32[num_hops + 2] */
     int32_t* const* indptr;    /* host array[num_hops] of device int32[indptr_cap[h]] */
-    const int64_t* indptr_cap; /* host int64[num_hops] */
+    int64_t* indptr_cap;       /* host int64[num_hops]; in, on RG_ERR_CAPACITY out: the required sizes */
     int32_t* const* nbr;       /* host array[num_hops] of device int32[nbr_cap[h]] */
     int32_t* const* nbr_local; /* host array[num_hops] of device int32[nbr_cap[h]], or NULL to skip relabelling */
-    const int64_t* nbr_cap;    /* host int64[num_hops] */
+    int64_t* nbr_cap;          /* host int64[num_hops]; in, on RG_ERR_CAPACITY out: the required sizes */
     int32_t* num_edges;        /* device int32[num_hops] or NULL: |nbr[h]| (the same value as indptr[h][|frontier_h|]) */
 } rg_blocks;
 
@@ -151,10 +157,12 @@ RG_API rg_status rg_blocks_bounds(int64_t num_nodes, int64_t num_edges, int64_t 
 
 /* seeds: device int32[num_seeds], distinct, num_seeds >= 0; fanouts: host int32[num_hops],
  * each in [0, RG_MAX_FANOUT] or RG_FANOUT_ALL; 1 <= num_hops <= RG_MAX_HOPS.
- * Errors: RG_ERR_INVALID_ARG, RG_ERR_CAPACITY (buffers below the bounds), RG_ERR_OOM. */
+ * Errors: RG_ERR_INVALID_ARG; RG_ERR_OOM; RG_ERR_CAPACITY when a buffer is below its bound: nothing
+ * is launched and nodes_cap, indptr_cap[h] and nbr_cap[h] of the offending rg_blocks are overwritten
+ * with the required sizes (the values rg_blocks_bounds gives), so the caller can reallocate and retry. */
 RG_API rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds, int32_t num_seeds,
                            const int32_t* fanouts, int32_t num_hops, uint64_t seed, uint32_t epoch,
-                           const rg_blocks* out, void* stream);
+                           rg_blocks* out, void* stream);
 
 /* The same for `group` batches at once (1 <= group <= RG_MAX_GROUP): batch g has seeds[g]
  * (num_seeds[g] of them) and writes out[g]; fan-outs, seed and epoch are shared.  The results are
@@ -163,7 +171,7 @@ RG_API rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t*
  * pointers; num_seeds: host int32[group]; out: host array[group]. */
 RG_API rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, const int32_t* const* seeds,
                                         const int32_t* num_seeds, const int32_t* fanouts, int32_t num_hops,
-                                        uint64_t seed, uint32_t epoch, const rg_blocks* out, void* stream);
+                                        uint64_t seed, uint32_t epoch, rg_blocks* out, void* stream);
 
 /* ---- Alg. 1 line 2 / Section IV: access frequency freq(n) -------------------------------
  * counts[v] += number of occurrences of v in nodes[0..n).  counts accumulates over calls
@@ -272,40 +280,6 @@ RG_API rg_status rg_plan_prefetch(rg_ctx* ctx, const rg_cache* cache, const int3
 RG_API rg_status rg_prefetch_planned(rg_ctx* ctx, const rg_prefetch_plan* plan, int32_t batch, const rg_cache* cache,
                                      const float* remote_store, int64_t remote_stride, int32_t dim, void* stream);
 
-/* ---- early pull: VectorPull started during the precompute stage ------------------------------
- * When the cache can hold every remote node (capacity_rows >= number of remote nodes), every remote
- * node a batch touches will be selected by TopHot, so its row can be pulled as soon as the batch has
- * been sampled, while the remaining batches are still being sampled.  The final slot of a row (its
- * rank among the selected ids) is only known after TopHot, so rows are pulled into a staging area
- * and moved to their slots (HBM to HBM) afterwards.
- *   rg_stage_rows(batch b):  for each remote node of input_nodes not claimed earlier in this period:
- *       take the next staging slot, record slot_of[v] and owner[v] = batch_tag, pull the row from the
- *       remote store into the staging slot.  Nodes that find the staging area full are not staged.
- *   rg_commit_staged_rows(batch b), after rg_build_cache (select only):  for each node staged under
- *       batch_tag whose location word names a cache slot: copy the staged row to the slot and mark it
- *       resident.  Nodes that were staged but not selected are skipped (their pull was wasted).
- * Rows that were never staged stay non-resident; rg_prefetch_cache_rows pulls those.  Results
- * (cache_ids, loc, cached rows, gathers) are identical to the bulk pull.
- * The caller zeroes `touched` and `cursor` at the start of a period.  Calls of rg_stage_rows on one
- * rg_stage must be ordered with each other; a commit must follow the stage call of the same tag and
- * the TopHot selection.  batch_tag >= 0. */
-typedef struct {
-    float* rows;              /* device float[capacity_rows * row_stride] */
-    int64_t capacity_rows;
-    int64_t row_stride;       /* floats, >= dim */
-    int32_t* slot_of;         /* device int32[num_nodes]: staging slot of a claimed node (-1: none) */
-    int32_t* owner;           /* device int32[num_nodes]: batch_tag of the call that claimed the node */
-    uint32_t* touched;        /* device uint32[ceil(num_nodes / 32)]: node claimed in this period */
-    uint32_t* cursor;         /* device uint32[1]: number of claims so far */
-} rg_stage;
-
-RG_API rg_status rg_stage_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
-                               const int32_t* home, const rg_stage* stage, int32_t batch_tag,
-                               const float* remote_store, int64_t remote_stride, int32_t dim, void* stream);
-RG_API rg_status rg_commit_staged_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
-                                       const int32_t* home, const rg_stage* stage, int32_t batch_tag,
-                                       const rg_cache* cache, int32_t dim, void* stream);
-
 /* ---- Alg. 1 lines 12-14: feature assembly for one batch ---------------------------------
  * out[i][0:dim] = feature row of input_nodes[i], read from the store loc[] names: local
  * store (HBM), cache (HBM, GetFeatureFromCache) or remote store (fallback pull of the
@@ -354,7 +328,7 @@ RG_API rg_status rg_gather_run(rg_ctx* ctx, int32_t ticket, int64_t n, const int
  * For the outermost hop, feat is the output of rg_gather_features (rows in input-node order).
  * indptr: device int32[n_dst + 1]; nbr_local: device int32[indptr[n_dst]]; n_dst_dev: optional
  * device count as for rg_access_histogram; feat: device float[rows * feat_stride]; agg: device
- * float[n_dst * agg_stride].  Row padding rule as for the gather. */
+ * float[n_dst * agg_stride].  Only floats [0, dim) of an agg row are written. */
 RG_API rg_status rg_mean_aggregate(rg_ctx* ctx, const int32_t* indptr, const int32_t* nbr_local, int64_t n_dst,
                                    const int32_t* n_dst_dev, const float* feat, int64_t feat_stride, int32_t dim,
                                    float* agg, int64_t agg_stride, void* stream);

@@ -55,11 +55,6 @@ class rg_prefetch_plan(ctypes.Structure):
     _fields_ = [("list", c_p), ("list_capacity", c_i64), ("offsets", c_p), ("num_batches", c_i32)]
 
 
-class rg_stage(ctypes.Structure):
-    _fields_ = [("rows", c_p), ("capacity_rows", c_i64), ("row_stride", c_i64), ("slot_of", c_p),
-                ("owner", c_p), ("touched", c_p), ("cursor", c_p)]
-
-
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
@@ -72,7 +67,7 @@ def _load():
     L.rg_last_error.restype = ctypes.c_char_p
     L.rg_version.argtypes = []
     L.rg_version.restype = ctypes.c_char_p
-    L.rg_reserve.argtypes = [c_p, c_i64, c_i64, c_i64]
+    L.rg_reserve.argtypes = [c_p, c_i64, c_i64, c_i64, c_i32]
     L.rg_epoch_schedule.argtypes = [c_p, c_p, c_i64, c_u64, c_u32, c_p, c_p]
     L.rg_blocks_bounds.argtypes = [c_i64, c_i64, c_i64, c_p, c_i32, c_p, c_p]
     L.rg_sample_blocks.argtypes = [c_p, ctypes.POINTER(rg_csr), c_p, c_i32, c_p, c_i32, c_u64, c_u32,
@@ -86,9 +81,6 @@ def _load():
     L.rg_build_cache.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i64, c_i32, ctypes.POINTER(rg_cache), c_p]
     L.rg_cache_hit_curve.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i32, c_p, c_p, c_p]
     L.rg_prefetch_cache_rows.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_p, c_i64, c_i32, c_p]
-    L.rg_stage_rows.argtypes = [c_p, c_p, c_i64, c_p, c_p, ctypes.POINTER(rg_stage), c_i32, c_p, c_i64, c_i32, c_p]
-    L.rg_commit_staged_rows.argtypes = [c_p, c_p, c_i64, c_p, c_p, ctypes.POINTER(rg_stage), c_i32,
-                                        ctypes.POINTER(rg_cache), c_i32, c_p]
     L.rg_gather_prepare.argtypes = [c_p, c_i32, c_i32, ctypes.POINTER(c_p), ctypes.POINTER(c_i64), ctypes.POINTER(c_p),
                                     ctypes.POINTER(rg_cache), ctypes.POINTER(c_p), c_p]
     L.rg_gather_run.argtypes = [c_p, c_i32, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_i64, c_p, c_i64, c_i32, c_p, c_i64,
@@ -101,7 +93,9 @@ def _load():
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group",
                  "rg_access_histogram", "rg_access_histogram_epoch", "rg_build_cache", "rg_cache_hit_curve",
-                 "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_prefetch_planned", "rg_stage_rows", "rg_commit_staged_rows", "rg_gather_features", "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"):
+                 "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_prefetch_planned", "rg_gather_features",
+                 "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable",
+                 "rg_profile_reset", "rg_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -112,8 +106,8 @@ EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "r
                     "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group", "rg_access_histogram",
                     "rg_access_histogram_epoch",
                     "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_plan_prefetch",
-                    "rg_prefetch_planned", "rg_stage_rows", "rg_commit_staged_rows",
-                    "rg_gather_features", "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
+                    "rg_prefetch_planned", "rg_gather_features", "rg_gather_prepare",
+                    "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
 
 
 def _ptr(t, dtype=None, device_type=None, name="tensor"):
@@ -166,8 +160,8 @@ class Context:
             raise RgError(st, _lib.rg_last_error(self._h).decode())
 
     # -- rg_reserve
-    def reserve(self, num_nodes, max_frontier, max_rows):
-        self._check(_lib.rg_reserve(self._h, int(num_nodes), int(max_frontier), int(max_rows)))
+    def reserve(self, num_nodes, max_frontier, max_rows, sample_group=1):
+        self._check(_lib.rg_reserve(self._h, int(num_nodes), int(max_frontier), int(max_rows), int(sample_group)))
 
     # -- rg_epoch_schedule
     def epoch_schedule(self, train_ids, seed, epoch, order_out=None, stream=None):
@@ -260,22 +254,6 @@ class Context:
             _ptr(n_dev, torch.int32, "cuda", "n_dev"), ctypes.byref(cache.c_struct),
             _ptr(home, torch.int32, "cuda", "home"),
             _ptr(remote_store, torch.float32, "mapped", "remote_store"), remote_store.stride(0), int(dim),
-            _stream_handle(stream)))
-
-    # -- rg_stage_rows / rg_commit_staged_rows
-    def stage_rows(self, input_nodes, n, home, stage, batch_tag, remote_store, dim, n_dev=None, stream=None):
-        self._check(_lib.rg_stage_rows(
-            self._h, _ptr(input_nodes, torch.int32, "cuda", "input_nodes"), int(n),
-            _ptr(n_dev, torch.int32, "cuda", "n_dev"), _ptr(home, torch.int32, "cuda", "home"),
-            ctypes.byref(stage.c_struct), int(batch_tag),
-            _ptr(remote_store, torch.float32, "mapped", "remote_store"), remote_store.stride(0), int(dim),
-            _stream_handle(stream)))
-
-    def commit_staged_rows(self, input_nodes, n, home, stage, batch_tag, cache, dim, n_dev=None, stream=None):
-        self._check(_lib.rg_commit_staged_rows(
-            self._h, _ptr(input_nodes, torch.int32, "cuda", "input_nodes"), int(n),
-            _ptr(n_dev, torch.int32, "cuda", "n_dev"), _ptr(home, torch.int32, "cuda", "home"),
-            ctypes.byref(stage.c_struct), int(batch_tag), ctypes.byref(cache.c_struct), int(dim),
             _stream_handle(stream)))
 
     # -- rg_gather_features
@@ -438,25 +416,6 @@ class FeatureCache:
         self.filled = torch.zeros(max((min(self.capacity_rows, num_nodes) + 31) // 32, 1), dtype=torch.int32, device=device)
         self.c_struct = rg_cache(self.cache_ids.data_ptr(), self.cache_rows.data_ptr(), self.capacity_rows,
                                  int(row_stride), self.loc.data_ptr(), self.num_cached.data_ptr(), self.filled.data_ptr())
-
-
-class StagingArea:
-    """rg_stage over caller-owned cuda tensors: rows pulled before their cache slot is known."""
-
-    def __init__(self, num_nodes, capacity_rows, row_stride, device):
-        self.capacity_rows = int(capacity_rows)
-        self.rows = torch.empty(max(self.capacity_rows, 1), int(row_stride), dtype=torch.float32, device=device)
-        self.slot_of = torch.empty(max(num_nodes, 1), dtype=torch.int32, device=device)
-        self.owner = torch.empty(max(num_nodes, 1), dtype=torch.int32, device=device)
-        self.touched = torch.zeros(max((num_nodes + 31) // 32, 1), dtype=torch.int32, device=device)
-        self.cursor = torch.zeros(1, dtype=torch.int32, device=device)
-        self.c_struct = rg_stage(self.rows.data_ptr(), self.capacity_rows, int(row_stride), self.slot_of.data_ptr(),
-                                 self.owner.data_ptr(), self.touched.data_ptr(), self.cursor.data_ptr())
-
-    def reset(self):
-        """Start a new period (queued on the current stream)."""
-        self.touched.zero_()
-        self.cursor.zero_()
 
 
 class PrefetchPlan:

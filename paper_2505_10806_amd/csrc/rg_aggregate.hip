@@ -11,7 +11,7 @@ template <int VEC, int E>
 __global__ void __launch_bounds__(256) k_mean_aggregate(const int32_t* __restrict__ indptr, const int32_t* __restrict__ nbr_local,
                                                         int64_t n_dst, const int32_t* __restrict__ n_dst_dev,
                                                         const float* __restrict__ feat, int64_t feat_stride,
-                                                        float* __restrict__ agg, int64_t agg_stride, int cpr, int log2L) {
+                                                        float* __restrict__ agg, int64_t agg_stride, int cpr, int log2L, int tail) {
     typedef typename RgVec<VEC>::type V;
     int64_t n_act = n_dst;
     if (n_dst_dev) { const int64_t d = *n_dst_dev; n_act = d < n_dst ? d : n_dst; }
@@ -48,8 +48,9 @@ __global__ void __launch_bounds__(256) k_mean_aggregate(const int32_t* __restric
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) ((float*)&acc)[q] = ((float*)&acc)[q] / m;
             }
-            // a 16-byte chunk may reach into the row padding: those lanes hold the mean of the sources' padding
-            __builtin_nontemporal_store(acc, &dst[c]);
+            // a 16-byte chunk may reach into the sources' row padding: only the row's own floats are stored
+            if (tail < VEC && c == cpr - 1) rg_store_head(&dst[c], acc, tail);
+            else __builtin_nontemporal_store(acc, &dst[c]);
         }
     }
 }
@@ -76,11 +77,11 @@ rg_status rg_mean_aggregate(rg_ctx* ctx, const int32_t* indptr, const int32_t* n
     const int grid = (int)rg_max64(1, rg_min64(rg_div_up(n_dst, rows_per_block), (int64_t)ctx->num_cus * 64));
     const int tok = rg_prof_begin(ctx, RG_K_AGGREGATE, s);
     if (vec == 4)
-        k_mean_aggregate<4, 4><<<grid, 256, 0, s>>>(indptr, nbr_local, n_dst, n_dst_dev, feat, feat_stride, agg, agg_stride, shp.cpr, shp.log2L);
+        k_mean_aggregate<4, 4><<<grid, 256, 0, s>>>(indptr, nbr_local, n_dst, n_dst_dev, feat, feat_stride, agg, agg_stride, shp.cpr, shp.log2L, shp.tail);
     else if (vec == 2)
-        k_mean_aggregate<2, 4><<<grid, 256, 0, s>>>(indptr, nbr_local, n_dst, n_dst_dev, feat, feat_stride, agg, agg_stride, shp.cpr, shp.log2L);
+        k_mean_aggregate<2, 4><<<grid, 256, 0, s>>>(indptr, nbr_local, n_dst, n_dst_dev, feat, feat_stride, agg, agg_stride, shp.cpr, shp.log2L, shp.tail);
     else
-        k_mean_aggregate<1, 4><<<grid, 256, 0, s>>>(indptr, nbr_local, n_dst, n_dst_dev, feat, feat_stride, agg, agg_stride, shp.cpr, shp.log2L);
+        k_mean_aggregate<1, 4><<<grid, 256, 0, s>>>(indptr, nbr_local, n_dst, n_dst_dev, feat, feat_stride, agg, agg_stride, shp.cpr, shp.log2L, shp.tail);
     rg_prof_end(ctx, tok, s);
     RG_LAUNCH_CHECK(ctx, "k_mean_aggregate");
     return RG_OK;

@@ -1,9 +1,11 @@
 // Context, error reporting, scratch management and kernel timing of librapidgnn.
 #include <stdarg.h>
+#include <stdlib.h>
+#include <string.h>
 
 #include "rg_internal.h"
 
-static std::string g_create_error;
+static char g_create_error[512];
 
 rg_status rg_set_error(rg_ctx* ctx, rg_status code, const char* fmt, ...) {
     char buf[512];
@@ -11,7 +13,7 @@ rg_status rg_set_error(rg_ctx* ctx, rg_status code, const char* fmt, ...) {
     va_start(ap, fmt);
     vsnprintf(buf, sizeof(buf), fmt, ap);
     va_end(ap);
-    if (ctx) ctx->err = buf; else g_create_error = buf;
+    memcpy(ctx ? ctx->err : g_create_error, buf, sizeof(buf));
     return code;
 }
 
@@ -70,6 +72,13 @@ rg_status rg_gather_reserve(rg_ctx* ctx, int64_t rows) {
     return RG_OK;
 }
 
+static int env_int(const char* name, int dflt) {
+    const char* v = getenv(name);
+    if (!v || !*v) return dflt;
+    const int x = atoi(v);
+    return x > 0 ? x : dflt;
+}
+
 extern "C" {
 
 const char* rg_version(void) { return "rapidgnn-mi355x 0.1 (gfx950)"; }
@@ -98,6 +107,15 @@ rg_status rg_create(int device, rg_ctx** out) {
         delete ctx;
         return rg_set_error(nullptr, RG_ERR_HIP, "rg_create: hipEventCreate failed");
     }
+    // launch-shape knobs: read here once, never on the call paths
+    RgKnobs& k = ctx->knobs;
+    const int unroll = env_int("RG_GATHER_UNROLL", k.gather_unroll);
+    if (unroll == 2 || unroll == 4 || unroll == 8) k.gather_unroll = unroll;
+    k.gather_blocks_per_cu = env_int("RG_GATHER_BLOCKS_PER_CU", k.gather_blocks_per_cu);
+    k.pull_blocks = env_int("RG_PULL_BLOCKS", k.pull_blocks);
+    const int threads = env_int("RG_PULL_THREADS", k.pull_threads);
+    if (threads == 64 || threads == 256 || threads == 1024) k.pull_threads = threads;
+    k.miss_blocks = env_int("RG_MISS_BLOCKS", k.miss_blocks);
     *out = ctx;
     return RG_OK;
 }
@@ -107,7 +125,8 @@ void rg_destroy(rg_ctx* ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
     RgBuf* bufs[] = {&ctx->visited, &ctx->fresh, &ctx->pos, &ctx->chunk_sum, &ctx->row_start, &ctx->row_deg, &ctx->sched_keys, &ctx->sched_ids,
-                     &ctx->topk_ctl, &ctx->topk_blk, &ctx->pf_list, &ctx->pf_ctl, &ctx->stage_list, &ctx->stage_ctl, &ctx->commit_list, &ctx->commit_ctl, &ctx->plan_cursor, &ctx->gather_src, &ctx->miss_list, &ctx->gather_ctl};
+                     &ctx->topk_ctl, &ctx->topk_blk, &ctx->topk_caps, &ctx->pf_list, &ctx->pf_ctl, &ctx->plan_cursor, &ctx->gather_src, &ctx->miss_list,
+                     &ctx->gather_ctl};
     for (RgBuf* b : bufs)
         if (b->p) (void)hipFree(b->p);
     for (auto& s : ctx->spans) { (void)hipEventDestroy(s.start); (void)hipEventDestroy(s.stop); }
@@ -117,32 +136,20 @@ void rg_destroy(rg_ctx* ctx) {
     delete ctx;
 }
 
-const char* rg_last_error(const rg_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+const char* rg_last_error(const rg_ctx* ctx) { return ctx ? ctx->err : g_create_error; }
 
-rg_status rg_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int64_t max_rows) {
+rg_status rg_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int64_t max_rows, int32_t sample_group) {
     if (!ctx) return RG_ERR_INVALID_ARG;
     RG_REQUIRE(ctx, num_nodes >= 0 && max_frontier >= 0 && max_rows >= 0, "rg_reserve: negative size");
     RG_REQUIRE(ctx, num_nodes <= (int64_t)RG_ROW_MASK + 1, "rg_reserve: num_nodes exceeds 2^30");
+    RG_REQUIRE(ctx, sample_group >= 1 && sample_group <= RG_MAX_GROUP, "rg_reserve: sample_group = %d not in [1,%d]", sample_group, RG_MAX_GROUP);
     RG_HIP(ctx, hipSetDevice(ctx->device));
-    const size_t words = (size_t)rg_div_up(num_nodes, 32);
     rg_status st;
-    if ((st = rg_ensure(ctx, ctx->visited, words * 4)) != RG_OK) return st;
-    const size_t before = ctx->fresh.bytes;
-    if ((st = rg_ensure(ctx, ctx->fresh, words * 4, true)) != RG_OK) return st;
-    (void)before;
-    if ((st = rg_ensure(ctx, ctx->pos, (size_t)num_nodes * 4)) != RG_OK) return st;
-    const size_t chunks = (size_t)rg_max64(rg_div_up(max_frontier, 256), rg_div_up((int64_t)words, 1024)) + 2;
-    if ((st = rg_ensure(ctx, ctx->chunk_sum, chunks * 4)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->row_start, (size_t)max_frontier * 8)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->row_deg, (size_t)max_frontier * 4)) != RG_OK) return st;
+    if ((st = rg_sampler_reserve(ctx, num_nodes, max_frontier, sample_group)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->topk_blk, ((size_t)rg_div_up(num_nodes, 1024) + 2) * 8)) != RG_OK) return st;
     if ((st = rg_gather_reserve(ctx, max_rows)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->pf_list, (size_t)max_rows * 8)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->pf_ctl, 64)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->stage_list, (size_t)max_rows * 8)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->stage_ctl, 64)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->commit_list, (size_t)max_rows * 8)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->commit_ctl, 64)) != RG_OK) return st;
     return RG_OK;
 }
 

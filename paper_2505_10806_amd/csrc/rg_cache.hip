@@ -1,9 +1,7 @@
 // Access-frequency histogram (Section IV, offline stage), TopHot selection (Alg. 1 line 3), the hit curve
-// against cache size (Section V), and VectorPull (Alg. 1 line 4) in its three forms: one bulk pull, pulls by
+// against cache size (Section V), and VectorPull (Alg. 1 line 4) in its two forms: one bulk pull, or pulls by
 // first use ahead of the gathers (the prefetcher of Section III: with a per-batch claim pass or from a
-// per-epoch plan), and early pulls into a staging area during the offline stage.
-#include <stdlib.h>
-
+// per-epoch plan).
 #include "rg_rowcopy.h"
 
 namespace {
@@ -101,29 +99,112 @@ __global__ void __launch_bounds__(256) k_histogram_seeds(const int32_t* __restri
     }
 }
 
-// ---------------------------------------------------------------------------- radix select
-// Finds the count threshold T of the K_eff-th best candidate, most significant byte first.
+// ---------------------------------------------------------------------------- threshold select
+// Finds the count threshold T of the K_eff-th best candidate.  Access counts are bounded by the number of batches of
+// the period (a few hundred), so one streaming pass with a histogram of the counts clamped to kLowBins - 1 resolves T
+// whenever T < kLowBins - 1.  Only when the K_eff-th best candidate sits in the clamped last bin do the four byte passes
+// of a most-significant-byte-first radix select run; otherwise their kernels return at once.
+constexpr int kLowBins = 2048;
+constexpr int kBallotBins = 4;       // counts 1..kBallotBins are tallied with wave ballots instead of LDS atomics
+
 struct TopkCtl {
-    uint32_t prefix;     // resolved high bytes of T
-    uint32_t need;       // how many of the candidates matching the prefix are still to be taken
+    uint32_t prefix;     // the threshold T (radix passes: its resolved high bytes)
+    uint32_t need;       // how many of the candidates tied with T are to be taken
     uint32_t k_eff;
-    uint32_t pad;
+    uint32_t resolved;   // 1: T and need are final, the radix passes are skipped
     uint32_t hist[4][256];
+    uint32_t low[kLowBins];          // candidates per clamped count
+    unsigned long long ovf_sum;      // sum of the counts of the candidates in the last (clamped) bin
 };
 
 __device__ __forceinline__ bool rg_is_candidate(uint32_t home_word, uint32_t count) {
     return (home_word >> RG_TAG_SHIFT) == RG_TAG_REMOTE && count >= 1u;
 }
 
-__global__ void __launch_bounds__(256) k_topk_init(TopkCtl* __restrict__ ctl) {
-    for (int i = threadIdx.x; i < 4 * 256; i += 256) (&ctl->hist[0][0])[i] = 0u;
-    if (threadIdx.x == 0) { ctl->prefix = 0u; ctl->need = 0u; ctl->k_eff = 0u; ctl->pad = 0u; }
+// force_radix = the address of a flag that, when set, sends this selection through the radix passes.
+__global__ void __launch_bounds__(256) k_topk_init(TopkCtl* __restrict__ ctl, const uint32_t* __restrict__ skip_flag) {
+    if (skip_flag) {                 // a later selection of the hit curve: keep the low histogram, redo only the radix state
+        for (int i = threadIdx.x; i < 4 * 256; i += 256) (&ctl->hist[0][0])[i] = 0u;
+        if (threadIdx.x == 0) { ctl->prefix = 0u; ctl->need = 0u; ctl->k_eff = 0u; ctl->resolved = *skip_flag; }
+        return;
+    }
+    uint32_t* w = (uint32_t*)ctl;
+    for (int i = threadIdx.x; i < (int)(sizeof(TopkCtl) / 4); i += 256) w[i] = 0u;
+}
+
+// low[min(count, kLowBins - 1)] += 1 for every candidate; ovf_sum += count for those in the last bin.
+__global__ void __launch_bounds__(256) k_topk_hist_low(const uint32_t* __restrict__ counts, const int32_t* __restrict__ home, int64_t n,
+                                                       TopkCtl* __restrict__ ctl) {
+    __shared__ uint32_t h[kLowBins];
+    __shared__ unsigned long long ovf_s;
+    for (int i = threadIdx.x; i < kLowBins; i += 256) h[i] = 0u;
+    if (threadIdx.x == 0) ovf_s = 0ull;
+    __syncthreads();
+    unsigned long long ovf = 0ull;
+    const int lane = rg_lane();
+    for (int64_t v0 = (int64_t)blockIdx.x * 256; v0 < n; v0 += (int64_t)gridDim.x * 256) {     // uniform per workgroup
+        const int64_t v = v0 + threadIdx.x;
+        uint32_t bin = 0u;                                   // bin 0: not a candidate
+        if (v < n) {
+            const uint32_t c = counts[v];
+            if (rg_is_candidate((uint32_t)home[v], c)) {
+                bin = c < (uint32_t)(kLowBins - 1) ? c : (uint32_t)(kLowBins - 1);
+                if (c >= (uint32_t)(kLowBins - 1)) ovf += c;
+            }
+        }
+        // most candidates of a long-tailed distribution have a count of 1..4: one LDS atomic per wavefront for each
+#pragma unroll
+        for (uint32_t q = 1; q <= (uint32_t)kBallotBins; ++q) {
+            const unsigned long long m = __ballot(bin == q);
+            if (lane == 0 && m) atomicAdd(&h[q], (uint32_t)__popcll(m));
+        }
+        if (bin > (uint32_t)kBallotBins) atomicAdd(&h[bin], 1u);
+    }
+    if (ovf) atomicAdd(&ovf_s, ovf);
+    __syncthreads();
+    for (int i = threadIdx.x; i < kLowBins; i += 256) {
+        const uint32_t mine = h[i];
+        if (mine) atomicAdd(&ctl->low[i], mine);
+    }
+    if (threadIdx.x == 0 && ovf_s) atomicAdd(&ctl->ovf_sum, ovf_s);
+}
+
+// One workgroup: K_eff = min(capacity, #candidates); T = the bin holding the K_eff-th best candidate.
+__global__ void __launch_bounds__(256) k_topk_pick_low(TopkCtl* __restrict__ ctl, int64_t capacity, int64_t* __restrict__ num_cached) {
+    __shared__ int smem[256 / RG_WAVE + 1];
+    constexpr int PER = kLowBins / 256;                      // thread t owns bins kLowBins-1-PER*t downwards
+    uint32_t h[PER];
+    int mine = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        h[j] = ctl->low[kLowBins - 1 - (PER * (int)threadIdx.x + j)];
+        mine += (int)h[j];
+    }
+    int total;
+    int above = rg_block_excl_scan<256 / RG_WAVE>(mine, smem, &total);     // candidates in strictly larger bins
+    const uint64_t k = (uint64_t)capacity < (uint64_t)total ? (uint64_t)capacity : (uint64_t)total;
+    if (threadIdx.x == 0) {
+        ctl->k_eff = (uint32_t)k;
+        if (num_cached) *num_cached = (int64_t)k;
+        if (k == 0) { ctl->prefix = 0xFFFFFFFFu; ctl->need = 0u; ctl->resolved = 1u; }   // a threshold no count reaches
+    }
+    if (k == 0) return;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        const int bin = kLowBins - 1 - (PER * (int)threadIdx.x + j);
+        if ((uint64_t)above < k && k <= (uint64_t)above + h[j]) {         // exactly one bin satisfies this
+            if (bin < kLowBins - 1) { ctl->prefix = (uint32_t)bin; ctl->need = (uint32_t)(k - above); ctl->resolved = 1u; }
+            else ctl->resolved = 0u;                                       // inside the clamped bin: radix passes decide
+        }
+        above += (int)h[j];
+    }
 }
 
 // Histogram of byte `pass` (0 = most significant) of the counts of candidates that match the prefix.
 __global__ void __launch_bounds__(256) k_topk_hist(const uint32_t* __restrict__ counts, const int32_t* __restrict__ home, int64_t n,
                                                    int pass, TopkCtl* __restrict__ ctl) {
     __shared__ uint32_t h[256];
+    if (ctl->resolved) return;                               // uniform
     h[threadIdx.x] = 0u;
     __syncthreads();
     const int shift = 24 - 8 * pass;
@@ -140,10 +221,11 @@ __global__ void __launch_bounds__(256) k_topk_hist(const uint32_t* __restrict__ 
 }
 
 // One workgroup: pick the byte value holding the need-th largest remaining candidate.
-__global__ void __launch_bounds__(256) k_topk_pick(TopkCtl* __restrict__ ctl, int pass, int64_t capacity, int64_t* __restrict__ num_cached) {
+__global__ void __launch_bounds__(256) k_topk_pick(TopkCtl* __restrict__ ctl, int pass, int64_t capacity) {
     __shared__ uint32_t h[256];
     __shared__ uint32_t above[256];      // candidates in strictly larger byte values
     __shared__ uint32_t need_s;
+    if (ctl->resolved) return;           // uniform
     h[threadIdx.x] = ctl->hist[pass][threadIdx.x];
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -154,7 +236,6 @@ __global__ void __launch_bounds__(256) k_topk_pick(TopkCtl* __restrict__ ctl, in
             const uint64_t k = (uint64_t)capacity < (uint64_t)run ? (uint64_t)capacity : (uint64_t)run;
             ctl->k_eff = (uint32_t)k;
             ctl->need = (uint32_t)k;
-            if (num_cached) *num_cached = (int64_t)k;
             need0 = (uint32_t)k;
         }
         need_s = need0;
@@ -171,6 +252,57 @@ __global__ void __launch_bounds__(256) k_topk_pick(TopkCtl* __restrict__ ctl, in
     if (above[d] < need && need <= above[d] + h[d]) {     // exactly one byte value satisfies this
         ctl->prefix |= (uint32_t)d << shift;
         ctl->need = need - above[d];
+    }
+}
+
+constexpr int kCapChunk = 64;
+struct CapChunk { int64_t v[kCapChunk]; };
+
+__global__ void k_store_caps(int64_t* __restrict__ dst, const CapChunk chunk, int count) {
+    if ((int)threadIdx.x < count) dst[threadIdx.x] = chunk.v[threadIdx.x];
+}
+
+// One workgroup, after k_topk_hist_low: requests served by a cache of each capacity, read off the histogram.
+// hits[j] = sum of the counts above the threshold of capacity j + (ties taken) x threshold.  A capacity whose
+// threshold lies inside the clamped last bin is left to the radix passes: radix_flag[j] = 0 ("not resolved").
+__global__ void __launch_bounds__(256) k_hit_curve_low(const TopkCtl* __restrict__ ctl, const int64_t* __restrict__ capacities,
+                                                       int num_capacities, unsigned long long* __restrict__ hits,
+                                                       unsigned long long* __restrict__ total_out, uint32_t* __restrict__ resolved_flag) {
+    __shared__ uint32_t cnt_above[kLowBins];                 // candidates with a larger clamped count
+    __shared__ unsigned long long sum_above[kLowBins];       // and the sum of their counts
+    __shared__ unsigned long long grand_s;
+    if (threadIdx.x == 0) {
+        uint32_t cnt = 0u;
+        unsigned long long sum = 0ull;
+        for (int b = kLowBins - 1; b >= 1; --b) {
+            cnt_above[b] = cnt;
+            sum_above[b] = sum;
+            const uint32_t hb = ctl->low[b];
+            cnt += hb;
+            sum += b == kLowBins - 1 ? ctl->ovf_sum : (unsigned long long)hb * (unsigned long long)b;
+        }
+        cnt_above[0] = cnt;                                  // = number of candidates (bin 0 holds none)
+        sum_above[0] = sum;
+        grand_s = sum;
+        if (total_out) *total_out = sum;
+    }
+    __syncthreads();
+    const uint32_t n_cand = cnt_above[0];
+    for (int j = threadIdx.x; j < num_capacities; j += 256) {
+        const uint64_t cap = (uint64_t)capacities[j];
+        const uint32_t k = cap < (uint64_t)n_cand ? (uint32_t)cap : n_cand;
+        if (k == 0u) { hits[j] = 0ull; resolved_flag[j] = 1u; continue; }
+        if (k == n_cand) { hits[j] = grand_s; resolved_flag[j] = 1u; continue; }
+        // the threshold bin T holds the k-th best candidate: cnt_above[T] < k <= cnt_above[T - 1].  cnt_above falls as
+        // the bin index rises and cnt_above[kLowBins - 1] = 0 < k, so T is the smallest bin with cnt_above[T] < k.
+        int lo = 1, hi = kLowBins - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (cnt_above[mid] < k) hi = mid; else lo = mid + 1;
+        }
+        if (lo == kLowBins - 1) { hits[j] = 0ull; resolved_flag[j] = 0u; continue; }
+        hits[j] = sum_above[lo] + (unsigned long long)(k - cnt_above[lo]) * (unsigned long long)lo;
+        resolved_flag[j] = 1u;
     }
 }
 
@@ -274,39 +406,28 @@ __global__ void __launch_bounds__(256) k_topk_emit(const uint32_t* __restrict__ 
     }
 }
 
-// hits += sum of the counts above the threshold plus (ties taken) x threshold: the accesses a cache holding the
-// selected set would serve.  total += sum of the counts of all candidates (written when total != NULL).
+// Radix path of the hit curve: hits += sum of the counts above the threshold plus (ties taken) x threshold.
+// `resolved` = 1 when the histogram pass already produced this capacity's value.
 __global__ void __launch_bounds__(256) k_hit_sum(const uint32_t* __restrict__ counts, const int32_t* __restrict__ home, int64_t n,
-                                                 const TopkCtl* __restrict__ ctl, unsigned long long* __restrict__ hits,
-                                                 unsigned long long* __restrict__ total) {
+                                                 const TopkCtl* __restrict__ ctl, const uint32_t* __restrict__ resolved,
+                                                 unsigned long long* __restrict__ hits) {
+    if (*resolved) return;                                   // uniform
     const uint32_t T = ctl->prefix;
-    unsigned long long above = 0ull, all = 0ull;
+    unsigned long long above = 0ull;
     for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += (int64_t)gridDim.x * blockDim.x) {
         const uint32_t c = counts[v];
-        if (!rg_is_candidate((uint32_t)home[v], c)) continue;
-        all += c;
-        if (c > T) above += c;
+        if (rg_is_candidate((uint32_t)home[v], c) && c > T) above += c;
     }
 #pragma unroll
-    for (int off = RG_WAVE / 2; off > 0; off >>= 1) {
-        above += __shfl_xor(above, off, RG_WAVE);
-        all += __shfl_xor(all, off, RG_WAVE);
-    }
-    __shared__ unsigned long long pa[4], pt[4];
-    if (rg_lane() == 0) { pa[threadIdx.x >> 6] = above; pt[threadIdx.x >> 6] = all; }
+    for (int off = RG_WAVE / 2; off > 0; off >>= 1) above += __shfl_xor(above, off, RG_WAVE);
+    __shared__ unsigned long long pa[4];
+    if (rg_lane() == 0) pa[threadIdx.x >> 6] = above;
     __syncthreads();
     if (threadIdx.x == 0) {
         unsigned long long a = pa[0] + pa[1] + pa[2] + pa[3];
         if (blockIdx.x == 0) a += (unsigned long long)ctl->need * (unsigned long long)T;   // need == 0 when nothing is selected
         if (a) atomicAdd(hits, a);
-        const unsigned long long t = pt[0] + pt[1] + pt[2] + pt[3];
-        if (total && t) atomicAdd(total, t);
     }
-}
-
-__global__ void k_zero_u64(unsigned long long* __restrict__ p, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0ull;
 }
 
 // ---------------------------------------------------------------------------- VectorPull
@@ -315,7 +436,7 @@ template <int VEC>
 __global__ void __launch_bounds__(256) k_cache_fill(const int32_t* __restrict__ cache_ids, const int32_t* __restrict__ home,
                                                     const int64_t* __restrict__ num_cached, const float* __restrict__ remote_store,
                                                     int64_t remote_stride, float* __restrict__ cache_rows, int64_t cache_stride,
-                                                    int cpr, int log2L) {
+                                                    int cpr, int log2L, int tail) {
     typedef typename RgVec<VEC>::type V;
     constexpr int U = 4;
     const int64_t n = *num_cached;
@@ -345,9 +466,13 @@ __global__ void __launch_bounds__(256) k_cache_fill(const int32_t* __restrict__ 
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (src[u]) val[u] = src[u][c];
+            const bool head_only = tail < VEC && c == cpr - 1;      // only the row's own floats of its last chunk are stored
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (dst[u]) dst[u][c] = val[u];
+                if (dst[u]) {
+                    if (head_only) rg_store_head(&dst[u][c], val[u], tail);
+                    else dst[u][c] = val[u];
+                }
         }
     }
 }
@@ -409,102 +534,6 @@ __global__ void __launch_bounds__(256) k_prefetch_select(const int32_t* __restri
     }
 }
 
-// Early pull, step 1.  For every listed node whose home is the remote store and that no earlier call of this
-// period has claimed (atomic test-and-set of its `touched` bit): take the next staging slot, remember it in
-// slot_of[v], tag owner[v] with this call's batch tag and append (staging slot, remote row) to the pull list.
-// Nodes for which no staging slot is left are not claimed further: they stay without a staged row.
-__global__ void __launch_bounds__(256) k_stage_select(const int32_t* __restrict__ nodes, int64_t n, const int32_t* __restrict__ n_dev,
-                                                      const int32_t* __restrict__ home, uint32_t* __restrict__ touched,
-                                                      int32_t* __restrict__ slot_of, int32_t* __restrict__ owner, int32_t batch_tag,
-                                                      uint32_t* __restrict__ cursor, int64_t stage_capacity,
-                                                      int32_t* __restrict__ list, uint32_t* __restrict__ pctl) {
-    __shared__ int smem[256 / RG_WAVE + 1];
-    __shared__ uint32_t slot_base_s, list_base_s;
-    int64_t n_act = n;
-    if (n_dev) { const int64_t d = *n_dev; n_act = d < n ? d : n; }
-    if ((int64_t)blockIdx.x * blockDim.x >= n_act) return;        // uniform per workgroup
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int take = 0;
-    int32_t v = 0;
-    uint32_t rrow = 0u;
-    if (i < n_act) {
-        v = nodes[i];
-        const uint32_t hw = (uint32_t)home[v];
-        if ((hw >> RG_TAG_SHIFT) == RG_TAG_REMOTE) {
-            const uint32_t bit = 1u << (v & 31);
-            if (!(touched[(uint32_t)v >> 5] & bit)) {
-                const uint32_t old = atomicOr(&touched[(uint32_t)v >> 5], bit);
-                if (!(old & bit)) { take = 1; rrow = hw & RG_ROW_MASK; }
-            }
-        }
-    }
-    int total;
-    const int excl = rg_block_excl_scan<256 / RG_WAVE>(take, smem, &total);
-    if (total == 0) return;                                        // uniform
-    if (threadIdx.x == 0) slot_base_s = atomicAdd(cursor, (uint32_t)total);
-    __syncthreads();
-    const int64_t slot = (int64_t)slot_base_s + excl;
-    const int staged = take && slot < stage_capacity;
-    if (take) {
-        slot_of[v] = staged ? (int32_t)slot : -1;
-        owner[v] = staged ? batch_tag : -1;
-    }
-    // second compaction: only rows that got a staging slot are pulled
-    int total2;
-    const int excl2 = rg_block_excl_scan<256 / RG_WAVE>(staged, smem, &total2);
-    if (total2 == 0) return;
-    if (threadIdx.x == 0) list_base_s = atomicAdd(&pctl[0], (uint32_t)total2);
-    __syncthreads();
-    if (staged) {
-        const int64_t j = (int64_t)list_base_s + excl2;
-        list[2 * j] = (int32_t)slot;
-        list[2 * j + 1] = (int32_t)rrow;
-    }
-}
-
-// Early pull, step 2 (after TopHot).  For every listed node staged by the call with this batch tag whose
-// location word now names a cache slot: claim the slot's resident bit and append (cache slot, staging slot).
-__global__ void __launch_bounds__(256) k_commit_select(const int32_t* __restrict__ nodes, int64_t n, const int32_t* __restrict__ n_dev,
-                                                       const int32_t* __restrict__ home, const int32_t* __restrict__ loc,
-                                                       const uint32_t* __restrict__ touched, const int32_t* __restrict__ slot_of,
-                                                       const int32_t* __restrict__ owner, int32_t batch_tag,
-                                                       uint32_t* __restrict__ filled, int32_t* __restrict__ list,
-                                                       uint32_t* __restrict__ pctl) {
-    __shared__ int smem[256 / RG_WAVE + 1];
-    __shared__ uint32_t base_s;
-    int64_t n_act = n;
-    if (n_dev) { const int64_t d = *n_dev; n_act = d < n ? d : n; }
-    if ((int64_t)blockIdx.x * blockDim.x >= n_act) return;        // uniform per workgroup
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int take = 0;
-    uint32_t cslot = 0u;
-    int32_t sslot = 0;
-    if (i < n_act) {
-        const int32_t v = nodes[i];
-        const uint32_t bit = 1u << (v & 31);
-        if (((uint32_t)home[v] >> RG_TAG_SHIFT) == RG_TAG_REMOTE && (touched[(uint32_t)v >> 5] & bit) && owner[v] == batch_tag) {
-            const uint32_t w = (uint32_t)loc[v];
-            sslot = slot_of[v];
-            if ((w >> RG_TAG_SHIFT) == RG_TAG_CACHE && sslot >= 0) {
-                cslot = w & RG_ROW_MASK;
-                const uint32_t fbit = 1u << (cslot & 31u);
-                const uint32_t old = atomicOr(&filled[cslot >> 5], fbit);
-                take = !(old & fbit);
-            }
-        }
-    }
-    int total;
-    const int excl = rg_block_excl_scan<256 / RG_WAVE>(take, smem, &total);
-    if (total == 0) return;                                        // uniform
-    if (threadIdx.x == 0) base_s = atomicAdd(&pctl[0], (uint32_t)total);
-    __syncthreads();
-    if (take) {
-        const int64_t j = (int64_t)base_s + excl;
-        list[2 * j] = (int32_t)cslot;
-        list[2 * j + 1] = sslot;
-    }
-}
-
 // dst_rows[list[2j]] = src_rows[list[2j+1]] for every pair of the list (host link or HBM source alike).
 // Marks the slots of list[seg_off[0]..seg_off[1]) resident (queued behind the pull of the same segment).
 __global__ void __launch_bounds__(256) k_mark_segment(const int32_t* __restrict__ list, const int32_t* __restrict__ seg_off,
@@ -523,7 +552,7 @@ __global__ void __launch_bounds__(1024) k_prefetch_pull(const int32_t* __restric
                                                        const int32_t* __restrict__ seg_off,
                                                        const float* __restrict__ remote_store, int64_t remote_stride,
                                                        float* __restrict__ cache_rows, int64_t cache_stride, int64_t dst_rows,
-                                                       int cpr, int log2L) {
+                                                       int cpr, int log2L, int tail) {
     typedef typename RgVec<VEC>::type V;
     constexpr int U = 4;
     int64_t n;
@@ -558,9 +587,13 @@ __global__ void __launch_bounds__(1024) k_prefetch_pull(const int32_t* __restric
             V val[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) val[u] = src[u][c];
+            const bool head_only = tail < VEC && c == cpr - 1;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (dst[u]) dst[u][c] = val[u];
+                if (dst[u]) {
+                    if (head_only) rg_store_head(&dst[u][c], val[u], tail);
+                    else dst[u][c] = val[u];
+                }
         }
     }
 }
@@ -706,11 +739,11 @@ rg_status launch_list_copy(rg_ctx* ctx, const int32_t* list, const uint32_t* pct
     const int grid = (int)rg_max64(1, rg_min64(rg_div_up(n_upper, rows_per_block), blocks));
     const int tok = rg_prof_begin(ctx, RG_K_CACHE_FILL, s);
     if (vec == 4)
-        k_prefetch_pull<4><<<grid, threads, 0, s>>>(list, pctl, seg_off, src, src_stride, dst, dst_stride, dst_rows, shp.cpr, shp.log2L);
+        k_prefetch_pull<4><<<grid, threads, 0, s>>>(list, pctl, seg_off, src, src_stride, dst, dst_stride, dst_rows, shp.cpr, shp.log2L, shp.tail);
     else if (vec == 2)
-        k_prefetch_pull<2><<<grid, threads, 0, s>>>(list, pctl, seg_off, src, src_stride, dst, dst_stride, dst_rows, shp.cpr, shp.log2L);
+        k_prefetch_pull<2><<<grid, threads, 0, s>>>(list, pctl, seg_off, src, src_stride, dst, dst_stride, dst_rows, shp.cpr, shp.log2L, shp.tail);
     else
-        k_prefetch_pull<1><<<grid, threads, 0, s>>>(list, pctl, seg_off, src, src_stride, dst, dst_stride, dst_rows, shp.cpr, shp.log2L);
+        k_prefetch_pull<1><<<grid, threads, 0, s>>>(list, pctl, seg_off, src, src_stride, dst, dst_stride, dst_rows, shp.cpr, shp.log2L, shp.tail);
     rg_prof_end(ctx, tok, s);
     RG_LAUNCH_CHECK(ctx, "k_prefetch_pull");
     return RG_OK;
@@ -796,13 +829,17 @@ rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32_t* hom
     int32_t* blk_gt = (int32_t*)ctx->topk_blk.p;
     int32_t* blk_eq = blk_gt + nblocks;
 
-    k_topk_init<<<1, 256, 0, s>>>(ctl);
+    k_topk_init<<<1, 256, 0, s>>>(ctl, nullptr);
     RG_LAUNCH_CHECK(ctx, "k_topk_init");
     const int hist_grid = (int)rg_max64(1, rg_min64(rg_div_up(num_nodes, 256 * 8), (int64_t)ctx->num_cus * 8));
-    for (int pass = 0; pass < 4; ++pass) {
+    k_topk_hist_low<<<hist_grid, 256, 0, s>>>(counts, home, num_nodes, ctl);
+    RG_LAUNCH_CHECK(ctx, "k_topk_hist_low");
+    k_topk_pick_low<<<1, 256, 0, s>>>(ctl, cache->capacity_rows, cache->num_cached);
+    RG_LAUNCH_CHECK(ctx, "k_topk_pick_low");
+    for (int pass = 0; pass < 4; ++pass) {                   // return at once unless the threshold is in the clamped bin
         k_topk_hist<<<hist_grid, 256, 0, s>>>(counts, home, num_nodes, pass, ctl);
         RG_LAUNCH_CHECK(ctx, "k_topk_hist");
-        k_topk_pick<<<1, 256, 0, s>>>(ctl, pass, cache->capacity_rows, cache->num_cached);
+        k_topk_pick<<<1, 256, 0, s>>>(ctl, pass, cache->capacity_rows);
         RG_LAUNCH_CHECK(ctx, "k_topk_pick");
     }
     k_topk_count<<<(int)nblocks, 256, 0, s>>>(counts, home, num_nodes, ctl, blk_gt, blk_eq);
@@ -823,11 +860,11 @@ rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32_t* hom
         const int grid = (int)rg_max64(1, rg_min64(rg_div_up(rows_ub, rows_per_block), (int64_t)ctx->num_cus * 16));
         const int tok = rg_prof_begin(ctx, RG_K_CACHE_FILL, s);
         if (vec == 4)
-            k_cache_fill<4><<<grid, 256, 0, s>>>(cache->cache_ids, home, cache->num_cached, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L);
+            k_cache_fill<4><<<grid, 256, 0, s>>>(cache->cache_ids, home, cache->num_cached, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L, shp.tail);
         else if (vec == 2)
-            k_cache_fill<2><<<grid, 256, 0, s>>>(cache->cache_ids, home, cache->num_cached, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L);
+            k_cache_fill<2><<<grid, 256, 0, s>>>(cache->cache_ids, home, cache->num_cached, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L, shp.tail);
         else
-            k_cache_fill<1><<<grid, 256, 0, s>>>(cache->cache_ids, home, cache->num_cached, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L);
+            k_cache_fill<1><<<grid, 256, 0, s>>>(cache->cache_ids, home, cache->num_cached, remote_store, remote_stride, cache->cache_rows, cache->row_stride, shp.cpr, shp.log2L, shp.tail);
         rg_prof_end(ctx, tok, s);
         RG_LAUNCH_CHECK(ctx, "k_cache_fill");
     }
@@ -853,32 +890,39 @@ rg_status rg_cache_hit_curve(rg_ctx* ctx, const uint32_t* counts, const int32_t*
     rg_status st;
     if ((st = rg_ensure(ctx, ctx->topk_ctl, sizeof(TopkCtl))) != RG_OK) return st;
     TopkCtl* ctl = (TopkCtl*)ctx->topk_ctl.p;
-    if (num_capacities > 0) {
-        k_zero_u64<<<(num_capacities + 255) / 256, 256, 0, s>>>((unsigned long long*)hits, num_capacities);
-        RG_LAUNCH_CHECK(ctx, "k_zero_u64");
-    }
-    if (remote_total) {
-        k_zero_u64<<<1, 64, 0, s>>>((unsigned long long*)remote_total, 1);
-        RG_LAUNCH_CHECK(ctx, "k_zero_u64");
+    // device copy of the capacities and one "resolved" flag per capacity
+    const size_t caps_bytes = (size_t)rg_max64(num_capacities, 1) * 8;
+    if ((st = rg_ensure(ctx, ctx->topk_caps, caps_bytes + (size_t)rg_max64(num_capacities, 1) * 4)) != RG_OK) return st;
+    int64_t* caps_dev = (int64_t*)ctx->topk_caps.p;
+    uint32_t* resolved = (uint32_t*)((char*)ctx->topk_caps.p + caps_bytes);
+    for (int j0 = 0; j0 < num_capacities; j0 += kCapChunk) {             // by value: the host array is not read after the call
+        CapChunk chunk;
+        const int cnt = num_capacities - j0 < kCapChunk ? num_capacities - j0 : kCapChunk;
+        for (int j = 0; j < kCapChunk; ++j) chunk.v[j] = j < cnt ? capacities[j0 + j] : 0;
+        k_store_caps<<<1, kCapChunk, 0, s>>>(caps_dev + j0, chunk, cnt);
+        RG_LAUNCH_CHECK(ctx, "k_store_caps");
     }
     const int grid = (int)rg_max64(1, rg_min64(rg_div_up(num_nodes, 256 * 8), (int64_t)ctx->num_cus * 8));
-    bool total_done = remote_total == nullptr;
-    for (int j = 0; j < num_capacities || !total_done; ++j) {
-        const int64_t cap = j < num_capacities ? capacities[j] : 0;
-        k_topk_init<<<1, 256, 0, s>>>(ctl);
+    // one pass over the nodes gives the histogram of the counts; every capacity is read off it
+    k_topk_init<<<1, 256, 0, s>>>(ctl, nullptr);
+    RG_LAUNCH_CHECK(ctx, "k_topk_init");
+    k_topk_hist_low<<<grid, 256, 0, s>>>(counts, home, num_nodes, ctl);
+    RG_LAUNCH_CHECK(ctx, "k_topk_hist_low");
+    k_hit_curve_low<<<1, 256, 0, s>>>(ctl, caps_dev, num_capacities, (unsigned long long*)hits, (unsigned long long*)remote_total, resolved);
+    RG_LAUNCH_CHECK(ctx, "k_hit_curve_low");
+    // capacities whose threshold lies among counts >= kLowBins - 1 (never the case when the counts are bounded by a few
+    // hundred batches) go through the radix select one by one; for all others these kernels return at once
+    for (int j = 0; j < num_capacities; ++j) {
+        k_topk_init<<<1, 256, 0, s>>>(ctl, resolved + j);
         RG_LAUNCH_CHECK(ctx, "k_topk_init");
         for (int pass = 0; pass < 4; ++pass) {
             k_topk_hist<<<grid, 256, 0, s>>>(counts, home, num_nodes, pass, ctl);
             RG_LAUNCH_CHECK(ctx, "k_topk_hist");
-            k_topk_pick<<<1, 256, 0, s>>>(ctl, pass, cap, nullptr);
+            k_topk_pick<<<1, 256, 0, s>>>(ctl, pass, capacities[j]);
             RG_LAUNCH_CHECK(ctx, "k_topk_pick");
         }
-        // the first pass over the nodes also accumulates the total; when no capacity is given a throw-away slot
-        // of the control block's histogram area receives the (zero) hit sum
-        unsigned long long* hit_slot = j < num_capacities ? (unsigned long long*)hits + j : (unsigned long long*)&ctl->hist[3][0];
-        k_hit_sum<<<grid, 256, 0, s>>>(counts, home, num_nodes, ctl, hit_slot, total_done ? nullptr : (unsigned long long*)remote_total);
+        k_hit_sum<<<grid, 256, 0, s>>>(counts, home, num_nodes, ctl, resolved + j, (unsigned long long*)hits + j);
         RG_LAUNCH_CHECK(ctx, "k_hit_sum");
-        total_done = true;
     }
     return RG_OK;
 }
@@ -904,11 +948,8 @@ rg_status rg_prefetch_cache_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_
     RG_LAUNCH_CHECK(ctx, "k_prefetch_reset");
     k_prefetch_select<<<(int)rg_div_up(n, 256), 256, 0, s>>>(input_nodes, n, n_dev, cache->loc, home, cache->filled, list, pctl);
     RG_LAUNCH_CHECK(ctx, "k_prefetch_select");
-    int64_t blocks;
-    int threads;
-    rg_hostlink_launch_shape(&blocks, &threads);
     return launch_list_copy(ctx, list, pctl, remote_store, remote_stride, cache->cache_rows, cache->row_stride,
-                            cache->capacity_rows, dim, n, blocks, threads, s);
+                            cache->capacity_rows, dim, n, ctx->knobs.pull_blocks, ctx->knobs.pull_threads, s);
 }
 
 rg_status rg_plan_prefetch(rg_ctx* ctx, const rg_cache* cache, const int32_t* home, const uint32_t* first_batch,
@@ -973,77 +1014,14 @@ rg_status rg_prefetch_planned(rg_ctx* ctx, const rg_prefetch_plan* plan, int32_t
     RG_REQUIRE(ctx, dim >= 1 && cache->row_stride >= dim && remote_stride >= dim, "rg_prefetch_planned: bad dim / stride");
     RG_HIP(ctx, hipSetDevice(ctx->device));
     { const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_prefetch_planned: remote_store"); if (chk != RG_OK) return chk; }
-    int64_t blocks;
-    int threads;
-    rg_hostlink_launch_shape(&blocks, &threads);
     hipStream_t s = (hipStream_t)stream;
     rg_status st = launch_list_copy(ctx, plan->list, nullptr, remote_store, remote_stride, cache->cache_rows, cache->row_stride,
-                                    cache->capacity_rows, dim, rg_max64(plan->list_capacity, 1), blocks, threads, s,
-                                    plan->offsets + batch);
+                                    cache->capacity_rows, dim, rg_max64(plan->list_capacity, 1), ctx->knobs.pull_blocks,
+                                    ctx->knobs.pull_threads, s, plan->offsets + batch);
     if (st != RG_OK) return st;
     k_mark_segment<<<ctx->num_cus, 256, 0, s>>>(plan->list, plan->offsets + batch, cache->filled, cache->capacity_rows);
     RG_LAUNCH_CHECK(ctx, "k_mark_segment");
     return RG_OK;
-}
-
-rg_status rg_stage_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev, const int32_t* home,
-                        const rg_stage* stage, int32_t batch_tag, const float* remote_store, int64_t remote_stride,
-                        int32_t dim, void* stream) {
-    if (!ctx) return RG_ERR_INVALID_ARG;
-    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_stage_rows: n = %lld out of range", (long long)n);
-    RG_REQUIRE(ctx, batch_tag >= 0, "rg_stage_rows: batch_tag must be non-negative");
-    if (n == 0) return RG_OK;
-    RG_REQUIRE(ctx, stage && stage->rows && stage->slot_of && stage->owner && stage->touched && stage->cursor,
-               "rg_stage_rows: incomplete rg_stage");
-    RG_REQUIRE(ctx, stage->capacity_rows >= 0 && stage->capacity_rows <= (int64_t)RG_ROW_MASK + 1, "rg_stage_rows: bad staging capacity");
-    RG_REQUIRE(ctx, input_nodes && home && remote_store, "rg_stage_rows: null pointer");
-    RG_REQUIRE(ctx, dim >= 1 && stage->row_stride >= dim && remote_stride >= dim, "rg_stage_rows: bad dim / stride");
-    RG_HIP(ctx, hipSetDevice(ctx->device));
-    { const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_stage_rows: remote_store"); if (chk != RG_OK) return chk; }
-    hipStream_t s = (hipStream_t)stream;
-    rg_status st;
-    if ((st = rg_ensure(ctx, ctx->stage_ctl, 64)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->stage_list, (size_t)n * 8)) != RG_OK) return st;
-    uint32_t* pctl = (uint32_t*)ctx->stage_ctl.p;
-    int32_t* list = (int32_t*)ctx->stage_list.p;
-    k_prefetch_reset<<<1, 64, 0, s>>>(pctl);
-    RG_LAUNCH_CHECK(ctx, "k_prefetch_reset");
-    k_stage_select<<<(int)rg_div_up(n, 256), 256, 0, s>>>(input_nodes, n, n_dev, home, stage->touched, stage->slot_of, stage->owner,
-                                                         batch_tag, stage->cursor, stage->capacity_rows, list, pctl);
-    RG_LAUNCH_CHECK(ctx, "k_stage_select");
-    int64_t blocks;
-    int threads;
-    rg_hostlink_launch_shape(&blocks, &threads);
-    return launch_list_copy(ctx, list, pctl, remote_store, remote_stride, stage->rows, stage->row_stride, stage->capacity_rows, dim,
-                            n, blocks, threads, s);
-}
-
-rg_status rg_commit_staged_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
-                                const int32_t* home, const rg_stage* stage, int32_t batch_tag, const rg_cache* cache,
-                                int32_t dim, void* stream) {
-    if (!ctx) return RG_ERR_INVALID_ARG;
-    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_commit_staged_rows: n = %lld out of range", (long long)n);
-    RG_REQUIRE(ctx, batch_tag >= 0, "rg_commit_staged_rows: batch_tag must be non-negative");
-    if (n == 0) return RG_OK;
-    RG_REQUIRE(ctx, stage && stage->rows && stage->slot_of && stage->owner && stage->touched, "rg_commit_staged_rows: incomplete rg_stage");
-    RG_REQUIRE(ctx, cache && cache->loc && cache->filled && cache->cache_rows, "rg_commit_staged_rows: cache needs loc, filled and cache_rows");
-    RG_REQUIRE(ctx, input_nodes && home, "rg_commit_staged_rows: null pointer");
-    RG_REQUIRE(ctx, dim >= 1 && stage->row_stride >= dim && cache->row_stride >= dim, "rg_commit_staged_rows: bad dim / stride");
-    RG_HIP(ctx, hipSetDevice(ctx->device));
-    hipStream_t s = (hipStream_t)stream;
-    rg_status st;
-    if ((st = rg_ensure(ctx, ctx->commit_ctl, 64)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->commit_list, (size_t)n * 8)) != RG_OK) return st;
-    uint32_t* pctl = (uint32_t*)ctx->commit_ctl.p;
-    int32_t* list = (int32_t*)ctx->commit_list.p;
-    k_prefetch_reset<<<1, 64, 0, s>>>(pctl);
-    RG_LAUNCH_CHECK(ctx, "k_prefetch_reset");
-    k_commit_select<<<(int)rg_div_up(n, 256), 256, 0, s>>>(input_nodes, n, n_dev, home, cache->loc, stage->touched, stage->slot_of,
-                                                          stage->owner, batch_tag, cache->filled, list, pctl);
-    RG_LAUNCH_CHECK(ctx, "k_commit_select");
-    // HBM to HBM: bandwidth-bound, so the whole device may take part
-    return launch_list_copy(ctx, list, pctl, stage->rows, stage->row_stride, cache->cache_rows, cache->row_stride,
-                            cache->capacity_rows, dim, n, (int64_t)ctx->num_cus * 8, 256, s);
 }
 
 }  // extern "C"

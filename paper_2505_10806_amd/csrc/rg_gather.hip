@@ -5,11 +5,24 @@
 // per row), counts the three classes and compacts the indices of the miss rows; the HBM kernel copies
 // local and cached rows; the miss kernel copies the remote rows and may run on a second stream so the
 // host-link transfers overlap the HBM copies.
-#include <stdlib.h>
-
 #include "rg_rowcopy.h"
 
 namespace {
+
+// Where one batch's lookup results live: a ticket's slices of the context scratch.
+struct GatherScratch {
+    uint32_t* src;        // [rows] resolved location word per output row
+    int32_t* miss_list;   // [2 * rows] (output row, remote row) pairs
+    uint32_t* gctl;       // [0] = number of misses
+};
+
+GatherScratch ticket_scratch(rg_ctx* ctx, int t) {
+    GatherScratch g;
+    g.src = (uint32_t*)ctx->gather_src.p + (int64_t)t * ctx->gather_cap;
+    g.miss_list = (int32_t*)ctx->miss_list.p + (int64_t)t * 2 * ctx->gather_cap;
+    g.gctl = (uint32_t*)ctx->gather_ctl.p + t * 16;
+    return g;
+}
 
 __device__ __forceinline__ int64_t rg_actual_n(int64_t n, const int32_t* __restrict__ n_dev) {
     if (!n_dev) return n;
@@ -101,7 +114,8 @@ template <int VEC, int T>
 __global__ void __launch_bounds__(256) k_gather_hbm(const uint32_t* __restrict__ src, int64_t n, const int32_t* __restrict__ n_dev,
                                                          const float* __restrict__ local_store, int64_t local_stride,
                                                          const float* __restrict__ cache_rows, int64_t cache_stride,
-                                                         float* __restrict__ out, int64_t out_stride, int cpr, float inv_cpr) {
+                                                         float* __restrict__ out, int64_t out_stride, int cpr, float inv_cpr,
+                                                         int tail) {
     typedef typename RgVec<VEC>::type V;
     const int64_t n_act = rg_actual_n(n, n_dev);
     const int lane = rg_lane();
@@ -114,12 +128,14 @@ __global__ void __launch_bounds__(256) k_gather_hbm(const uint32_t* __restrict__
         const int off0 = (int)(q0 - row0 * cpr);
         const V* sp[T];
         V* dp[T];
+        bool last[T];                                           // the row's last chunk, of which only `tail` floats are stored
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             const int ql = off0 + lane + RG_WAVE * t;           // < cpr + 64*T: exact in fp32
             int r = (int)((float)ql * inv_cpr);
             if (r * cpr > ql) --r; else if ((r + 1) * cpr <= ql) ++r;
             const int c = ql - r * cpr;
+            last[t] = tail < VEC && c == cpr - 1;
             const int64_t i = row0 + r;
             sp[t] = nullptr;
             dp[t] = nullptr;
@@ -139,16 +155,19 @@ __global__ void __launch_bounds__(256) k_gather_hbm(const uint32_t* __restrict__
             if (sp[t]) val[t] = *sp[t];
 #pragma unroll
         for (int t = 0; t < T; ++t)
-            if (dp[t]) __builtin_nontemporal_store(val[t], dp[t]);
+            if (dp[t]) {
+                if (last[t]) rg_store_head(dp[t], val[t], tail);
+                else __builtin_nontemporal_store(val[t], dp[t]);
+            }
     }
 }
 
 // Rows whose source is the remote store: walks the compacted miss list.
 template <int VEC, int U>
-__global__ void __launch_bounds__(1024) k_gather_miss(const int32_t* __restrict__ miss_list,
-                                                     const uint32_t* __restrict__ gctl, const float* __restrict__ remote_store,
-                                                     int64_t remote_stride, float* __restrict__ out, int64_t out_stride,
-                                                     int cpr, int log2L) {
+__global__ void __launch_bounds__(256) k_gather_miss(const int32_t* __restrict__ miss_list,
+                                                    const uint32_t* __restrict__ gctl, const float* __restrict__ remote_store,
+                                                    int64_t remote_stride, float* __restrict__ out, int64_t out_stride,
+                                                    int cpr, int log2L, int tail) {
     typedef typename RgVec<VEC>::type V;
     const int64_t n_miss = gctl[0];
     const int lane = rg_lane();
@@ -179,18 +198,114 @@ __global__ void __launch_bounds__(1024) k_gather_miss(const int32_t* __restrict_
             V val[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) val[u] = sp[u][c];
+            const bool head_only = tail < VEC && c == cpr - 1;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (dp[u]) __builtin_nontemporal_store(val[u], &dp[u][c]);
+                if (dp[u]) {
+                    if (head_only) rg_store_head(&dp[u][c], val[u], tail);
+                    else __builtin_nontemporal_store(val[u], &dp[u][c]);
+                }
         }
     }
 }
 
-int env_int(const char* name, int dflt) {
-    const char* v = getenv(name);
-    if (!v || !*v) return dflt;
-    const int x = atoi(v);
-    return x > 0 ? x : dflt;
+// Lookups of `count` batches in one launch; scr[k] receives batch k's results.
+rg_status launch_classify(rg_ctx* ctx, int count, const int32_t* const* input_nodes, const int64_t* n, const int32_t* const* n_dev,
+                          const rg_cache* cache, rg_gather_stats* const* stats, const GatherScratch* scr, hipStream_t s) {
+    ClassifyGroup C;
+    int64_t n_max = 0;
+    for (int k = 0; k < RG_GATHER_TICKETS; ++k) {
+        const bool live = k < count;
+        const GatherScratch& g = scr[live ? k : 0];
+        C.nodes[k] = live ? input_nodes[k] : nullptr;
+        C.n_dev[k] = live && n_dev ? n_dev[k] : nullptr;
+        C.n[k] = live ? n[k] : 0;
+        C.src[k] = g.src;
+        C.miss_list[k] = g.miss_list;
+        C.gctl[k] = g.gctl;
+        C.stats[k] = live ? (unsigned long long*)stats[k] : nullptr;
+        if (live) n_max = rg_max64(n_max, n[k]);
+    }
+    k_gather_reset<<<count, 64, 0, s>>>(C);
+    RG_LAUNCH_CHECK(ctx, "k_gather_reset");
+    if (n_max > 0) {
+        k_classify<<<dim3((unsigned)rg_div_up(n_max, 256 * kClassifyRows), (unsigned)count), 256, 0, s>>>(C, cache->loc);
+        RG_LAUNCH_CHECK(ctx, "k_classify");
+    }
+    return RG_OK;
+}
+
+// Copies the rows of one classified batch: HBM rows on sh, miss rows on sm (joined back into sh when they differ).
+// Every argument has been validated by the caller; `timed` brackets the kernels for rg_profile_read.
+rg_status launch_copies(rg_ctx* ctx, const GatherScratch& scr, int64_t n, const int32_t* n_dev, const rg_cache* cache,
+                        const float* local_store, int64_t local_stride, const float* remote_store, int64_t remote_stride,
+                        int32_t dim, float* out, int64_t out_stride, hipStream_t sh, hipStream_t sm, bool timed) {
+    const bool two_streams = sm != sh;
+    if (two_streams) {
+        RG_HIP(ctx, hipEventRecord(ctx->ev_classified, sh));
+        RG_HIP(ctx, hipStreamWaitEvent(sm, ctx->ev_classified, 0));
+    }
+    const void* ptrs[4] = {local_store, remote_store, cache->cache_rows, out};
+    const int64_t strides[4] = {local_stride, remote_stride, cache->cache_rows ? cache->row_stride : 0, out_stride};
+    const int vec = rg_pick_vec(dim, ptrs, 4, strides, 4);
+    const RgRowShape shp = rg_row_shape(dim, vec);
+    constexpr int U = 4;                                    // rows in flight per lane group in the miss kernel
+    // T chunks in flight per lane; swept on the device: 2 is best (T = 4: -2 %, T = 8: -12 %), and non-temporal
+    // stores make no difference.
+    const int T = vec == 4 ? ctx->knobs.gather_unroll : 4;
+    const int64_t chunks_per_block = 4ll * RG_WAVE * T;
+    int64_t grid64 = rg_div_up(n * (int64_t)shp.cpr, chunks_per_block);
+    if (ctx->knobs.gather_blocks_per_cu > 0) grid64 = rg_min64(grid64, (int64_t)ctx->num_cus * ctx->knobs.gather_blocks_per_cu);
+    const int grid = (int)rg_max64(1, grid64);
+    const float inv_cpr = 1.0f / (float)shp.cpr;
+    const float* cache_rows = cache->cache_rows ? cache->cache_rows : local_store;   // never dereferenced without cache words
+
+    int tok = timed ? rg_prof_begin(ctx, RG_K_GATHER_HBM, sh) : -1;
+#define RG_LAUNCH_HBM(V, TT)                                                                                            \
+    k_gather_hbm<V, TT><<<grid, 256, 0, sh>>>(scr.src, n, n_dev, local_store, local_stride, cache_rows, cache->row_stride, \
+                                              out, out_stride, shp.cpr, inv_cpr, shp.tail)
+    if (vec == 4) { if (T == 2) RG_LAUNCH_HBM(4, 2); else if (T == 8) RG_LAUNCH_HBM(4, 8); else RG_LAUNCH_HBM(4, 4); }
+    else if (vec == 2) RG_LAUNCH_HBM(2, 4);
+    else RG_LAUNCH_HBM(1, 4);
+#undef RG_LAUNCH_HBM
+    rg_prof_end(ctx, tok, sh);
+    RG_LAUNCH_CHECK(ctx, "k_gather_hbm");
+
+    const int miss_threads = 256;
+    const int miss_rows_per_block = (miss_threads / RG_WAVE) * (RG_WAVE >> shp.log2L) * U;
+    const int miss_grid = (int)rg_max64(1, rg_min64(rg_div_up(n, miss_rows_per_block), ctx->knobs.miss_blocks));
+    tok = timed ? rg_prof_begin(ctx, RG_K_GATHER_MISS, sm) : -1;
+#define RG_LAUNCH_MISS(V)                                                                                               \
+    k_gather_miss<V, U><<<miss_grid, miss_threads, 0, sm>>>(scr.miss_list, scr.gctl, remote_store, remote_stride, out, out_stride, \
+                                                            shp.cpr, shp.log2L, shp.tail)
+    if (vec == 4) RG_LAUNCH_MISS(4); else if (vec == 2) RG_LAUNCH_MISS(2); else RG_LAUNCH_MISS(1);
+#undef RG_LAUNCH_MISS
+    rg_prof_end(ctx, tok, sm);
+    RG_LAUNCH_CHECK(ctx, "k_gather_miss");
+    if (two_streams) {
+        RG_HIP(ctx, hipEventRecord(ctx->ev_miss_done, sm));
+        RG_HIP(ctx, hipStreamWaitEvent(sh, ctx->ev_miss_done, 0));
+    }
+    return RG_OK;
+}
+
+// Argument checks shared by the entry points that copy rows.
+rg_status check_copy_args(rg_ctx* ctx, const char* fn, int64_t n, int32_t dim, const rg_cache* cache, const float* local_store,
+                          int64_t local_stride, const float* remote_store, int64_t remote_stride, const float* out,
+                          int64_t out_stride) {
+    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "%s: n = %lld out of range", fn, (long long)n);
+    RG_REQUIRE(ctx, dim >= 1, "%s: dim = %d must be positive", fn, dim);
+    RG_REQUIRE(ctx, cache && cache->loc, "%s: cache / cache->loc is NULL", fn);
+    RG_REQUIRE(ctx, out_stride >= dim, "%s: out_stride < dim", fn);
+    RG_REQUIRE(ctx, !local_store || local_stride >= dim, "%s: local_stride < dim", fn);
+    RG_REQUIRE(ctx, !remote_store || remote_stride >= dim, "%s: remote_stride < dim", fn);
+    RG_REQUIRE(ctx, !cache->cache_rows || cache->row_stride >= dim, "%s: cache row_stride < dim", fn);
+    RG_REQUIRE(ctx, n == 0 || out, "%s: out is NULL", fn);
+    // A store may be absent only if no location word can point into it; that cannot be verified on the
+    // host, so all three are required whenever rows are requested.
+    RG_REQUIRE(ctx, n == 0 || (local_store && remote_store), "%s: null feature store", fn);
+    RG_REQUIRE(ctx, n == 0 || cache->cache_rows || cache->capacity_rows == 0, "%s: cache_rows is NULL", fn);
+    return RG_OK;
 }
 
 }  // namespace
@@ -214,28 +329,14 @@ rg_status rg_gather_prepare(rg_ctx* ctx, int32_t first_ticket, int32_t count, co
         n_max = rg_max64(n_max, n[k]);
     }
     RG_HIP(ctx, hipSetDevice(ctx->device));
-    hipStream_t s = (hipStream_t)stream;
     rg_status st = rg_gather_reserve(ctx, rg_max64(n_max, 1));
     if (st != RG_OK) return st;
-    ClassifyGroup C;
-    for (int k = 0; k < RG_GATHER_TICKETS; ++k) {
-        const bool live = k < count;
-        const int t = first_ticket + (live ? k : 0);
-        C.nodes[k] = live ? input_nodes[k] : nullptr;
-        C.n_dev[k] = live && n_dev ? n_dev[k] : nullptr;
-        C.n[k] = live ? n[k] : 0;
-        C.src[k] = (uint32_t*)ctx->gather_src.p + (int64_t)t * ctx->gather_cap;
-        C.miss_list[k] = (int32_t*)ctx->miss_list.p + (int64_t)t * 2 * ctx->gather_cap;
-        C.gctl[k] = (uint32_t*)ctx->gather_ctl.p + t * 16;
-        C.stats[k] = live ? (unsigned long long*)stats[k] : nullptr;
-        if (live) ctx->gather_rows[t] = -1;
+    GatherScratch scr[RG_GATHER_TICKETS];
+    for (int k = 0; k < count; ++k) {
+        scr[k] = ticket_scratch(ctx, first_ticket + k);
+        ctx->gather_rows[first_ticket + k] = -1;
     }
-    k_gather_reset<<<count, 64, 0, s>>>(C);
-    RG_LAUNCH_CHECK(ctx, "k_gather_reset");
-    if (n_max > 0) {
-        k_classify<<<dim3((unsigned)rg_div_up(n_max, 256 * kClassifyRows), (unsigned)count), 256, 0, s>>>(C, cache->loc);
-        RG_LAUNCH_CHECK(ctx, "k_classify");
-    }
+    if ((st = launch_classify(ctx, count, input_nodes, n, n_dev, cache, stats, scr, (hipStream_t)stream)) != RG_OK) return st;
     for (int k = 0; k < count; ++k) ctx->gather_rows[first_ticket + k] = n[k];
     return RG_OK;
 }
@@ -245,83 +346,18 @@ rg_status rg_gather_run(rg_ctx* ctx, int32_t ticket, int64_t n, const int32_t* n
                         int32_t dim, float* out, int64_t out_stride, void* hit_stream, void* miss_stream) {
     if (!ctx) return RG_ERR_INVALID_ARG;
     RG_REQUIRE(ctx, ticket >= 0 && ticket < RG_GATHER_TICKETS, "rg_gather_run: ticket = %d not in [0,%d)", ticket, RG_GATHER_TICKETS);
-    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_gather_run: n = %lld out of range", (long long)n);
-    RG_REQUIRE(ctx, dim >= 1, "rg_gather_run: dim = %d must be positive", dim);
-    RG_REQUIRE(ctx, cache && cache->loc, "rg_gather_run: cache / cache->loc is NULL");
-    RG_REQUIRE(ctx, out_stride >= dim, "rg_gather_run: out_stride < dim");
-    RG_REQUIRE(ctx, !local_store || local_stride >= dim, "rg_gather_run: local_stride < dim");
-    RG_REQUIRE(ctx, !remote_store || remote_stride >= dim, "rg_gather_run: remote_stride < dim");
-    RG_REQUIRE(ctx, !cache->cache_rows || cache->row_stride >= dim, "rg_gather_run: cache row_stride < dim");
-    RG_REQUIRE(ctx, n == 0 || out, "rg_gather_run: out is NULL");
-    // A store may be absent only if no location word can point into it; that cannot be verified on the
-    // host, so all three are required whenever rows are requested.
-    RG_REQUIRE(ctx, n == 0 || (local_store && remote_store), "rg_gather_run: null feature store");
-    RG_REQUIRE(ctx, n == 0 || cache->cache_rows || cache->capacity_rows == 0, "rg_gather_run: cache_rows is NULL");
+    rg_status st = check_copy_args(ctx, "rg_gather_run", n, dim, cache, local_store, local_stride, remote_store, remote_stride, out, out_stride);
+    if (st != RG_OK) return st;
     if (ctx->gather_rows[ticket] != n)
         return rg_set_error(ctx, RG_ERR_STATE, "rg_gather_run: ticket %d was prepared for %lld rows, not %lld", ticket,
                             (long long)ctx->gather_rows[ticket], (long long)n);
     if (n == 0) return RG_OK;
     RG_HIP(ctx, hipSetDevice(ctx->device));
-    {
-        const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_gather_run: remote_store");
-        if (chk != RG_OK) return chk;
-    }
+    if ((st = rg_check_device_readable(ctx, remote_store, "rg_gather_run: remote_store")) != RG_OK) return st;
     hipStream_t sh = (hipStream_t)hit_stream;
     hipStream_t sm = miss_stream ? (hipStream_t)miss_stream : sh;
-    const bool two_streams = sm != sh;
-    uint32_t* gctl = (uint32_t*)ctx->gather_ctl.p + ticket * 16;
-    uint32_t* src = (uint32_t*)ctx->gather_src.p + (int64_t)ticket * ctx->gather_cap;
-    int32_t* miss_list = (int32_t*)ctx->miss_list.p + (int64_t)ticket * 2 * ctx->gather_cap;
-    if (two_streams) {
-        RG_HIP(ctx, hipEventRecord(ctx->ev_classified, sh));
-        RG_HIP(ctx, hipStreamWaitEvent(sm, ctx->ev_classified, 0));
-    }
-
-    const void* ptrs[4] = {local_store, remote_store, cache->cache_rows, out};
-    const int64_t strides[4] = {local_stride, remote_stride, cache->cache_rows ? cache->row_stride : 0, out_stride};
-    const int vec = rg_pick_vec(dim, ptrs, 4, strides, 4);
-    const RgRowShape shp = rg_row_shape(dim, vec);
-    constexpr int U = 4;                                    // rows in flight per lane group in the miss kernel
-    // T chunks in flight per lane; swept on the box: 2 is best (T = 4: -2 %, T = 8: -12 %), an uncapped grid
-    // (one step per wavefront) beats a persistent one, and non-temporal stores make no difference.
-    int T = env_int("RG_GATHER_UNROLL", 2);
-    if (vec != 4 || (T != 2 && T != 4 && T != 8)) T = (vec == 4) ? 2 : 4;
-    const int per_cu = env_int("RG_GATHER_BLOCKS_PER_CU", 4096);
-    const int64_t chunks_per_block = 4ll * RG_WAVE * T;
-    const int grid = (int)rg_max64(1, rg_min64(rg_div_up(n * (int64_t)shp.cpr, chunks_per_block), (int64_t)ctx->num_cus * per_cu));
-    const float inv_cpr = 1.0f / (float)shp.cpr;
-    const float* cache_rows = cache->cache_rows ? cache->cache_rows : local_store;   // never dereferenced without cache words
-
-    int tok = rg_prof_begin(ctx, RG_K_GATHER_HBM, sh);
-#define RG_LAUNCH_HBM(V, TT)                                                                                     \
-    k_gather_hbm<V, TT><<<grid, 256, 0, sh>>>(src, n, n_dev, local_store, local_stride, cache_rows, cache->row_stride, \
-                                              out, out_stride, shp.cpr, inv_cpr)
-    if (vec == 4) { if (T == 2) RG_LAUNCH_HBM(4, 2); else if (T == 8) RG_LAUNCH_HBM(4, 8); else RG_LAUNCH_HBM(4, 4); }
-    else if (vec == 2) RG_LAUNCH_HBM(2, 4);
-    else RG_LAUNCH_HBM(1, 4);
-#undef RG_LAUNCH_HBM
-    rg_prof_end(ctx, tok, sh);
-    RG_LAUNCH_CHECK(ctx, "k_gather_hbm");
-
-    int64_t miss_blocks;
-    int miss_threads;
-    rg_hostlink_launch_shape(&miss_blocks, &miss_threads, true);
-    const int miss_rows_per_block = (miss_threads / RG_WAVE) * (RG_WAVE >> shp.log2L) * U;
-    const int miss_grid = (int)rg_max64(1, rg_min64(rg_div_up(n, miss_rows_per_block), miss_blocks));
-    tok = rg_prof_begin(ctx, RG_K_GATHER_MISS, sm);
-    if (vec == 4)
-        k_gather_miss<4, U><<<miss_grid, miss_threads, 0, sm>>>(miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
-    else if (vec == 2)
-        k_gather_miss<2, U><<<miss_grid, miss_threads, 0, sm>>>(miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
-    else
-        k_gather_miss<1, U><<<miss_grid, miss_threads, 0, sm>>>(miss_list, gctl, remote_store, remote_stride, out, out_stride, shp.cpr, shp.log2L);
-    rg_prof_end(ctx, tok, sm);
-    RG_LAUNCH_CHECK(ctx, "k_gather_miss");
-    if (two_streams) {
-        RG_HIP(ctx, hipEventRecord(ctx->ev_miss_done, sm));
-        RG_HIP(ctx, hipStreamWaitEvent(sh, ctx->ev_miss_done, 0));
-    }
-    return RG_OK;
+    return launch_copies(ctx, ticket_scratch(ctx, ticket), n, n_dev, cache, local_store, local_stride, remote_store, remote_stride,
+                         dim, out, out_stride, sh, sm, true);
 }
 
 rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
@@ -331,19 +367,15 @@ rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n,
     if (!ctx) return RG_ERR_INVALID_ARG;
     RG_REQUIRE(ctx, stats, "rg_gather_features: stats is NULL");
     // argument errors of the copy step are reported before anything is queued
-    RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_gather_features: n = %lld out of range", (long long)n);
-    RG_REQUIRE(ctx, dim >= 1, "rg_gather_features: dim = %d must be positive", dim);
-    RG_REQUIRE(ctx, cache && cache->loc, "rg_gather_features: cache / cache->loc is NULL");
-    RG_REQUIRE(ctx, out_stride >= dim && (!local_store || local_stride >= dim) && (!remote_store || remote_stride >= dim) &&
-                        (!cache->cache_rows || cache->row_stride >= dim), "rg_gather_features: a row stride is smaller than dim");
-    RG_REQUIRE(ctx, n == 0 || (input_nodes && out && local_store && remote_store), "rg_gather_features: null pointer");
-    RG_REQUIRE(ctx, n == 0 || cache->cache_rows || cache->capacity_rows == 0, "rg_gather_features: cache_rows is NULL");
+    rg_status st = check_copy_args(ctx, "rg_gather_features", n, dim, cache, local_store, local_stride, remote_store, remote_stride, out,
+                                   out_stride);
+    if (st != RG_OK) return st;
+    RG_REQUIRE(ctx, n == 0 || input_nodes, "rg_gather_features: input_nodes is NULL");
     if (n > 0) {
         RG_HIP(ctx, hipSetDevice(ctx->device));
-        const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_gather_features: remote_store");
-        if (chk != RG_OK) return chk;
+        if ((st = rg_check_device_readable(ctx, remote_store, "rg_gather_features: remote_store")) != RG_OK) return st;
     }
-    rg_status st = rg_gather_prepare(ctx, 0, 1, &input_nodes, &n, &n_dev, cache, &stats, hit_stream);
+    st = rg_gather_prepare(ctx, 0, 1, &input_nodes, &n, &n_dev, cache, &stats, hit_stream);
     if (st != RG_OK) return st;
     return rg_gather_run(ctx, 0, n, n_dev, cache, local_store, local_stride, remote_store, remote_stride, dim, out, out_stride,
                          hit_stream, miss_stream);

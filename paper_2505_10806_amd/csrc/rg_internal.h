@@ -20,10 +20,20 @@ struct RgProfSpan {
     int kernel;
 };
 
+// Launch-shape knobs, read from the environment once per context (rg_create); the defaults are the swept optima.
+struct RgKnobs {
+    int gather_unroll = 2;            // RG_GATHER_UNROLL: 16-byte chunks in flight per lane of the HBM gather (2, 4 or 8)
+    int gather_blocks_per_cu = 0;     // RG_GATHER_BLOCKS_PER_CU: grid cap of the HBM gather (0 = one step per wavefront)
+    int pull_blocks = 48;             // RG_PULL_BLOCKS / RG_PULL_THREADS: grid of the host-link pull kernels
+    int pull_threads = 256;
+    int miss_blocks = 192;            // RG_MISS_BLOCKS: grid of the miss-row kernel
+};
+
 struct rg_ctx {
     int device = 0;
     int num_cus = 256;
-    std::string err;
+    char err[512] = {0};
+    RgKnobs knobs;
 
     // sampler scratch
     RgBuf visited;      // uint32[ceil(N/32)] bitmap of cumulative-frontier members
@@ -33,19 +43,17 @@ struct rg_ctx {
     RgBuf row_start;    // int64[max_frontier] adjacency row start of every frontier node (current hop)
     RgBuf row_deg;      // int32[max_frontier] its degree
     bool sampler_dirty = false;   // a sampling call was cut short by an error: `fresh` may hold stale bits
-    int64_t fresh_words_clean = 0;   // number of leading words of `fresh` known to be zero
     // schedule scratch
     RgBuf sched_keys;   // uint64[npad]
     RgBuf sched_ids;    // int32[npad]
     // top-K scratch
     RgBuf topk_ctl;     // TopkCtl
     RgBuf topk_blk;     // int32[2 * nblocks]
+    RgBuf topk_caps;    // rg_cache_hit_curve: int64[num_capacities] capacities, then uint32[num_capacities] flags
     // prefetch scratch
     RgBuf pf_list;      // int32[2 * n]: (slot, remote row) pairs still to pull
     RgBuf pf_ctl;       // uint32[4]: [0] = number of pairs
-    RgBuf stage_list, stage_ctl;     // the same for rg_stage_rows
     RgBuf plan_cursor;               // rg_plan_prefetch: per-chunk per-batch counts (ordered plan) or scatter cursors
-    RgBuf commit_list, commit_ctl;   // the same for rg_commit_staged_rows
     // gather scratch
     // RG_GATHER_TICKETS entries each, so that several batches can be classified by one launch ahead of their copies
     RgBuf gather_src;   // [ticket][gather_cap] uint32: resolved location word per output row
@@ -69,6 +77,9 @@ rg_status rg_ensure(rg_ctx* ctx, RgBuf& buf, size_t bytes, bool zero_new = false
 rg_status rg_check_device_readable(rg_ctx* ctx, const void* p, const char* what);
 // Makes every gather ticket hold at least `rows` rows (a reallocation invalidates prepared tickets).
 rg_status rg_gather_reserve(rg_ctx* ctx, int64_t rows);
+// Sizes the sampler scratch for `group` batches side by side on a graph of num_nodes nodes with cumulative
+// frontiers of up to max_frontier nodes (what rg_sample_blocks_group would otherwise grow on demand).
+rg_status rg_sampler_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int group);
 // Profiling brackets (no-ops unless profiling is enabled).
 int rg_prof_begin(rg_ctx* ctx, int kernel, hipStream_t s);
 void rg_prof_end(rg_ctx* ctx, int token, hipStream_t s);

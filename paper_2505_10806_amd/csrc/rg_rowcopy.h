@@ -7,8 +7,6 @@
 // the work by chunks instead of rows.)
 #pragma once
 
-#include <stdlib.h>
-
 #include "rg_internal.h"
 
 template <int VEC> struct RgVec;
@@ -16,9 +14,18 @@ template <> struct RgVec<4> { typedef float type __attribute__((ext_vector_type(
 template <> struct RgVec<2> { typedef float type __attribute__((ext_vector_type(2))); };
 template <> struct RgVec<1> { typedef float type; };
 
+// Stores the first `count` floats of a chunk (a row's last chunk when dim is not a multiple of the chunk width).
+template <typename V>
+__device__ __forceinline__ void rg_store_head(V* dst, const V& val, int count) {
+    float* d = (float*)dst;
+    const float* v = (const float*)&val;
+    for (int q = 0; q < count; ++q) d[q] = v[q];
+}
+
 struct RgRowShape {
     int cpr;      // chunks per row = ceil(dim / VEC)
     int log2L;    // lanes per row group = 1 << log2L (<= 64)
+    int tail;     // floats of the row's last chunk that belong to the row (1..VEC); only those are stored
 };
 
 static inline int rg_pick_vec(int32_t dim, const void* const* ptrs, int nptrs, const int64_t* strides, int nstrides) {
@@ -30,8 +37,8 @@ static inline int rg_pick_vec(int32_t dim, const void* const* ptrs, int nptrs, c
     }
     for (int i = 0; i < nstrides; ++i)
         while (vec > 1 && (strides[i] % vec) != 0) vec >>= 1;
-    // 16-byte chunks may cover the row padding (stride >= round_up(dim, 4) is implied by stride % 4 == 0
-    // and stride >= dim); narrower chunks must tile dim exactly.
+    // A 16-byte chunk may read the padding behind a source row (stride >= round_up(dim, 4) is implied by
+    // stride % 4 == 0 and stride >= dim); stores are trimmed to dim.  Narrower chunks tile dim exactly.
     if (vec == 2 && (dim % 2) != 0) vec = 1;
     return vec;
 }
@@ -42,19 +49,14 @@ static inline RgRowShape rg_row_shape(int32_t dim, int vec) {
     int l = 0;
     while ((1 << l) < s.cpr && l < 6) ++l;
     s.log2L = l;
+    s.tail = dim - (s.cpr - 1) * vec;
     return s;
 }
 
-// Launch shape of kernels that read rows over the host link (cache pulls, miss rows).  They wait on the link, not on
-// the GPU: a few hundred wavefronts keep it busy (48 x 256 threads, 4 rows in flight per lane group), and a small
-// grid leaves the wave slots of every CU to the HBM kernels that run beside them.  Measured on the pull kernel:
-// 2048 workgroups -> the gathers beside it take 153 ms per epoch, 48 -> 79 ms, link rate unchanged.
-static inline void rg_hostlink_launch_shape(int64_t* blocks, int* threads, bool miss_rows = false) {
-    const char* pb = getenv(miss_rows ? "RG_MISS_BLOCKS" : "RG_PULL_BLOCKS");
-    // Miss rows go through one more dependent lookup per step than the pulls and need more wavefronts to fill the
-    // link (swept on the 602-dim workload: 48 workgroups 46 GB/s, 192 -> 51, 384 -> 53, where the HBM kernel beside
-    // them is starved for as long as the miss kernel runs); 192 keeps both moving.
-    *blocks = (pb && atoi(pb) > 0) ? atoi(pb) : (miss_rows ? 192 : 48);
-    const char* pt = getenv("RG_PULL_THREADS");
-    *threads = (pt && (atoi(pt) == 64 || atoi(pt) == 256 || atoi(pt) == 1024)) ? atoi(pt) : 256;
-}
+// Kernels that read rows over the host link (cache pulls, miss rows) wait on the link, not on the GPU: a few hundred
+// wavefronts keep it busy (48 x 256 threads, 4 rows in flight per lane group), and a small grid leaves the wave slots
+// of every CU to the HBM kernels that run beside them.  Measured on the pull kernel: 2048 workgroups -> the gathers
+// beside it take 153 ms per epoch, 48 -> 79 ms, link rate unchanged.  Miss rows go through one more dependent lookup
+// per step than the pulls and need more wavefronts to fill the link (swept on the 602-dim workload: 48 workgroups
+// 46 GB/s, 192 -> 51, 384 -> 53, where the HBM kernel beside them is starved for as long as the miss kernel runs);
+// 192 keeps both moving.  The grids are RgKnobs::pull_blocks x pull_threads and RgKnobs::miss_blocks x 256.

@@ -409,6 +409,14 @@ __global__ void __launch_bounds__(256) k_relabel(const SampleGroup G, const Samp
         nbr_local[e] = pos[nbr[e]];
 }
 
+// Per-batch strides of the scratch slices for a graph of N nodes and frontiers of up to `frontier` nodes.
+void sampler_scratch_shape(int64_t N, int64_t frontier, SampleScratch& S) {
+    S.words = rg_div_up(N, 32);
+    S.num_nodes = N;
+    S.frontier_stride = rg_max64(frontier, 1);
+    S.chunk_stride = rg_max64(rg_div_up(S.frontier_stride, kChunk), rg_max64(1, rg_div_up(S.words, kWordsPerBlock))) + 2;
+}
+
 int grid_for(int64_t work_items, int per_block, int64_t cap) {
     int64_t g = rg_div_up(work_items, per_block);
     if (g < 1) g = 1;
@@ -417,6 +425,21 @@ int grid_for(int64_t work_items, int per_block, int64_t cap) {
 }
 
 }  // namespace
+
+rg_status rg_sampler_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int group) {
+    SampleScratch S;
+    sampler_scratch_shape(num_nodes, max_frontier, S);
+    const size_t g = (size_t)group;
+    rg_status st;
+    if ((st = rg_ensure(ctx, ctx->visited, g * S.words * 4)) != RG_OK) return st;
+    // `fresh` must be all-zero between hops: a new allocation starts zeroed and every hop leaves it zeroed
+    if ((st = rg_ensure(ctx, ctx->fresh, g * S.words * 4, true)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->pos, g * (size_t)num_nodes * 4)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->chunk_sum, g * S.chunk_stride * 4)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->row_start, g * S.frontier_stride * 8)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->row_deg, g * S.frontier_stride * 4)) != RG_OK) return st;
+    return RG_OK;
+}
 
 extern "C" {
 
@@ -458,7 +481,7 @@ rg_status rg_epoch_schedule(rg_ctx* ctx, const int32_t* train_ids, int64_t n, ui
 
 rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, const int32_t* const* seeds,
                                  const int32_t* num_seeds, const int32_t* fanouts, int32_t num_hops, uint64_t seed,
-                                 uint32_t epoch, const rg_blocks* out, void* stream) {
+                                 uint32_t epoch, rg_blocks* out, void* stream) {
     if (!ctx) return RG_ERR_INVALID_ARG;
     RG_REQUIRE(ctx, group >= 1 && group <= RG_MAX_GROUP, "rg_sample_blocks: group = %d not in [1,%d]", group, RG_MAX_GROUP);
     RG_REQUIRE(ctx, csr && out && fanouts && seeds && num_seeds, "rg_sample_blocks: null argument");
@@ -474,8 +497,9 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
     // static bounds: per batch for the capacity checks, their maximum for the launch shapes
     int64_t fub_max[RG_MAX_HOPS + 1] = {0}, eub_max[RG_MAX_HOPS] = {0};
     int32_t seeds_max = 0;
+    bool capacity_error = false;
     for (int g = 0; g < group; ++g) {
-        const rg_blocks* o = out + g;
+        rg_blocks* o = out + g;
         RG_REQUIRE(ctx, num_seeds[g] >= 0, "rg_sample_blocks: num_seeds is negative (batch %d)", g);
         RG_REQUIRE(ctx, num_seeds[g] <= csr->num_nodes, "rg_sample_blocks: more seeds than nodes (seeds must be distinct; batch %d)", g);
         RG_REQUIRE(ctx, seeds[g] || num_seeds[g] == 0, "rg_sample_blocks: seeds is NULL (batch %d)", g);
@@ -483,43 +507,37 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
                    "rg_sample_blocks: null output pointer (batch %d)", g);
         int64_t fub[RG_MAX_HOPS + 1], eub[RG_MAX_HOPS];
         rg_blocks_bounds(csr->num_nodes, csr->num_edges, num_seeds[g], fanouts, num_hops, fub, eub);
+        bool too_small = o->nodes_cap < fub[num_hops];
         for (int h = 0; h < num_hops; ++h) {
             RG_REQUIRE(ctx, eub[h] < (1ll << 31), "rg_sample_blocks: hop %d may produce >= 2^31 edges", h);
             RG_REQUIRE(ctx, o->indptr[h] && (o->nbr[h] || eub[h] == 0), "rg_sample_blocks: null buffer for hop %d (batch %d)", h, g);
-            if (o->indptr_cap[h] < fub[h] + 1)
-                return rg_set_error(ctx, RG_ERR_CAPACITY, "rg_sample_blocks: indptr_cap[%d] = %lld < %lld (batch %d)", h,
-                                    (long long)o->indptr_cap[h], (long long)(fub[h] + 1), g);
-            if (o->nbr_cap[h] < eub[h])
-                return rg_set_error(ctx, RG_ERR_CAPACITY, "rg_sample_blocks: nbr_cap[%d] = %lld < %lld (batch %d)", h,
-                                    (long long)o->nbr_cap[h], (long long)eub[h], g);
             RG_REQUIRE(ctx, !o->nbr_local || o->nbr_local[h] || eub[h] == 0, "rg_sample_blocks: nbr_local[%d] is NULL (batch %d)", h, g);
+            too_small = too_small || o->indptr_cap[h] < fub[h] + 1 || o->nbr_cap[h] < eub[h];
             eub_max[h] = rg_max64(eub_max[h], eub[h]);
         }
-        if (o->nodes_cap < fub[num_hops])
-            return rg_set_error(ctx, RG_ERR_CAPACITY, "rg_sample_blocks: nodes_cap = %lld < %lld (batch %d)", (long long)o->nodes_cap,
-                                (long long)fub[num_hops], g);
+        if (too_small) {
+            // the required sizes go back to the caller in place of the capacities that were passed in
+            rg_set_error(ctx, RG_ERR_CAPACITY, "rg_sample_blocks: output buffers of batch %d are below the static bounds "
+                         "(nodes_cap %lld < %lld, or a hop's indptr_cap / nbr_cap); the required sizes were written back",
+                         g, (long long)o->nodes_cap, (long long)fub[num_hops]);
+            o->nodes_cap = fub[num_hops];
+            for (int h = 0; h < num_hops; ++h) { o->indptr_cap[h] = fub[h] + 1; o->nbr_cap[h] = eub[h]; }
+            capacity_error = true;
+        }
         for (int h = 0; h <= num_hops; ++h) fub_max[h] = rg_max64(fub_max[h], fub[h]);
         seeds_max = num_seeds[g] > seeds_max ? num_seeds[g] : seeds_max;
     }
+    if (capacity_error) return RG_ERR_CAPACITY;
 
     RG_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t s = (hipStream_t)stream;
     const int64_t N = csr->num_nodes;
-    const int64_t words = rg_div_up(N, 32);
-    const int tier_blocks = (int)rg_max64(1, rg_div_up(words, kWordsPerBlock));
     SampleScratch S;
-    S.words = words;
-    S.num_nodes = N;
-    S.frontier_stride = rg_max64(fub_max[num_hops], 1);
-    S.chunk_stride = rg_max64(rg_div_up(S.frontier_stride, kChunk), tier_blocks) + 2;
-    rg_status st;
-    if ((st = rg_ensure(ctx, ctx->visited, (size_t)group * words * 4)) != RG_OK) return st;
-    // `fresh` must be all-zero between hops: a new allocation starts zeroed and every hop leaves it zeroed
-    if ((st = rg_ensure(ctx, ctx->fresh, (size_t)group * words * 4, true)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->pos, (size_t)group * N * 4)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->chunk_sum, (size_t)group * S.chunk_stride * 4)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->row_start, (size_t)group * S.frontier_stride * 8)) != RG_OK) return st;
-    if ((st = rg_ensure(ctx, ctx->row_deg, (size_t)group * S.frontier_stride * 4)) != RG_OK) return st;
+    sampler_scratch_shape(N, fub_max[num_hops], S);
+    const int64_t words = S.words;
+    const int tier_blocks = (int)rg_max64(1, rg_div_up(words, kWordsPerBlock));
+    rg_status st = rg_sampler_reserve(ctx, N, fub_max[num_hops], group);
+    if (st != RG_OK) return st;
     S.visited = (uint32_t*)ctx->visited.p;
     S.fresh = (uint32_t*)ctx->fresh.p;
     S.pos = (int32_t*)ctx->pos.p;
@@ -608,7 +626,7 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
 
 rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds, int32_t num_seeds,
                            const int32_t* fanouts, int32_t num_hops, uint64_t seed, uint32_t epoch,
-                           const rg_blocks* out, void* stream) {
+                           rg_blocks* out, void* stream) {
     return rg_sample_blocks_group(ctx, csr, 1, &seeds, &num_seeds, fanouts, num_hops, seed, epoch, out, stream);
 }
 

@@ -9,8 +9,9 @@ batches, count accesses, TopHot, VectorPull) followed by the online per-batch fe
   buffers are swapped at the epoch boundary.
 
 Host code only sequences library calls and owns the buffers; every step runs in the library's kernels.
-No host synchronisation happens inside the offline stage: frontier sizes stay on the device and are
-read back once per epoch, before its online stage.
+No host synchronisation happens inside the offline stage: frontier sizes stay on the device.  They are
+copied to pinned host memory as soon as the last batch has been sampled, so the host can size and queue the
+online stage's launches while the histogram, TopHot and the prefetch plan are still running.
 """
 import torch
 
@@ -20,15 +21,13 @@ from . import binding as B
 class _EpochState:
     """Everything one precomputed epoch owns: input-node lists, tier offsets, counts and the cache."""
 
-    def __init__(self, wl, H, slot, max_batches, device, keep_block=None):
+    def __init__(self, wl, H, slot, max_batches, device, keep_hops=None):
         cfg = wl.cfg
-        # the outermost hop's block of every batch, kept for the consumer of the gathered rows
-        self.blk_indptr = self.blk_nbr = self.blk_nbr_local = None
-        if keep_block is not None:
-            n_ip, n_e = keep_block
-            self.blk_indptr = torch.empty(max_batches, n_ip, dtype=torch.int32, device=device)
-            self.blk_nbr = torch.empty(max_batches, max(n_e, 1), dtype=torch.int32, device=device)
-            self.blk_nbr_local = torch.empty(max_batches, max(n_e, 1), dtype=torch.int32, device=device)
+        # per-batch blocks that outlive the sampling call: hop -> (indptr, nbr, nbr_local), each [max_batches, cap].
+        # The outermost hop is kept for the consumer of the gathered rows; all hops when every block is wanted.
+        self.blk = {}
+        for h, (n_ip, n_e) in (keep_hops or {}).items():
+            self.blk[h] = tuple(torch.empty(max_batches, max(c, 1), dtype=torch.int32, device=device) for c in (n_ip, n_e, n_e))
         # one slot of input nodes and one row of tier offsets per precomputed batch
         self.arena = torch.empty(max_batches, max(slot, 1), dtype=torch.int32, device=device)
         self.tier_offs = torch.zeros(max_batches, H + 2, dtype=torch.int32, device=device)
@@ -38,20 +37,21 @@ class _EpochState:
         self.stats = torch.zeros(max_batches, 3, dtype=torch.int64, device=device)
         self.pf_events = [torch.cuda.Event() for _ in range(max_batches)]
         self.sampled = [torch.cuda.Event() for _ in range(max_batches)]
-        self.stage = None                      # StagingArea when rows are pulled during the offline stage
         self.first_batch = None                # per node: first batch of the epoch that needs it (planned prefetch)
         self.plan = None
         self.built = torch.cuda.Event()        # offline stage of this state finished
         self.served = torch.cuda.Event()       # online stage of this state finished
         self.sizes = None
+        self.sizes_host = torch.zeros(max_batches, H + 2, dtype=torch.int32).pin_memory()
+        self.sizes_ready = torch.cuda.Event()  # the copy of the tier offsets into sizes_host has finished
         self.n_batches = 0
         self.pulls_queued = False
 
 
 class EpochPipeline:
     def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True,
-                 epoch_histogram=True, sampler_streams=2, double_buffer=False, early_pull=False,
-                 queue_depth=1, consumer=None, planned_prefetch=True, sample_group=8):
+                 epoch_histogram=True, sampler_streams=2, double_buffer=False,
+                 queue_depth=1, consumer=None, planned_prefetch=True, sample_group=8, keep_blocks=False):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -80,7 +80,10 @@ class EpochPipeline:
             raise ValueError("consumer must be None or 'mean'")
         self.consumer = consumer
         self.queue_depth = max(1, int(queue_depth))
-        keep = (self.bufs.frontier_ub[self.H - 1] + 1, self.bufs.edges_ub[self.H - 1]) if consumer else None
+        # keep_blocks: every hop's block of every batch stays in per-batch buffers (the sampler writes them there
+        # directly), e.g. to hand whole message-flow graphs to a trainer or to compare them after the epoch
+        hops = range(self.H) if keep_blocks else ([self.H - 1] if consumer else [])
+        keep = {h: (self.bufs.frontier_ub[h] + 1, self.bufs.edges_ub[h]) for h in hops}
         self.states = [_EpochState(wl, self.H, self.slot, self.max_batches, device, keep) for _ in range(2 if double_buffer else 1)]
         self.cur = 0
         self.out_ring = [torch.empty(max(self.slot, 1), wl.stride, dtype=torch.float32, device=device)
@@ -101,18 +104,9 @@ class EpochPipeline:
         # one LDS-privatised histogram over the whole epoch instead of one global-atomic pass per batch
         self.epoch_histogram = epoch_histogram
         self.pf_stream = torch.cuda.Stream(device=device) if prefetch else None
-        # early pull (off by default): when the cache can hold every remote node, each batch's remote rows are pulled
-        # into a staging area right after the batch is sampled, so the host link already works during the offline
-        # stage.  Measured on the stress workload it buys nothing (1255 against 1229 batches/s from a cold start,
-        # and it loses with double buffering): the pulls and the sampler slow each other down, and the end of the
-        # epoch is bound by the gathers that follow the last pulls either way.
-        self.early_pull = bool(prefetch and early_pull and wl.capacity_rows >= wl.n_remote and wl.n_remote > 0)
-        if self.early_pull:
-            for st in self.states:
-                st.stage = B.StagingArea(cfg.num_nodes, wl.n_remote, wl.stride, device)
         # planned prefetch: the epoch histogram also records the first batch that needs each node, the selected
         # slots are grouped by that batch once, and the prefetch stream then carries nothing but pulls
-        self.planned = bool(prefetch and planned_prefetch and epoch_histogram and not self.early_pull)
+        self.planned = bool(prefetch and planned_prefetch and epoch_histogram)
         if self.planned:
             for st in self.states:
                 st.first_batch = torch.empty(cfg.num_nodes, dtype=torch.int32, device=device)
@@ -120,14 +114,14 @@ class EpochPipeline:
         # The sampler lanes reuse the streams that are idle during the offline stage (miss and prefetch streams);
         # only lanes beyond those get streams of their own.  The device exposes few hardware queues, and streams
         # that end up sharing one would serialise work that is meant to overlap.
-        spare = [st for st in (self.side, None if self.early_pull else self.pf_stream) if st is not None]
+        spare = [st for st in (self.side, self.pf_stream) if st is not None]
         self.lane_stream = [None] + spare[:self.n_lanes - 1]
         while len(self.lane_stream) < self.n_lanes:
             self.lane_stream.append(torch.cuda.Stream(device=device))
         # with double buffering the next epoch is precomputed on one stream of its own while the current one is served
         self.build_stream = torch.cuda.Stream(device=device) if double_buffer else None
         for c in self.lane_ctx:
-            c.reserve(cfg.num_nodes, self.slot, self.slot if c is self.ctx else 0)
+            c.reserve(cfg.num_nodes, self.slot, self.slot if c is self.ctx else 0, self.sample_group)
 
     # ---- the current epoch's buffers under their historical names
     @property
@@ -176,9 +170,6 @@ class EpochPipeline:
         with torch.cuda.stream(head):
             head_ctx.epoch_schedule(self.wl.train_ids, self.wl.seed, epoch, self.order)
             st.counts.zero_()
-            if self.early_pull:
-                st.stage.reset()
-                self.pf_stream.wait_stream(head)
             for _, _, s in lanes[1:]:
                 s.wait_stream(head)
             n_train = self.order.numel()
@@ -191,21 +182,19 @@ class EpochPipeline:
                     seeds_list.append(self.order[b * cfg.batch_size:min((b + 1) * cfg.batch_size, n_train)])
                     bufs = bufs_list[k]
                     bufs.set_outputs(st.arena[i], st.tier_offs[i], st.edge_counts[i])
-                    if st.blk_indptr is not None:
-                        bufs.set_hop(self.H - 1, st.blk_indptr[i], st.blk_nbr[i], st.blk_nbr_local[i])
+                    for h, (ip, nb, nl) in st.blk.items():
+                        bufs.set_hop(h, ip[i], nb[i], nl[i])
                     outs.append(bufs)
                 c.sample_blocks_group(self.csr, seeds_list, cfg.fanouts, self.wl.seed, epoch, outs, stream=s or head)
-                for i in range(i0, min(i0 + gsz, len(ids))):
-                    if self.early_pull:
-                        st.sampled[i].record(s or head)
-                        self.pf_stream.wait_event(st.sampled[i])
-                        self.ctx.stage_rows(st.arena[i], self.slot, self.wl.home, st.stage, i, self.wl.remote_store, cfg.feat_dim,
-                                            n_dev=st.tier_offs[i, self.H + 1:], stream=self.pf_stream)
-                        st.pf_events[i].record(self.pf_stream)
-                    if not self.epoch_histogram:
+                if not self.epoch_histogram:
+                    for i in range(i0, min(i0 + gsz, len(ids))):
                         head_ctx.access_histogram(st.arena[i], self.slot, st.counts, n_dev=st.tier_offs[i, self.H + 1:], stream=head)
             for _, _, s in lanes[1:]:
                 head.wait_stream(s)
+            # the host needs the batch sizes to shape the online stage's launches: copy them out now, so that it can
+            # queue that stage while the histogram, TopHot and the plan below are still running
+            st.sizes_host[:len(ids)].copy_(st.tier_offs[:len(ids)], non_blocking=True)
+            st.sizes_ready.record(head)
             if self.epoch_histogram:
                 if self.planned:
                     st.first_batch.fill_(-1)
@@ -219,7 +208,7 @@ class EpochPipeline:
             st.built.record(head)
         st.n_batches = len(ids)
         st.sizes = None
-        st.pulls_queued = self.early_pull
+        st.pulls_queued = False
 
     def precompute(self, epoch, n_batches=None, batch_ids=None):
         """Offline stage (asynchronous) for the first n_batches batches of `epoch`, or for the listed
@@ -230,10 +219,11 @@ class EpochPipeline:
         self._offline(self.state, epoch, ids, lanes)
 
     def read_sizes(self):
-        """One device-to-host copy of every batch's input-node count (synchronises the current stream)."""
+        """Every batch's input-node count on the host: waits for the copy queued right behind the sampling (not for
+        the rest of the offline stage)."""
         st = self.state
-        st.built.synchronize()
-        st.sizes = st.tier_offs[:st.n_batches, self.H + 1].cpu().tolist()
+        st.sizes_ready.synchronize()
+        st.sizes = st.sizes_host[:st.n_batches, self.H + 1].tolist()
         return st.sizes
 
     def sampled_edges(self):
@@ -263,7 +253,8 @@ class EpochPipeline:
             self.ready[q].record(main)
             cs = self.consumer_stream
             cs.wait_event(self.ready[q])
-            self.ctx.mean_aggregate(st.blk_indptr[b], st.blk_nbr_local[b], self.bufs.frontier_ub[self.H - 1], self.out,
+            blk_indptr, _, blk_nbr_local = st.blk[self.H - 1]
+            self.ctx.mean_aggregate(blk_indptr[b], blk_nbr_local[b], self.bufs.frontier_ub[self.H - 1], self.out,
                                     self.cfg.feat_dim, self.agg, n_dst_dev=st.tier_offs[b, self.H:], stream=cs)
             self.consumed[q].record(cs)
         return n
@@ -286,11 +277,6 @@ class EpochPipeline:
         self.ctx.prefetch_cache_rows(st.arena[b], self.slot, st.cache, self.wl.home, self.wl.remote_store,
                                      self.cfg.feat_dim, n_dev=st.tier_offs[b, self.H + 1:], stream=stream)
 
-    def commit_rows(self, b, st=None):
-        """Early-pull mode: move the rows staged for batch b to their cache slots (current stream)."""
-        st = st or self.state
-        self.ctx.commit_staged_rows(st.arena[b], st.sizes[b], self.wl.home, st.stage, b, st.cache, self.cfg.feat_dim)
-
     def _queue_pulls(self, st):
         """All of an epoch's pulls on the prefetch stream, behind its TopHot, one event per batch."""
         if st.pulls_queued:
@@ -309,8 +295,7 @@ class EpochPipeline:
         main = torch.cuda.current_stream()
         if self.prefetch and not st.pulls_queued:
             self.pf_stream.wait_stream(main)
-        if self.early_pull:
-            main.wait_event(st.built)                   # the commits need this epoch's TopHot
+        main.wait_event(st.built)                       # the offline stage may have run on other streams
         for b in range(n_batches):
             if b % B.RG_GATHER_TICKETS == 0:
                 self._prepare(st, list(range(b, min(b + B.RG_GATHER_TICKETS, n_batches))))
@@ -319,8 +304,6 @@ class EpochPipeline:
                     self.prefetch_rows(b, stream=self.pf_stream)
                     st.pf_events[b].record(self.pf_stream)
                 main.wait_event(st.pf_events[b])
-                if self.early_pull:
-                    self.commit_rows(b)
             self.gather(b)
             if on_batch:
                 on_batch(self, b)

@@ -50,3 +50,32 @@ def assert_batch_equal(hip, orc, num_hops, tag=""):
 
 def host_graph(wl):
     return wl.row_ptr.cpu().numpy().astype(np.int64), wl.col_idx.cpu().numpy()
+
+
+class OracleAhead:
+    """Runs fn(item) for a list of items on a few host threads, a bounded number of items ahead of the
+    consumer (the oracle is single-threaded C called through ctypes, which releases the GIL).  Results are
+    handed out strictly in order; nothing about a result depends on the threading."""
+
+    def __init__(self, fn, items, workers=8, window=12):
+        import concurrent.futures
+        self._pool = concurrent.futures.ThreadPoolExecutor(max_workers=workers)
+        self._fn, self._items, self._window = fn, list(items), window
+        self._futures, self._next_submit, self._next_take = {}, 0, 0
+        self._fill()
+
+    def _fill(self):
+        while self._next_submit < len(self._items) and self._next_submit < self._next_take + self._window:
+            self._futures[self._next_submit] = self._pool.submit(self._fn, self._items[self._next_submit])
+            self._next_submit += 1
+
+    def take(self):
+        """Result for the next item (blocks until it is ready)."""
+        i = self._next_take
+        res = self._futures.pop(i).result()
+        self._next_take += 1
+        self._fill()
+        return res
+
+    def close(self):
+        self._pool.shutdown(wait=True, cancel_futures=True)

@@ -27,9 +27,15 @@ def test_bench_line_has_the_contract_fields():
     assert d["n_gpus"] == 1 and d["steps"] == 4 and d["warmup"] == 2 and d["higher_is_better"] is True
     assert d["vs_baseline"] is None and d["data"] == "synthetic" and d["config"]["workload"] == "tiny"
     assert d["value"] > 0 and abs(d["ms_per_step"] * d["value"] - 1000.0) < 1e-6 * 1000.0
+    t = d["timing"]
+    assert t["reps"] >= 5 and t["min_ms"] <= t["median_ms"] <= t["max_ms"]
+    assert abs(t["median_ms"] - d["ms_per_step"] * d["steps"]) < 1e-6 * t["median_ms"]
+    assert d["full_epoch"]["batches"] == 4 and d["full_epoch"]["batches_per_s_median"] > 0
+    assert d["config"]["GPU_MAX_HW_QUEUES"] is not None
     roof = d["roofline"]
     assert roof["bound"] == "hbm" and roof["unit"] == "GB/s" and roof["peak"] == 8000.0
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-12
+    assert roof["traffic"] is None and roof["traffic_source"] is None        # no counter run is recorded for `tiny`
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] == 1 and cpu["value"] > 0 and cpu["unit"] == d["unit"]
     g = d["gather"]

@@ -346,15 +346,13 @@ def test_pipeline_epochs_back_to_back(B, double_buffer, full_cache):
     import dataclasses
     from paper_2505_10806_amd.pipeline import EpochPipeline
     base = synth.get_config("tiny")
-    # full_cache: the cache can hold every remote node, which switches the pipeline to pulling rows into a
-    # staging area during the offline stage and committing them to their slots before each gather
+    # full_cache: the cache can hold every remote node, so every touched remote row is selected and no row misses
     wl = synth.build_workload(dataclasses.replace(base, cache_frac=1.0) if full_cache else base, seed=5, device=DEV)
     cfg = wl.cfg
     rp, ci = host_graph(wl)
     X = wl.features.cpu().numpy()
     home_np, train_np = wl.home.cpu().numpy(), wl.train_ids.cpu().numpy()
-    pipe = EpochPipeline(wl, device=DEV, double_buffer=double_buffer, early_pull=True)
-    assert pipe.early_pull == full_cache
+    pipe = EpochPipeline(wl, device=DEV, double_buffer=double_buffer)
     nb = pipe.batches_per_epoch
     expected = {}
 
@@ -391,74 +389,6 @@ def test_pipeline_epochs_back_to_back(B, double_buffer, full_cache):
     torch.cuda.synchronize()
     assert sorted(expected) == [0, 1, 2]
     assert not np.array_equal(expected[0][0][0], expected[1][0][0])       # epochs differ
-
-
-@pytest.mark.parametrize("stage_cap,cache_cap", [(10_000, 10_000), (700, 10_000), (10_000, 300), (0, 500)])
-def test_stage_and_commit_match_bulk_fill(B, ctx, stage_cap, cache_cap):
-    """Early pull through the C ABI: rows staged batch by batch before TopHot, committed to their slots after.
-    A staging area that is too small leaves rows unstaged (the prefetch call pulls those); a cache that is
-    smaller than the candidate set leaves staged rows unselected.  Either way the gathers and the resident
-    rows equal the oracle's."""
-    log(f"[stage/commit] stage_cap={stage_cap} cache_cap={cache_cap}")
-    wl = synth.build_workload("tiny", seed=23, device=DEV)
-    cfg = wl.cfg
-    H = len(cfg.fanouts)
-    rp, ci = host_graph(wl)
-    X = wl.features.cpu().numpy()
-    home_np = wl.home.cpu().numpy()
-    csr = B.CsrGraph(wl.row_ptr, wl.col_idx)
-    bufs = B.BlockBuffers(cfg.num_nodes, wl.nnz, cfg.batch_size, cfg.fanouts, DEV)
-    order = ctx.epoch_schedule(wl.train_ids, wl.seed, 0)
-    torch.cuda.synchronize()
-    orc_batches = oracle.epoch_batches(wl.train_ids.cpu().numpy(), cfg.batch_size, wl.seed, 0, 4)
-    stage = B.StagingArea(cfg.num_nodes, stage_cap, wl.stride, DEV)
-    stage.rows.fill_(float("nan"))
-    stage.touched.fill_(-1)
-    stage.cursor.fill_(77)
-    stage.reset()
-    counts = torch.zeros(cfg.num_nodes, dtype=torch.int32, device=DEV)
-    counts_orc = np.zeros(cfg.num_nodes, dtype=np.uint32)
-    inputs_dev, inputs_orc = [], []
-    side = torch.cuda.Stream()
-    for b in range(4):
-        seeds = order[b * cfg.batch_size:(b + 1) * cfg.batch_size]
-        ctx.sample_blocks(csr, seeds, seeds.numel(), cfg.fanouts, wl.seed, 0, bufs)
-        torch.cuda.synchronize()
-        n = int(bufs.tier_off[H + 1].item())
-        inputs_dev.append(bufs.nodes[:n].clone())
-        ctx.access_histogram(inputs_dev[-1], n, counts)
-        ctx.stage_rows(inputs_dev[-1], n, wl.home, stage, b, wl.remote_store, cfg.feat_dim, stream=side)
-        orc = oracle.sample_blocks(rp, ci, orc_batches[b], cfg.fanouts, wl.seed, 0)
-        oracle.access_histogram(orc.input_nodes, counts_orc)
-        inputs_orc.append(orc.input_nodes)
-    torch.cuda.synchronize()
-    remote = ((home_np.astype(np.int64) & 0xFFFFFFFF) >> 30) == 2
-    touched_remote = np.flatnonzero(remote & (counts_orc > 0))
-    assert int(stage.cursor.item()) == touched_remote.size                   # every touched remote node claimed once
-    slot_of = stage.slot_of.cpu().numpy()
-    staged = touched_remote[slot_of[touched_remote] >= 0]
-    assert staged.size == min(stage_cap, touched_remote.size)
-    assert len(set(slot_of[staged].tolist())) == staged.size and (slot_of[staged] < stage_cap).all()
-    if staged.size:
-        assert np.array_equal(stage.rows[torch.as_tensor(slot_of[staged], device=DEV).long(), :cfg.feat_dim].cpu().numpy(), X[staged])
-    cache = B.FeatureCache(cfg.num_nodes, min(cache_cap, wl.n_remote), wl.stride, DEV)
-    cache.cache_rows.fill_(float("nan"))
-    ctx.build_cache(counts, wl.home, None, cfg.feat_dim, cache)
-    ids_orc, loc_orc = oracle.build_cache(counts_orc, home_np, min(cache_cap, wl.n_remote))
-    out = torch.empty(bufs.frontier_ub[H], wl.stride, device=DEV)
-    stats = torch.zeros(3, dtype=torch.int64, device=DEV)
-    for b in range(4):
-        n = inputs_dev[b].numel()
-        ctx.commit_staged_rows(inputs_dev[b], n, wl.home, stage, b, cache, cfg.feat_dim)
-        ctx.prefetch_cache_rows(inputs_dev[b], n, cache, wl.home, wl.remote_store, cfg.feat_dim)   # rows never staged
-        ctx.gather_features(inputs_dev[b], n, cache, wl.local_store, wl.remote_store, cfg.feat_dim, out, stats)
-        torch.cuda.synchronize()
-        want, st = oracle.gather_features(X, inputs_orc[b], loc_orc)
-        assert np.array_equal(out[:n, :cfg.feat_dim].cpu().numpy(), want), f"batch {b}"
-        assert tuple(stats.cpu().tolist()) == st
-    k = ids_orc.size
-    assert int(cache.num_cached.item()) == k
-    assert np.array_equal(cache.cache_rows[:k, :cfg.feat_dim].cpu().numpy(), X[ids_orc])
 
 
 @pytest.mark.parametrize("num_batches", [0, 1, 7, 1023, 1500])
@@ -653,6 +583,7 @@ def test_gather_shapes_and_tags(B, ctx, dim, pad, two_streams):
         want, st = oracle.gather_features(X, nodes, loc32)
         assert np.array_equal(out[:n, :dim].cpu().numpy(), want), f"n={n}"
         assert tuple(stats.cpu().tolist()) == st
+        assert torch.isnan(out[:, dim:]).all(), "the padding behind an output row was written"
     # count read from the device: the launch is sized for 4097 rows but only 1000 are valid
     nodes = rng.integers(0, n_nodes, size=4097).astype(np.int32)
     n_dev = torch.tensor([1000], dtype=torch.int32, device=DEV)
@@ -947,9 +878,13 @@ def test_argument_errors_are_reported_not_launched(B, ctx):
         ctx.sample_blocks(csr, seeds, -1, (2,), 1, 0, bufs)
     assert e.value.status == B.RG_ERR_INVALID_ARG
     small = B.BlockBuffers(2, 2, 1, (2,), DEV)          # sized for one seed, used with two
+    assert (small.c_struct.nodes_cap, small._indptr_cap[0], small._nbr_cap[0]) == (2, 2, 2)
     with pytest.raises(B.RgError) as e:
         ctx.sample_blocks(csr, seeds, 2, (2,), 1, 0, small)
     assert e.value.status == B.RG_ERR_CAPACITY
+    # the required sizes come back in place of the capacities: frontier bounds [2, 2], edge bound 2
+    assert (small.c_struct.nodes_cap, small._indptr_cap[0], small._nbr_cap[0]) == (2, 3, 2)
+    assert B.blocks_bounds(2, 2, 2, (2,)) == ([2, 2], [2])
     cache = B.FeatureCache(2, 1, 4, DEV)
     store = torch.zeros(2, 4, device=DEV)
     pinned = torch.zeros(2, 4, pin_memory=True)
@@ -984,10 +919,6 @@ def test_argument_errors_are_reported_not_launched(B, ctx):
     good_plan = B.PrefetchPlan(1, 2, DEV)
     with pytest.raises(B.RgError) as e:
         ctx.prefetch_planned(good_plan, 4, cache, pinned, 4)   # batch beyond the plan
-    assert e.value.status == B.RG_ERR_INVALID_ARG
-    stage = B.StagingArea(2, 2, 4, DEV)
-    with pytest.raises(B.RgError) as e:
-        ctx.stage_rows(seeds, 2, seeds, stage, -1, pinned, 4)
     assert e.value.status == B.RG_ERR_INVALID_ARG
     with pytest.raises(B.RgError) as e:
         ctx.mean_aggregate(seeds, seeds, 1, store, 8, out)     # dim larger than the strides
