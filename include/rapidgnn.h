@@ -319,6 +319,25 @@ RG_API rg_status rg_gather_run(rg_ctx* ctx, int32_t ticket, int64_t n, const int
                                const float* remote_store, int64_t remote_stride,
                                int32_t dim, float* out, int64_t out_stride, void* hit_stream, void* miss_stream);
 
+/* ---- feature assembly for callers that cannot allocate -----------------------------------
+ * The same result as rg_gather_features (same arguments, same stream semantics), for callers
+ * that must not trigger a device allocation: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The per-row lookup results and the miss list go to a
+ * file-scope device array inside the library instead of the context's growable scratch, so the
+ * call never calls hipMalloc / hipFree, whatever n was in earlier calls.  The array holds
+ * RG_STATIC_GATHER_MAX_ROWS rows (12 B per row, about 12.6 MB, resident on every GPU the
+ * library has run on until the process ends); n above that returns RG_ERR_CAPACITY and queues
+ * nothing.  Every call on one GPU, from any context, shares that GPU's array: calls that
+ * overlap in time on one GPU race, so the caller orders them (one stream, or events).  The
+ * kernels are not bracketed for rg_profile_read. */
+#define RG_STATIC_GATHER_MAX_ROWS (1 << 20)
+RG_API rg_status rg_gather_features_static(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
+                                           const rg_cache* cache,
+                                           const float* local_store, int64_t local_stride,
+                                           const float* remote_store, int64_t remote_stride,
+                                           int32_t dim, float* out, int64_t out_stride,
+                                           rg_gather_stats* stats, void* hit_stream, void* miss_stream);
+
 /* ---- consumer of the gathered rows: Eq. 1 with AGG = mean (GraphSAGE, Section II-A) -------------
  * For the block of one hop (destination i = position in frontier_h, sources = positions in
  * frontier_{h+1} given by nbr_local[h]):

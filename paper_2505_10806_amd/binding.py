@@ -19,6 +19,7 @@ RG_FANOUT_ALL = -1
 RG_MAX_HOPS = 8
 RG_MAX_GROUP = 8
 RG_GATHER_TICKETS = 8
+RG_STATIC_GATHER_MAX_ROWS = 1 << 20
 RG_K_GATHER_HBM, RG_K_GATHER_MISS, RG_K_SAMPLE, RG_K_HISTOGRAM, RG_K_CACHE_FILL, RG_K_AGGREGATE = range(6)
 
 _STATUS_NAMES = {0: "RG_OK", 1: "RG_ERR_INVALID_ARG", 2: "RG_ERR_CAPACITY", 3: "RG_ERR_OOM",
@@ -88,13 +89,14 @@ def _load():
     L.rg_mean_aggregate.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_p, c_i64, c_i32, c_p, c_i64, c_p]
     L.rg_gather_features.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_i64, c_p, c_i64,
                                      c_i32, c_p, c_i64, c_p, c_p, c_p]
+    L.rg_gather_features_static.argtypes = L.rg_gather_features.argtypes
     L.rg_profile_enable.argtypes = [c_p, ctypes.c_int]
     L.rg_profile_reset.argtypes = [c_p]
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group",
                  "rg_access_histogram", "rg_access_histogram_epoch", "rg_build_cache", "rg_cache_hit_curve",
                  "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_prefetch_planned", "rg_gather_features",
-                 "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable",
+                 "rg_gather_features_static", "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable",
                  "rg_profile_reset", "rg_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     return L
@@ -106,7 +108,7 @@ EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "r
                     "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group", "rg_access_histogram",
                     "rg_access_histogram_epoch",
                     "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_plan_prefetch",
-                    "rg_prefetch_planned", "rg_gather_features", "rg_gather_prepare",
+                    "rg_prefetch_planned", "rg_gather_features", "rg_gather_features_static", "rg_gather_prepare",
                     "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
 
 
@@ -260,6 +262,18 @@ class Context:
     def gather_features(self, input_nodes, n, cache, local_store, remote_store, dim, out, stats,
                         n_dev=None, hit_stream=None, miss_stream=None):
         self._check(_lib.rg_gather_features(
+            self._h, _ptr(input_nodes, torch.int32, "cuda", "input_nodes"), int(n),
+            _ptr(n_dev, torch.int32, "cuda", "n_dev"), ctypes.byref(cache.c_struct),
+            _ptr(local_store, torch.float32, "cuda", "local_store"), local_store.stride(0),
+            _ptr(remote_store, torch.float32, "mapped", "remote_store"), remote_store.stride(0),
+            int(dim), _ptr(out, torch.float32, "cuda", "out"), out.stride(0),
+            _ptr(stats, torch.int64, "cuda", "stats"), _stream_handle(hit_stream),
+            None if miss_stream is None else _stream_handle(miss_stream)))
+
+    # -- rg_gather_features_static
+    def gather_features_static(self, input_nodes, n, cache, local_store, remote_store, dim, out, stats,
+                               n_dev=None, hit_stream=None, miss_stream=None):
+        self._check(_lib.rg_gather_features_static(
             self._h, _ptr(input_nodes, torch.int32, "cuda", "input_nodes"), int(n),
             _ptr(n_dev, torch.int32, "cuda", "n_dev"), ctypes.byref(cache.c_struct),
             _ptr(local_store, torch.float32, "cuda", "local_store"), local_store.stride(0),

@@ -107,6 +107,11 @@ rg_status rg_create(int device, rg_ctx** out) {
         delete ctx;
         return rg_set_error(nullptr, RG_ERR_HIP, "rg_create: hipEventCreate failed");
     }
+    if (rg_gather_static_init(ctx) != RG_OK) {
+        memcpy(g_create_error, ctx->err, sizeof(g_create_error));
+        rg_destroy(ctx);
+        return RG_ERR_HIP;
+    }
     // launch-shape knobs: read here once, never on the call paths
     RgKnobs& k = ctx->knobs;
     const int unroll = env_int("RG_GATHER_UNROLL", k.gather_unroll);

@@ -7,9 +7,26 @@
 // host-link transfers overlap the HBM copies.
 #include "rg_rowcopy.h"
 
+// Scratch of rg_gather_features_static: one control block, the resolved location word of every output row and
+// the (output row, remote row) pairs of the miss rows, for up to RG_STATIC_GATHER_MAX_ROWS rows.  Every GPU the
+// library runs on holds its own copy of this array until the process ends.  Host code must not use the array's
+// name as an address: rg_gather_static_init resolves the device address once per context.
+constexpr size_t kStaticCtlBytes = 256;
+constexpr size_t kStaticSrcBytes = (size_t)RG_STATIC_GATHER_MAX_ROWS * 4;
+constexpr size_t kStaticMissBytes = (size_t)RG_STATIC_GATHER_MAX_ROWS * 8;
+static __device__ __align__(256) unsigned char scratch[kStaticCtlBytes + kStaticSrcBytes + kStaticMissBytes];
+
+rg_status rg_gather_static_init(rg_ctx* ctx) {
+    void* ptr = nullptr;
+    RG_HIP(ctx, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return rg_set_error(ctx, RG_ERR_HIP, "hipGetSymbolAddress returned a null address for the gather scratch");
+    ctx->static_scratch = ptr;
+    return RG_OK;
+}
+
 namespace {
 
-// Where one batch's lookup results live: a ticket's slices of the context scratch.
+// Where one batch's lookup results live: a ticket's slices of the context scratch, or the static scratch.
 struct GatherScratch {
     uint32_t* src;        // [rows] resolved location word per output row
     int32_t* miss_list;   // [2 * rows] (output row, remote row) pairs
@@ -23,6 +40,16 @@ GatherScratch ticket_scratch(rg_ctx* ctx, int t) {
     g.gctl = (uint32_t*)ctx->gather_ctl.p + t * 16;
     return g;
 }
+
+GatherScratch static_scratch(rg_ctx* ctx) {
+    unsigned char* base = (unsigned char*)ctx->static_scratch;
+    GatherScratch g;
+    g.gctl = (uint32_t*)base;
+    g.src = (uint32_t*)(base + kStaticCtlBytes);
+    g.miss_list = (int32_t*)(base + kStaticCtlBytes + kStaticSrcBytes);
+    return g;
+}
+
 
 __device__ __forceinline__ int64_t rg_actual_n(int64_t n, const int32_t* __restrict__ n_dev) {
     if (!n_dev) return n;
@@ -379,6 +406,32 @@ rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n,
     if (st != RG_OK) return st;
     return rg_gather_run(ctx, 0, n, n_dev, cache, local_store, local_stride, remote_store, remote_stride, dim, out, out_stride,
                          hit_stream, miss_stream);
+}
+
+rg_status rg_gather_features_static(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,
+                                    const rg_cache* cache, const float* local_store, int64_t local_stride,
+                                    const float* remote_store, int64_t remote_stride, int32_t dim, float* out,
+                                    int64_t out_stride, rg_gather_stats* stats, void* hit_stream, void* miss_stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, stats, "rg_gather_features_static: stats is NULL");
+    rg_status st = check_copy_args(ctx, "rg_gather_features_static", n, dim, cache, local_store, local_stride, remote_store,
+                                   remote_stride, out, out_stride);
+    if (st != RG_OK) return st;
+    RG_REQUIRE(ctx, n == 0 || input_nodes, "rg_gather_features_static: input_nodes is NULL");
+    if (n > RG_STATIC_GATHER_MAX_ROWS)
+        return rg_set_error(ctx, RG_ERR_CAPACITY, "rg_gather_features_static: n = %lld exceeds the static scratch of %d rows "
+                            "(use rg_gather_features)", (long long)n, RG_STATIC_GATHER_MAX_ROWS);
+    RG_REQUIRE(ctx, ctx->static_scratch, "rg_gather_features_static: the static scratch was not resolved for this device");
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    if (n > 0 && (st = rg_check_device_readable(ctx, remote_store, "rg_gather_features_static: remote_store")) != RG_OK) return st;
+    hipStream_t sh = (hipStream_t)hit_stream;
+    hipStream_t sm = miss_stream ? (hipStream_t)miss_stream : sh;
+    // the reset kernel zeroes the miss counter and the statistics the previous call left behind
+    const GatherScratch scr = static_scratch(ctx);
+    if ((st = launch_classify(ctx, 1, &input_nodes, &n, &n_dev, cache, &stats, &scr, sh)) != RG_OK) return st;
+    if (n == 0) return RG_OK;
+    return launch_copies(ctx, scr, n, n_dev, cache, local_store, local_stride, remote_store, remote_stride, dim, out, out_stride,
+                         sh, sm, false);
 }
 
 }  // extern "C"

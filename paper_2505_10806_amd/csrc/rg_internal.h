@@ -62,6 +62,7 @@ struct rg_ctx {
     int64_t gather_cap = 0;                                  // rows per ticket the buffers hold
     int64_t gather_rows[RG_GATHER_TICKETS] = {-1, -1, -1, -1, -1, -1, -1, -1};   // rows a ticket was prepared for (-1: none)
     hipEvent_t ev_classified = nullptr, ev_miss_done = nullptr;
+    void* static_scratch = nullptr;   // device address of the library's file-scope gather scratch on ctx->device
 
     // profiling
     bool profiling = false;
@@ -80,6 +81,8 @@ rg_status rg_gather_reserve(rg_ctx* ctx, int64_t rows);
 // Sizes the sampler scratch for `group` batches side by side on a graph of num_nodes nodes with cumulative
 // frontiers of up to max_frontier nodes (what rg_sample_blocks_group would otherwise grow on demand).
 rg_status rg_sampler_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int group);
+// Resolves the device address of the file-scope gather scratch for ctx->device (the device must be current).
+rg_status rg_gather_static_init(rg_ctx* ctx);
 // Profiling brackets (no-ops unless profiling is enabled).
 int rg_prof_begin(rg_ctx* ctx, int kernel, hipStream_t s);
 void rg_prof_end(rg_ctx* ctx, int token, hipStream_t s);
