@@ -41,7 +41,8 @@
  *    that rg_create reads once per context: RG_GATHER_UNROLL (2, 4 or 8 chunks in flight per
  *    lane of the HBM gather), RG_GATHER_BLOCKS_PER_CU (grid cap of the HBM gather, default
  *    none), RG_PULL_BLOCKS / RG_PULL_THREADS (grid of the host-link pull kernels, default
- *    48 x 256), RG_MISS_BLOCKS (grid of the miss-row kernel, default 192).
+ *    16 x 1024), RG_PULL_ROWS (rows in flight per lane group of the pull kernel, 4 or 8), RG_MISS_BLOCKS /
+ *    RG_MISS_THREADS (grid of the miss-row kernel, default 192 x 256).
  */
 #ifndef RAPIDGNN_H
 #define RAPIDGNN_H

@@ -50,6 +50,8 @@ def lib():
     L.orc_epoch_schedule.restype = None
     L.orc_sample_blocks.argtypes = [c_i64, P, P, P, c_i64, P, c_i32, c_u64, c_u32]
     L.orc_sample_blocks.restype = P
+    L.orc_sample_blocks_ordered.argtypes = [c_i64, P, P, P, c_i64, P, c_i32, c_u64, c_u32, c_i32]
+    L.orc_sample_blocks_ordered.restype = P
     L.orc_blocks_free.argtypes = [P]
     L.orc_blocks_free.restype = None
     L.orc_blocks_num_hops.argtypes = [P]
@@ -146,13 +148,16 @@ class Blocks:
         return self.nodes
 
 
-def sample_blocks(row_ptr, col_idx, seeds, fanouts, seed, epoch):
+ORDER_ASCENDING, ORDER_FIRST_SEEN = 0, 1
+
+
+def sample_blocks(row_ptr, col_idx, seeds, fanouts, seed, epoch, node_order=ORDER_ASCENDING):
     rp = _arr(row_ptr, np.int64)
     ci = _arr(col_idx, np.int32)
     sd = _arr(seeds, np.int32)
     fo = _arr(fanouts, np.int32)
     L = lib()
-    h = L.orc_sample_blocks(rp.size - 1, _p(rp), _p(ci), _p(sd), sd.size, _p(fo), fo.size, seed, epoch)
+    h = L.orc_sample_blocks_ordered(rp.size - 1, _p(rp), _p(ci), _p(sd), sd.size, _p(fo), fo.size, seed, epoch, int(node_order))
     try:
         H = fo.size
         tier_off = _copy(L.orc_blocks_tier_off(h), H + 2, np.int64)

@@ -104,10 +104,10 @@ static int orc_i32_cmp(const void* a, const void* b) {
     return (x > y) - (x < y);
 }
 
-orc_blocks* orc_sample_blocks(int64_t num_nodes, const int64_t* row_ptr, const int32_t* col_idx,
-                              const int32_t* seeds, int64_t num_seeds,
-                              const int32_t* fanouts, int32_t num_hops,
-                              uint64_t seed, uint32_t epoch) {
+orc_blocks* orc_sample_blocks_ordered(int64_t num_nodes, const int64_t* row_ptr, const int32_t* col_idx,
+                                      const int32_t* seeds, int64_t num_seeds,
+                                      const int32_t* fanouts, int32_t num_hops,
+                                      uint64_t seed, uint32_t epoch, int32_t node_order) {
     orc_blocks* b = (orc_blocks*)calloc(1, sizeof(orc_blocks));
     b->num_hops = num_hops;
     b->tier_off = (int64_t*)calloc((size_t)num_hops + 2, sizeof(int64_t));
@@ -162,25 +162,42 @@ orc_blocks* orc_sample_blocks(int64_t num_nodes, const int64_t* row_ptr, const i
             for (int64_t t = 0; t < m; ++t)
                 nbr[indptr[i] + t] = col_idx[row_ptr[v] + pos[t]];
         }
-        /* new tier: ids seen in nbr that are not yet frontier members, unique, ascending */
-        int32_t* fresh = (int32_t*)malloc((size_t)(E > 0 ? E : 1) * sizeof(int32_t));
-        int64_t n_fresh = 0;
-        for (int64_t e = 0; e < E; ++e)
-            if (where[nbr[e]] < 0) fresh[n_fresh++] = nbr[e];
-        qsort(fresh, (size_t)n_fresh, sizeof(int32_t), orc_i32_cmp);
-        int64_t n_unique = 0;
-        for (int64_t e = 0; e < n_fresh; ++e)
-            if (e == 0 || fresh[e] != fresh[e - 1]) fresh[n_unique++] = fresh[e];
-        if (n + n_unique > cap) {
-            cap = (n + n_unique) * 2;
-            nodes = (int32_t*)realloc(nodes, (size_t)cap * sizeof(int32_t));
+        if (node_order == ORC_ORDER_FIRST_SEEN) {
+            /* new tier: ids seen in nbr that are not yet frontier members, each once, in the order in which the hop's
+             * neighbour list first names them */
+            if (n + E > cap) {
+                cap = (n + E) * 2;
+                nodes = (int32_t*)realloc(nodes, (size_t)cap * sizeof(int32_t));
+            }
+            for (int64_t e = 0; e < E; ++e) {
+                int32_t u = nbr[e];
+                if (where[u] < 0) {
+                    nodes[n] = u;
+                    where[u] = n;
+                    ++n;
+                }
+            }
+        } else {
+            /* new tier: ids seen in nbr that are not yet frontier members, unique, ascending */
+            int32_t* fresh = (int32_t*)malloc((size_t)(E > 0 ? E : 1) * sizeof(int32_t));
+            int64_t n_fresh = 0;
+            for (int64_t e = 0; e < E; ++e)
+                if (where[nbr[e]] < 0) fresh[n_fresh++] = nbr[e];
+            qsort(fresh, (size_t)n_fresh, sizeof(int32_t), orc_i32_cmp);
+            int64_t n_unique = 0;
+            for (int64_t e = 0; e < n_fresh; ++e)
+                if (e == 0 || fresh[e] != fresh[e - 1]) fresh[n_unique++] = fresh[e];
+            if (n + n_unique > cap) {
+                cap = (n + n_unique) * 2;
+                nodes = (int32_t*)realloc(nodes, (size_t)cap * sizeof(int32_t));
+            }
+            for (int64_t e = 0; e < n_unique; ++e) {
+                nodes[n] = fresh[e];
+                where[fresh[e]] = n;
+                ++n;
+            }
+            free(fresh);
         }
-        for (int64_t e = 0; e < n_unique; ++e) {
-            nodes[n] = fresh[e];
-            where[fresh[e]] = n;
-            ++n;
-        }
-        free(fresh);
         /* neighbours relabelled to positions in frontier_{h+1} */
         int32_t* nbr_local = (int32_t*)malloc((size_t)(E > 0 ? E : 1) * sizeof(int32_t));
         for (int64_t e = 0; e < E; ++e) nbr_local[e] = (int32_t)where[nbr[e]];
@@ -195,6 +212,14 @@ orc_blocks* orc_sample_blocks(int64_t num_nodes, const int64_t* row_ptr, const i
     free(pos);
     free(where);
     return b;
+}
+
+orc_blocks* orc_sample_blocks(int64_t num_nodes, const int64_t* row_ptr, const int32_t* col_idx,
+                              const int32_t* seeds, int64_t num_seeds,
+                              const int32_t* fanouts, int32_t num_hops,
+                              uint64_t seed, uint32_t epoch) {
+    return orc_sample_blocks_ordered(num_nodes, row_ptr, col_idx, seeds, num_seeds, fanouts, num_hops, seed, epoch,
+                                     ORC_ORDER_ASCENDING);
 }
 
 void orc_blocks_free(orc_blocks* b) {

@@ -12,7 +12,8 @@
  *
  * Pins (tests/test_oracle_*.py): Philox known-answer vectors; Floyd subset uniformity
  * and inclusion probability k/d; every sampled neighbour is a real edge; count =
- * min(fanout, degree); BFS-ball special case against a textbook BFS; histogram against
+ * min(fanout, degree); BFS-ball special case against a textbook BFS (first-seen order: against the
+ * visiting order of a queue BFS); histogram against
  * numpy bincount; top-K against a full lexicographic sort; gather against plain
  * indexing; the hit-rate closed form; the paper's byte-accounting example; the mean aggregation
  * against a float64 sparse matrix product (scipy).
@@ -52,6 +53,16 @@ orc_blocks* orc_sample_blocks(int64_t num_nodes, const int64_t* row_ptr, const i
                               const int32_t* seeds, int64_t num_seeds,
                               const int32_t* fanouts, int32_t num_hops,
                               uint64_t seed, uint32_t epoch);
+/* The same with a choice of the order of the nodes inside a new tier (Section IV: the precomputed batches fix "the
+ * order of the input nodes"): ORC_ORDER_ASCENDING = ascending by id; ORC_ORDER_FIRST_SEEN = the order in which the
+ * hop's neighbour list (frontier order, per node in insertion order) first names them, the order a block-building
+ * pass over the sampled edges produces.  Which nodes a tier holds, and what every node draws, is the same. */
+#define ORC_ORDER_ASCENDING 0
+#define ORC_ORDER_FIRST_SEEN 1
+orc_blocks* orc_sample_blocks_ordered(int64_t num_nodes, const int64_t* row_ptr, const int32_t* col_idx,
+                                      const int32_t* seeds, int64_t num_seeds,
+                                      const int32_t* fanouts, int32_t num_hops,
+                                      uint64_t seed, uint32_t epoch, int32_t node_order);
 void orc_blocks_free(orc_blocks* b);
 int32_t orc_blocks_num_hops(const orc_blocks* b);
 const int64_t* orc_blocks_tier_off(const orc_blocks* b);      /* [num_hops + 2] */

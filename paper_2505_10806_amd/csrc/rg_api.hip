@@ -121,6 +121,9 @@ rg_status rg_create(int device, rg_ctx** out) {
     const int threads = env_int("RG_PULL_THREADS", k.pull_threads);
     if (threads == 64 || threads == 256 || threads == 1024) k.pull_threads = threads;
     k.miss_blocks = env_int("RG_MISS_BLOCKS", k.miss_blocks);
+    const int mthreads = env_int("RG_MISS_THREADS", k.miss_threads);
+    if (mthreads == 64 || mthreads == 256 || mthreads == 1024) k.miss_threads = mthreads;
+    if (env_int("RG_PULL_ROWS", k.pull_rows) == 8) k.pull_rows = 8;
     *out = ctx;
     return RG_OK;
 }

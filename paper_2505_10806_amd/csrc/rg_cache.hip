@@ -547,14 +547,13 @@ __global__ void __launch_bounds__(256) k_mark_segment(const int32_t* __restrict_
 }
 
 // The pairs are list[0..pctl[0]) or, when seg_off is given, list[seg_off[0]..seg_off[1]).
-template <int VEC>
+template <int VEC, int U>
 __global__ void __launch_bounds__(1024) k_prefetch_pull(const int32_t* __restrict__ list, const uint32_t* __restrict__ pctl,
                                                        const int32_t* __restrict__ seg_off,
                                                        const float* __restrict__ remote_store, int64_t remote_stride,
                                                        float* __restrict__ cache_rows, int64_t cache_stride, int64_t dst_rows,
                                                        int cpr, int log2L, int tail) {
     typedef typename RgVec<VEC>::type V;
-    constexpr int U = 4;
     int64_t n;
     if (seg_off) { list += 2 * (int64_t)seg_off[0]; n = seg_off[1] - seg_off[0]; } else { n = pctl[0]; }
     const int lane = rg_lane();
@@ -735,15 +734,17 @@ rg_status launch_list_copy(rg_ctx* ctx, const int32_t* list, const uint32_t* pct
     const int64_t strides[2] = {src_stride, dst_stride};
     const int vec = rg_pick_vec(dim, ptrs, 2, strides, 2);
     const RgRowShape shp = rg_row_shape(dim, vec);
-    const int rows_per_block = (threads / RG_WAVE) * (RG_WAVE >> shp.log2L) * 4;
+    const int U = ctx->knobs.pull_rows == 8 ? 8 : 4;        // rows in flight per lane group
+    const int rows_per_block = (threads / RG_WAVE) * (RG_WAVE >> shp.log2L) * U;
     const int grid = (int)rg_max64(1, rg_min64(rg_div_up(n_upper, rows_per_block), blocks));
     const int tok = rg_prof_begin(ctx, RG_K_CACHE_FILL, s);
-    if (vec == 4)
-        k_prefetch_pull<4><<<grid, threads, 0, s>>>(list, pctl, seg_off, src, src_stride, dst, dst_stride, dst_rows, shp.cpr, shp.log2L, shp.tail);
-    else if (vec == 2)
-        k_prefetch_pull<2><<<grid, threads, 0, s>>>(list, pctl, seg_off, src, src_stride, dst, dst_stride, dst_rows, shp.cpr, shp.log2L, shp.tail);
-    else
-        k_prefetch_pull<1><<<grid, threads, 0, s>>>(list, pctl, seg_off, src, src_stride, dst, dst_stride, dst_rows, shp.cpr, shp.log2L, shp.tail);
+#define RG_LAUNCH_PULL(V, UU)                                                                                          \
+    k_prefetch_pull<V, UU><<<grid, threads, 0, s>>>(list, pctl, seg_off, src, src_stride, dst, dst_stride, dst_rows, shp.cpr, \
+                                                    shp.log2L, shp.tail)
+    if (vec == 4) { if (U == 8) RG_LAUNCH_PULL(4, 8); else RG_LAUNCH_PULL(4, 4); }
+    else if (vec == 2) RG_LAUNCH_PULL(2, 4);
+    else RG_LAUNCH_PULL(1, 4);
+#undef RG_LAUNCH_PULL
     rg_prof_end(ctx, tok, s);
     RG_LAUNCH_CHECK(ctx, "k_prefetch_pull");
     return RG_OK;

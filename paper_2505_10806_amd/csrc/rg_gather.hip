@@ -191,7 +191,7 @@ __global__ void __launch_bounds__(256) k_gather_hbm(const uint32_t* __restrict__
 
 // Rows whose source is the remote store: walks the compacted miss list.
 template <int VEC, int U>
-__global__ void __launch_bounds__(256) k_gather_miss(const int32_t* __restrict__ miss_list,
+__global__ void __launch_bounds__(1024) k_gather_miss(const int32_t* __restrict__ miss_list,
                                                     const uint32_t* __restrict__ gctl, const float* __restrict__ remote_store,
                                                     int64_t remote_stride, float* __restrict__ out, int64_t out_stride,
                                                     int cpr, int log2L, int tail) {
@@ -298,7 +298,7 @@ rg_status launch_copies(rg_ctx* ctx, const GatherScratch& scr, int64_t n, const 
     rg_prof_end(ctx, tok, sh);
     RG_LAUNCH_CHECK(ctx, "k_gather_hbm");
 
-    const int miss_threads = 256;
+    const int miss_threads = ctx->knobs.miss_threads;
     const int miss_rows_per_block = (miss_threads / RG_WAVE) * (RG_WAVE >> shp.log2L) * U;
     const int miss_grid = (int)rg_max64(1, rg_min64(rg_div_up(n, miss_rows_per_block), ctx->knobs.miss_blocks));
     tok = timed ? rg_prof_begin(ctx, RG_K_GATHER_MISS, sm) : -1;

@@ -24,9 +24,11 @@ struct RgProfSpan {
 struct RgKnobs {
     int gather_unroll = 2;            // RG_GATHER_UNROLL: 16-byte chunks in flight per lane of the HBM gather (2, 4 or 8)
     int gather_blocks_per_cu = 0;     // RG_GATHER_BLOCKS_PER_CU: grid cap of the HBM gather (0 = one step per wavefront)
-    int pull_blocks = 48;             // RG_PULL_BLOCKS / RG_PULL_THREADS: grid of the host-link pull kernels
-    int pull_threads = 256;
-    int miss_blocks = 192;            // RG_MISS_BLOCKS: grid of the miss-row kernel
+    int pull_blocks = 16;             // RG_PULL_BLOCKS / RG_PULL_THREADS: grid of the host-link pull kernels
+    int pull_threads = 1024;
+    int pull_rows = 4;                // RG_PULL_ROWS: rows in flight per lane group of the pull kernel (4 or 8)
+    int miss_blocks = 192;            // RG_MISS_BLOCKS / RG_MISS_THREADS: grid of the miss-row kernel
+    int miss_threads = 256;
 };
 
 struct rg_ctx {

@@ -53,10 +53,16 @@ static inline RgRowShape rg_row_shape(int32_t dim, int vec) {
     return s;
 }
 
-// Kernels that read rows over the host link (cache pulls, miss rows) wait on the link, not on the GPU: a few hundred
-// wavefronts keep it busy (48 x 256 threads, 4 rows in flight per lane group), and a small grid leaves the wave slots
-// of every CU to the HBM kernels that run beside them.  Measured on the pull kernel: 2048 workgroups -> the gathers
-// beside it take 153 ms per epoch, 48 -> 79 ms, link rate unchanged.  Miss rows go through one more dependent lookup
-// per step than the pulls and need more wavefronts to fill the link (swept on the 602-dim workload: 48 workgroups
-// 46 GB/s, 192 -> 51, 384 -> 53, where the HBM kernel beside them is starved for as long as the miss kernel runs);
-// 192 keeps both moving.  The grids are RgKnobs::pull_blocks x pull_threads and RgKnobs::miss_blocks x 256.
+// Kernels that read rows over the host link (cache pulls, miss rows) wait on the link, not on the GPU.  A compute unit
+// that hosts their wavefronts is all but lost to the HBM kernels running beside them: loads that stay outstanding for
+// microseconds fill the unit's vector-memory queues, so a gather workgroup placed there crawls.  What matters is
+// therefore the number of compute units the link kernels touch, not their number of wavefronts: few, large workgroups.
+// Measured on the stress workload (pull grid -> link rate, HBM gather beside it as a fraction of peak, whole epoch):
+//   48 x 256 threads   53.0 GB/s   0.616   1354 batches/s
+//   16 x 1024          55.8 GB/s   0.656   1407 batches/s      (default)
+//    8 x 1024          47.3 GB/s   0.677   1292 batches/s      (too few loads in flight for the link)
+//    8 x 1024, 8 rows in flight per lane group   51.1 GB/s   0.675   1338 batches/s
+// against 56.9 GB/s for the pull kernel alone, 57.3 GB/s for a plain runtime copy from pinned memory and 0.69 for
+// the gather alone.  Miss rows go through one more dependent lookup per step than the pulls and need more wavefronts
+// to fill the link (swept on the 602-dim workload: 48 workgroups of 256 threads 46 GB/s, 192 -> 51, 384 -> 53).
+// The grids are RgKnobs::pull_blocks x pull_threads and RgKnobs::miss_blocks x miss_threads.

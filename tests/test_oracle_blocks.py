@@ -132,7 +132,7 @@ def _philox_py(ctr, key):
     return c
 
 
-def _blocks_py(adj, seeds, fanouts, seed, epoch):
+def _blocks_py(adj, seeds, fanouts, seed, epoch, first_seen=False):
     key = (seed & 0xFFFFFFFF, seed >> 32)
     frontier = list(seeds)
     tiers, hops = [list(seeds)], []
@@ -151,7 +151,10 @@ def _blocks_py(adj, seeds, fanouts, seed, epoch):
                     t = (r * (j + 1)) >> 32
                     chosen.append(j if t in chosen else t)
             rows.append([row[c] for c in chosen])
-        new = sorted(set(u for r in rows for u in r) - set(frontier))
+        if first_seen:          # the order in which the hop's neighbour lists first name a node (dict keeps insertion order)
+            new = list(dict.fromkeys(u for r in rows for u in r if u not in set(frontier)))
+        else:
+            new = sorted(set(u for r in rows for u in r) - set(frontier))
         frontier = frontier + new
         tiers.append(new)
         hops.append(rows)
@@ -173,9 +176,11 @@ def test_blocks_against_bruteforce_python():
     rp[1:] = np.cumsum([len(adj[v]) for v in range(n)])
     ci = np.array([u for v in range(n) for u in adj[v]], dtype=np.int32)
     seeds = [7, 0, 33, 59]
-    for fanouts, seed, epoch in [((3, 2), 5, 0), ((5, 5, 1), (1 << 40) + 3, 9), ((2,), 0, 1)]:
-        frontier, tiers, hops = _blocks_py(adj, seeds, fanouts, seed, epoch)
-        b = oracle.sample_blocks(rp, ci, seeds, fanouts, seed, epoch)
+    for fanouts, seed, epoch, first_seen in [((3, 2), 5, 0, False), ((5, 5, 1), (1 << 40) + 3, 9, False), ((2,), 0, 1, False),
+                                             ((3, 2), 5, 0, True), ((5, 5, 1), (1 << 40) + 3, 9, True), ((4, 4, 4, 4), 7, 2, True)]:
+        frontier, tiers, hops = _blocks_py(adj, seeds, fanouts, seed, epoch, first_seen)
+        b = oracle.sample_blocks(rp, ci, seeds, fanouts, seed, epoch,
+                                 oracle.ORDER_FIRST_SEEN if first_seen else oracle.ORDER_ASCENDING)
         assert b.nodes.tolist() == frontier
         for t, tier in enumerate(tiers):
             assert b.nodes[b.tier_off[t]:b.tier_off[t + 1]].tolist() == tier
@@ -215,18 +220,20 @@ def _graph_and_query(draw):
     fanouts = tuple(draw(st.lists(st.integers(0, 6), min_size=1, max_size=3)))
     seed = draw(st.integers(0, 2 ** 64 - 1))
     epoch = draw(st.integers(0, 2 ** 32 - 1))
-    return n, adj, seeds, fanouts, seed, epoch
+    first_seen = draw(st.booleans())
+    return n, adj, seeds, fanouts, seed, epoch, first_seen
 
 
 @settings(max_examples=150, deadline=None, derandomize=True, suppress_health_check=list(HealthCheck))
 @given(_graph_and_query())
 def test_blocks_against_bruteforce_on_generated_graphs(case):
-    n, adj, seeds, fanouts, seed, epoch = case
+    n, adj, seeds, fanouts, seed, epoch, first_seen = case
     rp = np.zeros(n + 1, dtype=np.int64)
     rp[1:] = np.cumsum([len(adj[v]) for v in range(n)])
     ci = np.array([u for v in range(n) for u in adj[v]], dtype=np.int32)
-    frontier, tiers, hops = _blocks_py(adj, seeds, fanouts, seed, epoch)
-    b = oracle.sample_blocks(rp, ci, np.array(seeds, dtype=np.int32), fanouts, seed, epoch)
+    frontier, tiers, hops = _blocks_py(adj, seeds, fanouts, seed, epoch, first_seen)
+    b = oracle.sample_blocks(rp, ci, np.array(seeds, dtype=np.int32), fanouts, seed, epoch,
+                             oracle.ORDER_FIRST_SEEN if first_seen else oracle.ORDER_ASCENDING)
     assert b.nodes.tolist() == frontier
     assert b.tier_off.tolist() == np.concatenate([[0], np.cumsum([len(t) for t in tiers])]).tolist()
     for h, rows in enumerate(hops):
@@ -234,3 +241,55 @@ def test_blocks_against_bruteforce_on_generated_graphs(case):
         assert b.indptr[h].tolist() == np.concatenate([[0], np.cumsum([len(r) for r in rows])]).tolist()
         pos = {v: i for i, v in enumerate(b.nodes.tolist())}
         assert b.nbr_local[h].tolist() == [pos[u] for r in rows for u in r]
+
+
+# ---- the second canonical node order: new nodes in the order in which the hop's neighbour list first names them
+
+@pytest.mark.parametrize("fanouts", [(10, 5), (3, 3, 3), (25,), (0, 4)])
+def test_first_seen_order_invariants(tiny_graph, fanouts):
+    """Same tiers as sets and the same draw per node as the ascending order; inside a tier the nodes appear in the
+    order of their first mention: walking nbr_local in edge order, every position beyond the old frontier that has
+    not been met yet is exactly the next free position."""
+    rp, ci = tiny_graph
+    n = rp.size - 1
+    rng = np.random.default_rng(15)
+    seeds = rng.choice(n, size=64, replace=False).astype(np.int32)
+    a = oracle.sample_blocks(rp, ci, seeds, fanouts, seed=11, epoch=2)
+    f = oracle.sample_blocks(rp, ci, seeds, fanouts, seed=11, epoch=2, node_order=oracle.ORDER_FIRST_SEEN)
+    H = len(fanouts)
+    assert f.tier_off.tolist() == a.tier_off.tolist()
+    assert f.nodes[:seeds.size].tolist() == seeds.tolist()
+    assert len(set(f.nodes.tolist())) == f.nodes.size
+
+    def rows(blk, h):
+        n_h = int(blk.tier_off[h + 1])
+        return {int(blk.nodes[i]): blk.nbr[h][blk.indptr[h][i]:blk.indptr[h][i + 1]].tolist() for i in range(n_h)}
+    reordered = False
+    for h in range(H):
+        lo, hi = int(f.tier_off[h + 1]), int(f.tier_off[h + 2])
+        tier_f, tier_a = f.nodes[lo:hi], a.nodes[lo:hi]
+        assert sorted(tier_f.tolist()) == tier_a.tolist()                 # the same nodes, another order
+        reordered = reordered or tier_f.tolist() != tier_a.tolist()
+        assert rows(f, h) == rows(a, h)                                    # a node's draw does not depend on the order
+        assert np.array_equal(f.nodes[:hi][f.nbr_local[h]], f.nbr[h])      # relabelling is consistent
+        next_free = lo
+        for p in f.nbr_local[h].tolist():
+            if p >= next_free:
+                assert p == next_free
+                next_free += 1
+        assert next_free == hi
+    assert reordered or sum(fanouts) == 0
+
+
+def test_first_seen_order_with_full_fanout_is_queue_bfs_order(tiny_graph):
+    """Every neighbour taken, one seed: new nodes are discovered by scanning the frontier in order and each row in
+    CSR order, which is the visiting order of a textbook queue BFS (scipy's breadth_first_order)."""
+    from scipy.sparse.csgraph import breadth_first_order
+    rp, ci = tiny_graph
+    n = rp.size - 1
+    a = sp.csr_matrix((np.ones(ci.size), ci, rp), shape=(n, n))
+    for source in (5, 900):
+        b = oracle.sample_blocks(rp, ci, np.array([source], dtype=np.int32), (-1, -1, -1), 1, 0, oracle.ORDER_FIRST_SEEN)
+        order = breadth_first_order(a, source, directed=True, return_predecessors=False)
+        assert b.nodes.size > 50
+        assert b.nodes.tolist() == order[:b.nodes.size].tolist()

@@ -38,6 +38,8 @@ MUTANTS = [
     ("blocks_hop_stream", "(uint32_t)v, (uint32_t)h, d, k, pos)", "(uint32_t)v, 0u, d, k, pos)"),
     ("blocks_tier_not_deduplicated", "if (e == 0 || fresh[e] != fresh[e - 1]) fresh[n_unique++] = fresh[e];", "fresh[n_unique++] = fresh[e];"),
     ("blocks_tier_includes_members", "if (where[nbr[e]] < 0) fresh[n_fresh++] = nbr[e];", "fresh[n_fresh++] = nbr[e];"),
+    ("blocks_first_seen_keeps_repeats", "if (where[u] < 0) {\n                    nodes[n] = u;\n                    where[u] = n;", "if (where[u] < 0 || where[u] >= n_h) {\n                    nodes[n] = u;\n                    where[u] = n;"),
+    ("blocks_first_seen_walks_backwards", "for (int64_t e = 0; e < E; ++e) {\n                int32_t u = nbr[e];", "for (int64_t e = E - 1; e >= 0; --e) {\n                int32_t u = nbr[e];"),
     ("blocks_row_offset", "col_idx[row_ptr[v] + pos[t]]", "col_idx[row_ptr[v + 1] - 1 - pos[t]]"),
     ("histogram_skips_repeats", "counts[nodes[i]] += 1u;", "counts[nodes[i]] = 1u;"),
     ("tophot_ascending_counts", "return x->count > y->count ? -1 : 1;   /* larger count first */", "return x->count < y->count ? -1 : 1;"),
@@ -143,6 +145,19 @@ def _compact_pins(orc, workload):
     for h, k in ((0, 6), (1, 4)):
         want = [int(ci[rp[v] + p]) for p in orc.sample_positions(11, 2, v, h, d, k)]
         assert rows[(h, v)] == want
+    # first-seen node order: same tiers as sets, positions handed out in order of first mention
+    f = orc.sample_blocks(rp, ci, seeds, (6, 4), 11, 2, orc.ORDER_FIRST_SEEN)
+    assert f.tier_off.tolist() == b.tier_off.tolist()
+    for h in range(2):
+        lo, hi = int(f.tier_off[h + 1]), int(f.tier_off[h + 2])
+        assert sorted(f.nodes[lo:hi].tolist()) == b.nodes[lo:hi].tolist()
+        assert np.array_equal(f.nodes[:hi][f.nbr_local[h]], f.nbr[h])
+        next_free = lo
+        for p in f.nbr_local[h].tolist():
+            if p >= next_free:
+                assert p == next_free
+                next_free += 1
+        assert next_free == hi
     # histogram, TopHot, fill, gather, hit curve
     counts = np.zeros(cfg.num_nodes, dtype=np.uint32)
     inputs = []
