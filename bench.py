@@ -207,6 +207,11 @@ def main():
                     help="prefetch with a claim pass over every batch instead of the per-epoch prefetch plan")
     ap.add_argument("--sample-group", type=int, default=8,
                     help="batches sampled by one rg_sample_blocks_group call")
+    ap.add_argument("--histogram", choices=["epoch", "sampled", "batch"], default="epoch",
+                    help="access counts from one LDS-privatised pass over the epoch's id lists, straight from the sampler's "
+                         "membership bitmaps after every group, or one global-atomic pass per batch")
+    ap.add_argument("--node-order", choices=["ascending", "first_seen"], default="ascending",
+                    help="order of the nodes inside a tier of a block")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the extra passes (whole-epoch rate, gather kernel without concurrent pulls, hit curve)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -257,6 +262,7 @@ def main():
         return EpochPipeline(wl, device=dev, two_streams=not args.one_stream, prefetch=prefetch,
                              sampler_streams=args.sampler_streams, double_buffer=(multi_epoch and not args.no_double_buffer),
                              planned_prefetch=not args.no_plan, sample_group=args.sample_group,
+                             histogram=args.histogram, node_order=args.node_order,
                              consumer=None if args.consumer == "none" else args.consumer,
                              queue_depth=args.queue_depth if args.consumer != "none" else 1)
 
@@ -313,6 +319,7 @@ def main():
                    "sampler_streams": args.sampler_streams, "sample_group": args.sample_group,
                    "double_buffered_cache": bool(multi_epoch and not args.no_double_buffer),
                    "planned_prefetch": pipe.planned, "consumer": args.consumer, "queue_depth": pipe.queue_depth,
+                   "histogram": pipe.histogram, "node_order": args.node_order,
                    "GPU_MAX_HW_QUEUES": os.environ.get("GPU_MAX_HW_QUEUES"), "GPU_MAX_HW_QUEUES_set_by": "user" if HWQ_SET_BY_USER else "bench.py"},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": roof["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": roof["frac"],

@@ -169,10 +169,19 @@ RG_API rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t*
  * (num_seeds[g] of them) and writes out[g]; fan-outs, seed and epoch are shared.  The results are
  * exactly those of `group` separate calls; the kernels of a hop take all the batches in one launch
  * (most per-batch kernels are far smaller than the device).  seeds: host array[group] of device
- * pointers; num_seeds: host int32[group]; out: host array[group]. */
+ * pointers; num_seeds: host int32[group]; out: host array[group].
+ * node_order chooses the order of the nodes inside a new tier (Section IV: the precomputed batches
+ * fix "the order of the input nodes"; the paper leaves the order itself open):
+ *   RG_ORDER_ASCENDING   ascending by id (what rg_sample_blocks produces);
+ *   RG_ORDER_FIRST_SEEN  the order in which nbr[h] (frontier order, per node in insertion order) first
+ *                        names them: the order a block-building pass over the sampled edges produces.
+ * Which nodes a tier holds and what every node draws do not depend on the order; nodes, nbr_local
+ * and the order of the rows of later hops do.  rg_access_histogram_epoch needs ascending tiers. */
+#define RG_ORDER_ASCENDING 0
+#define RG_ORDER_FIRST_SEEN 1
 RG_API rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, const int32_t* const* seeds,
                                         const int32_t* num_seeds, const int32_t* fanouts, int32_t num_hops,
-                                        uint64_t seed, uint32_t epoch, rg_blocks* out, void* stream);
+                                        uint64_t seed, uint32_t epoch, int32_t node_order, rg_blocks* out, void* stream);
 
 /* ---- Alg. 1 line 2 / Section IV: access frequency freq(n) -------------------------------
  * counts[v] += number of occurrences of v in nodes[0..n).  counts accumulates over calls
@@ -202,6 +211,18 @@ RG_API rg_status rg_access_histogram_epoch(rg_ctx* ctx, const int32_t* nodes, in
                                            const int32_t* tier_off, int32_t num_batches, int32_t num_hops,
                                            int32_t max_seeds, uint32_t* counts, uint32_t* first_batch,
                                            int64_t num_nodes, void* stream);
+
+/* The same counts without reading any id list (Section IV, offline stage: frequencies are taken as
+ * the batches are precomputed): adds the input-node sets of the `group` batches that the last
+ * rg_sample_blocks / rg_sample_blocks_group call of this context sampled, straight from the
+ * sampler's membership bitmaps: counts[v] += number of those batches whose input nodes contain v.
+ * Works for either node order.  With first_batch != NULL, first_batch[v] = min(first_batch[v],
+ * smallest batch_index[g] over those batches), as rg_access_histogram_epoch records it.
+ * Must follow that sampling call on the same stream, before the context samples again; group and
+ * num_nodes must match it (RG_ERR_STATE otherwise).  batch_index: host int32[group], the batches'
+ * indices within the period (may be NULL when first_batch is NULL). */
+RG_API rg_status rg_access_histogram_sampled(rg_ctx* ctx, int32_t group, const int32_t* batch_index, uint32_t* counts,
+                                             uint32_t* first_batch, int64_t num_nodes, void* stream);
 
 /* ---- Alg. 1 lines 3-4: TopHot + VectorPull -----------------------------------------------
  * Candidates = nodes whose home word is remote and whose count >= 1, ranked by

@@ -19,6 +19,7 @@ RG_FANOUT_ALL = -1
 RG_MAX_HOPS = 8
 RG_MAX_GROUP = 8
 RG_GATHER_TICKETS = 8
+RG_ORDER_ASCENDING, RG_ORDER_FIRST_SEEN = 0, 1
 RG_STATIC_GATHER_MAX_ROWS = 1 << 20
 RG_K_GATHER_HBM, RG_K_GATHER_MISS, RG_K_SAMPLE, RG_K_HISTOGRAM, RG_K_CACHE_FILL, RG_K_AGGREGATE = range(6)
 
@@ -74,7 +75,8 @@ def _load():
     L.rg_sample_blocks.argtypes = [c_p, ctypes.POINTER(rg_csr), c_p, c_i32, c_p, c_i32, c_u64, c_u32,
                                    ctypes.POINTER(rg_blocks), c_p]
     L.rg_sample_blocks_group.argtypes = [c_p, ctypes.POINTER(rg_csr), c_i32, ctypes.POINTER(c_p), ctypes.POINTER(c_i32), c_p,
-                                         c_i32, c_u64, c_u32, ctypes.POINTER(rg_blocks), c_p]
+                                         c_i32, c_u64, c_u32, c_i32, ctypes.POINTER(rg_blocks), c_p]
+    L.rg_access_histogram_sampled.argtypes = [c_p, c_i32, c_p, c_p, c_p, c_i64, c_p]
     L.rg_access_histogram.argtypes = [c_p, c_p, c_i64, c_p, c_p, c_i64, c_p]
     L.rg_access_histogram_epoch.argtypes = [c_p, c_p, c_i64, c_p, c_i32, c_i32, c_i32, c_p, c_p, c_i64, c_p]
     L.rg_plan_prefetch.argtypes = [c_p, ctypes.POINTER(rg_cache), c_p, c_p, c_i64, ctypes.POINTER(rg_prefetch_plan), c_p]
@@ -94,7 +96,7 @@ def _load():
     L.rg_profile_reset.argtypes = [c_p]
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group",
-                 "rg_access_histogram", "rg_access_histogram_epoch", "rg_build_cache", "rg_cache_hit_curve",
+                 "rg_access_histogram", "rg_access_histogram_epoch", "rg_access_histogram_sampled", "rg_build_cache", "rg_cache_hit_curve",
                  "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_prefetch_planned", "rg_gather_features",
                  "rg_gather_features_static", "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable",
                  "rg_profile_reset", "rg_profile_read"):
@@ -106,7 +108,7 @@ _lib = _load()
 
 EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "rg_reserve", "rg_epoch_schedule",
                     "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group", "rg_access_histogram",
-                    "rg_access_histogram_epoch",
+                    "rg_access_histogram_epoch", "rg_access_histogram_sampled",
                     "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_plan_prefetch",
                     "rg_prefetch_planned", "rg_gather_features", "rg_gather_features_static", "rg_gather_prepare",
                     "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
@@ -184,7 +186,7 @@ class Context:
                                           ctypes.byref(out.c_struct), _stream_handle(stream)))
 
     # -- rg_sample_blocks_group
-    def sample_blocks_group(self, csr, seeds, fanouts, seed, epoch, outs, stream=None):
+    def sample_blocks_group(self, csr, seeds, fanouts, seed, epoch, outs, stream=None, node_order=RG_ORDER_ASCENDING):
         """seeds: list of int32 cuda tensors (one per batch); outs: list of BlockBuffers of the same length."""
         g = len(seeds)
         if g != len(outs) or not 1 <= g <= RG_MAX_GROUP:
@@ -193,8 +195,12 @@ class Context:
         nums = (c_i32 * g)(*[t.numel() for t in seeds])
         structs = (rg_blocks * g)(*[o.c_struct for o in outs])
         fo = (c_i32 * len(fanouts))(*[int(f) for f in fanouts])
-        self._check(_lib.rg_sample_blocks_group(self._h, ctypes.byref(csr.c_struct), g, ptrs, nums, fo, len(fanouts),
-                                                int(seed), int(epoch), structs, _stream_handle(stream)))
+        status = _lib.rg_sample_blocks_group(self._h, ctypes.byref(csr.c_struct), g, ptrs, nums, fo, len(fanouts),
+                                             int(seed), int(epoch), int(node_order), structs, _stream_handle(stream))
+        if status == RG_ERR_CAPACITY:      # the required sizes came back in the structs (the per-hop arrays are shared)
+            for o, st in zip(outs, structs):
+                o.c_struct.nodes_cap = st.nodes_cap
+        self._check(status)
 
     # -- rg_access_histogram
     def access_histogram(self, nodes, n, counts, n_dev=None, stream=None):
@@ -202,6 +208,13 @@ class Context:
                                              _ptr(n_dev, torch.int32, "cuda", "n_dev"),
                                              _ptr(counts, torch.int32, "cuda", "counts"), counts.numel(),
                                              _stream_handle(stream)))
+
+    # -- rg_access_histogram_sampled
+    def access_histogram_sampled(self, group, counts, batch_index=None, first_batch=None, stream=None):
+        idx = None if batch_index is None else (c_i32 * group)(*[int(b) for b in batch_index])
+        self._check(_lib.rg_access_histogram_sampled(self._h, int(group), idx, _ptr(counts, torch.int32, "cuda", "counts"),
+                                                     _ptr(first_batch, torch.int32, "cuda", "first_batch"), counts.numel(),
+                                                     _stream_handle(stream)))
 
     # -- rg_access_histogram_epoch
     def access_histogram_epoch(self, arena, tier_offs, num_batches, num_hops, max_seeds, counts, first_batch=None,

@@ -37,7 +37,10 @@ rg_status rg_ensure(rg_ctx* ctx, RgBuf& buf, size_t bytes, bool zero_new) {
                             hipGetErrorString(e));
     }
     if (zero_new) {
+        // the fill runs on the null stream, which streams created as non-blocking do not wait for: finish it here,
+        // before a kernel on such a stream can touch the buffer
         RG_HIP(ctx, hipMemset(p, 0, want));
+        RG_HIP(ctx, hipDeviceSynchronize());
     }
     buf.p = p;
     buf.bytes = want;
@@ -132,7 +135,7 @@ void rg_destroy(rg_ctx* ctx) {
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
-    RgBuf* bufs[] = {&ctx->visited, &ctx->fresh, &ctx->pos, &ctx->chunk_sum, &ctx->row_start, &ctx->row_deg, &ctx->sched_keys, &ctx->sched_ids,
+    RgBuf* bufs[] = {&ctx->visited, &ctx->fresh, &ctx->pos, &ctx->chunk_sum, &ctx->row_start, &ctx->row_deg, &ctx->first_key, &ctx->sched_keys, &ctx->sched_ids,
                      &ctx->topk_ctl, &ctx->topk_blk, &ctx->topk_caps, &ctx->pf_list, &ctx->pf_ctl, &ctx->plan_cursor, &ctx->gather_src, &ctx->miss_list,
                      &ctx->gather_ctl};
     for (RgBuf* b : bufs)

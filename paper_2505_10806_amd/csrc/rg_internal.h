@@ -44,6 +44,9 @@ struct rg_ctx {
     RgBuf chunk_sum;    // int32[] per-256-node chunk edge counts / bitmap block counts
     RgBuf row_start;    // int64[max_frontier] adjacency row start of every frontier node (current hop)
     RgBuf row_deg;      // int32[max_frontier] its degree
+    RgBuf first_key;    // int32[N] per batch, first-seen node order only (see SampleScratch)
+    int last_sample_group = 0;     // batches of the last completed sampling call: their `visited` bitmaps are the batches'
+    int64_t last_sample_nodes = 0; // input-node sets (rg_access_histogram_sampled), on graphs of this many nodes
     bool sampler_dirty = false;   // a sampling call was cut short by an error: `fresh` may hold stale bits
     // schedule scratch
     RgBuf sched_keys;   // uint64[npad]
@@ -82,7 +85,8 @@ rg_status rg_check_device_readable(rg_ctx* ctx, const void* p, const char* what)
 rg_status rg_gather_reserve(rg_ctx* ctx, int64_t rows);
 // Sizes the sampler scratch for `group` batches side by side on a graph of num_nodes nodes with cumulative
 // frontiers of up to max_frontier nodes (what rg_sample_blocks_group would otherwise grow on demand).
-rg_status rg_sampler_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int group);
+rg_status rg_sampler_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int group, int64_t max_edges = 0,
+                             bool first_seen = false);
 // Resolves the device address of the file-scope gather scratch for ctx->device (the device must be current).
 rg_status rg_gather_static_init(rg_ctx* ctx);
 // Profiling brackets (no-ops unless profiling is enabled).

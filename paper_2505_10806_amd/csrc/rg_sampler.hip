@@ -124,6 +124,8 @@ struct SampleScratch {
     int32_t* chunk_sum;               // [group][chunk_stride]
     int64_t* row_start;               // [group][frontier_stride]
     int32_t* row_deg;                 // [group][frontier_stride]
+    int32_t* first_key;               // [group][num_nodes], first-seen order only: 0x7FFFFFFF - (index of the first edge of
+                                      // the current hop that names the node), 0 = not named (kept all-zero between hops)
     int64_t words, num_nodes, chunk_stride, frontier_stride;
 };
 
@@ -217,8 +219,19 @@ __device__ __forceinline__ void rg_mark_fresh(int32_t u, const uint32_t* __restr
     atomicOr(&fresh[w], bit);
 }
 
+// First-seen order: instead of a bit, remember the first edge of the hop that names a node outside the frontier.
+__device__ __forceinline__ void rg_note_first_edge(int32_t u, int64_t e, const uint32_t* __restrict__ visited,
+                                                   int32_t* __restrict__ first_key) {
+    const uint32_t w = (uint32_t)u >> 5, bit = 1u << (u & 31);
+    if (visited[w] & bit) return;
+    const int32_t key = 0x7FFFFFFF - (int32_t)e;
+    if (first_key[u] >= key) return;                  // a stale read only costs a redundant atomic
+    atomicMax(&first_key[u], key);
+}
+
 // General sampler: one wavefront (= one 64-thread workgroup) per frontier node, any fan-out up to
 // RG_MAX_FANOUT.  The Floyd set lives in LDS; step i tests membership of t with all lanes.
+template <bool FIRST_SEEN>
 __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int32_t* __restrict__ col_idx, const SampleGroup G,
                                                             const SampleScratch S, int fanout, uint32_t hop, uint32_t k0,
                                                             uint32_t k1, uint32_t epoch) {
@@ -234,6 +247,7 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int32_t* __re
     const int32_t* __restrict__ row_deg = S.row_deg + g * S.frontier_stride;
     const uint32_t* __restrict__ visited = S.visited + g * S.words;
     uint32_t* __restrict__ fresh = S.fresh + g * S.words;
+    int32_t* __restrict__ first_key = FIRST_SEEN ? S.first_key + g * S.num_nodes : nullptr;
     const int lane = threadIdx.x;
     for (int64_t i = blockIdx.x; i < n_h; i += gridDim.x) {
         const int32_t v = nodes[i];
@@ -245,7 +259,7 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int32_t* __re
             for (int64_t t = lane; t < deg; t += RG_WAVE) {
                 const int32_t u = col_idx[start + t];
                 nbr[base + t] = u;
-                rg_mark_fresh(u, visited, fresh);
+                if (FIRST_SEEN) rg_note_first_edge(u, base + t, visited, first_key); else rg_mark_fresh(u, visited, fresh);
             }
             continue;
         }
@@ -271,7 +285,7 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int32_t* __re
         for (int t = lane; t < k; t += RG_WAVE) {
             const int32_t u = col_idx[start + (int64_t)chosen[t]];
             nbr[base + t] = u;
-            rg_mark_fresh(u, visited, fresh);
+            if (FIRST_SEEN) rg_note_first_edge(u, base + t, visited, first_key); else rg_mark_fresh(u, visited, fresh);
         }
     }
 }
@@ -280,7 +294,7 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int32_t* __re
 // draws (Philox + Floyd entirely in registers), the 256 nodes of a workgroup stage the col_idx offsets
 // of their picks in LDS in output order, then the whole workgroup reads col_idx and writes nbr with
 // consecutive lanes on consecutive output slots.
-template <int KMAX>
+template <int KMAX, bool FIRST_SEEN>
 __global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const int32_t* __restrict__ col_idx, const SampleGroup G,
                                                               const SampleScratch S, int fanout, uint32_t hop, uint32_t k0,
                                                               uint32_t k1, uint32_t epoch) {
@@ -294,6 +308,7 @@ __global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const int32_t* __r
     const int32_t* __restrict__ chunk_sum = S.chunk_sum + g * S.chunk_stride;
     const uint32_t* __restrict__ visited = S.visited + g * S.words;
     uint32_t* __restrict__ fresh = S.fresh + g * S.words;
+    int32_t* __restrict__ first_key = FIRST_SEEN ? S.first_key + g * S.num_nodes : nullptr;
     const int64_t i = first + threadIdx.x;
     const int k = fanout;
     // chunk_sum[b] is the exclusive offset of chunk b; the chunk's edge count follows from its successor
@@ -338,7 +353,7 @@ __global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const int32_t* __r
     for (int e = threadIdx.x; e < chunk_edges; e += kChunk) {
         const int32_t u = col_idx[staged[e]];
         nbr[base + e] = u;
-        rg_mark_fresh(u, visited, fresh);
+        if (FIRST_SEEN) rg_note_first_edge(u, base + e, visited, first_key); else rg_mark_fresh(u, visited, fresh);
     }
 }
 
@@ -397,6 +412,72 @@ __global__ void __launch_bounds__(256) k_tier_emit(const SampleGroup G, const Sa
     }
 }
 
+// ---------------------------------------------------------------------------- per hop: new tier in first-seen order
+// Edge e opens a new node when it is the first edge of the hop naming a node outside the frontier.  Ordered
+// compaction over the hop's edge list: per-block counts, the scan of k_scan_tier, then the emit below.
+constexpr int kEdgesPerBlock = 1024;   // 256 threads x 4 consecutive edges
+
+__device__ __forceinline__ bool rg_opens_node(const int32_t* __restrict__ nbr, const int32_t* __restrict__ first_key, int64_t e) {
+    return first_key[nbr[e]] == 0x7FFFFFFF - (int32_t)e;
+}
+
+__global__ void __launch_bounds__(256) k_first_seen_count(const SampleGroup G, const SampleScratch S, int hop) {
+    const int g = blockIdx.y;
+    const int32_t* __restrict__ nbr = G.nbr[g];
+    const int32_t* __restrict__ first_key = S.first_key + g * S.num_nodes;
+    const int64_t n_edges = G.indptr[g][G.tier_off[g][hop + 1]];
+    const int64_t e0 = (int64_t)blockIdx.x * kEdgesPerBlock + threadIdx.x * 4;
+    int c = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (e0 + q < n_edges) c += rg_opens_node(nbr, first_key, e0 + q);
+    c = rg_wave_sum(c);
+    __shared__ int part[4];
+    if (rg_lane() == 0) part[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) S.chunk_sum[g * S.chunk_stride + blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+}
+
+// Appends the opened nodes behind the current frontier in edge order, records their positions, marks them visited
+// and clears their first-edge keys (the array is all-zero again when the hop is done).
+__global__ void __launch_bounds__(256) k_first_seen_emit(const SampleGroup G, const SampleScratch S, int hop) {
+    __shared__ int smem[256 / RG_WAVE + 1];
+    const int g = blockIdx.y;
+    const int32_t* __restrict__ nbr = G.nbr[g];
+    int32_t* __restrict__ first_key = S.first_key + g * S.num_nodes;
+    uint32_t* __restrict__ visited = S.visited + g * S.words;
+    int32_t* __restrict__ nodes = G.nodes[g];
+    int32_t* __restrict__ pos = S.pos + g * S.num_nodes;
+    const int64_t n_edges = G.indptr[g][G.tier_off[g][hop + 1]];
+    const int64_t e0 = (int64_t)blockIdx.x * kEdgesPerBlock + threadIdx.x * 4;
+    if ((int64_t)blockIdx.x * kEdgesPerBlock >= n_edges) return;          // uniform per workgroup
+    int32_t u[4];
+    bool opens[4];
+    int c = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        opens[q] = false;
+        if (e0 + q < n_edges) {
+            u[q] = nbr[e0 + q];
+            opens[q] = first_key[u[q]] == 0x7FFFFFFF - (int32_t)(e0 + q);
+        }
+        c += opens[q];
+    }
+    int total;
+    const int excl = rg_block_excl_scan<256 / RG_WAVE>(c, smem, &total);
+    if (total == 0) return;                                               // uniform
+    int out = G.tier_off[g][hop + 1] + S.chunk_sum[g * S.chunk_stride + blockIdx.x] + excl;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (opens[q]) {
+            nodes[out] = u[q];
+            pos[u[q]] = out;
+            ++out;
+            atomicOr(&visited[(uint32_t)u[q] >> 5], 1u << (u[q] & 31));
+            first_key[u[q]] = 0;                      // only the opening edge's thread touches this entry now
+        }
+}
+
 // nbr_local[e] = position of nbr[e] in the extended frontier; the hop's edge count is indptr[n_h].
 __global__ void __launch_bounds__(256) k_relabel(const SampleGroup G, const SampleScratch S, int hop) {
     const int g = blockIdx.y;
@@ -410,11 +491,50 @@ __global__ void __launch_bounds__(256) k_relabel(const SampleGroup G, const Samp
 }
 
 // Per-batch strides of the scratch slices for a graph of N nodes and frontiers of up to `frontier` nodes.
-void sampler_scratch_shape(int64_t N, int64_t frontier, SampleScratch& S) {
+// max_edges: the largest per-hop edge bound when tiers are built from the edge list (first-seen order), else 0.
+void sampler_scratch_shape(int64_t N, int64_t frontier, int64_t max_edges, SampleScratch& S) {
     S.words = rg_div_up(N, 32);
     S.num_nodes = N;
     S.frontier_stride = rg_max64(frontier, 1);
-    S.chunk_stride = rg_max64(rg_div_up(S.frontier_stride, kChunk), rg_max64(1, rg_div_up(S.words, kWordsPerBlock))) + 2;
+    S.chunk_stride = rg_max64(rg_max64(rg_div_up(S.frontier_stride, kChunk), rg_div_up(max_edges, kEdgesPerBlock)),
+                              rg_max64(1, rg_div_up(S.words, kWordsPerBlock))) + 2;
+    S.first_key = nullptr;
+}
+
+// ---------------------------------------------------------------------------- access counts straight from the bitmaps
+// After the last hop a batch's `visited` bitmap is exactly its input-node set.  One thread takes bitmap word w of
+// every batch of the group, counts for each of the 32 ids in how many of the batches it is set, and adds that to
+// counts[] (and lowers first_batch[] to the earliest of those batches).  No id list is read.
+struct BatchIndices { uint32_t v[kMaxGroup]; };
+
+__global__ void __launch_bounds__(256) k_histogram_bitmaps(const uint32_t* __restrict__ visited, int64_t words, int group,
+                                                           const BatchIndices batch, uint32_t* __restrict__ counts,
+                                                           uint32_t* __restrict__ first_batch, int64_t num_nodes) {
+    for (int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; w < words; w += (int64_t)gridDim.x * blockDim.x) {
+        uint32_t bits[kMaxGroup];
+        uint32_t any = 0u;
+#pragma unroll
+        for (int g = 0; g < kMaxGroup; ++g) {
+            bits[g] = g < group ? visited[g * words + w] : 0u;
+            any |= bits[g];
+        }
+        while (any) {
+            const int j = __ffs(any) - 1;
+            any &= any - 1u;
+            uint32_t c = 0u, first = 0xFFFFFFFFu;
+#pragma unroll
+            for (int g = 0; g < kMaxGroup; ++g)
+                if ((bits[g] >> j) & 1u) {
+                    ++c;
+                    first = batch.v[g] < first ? batch.v[g] : first;
+                }
+            const int64_t v = (w << 5) + j;
+            if (v < num_nodes) {                      // bits beyond the last node are never set; the check costs nothing
+                atomicAdd(&counts[v], c);
+                if (first_batch && first < first_batch[v]) atomicMin(&first_batch[v], first);
+            }
+        }
+    }
 }
 
 int grid_for(int64_t work_items, int per_block, int64_t cap) {
@@ -426,9 +546,9 @@ int grid_for(int64_t work_items, int per_block, int64_t cap) {
 
 }  // namespace
 
-rg_status rg_sampler_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int group) {
+rg_status rg_sampler_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int group, int64_t max_edges, bool first_seen) {
     SampleScratch S;
-    sampler_scratch_shape(num_nodes, max_frontier, S);
+    sampler_scratch_shape(num_nodes, max_frontier, max_edges, S);
     const size_t g = (size_t)group;
     rg_status st;
     if ((st = rg_ensure(ctx, ctx->visited, g * S.words * 4)) != RG_OK) return st;
@@ -438,6 +558,8 @@ rg_status rg_sampler_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontie
     if ((st = rg_ensure(ctx, ctx->chunk_sum, g * S.chunk_stride * 4)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->row_start, g * S.frontier_stride * 8)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->row_deg, g * S.frontier_stride * 4)) != RG_OK) return st;
+    // first-seen order: the first-edge keys must be all-zero between hops, like `fresh`
+    if (first_seen && (st = rg_ensure(ctx, ctx->first_key, g * (size_t)num_nodes * 4, true)) != RG_OK) return st;
     return RG_OK;
 }
 
@@ -481,8 +603,11 @@ rg_status rg_epoch_schedule(rg_ctx* ctx, const int32_t* train_ids, int64_t n, ui
 
 rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, const int32_t* const* seeds,
                                  const int32_t* num_seeds, const int32_t* fanouts, int32_t num_hops, uint64_t seed,
-                                 uint32_t epoch, rg_blocks* out, void* stream) {
+                                 uint32_t epoch, int32_t node_order, rg_blocks* out, void* stream) {
     if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, node_order == RG_ORDER_ASCENDING || node_order == RG_ORDER_FIRST_SEEN,
+               "rg_sample_blocks: node_order = %d is neither RG_ORDER_ASCENDING nor RG_ORDER_FIRST_SEEN", node_order);
+    const bool first_seen = node_order == RG_ORDER_FIRST_SEEN;
     RG_REQUIRE(ctx, group >= 1 && group <= RG_MAX_GROUP, "rg_sample_blocks: group = %d not in [1,%d]", group, RG_MAX_GROUP);
     RG_REQUIRE(ctx, csr && out && fanouts && seeds && num_seeds, "rg_sample_blocks: null argument");
     RG_REQUIRE(ctx, num_hops >= 1 && num_hops <= RG_MAX_HOPS, "rg_sample_blocks: num_hops = %d not in [1,%d]", num_hops, RG_MAX_HOPS);
@@ -532,12 +657,17 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
     RG_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t s = (hipStream_t)stream;
     const int64_t N = csr->num_nodes;
+    int64_t max_edges = 0;
+    if (first_seen)
+        for (int h = 0; h < num_hops; ++h) max_edges = rg_max64(max_edges, eub_max[h]);
     SampleScratch S;
-    sampler_scratch_shape(N, fub_max[num_hops], S);
+    sampler_scratch_shape(N, fub_max[num_hops], max_edges, S);
     const int64_t words = S.words;
     const int tier_blocks = (int)rg_max64(1, rg_div_up(words, kWordsPerBlock));
-    rg_status st = rg_sampler_reserve(ctx, N, fub_max[num_hops], group);
+    ctx->last_sample_group = 0;                       // no membership bitmaps to add until this call has been queued
+    rg_status st = rg_sampler_reserve(ctx, N, fub_max[num_hops], group, max_edges, first_seen);
     if (st != RG_OK) return st;
+    S.first_key = first_seen ? (int32_t*)ctx->first_key.p : nullptr;
     S.visited = (uint32_t*)ctx->visited.p;
     S.fresh = (uint32_t*)ctx->fresh.p;
     S.pos = (int32_t*)ctx->pos.p;
@@ -564,6 +694,11 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
         if (ctx->sampler_dirty) {        // an earlier call stopped between a draw kernel and its tier emit
             k_clear_words<<<(int)rg_div_up(fresh_words, 256), 256, 0, s>>>(S.fresh, fresh_words);
             RG_LAUNCH_CHECK(ctx, "k_clear_words");
+            const int64_t key_words = (int64_t)(ctx->first_key.bytes / 4);
+            if (key_words > 0) {
+                k_clear_words<<<(int)rg_div_up(key_words, 256), 256, 0, s>>>((uint32_t*)ctx->first_key.p, key_words);
+                RG_LAUNCH_CHECK(ctx, "k_clear_words");
+            }
         }
         ctx->sampler_dirty = true;       // cleared again when every launch of this call has been queued
         k_clear_words<<<(int)rg_div_up(visited_words, 256), 256, 0, s>>>(S.visited, visited_words);
@@ -596,24 +731,39 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
         if (F >= 1 && F <= 32 && csr->num_edges < (1ll << 32)) {
             const int kmax = F <= 8 ? 8 : (F <= 16 ? 16 : 32);
             const size_t lds = (size_t)kChunk * F * sizeof(uint32_t);
-#define RG_LAUNCH_FAST(KM)                                                                                            \
-    k_hop_sample_thread<KM><<<dim3(count_blocks, ug), kChunk, lds, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch)
-            if (kmax == 8) RG_LAUNCH_FAST(8); else if (kmax == 16) RG_LAUNCH_FAST(16); else RG_LAUNCH_FAST(32);
+#define RG_LAUNCH_FAST(KM, FS)                                                                                        \
+    k_hop_sample_thread<KM, FS><<<dim3(count_blocks, ug), kChunk, lds, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch)
+            if (first_seen) { if (kmax == 8) RG_LAUNCH_FAST(8, true); else if (kmax == 16) RG_LAUNCH_FAST(16, true); else RG_LAUNCH_FAST(32, true); }
+            else { if (kmax == 8) RG_LAUNCH_FAST(8, false); else if (kmax == 16) RG_LAUNCH_FAST(16, false); else RG_LAUNCH_FAST(32, false); }
 #undef RG_LAUNCH_FAST
         } else {
             const unsigned sample_blocks = (unsigned)grid_for(fub_max[h], 1, (int64_t)ctx->num_cus * 64);
-            k_hop_sample_wave<<<dim3(sample_blocks, ug), RG_WAVE, 0, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch);
+            if (first_seen)
+                k_hop_sample_wave<true><<<dim3(sample_blocks, ug), RG_WAVE, 0, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch);
+            else
+                k_hop_sample_wave<false><<<dim3(sample_blocks, ug), RG_WAVE, 0, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch);
         }
         rg_prof_end(ctx, tok, s);
         RG_LAUNCH_CHECK(ctx, "k_hop_sample");
 
-        // new tier: count fresh bits per block, scan, emit ascending
-        k_tier_count<<<dim3((unsigned)tier_blocks, ug), 256, 0, s>>>(S);
-        RG_LAUNCH_CHECK(ctx, "k_tier_count");
-        k_scan_tier<<<dim3(1, ug), 1024, 0, s>>>(G, S, h, tier_blocks);
-        RG_LAUNCH_CHECK(ctx, "k_scan_tier");
-        k_tier_emit<<<dim3((unsigned)tier_blocks, ug), 256, 0, s>>>(G, S, h);
-        RG_LAUNCH_CHECK(ctx, "k_tier_emit");
+        if (first_seen) {
+            // new tier: edges that open a node, counted per block of the edge list, scanned, emitted in edge order
+            const int fs_blocks = (int)rg_max64(1, rg_div_up(eub_max[h], kEdgesPerBlock));
+            k_first_seen_count<<<dim3((unsigned)fs_blocks, ug), 256, 0, s>>>(G, S, h);
+            RG_LAUNCH_CHECK(ctx, "k_first_seen_count");
+            k_scan_tier<<<dim3(1, ug), 1024, 0, s>>>(G, S, h, fs_blocks);
+            RG_LAUNCH_CHECK(ctx, "k_scan_tier");
+            k_first_seen_emit<<<dim3((unsigned)fs_blocks, ug), 256, 0, s>>>(G, S, h);
+            RG_LAUNCH_CHECK(ctx, "k_first_seen_emit");
+        } else {
+            // new tier: count fresh bits per block, scan, emit ascending
+            k_tier_count<<<dim3((unsigned)tier_blocks, ug), 256, 0, s>>>(S);
+            RG_LAUNCH_CHECK(ctx, "k_tier_count");
+            k_scan_tier<<<dim3(1, ug), 1024, 0, s>>>(G, S, h, tier_blocks);
+            RG_LAUNCH_CHECK(ctx, "k_scan_tier");
+            k_tier_emit<<<dim3((unsigned)tier_blocks, ug), 256, 0, s>>>(G, S, h);
+            RG_LAUNCH_CHECK(ctx, "k_tier_emit");
+        }
 
         if (any_local && eub_max[h] > 0) {
             k_relabel<<<dim3((unsigned)grid_for(eub_max[h], 256, (int64_t)ctx->num_cus * 16), ug), 256, 0, s>>>(G, S, h);
@@ -621,13 +771,41 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
         }
     }
     ctx->sampler_dirty = false;
+    ctx->last_sample_group = group;
+    ctx->last_sample_nodes = N;
+    return RG_OK;
+}
+
+rg_status rg_access_histogram_sampled(rg_ctx* ctx, int32_t group, const int32_t* batch_index, uint32_t* counts,
+                                      uint32_t* first_batch, int64_t num_nodes, void* stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, group >= 1 && group <= RG_MAX_GROUP, "rg_access_histogram_sampled: group = %d not in [1,%d]", group, RG_MAX_GROUP);
+    RG_REQUIRE(ctx, counts && (batch_index || !first_batch), "rg_access_histogram_sampled: null counts, or first_batch without batch_index");
+    if (ctx->last_sample_group != group || ctx->last_sample_nodes != num_nodes)
+        return rg_set_error(ctx, RG_ERR_STATE, "rg_access_histogram_sampled: the last sampling call of this context covered %d "
+                            "batches on %lld nodes, not %d on %lld", ctx->last_sample_group, (long long)ctx->last_sample_nodes,
+                            group, (long long)num_nodes);
+    BatchIndices batch;
+    for (int g = 0; g < kMaxGroup; ++g) {
+        RG_REQUIRE(ctx, g >= group || !batch_index || batch_index[g] >= 0, "rg_access_histogram_sampled: negative batch index");
+        batch.v[g] = g < group && batch_index ? (uint32_t)batch_index[g] : 0u;
+    }
+    if (num_nodes == 0) return RG_OK;
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t words = rg_div_up(num_nodes, 32);
+    const int tok = rg_prof_begin(ctx, RG_K_HISTOGRAM, s);
+    k_histogram_bitmaps<<<grid_for(words, 256, (int64_t)ctx->num_cus * 16), 256, 0, s>>>((const uint32_t*)ctx->visited.p, words, group,
+                                                                                         batch, counts, first_batch, num_nodes);
+    rg_prof_end(ctx, tok, s);
+    RG_LAUNCH_CHECK(ctx, "k_histogram_bitmaps");
     return RG_OK;
 }
 
 rg_status rg_sample_blocks(rg_ctx* ctx, const rg_csr* csr, const int32_t* seeds, int32_t num_seeds,
                            const int32_t* fanouts, int32_t num_hops, uint64_t seed, uint32_t epoch,
                            rg_blocks* out, void* stream) {
-    return rg_sample_blocks_group(ctx, csr, 1, &seeds, &num_seeds, fanouts, num_hops, seed, epoch, out, stream);
+    return rg_sample_blocks_group(ctx, csr, 1, &seeds, &num_seeds, fanouts, num_hops, seed, epoch, RG_ORDER_ASCENDING, out, stream);
 }
 
 }  // extern "C"

@@ -50,8 +50,9 @@ class _EpochState:
 
 class EpochPipeline:
     def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True,
-                 epoch_histogram=True, sampler_streams=2, double_buffer=False,
-                 queue_depth=1, consumer=None, planned_prefetch=True, sample_group=8, keep_blocks=False):
+                 histogram="epoch", sampler_streams=2, double_buffer=False,
+                 queue_depth=1, consumer=None, planned_prefetch=True, sample_group=8, keep_blocks=False,
+                 node_order="ascending"):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -61,7 +62,17 @@ class EpochPipeline:
         self.max_batches = min(max_batches or self.batches_per_epoch, self.batches_per_epoch)
         # Batches are independent, and most sampler kernels of one batch are far smaller than the GPU: several
         # batches are sampled side by side, each lane with its own stream, context (scratch) and hop buffers.
-        n_lanes = max(1, int(sampler_streams)) if epoch_histogram else 1
+        # node order inside a tier: "ascending" by id, or "first_seen" (the order in which the hop's neighbour list first
+        # names a node).  Access counts: "epoch" = one LDS-privatised pass over all id lists after sampling (needs
+        # ascending tiers), "sampled" = straight from the sampler's membership bitmaps after every group (any order, no
+        # id list read), "batch" = one global-atomic pass per batch.
+        if node_order not in ("ascending", "first_seen") or histogram not in ("epoch", "sampled", "batch"):
+            raise ValueError("node_order must be 'ascending' or 'first_seen'; histogram 'epoch', 'sampled' or 'batch'")
+        if node_order == "first_seen" and histogram == "epoch":
+            histogram = "sampled"
+        self.node_order = B.RG_ORDER_FIRST_SEEN if node_order == "first_seen" else B.RG_ORDER_ASCENDING
+        self.histogram = histogram
+        n_lanes = max(1, int(sampler_streams)) if histogram != "batch" else 1
         if double_buffer:
             n_lanes = max(n_lanes, 2)
         self.n_lanes = n_lanes
@@ -101,12 +112,10 @@ class EpochPipeline:
         # prefetch = pull cached rows batch by batch, in order of first use, on a stream of their own so the
         # host-link transfer overlaps the gathers; otherwise one bulk pull right after TopHot
         self.prefetch = prefetch
-        # one LDS-privatised histogram over the whole epoch instead of one global-atomic pass per batch
-        self.epoch_histogram = epoch_histogram
         self.pf_stream = torch.cuda.Stream(device=device) if prefetch else None
         # planned prefetch: the epoch histogram also records the first batch that needs each node, the selected
         # slots are grouped by that batch once, and the prefetch stream then carries nothing but pulls
-        self.planned = bool(prefetch and planned_prefetch and epoch_histogram)
+        self.planned = bool(prefetch and planned_prefetch and histogram != "batch")
         if self.planned:
             for st in self.states:
                 st.first_batch = torch.empty(cfg.num_nodes, dtype=torch.int32, device=device)
@@ -170,6 +179,8 @@ class EpochPipeline:
         with torch.cuda.stream(head):
             head_ctx.epoch_schedule(self.wl.train_ids, self.wl.seed, epoch, self.order)
             st.counts.zero_()
+            if self.planned:
+                st.first_batch.fill_(-1)
             for _, _, s in lanes[1:]:
                 s.wait_stream(head)
             n_train = self.order.numel()
@@ -185,8 +196,12 @@ class EpochPipeline:
                     for h, (ip, nb, nl) in st.blk.items():
                         bufs.set_hop(h, ip[i], nb[i], nl[i])
                     outs.append(bufs)
-                c.sample_blocks_group(self.csr, seeds_list, cfg.fanouts, self.wl.seed, epoch, outs, stream=s or head)
-                if not self.epoch_histogram:
+                c.sample_blocks_group(self.csr, seeds_list, cfg.fanouts, self.wl.seed, epoch, outs, stream=s or head,
+                                      node_order=self.node_order)
+                if self.histogram == "sampled":           # the group's membership bitmaps go straight into the counts
+                    c.access_histogram_sampled(len(outs), st.counts, batch_index=range(i0, i0 + len(outs)),
+                                               first_batch=st.first_batch, stream=s or head)
+                elif self.histogram == "batch":
                     for i in range(i0, min(i0 + gsz, len(ids))):
                         head_ctx.access_histogram(st.arena[i], self.slot, st.counts, n_dev=st.tier_offs[i, self.H + 1:], stream=head)
             for _, _, s in lanes[1:]:
@@ -195,9 +210,7 @@ class EpochPipeline:
             # queue that stage while the histogram, TopHot and the plan below are still running
             st.sizes_host[:len(ids)].copy_(st.tier_offs[:len(ids)], non_blocking=True)
             st.sizes_ready.record(head)
-            if self.epoch_histogram:
-                if self.planned:
-                    st.first_batch.fill_(-1)
+            if self.histogram == "epoch":
                 head_ctx.access_histogram_epoch(st.arena, st.tier_offs, len(ids), self.H, cfg.batch_size, st.counts,
                                                 first_batch=st.first_batch, stream=head)
             head_ctx.build_cache(st.counts, self.wl.home, None if self.prefetch else self.wl.remote_store, cfg.feat_dim,

@@ -49,10 +49,14 @@ def test_epoch_schedule_empty(ctx):
 
 
 # ------------------------------------------------------------------------------ sampler
-def _run_blocks(B, ctx, csr, seeds_np, fanouts, seed, epoch, bufs=None, with_local=True):
+def _run_blocks(B, ctx, csr, seeds_np, fanouts, seed, epoch, bufs=None, with_local=True, first_seen=False):
     if bufs is None:
         bufs = B.BlockBuffers(csr.num_nodes, csr.num_edges, max(len(seeds_np), 1), fanouts, DEV, with_local=with_local)
-    ctx.sample_blocks(csr, _i32(seeds_np), len(seeds_np), fanouts, seed, epoch, bufs)
+    if first_seen:      # the node order is a parameter of the group call
+        seeds = _i32(seeds_np) if len(seeds_np) else torch.empty(0, dtype=torch.int32, device=DEV)
+        ctx.sample_blocks_group(csr, [seeds], fanouts, seed, epoch, [bufs], node_order=B.RG_ORDER_FIRST_SEEN)
+    else:
+        ctx.sample_blocks(csr, _i32(seeds_np), len(seeds_np), fanouts, seed, epoch, bufs)
     return HipBatch(bufs, len(fanouts))
 
 
@@ -69,18 +73,20 @@ def _handmade_graph(n, p_dense, n_dense, p, rng):
     return rp, ci
 
 
+@pytest.mark.parametrize("first_seen", [False, True])
 @pytest.mark.parametrize("rp_dtype", [torch.int32, torch.int64])
 @pytest.mark.parametrize("fanouts", [(3, 2), (0, 4), (5,), (-1, 2), (-1, -1, -1), (64, 3), (100, 100), (1024,)])
-def test_blocks_handmade_graph(B, ctx, fanouts, rp_dtype):
-    """Dense core (degrees up to ~400) so that large fan-outs still take the Floyd branch."""
-    log(f"[blocks handmade] fanouts={fanouts} rp={rp_dtype}")
+def test_blocks_handmade_graph(B, ctx, fanouts, rp_dtype, first_seen):
+    """Dense core (degrees up to ~400) so that large fan-outs still take the Floyd branch.  Both node orders."""
+    log(f"[blocks handmade] fanouts={fanouts} rp={rp_dtype} first_seen={first_seen}")
+    order = oracle.ORDER_FIRST_SEEN if first_seen else oracle.ORDER_ASCENDING
     rng = np.random.default_rng(17)
     rp, ci = _handmade_graph(500, 0.8, 40, 0.01, rng)
     csr = B.CsrGraph(torch.as_tensor(rp, device=DEV).to(rp_dtype), _i32(ci))
     seeds = np.array([3, 499, 41, 0, 250, 77], dtype=np.int32)
     for seed, epoch in [(5, 0), ((1 << 40) + 9, 7)]:
-        hip = _run_blocks(B, ctx, csr, seeds, fanouts, seed, epoch)
-        orc = oracle.sample_blocks(rp, ci, seeds, fanouts, seed, epoch)
+        hip = _run_blocks(B, ctx, csr, seeds, fanouts, seed, epoch, first_seen=first_seen)
+        orc = oracle.sample_blocks(rp, ci, seeds, fanouts, seed, epoch, order)
         assert_batch_equal(hip, orc, len(fanouts), f"seed={seed} epoch={epoch}")
 
 
@@ -95,30 +101,34 @@ def test_blocks_on_generated_csr(B, ctx):
         rows = [draw(st.lists(st.integers(0, n - 1), max_size=draw(st.sampled_from([0, 3, 8, 45])))) for _ in range(n)]
         seeds = draw(st.lists(st.integers(0, n - 1), max_size=min(n, 12), unique=True))
         fanouts = tuple(draw(st.lists(st.sampled_from([-1, 0, 1, 2, 5, 8, 9, 16, 17, 32, 33, 40]), min_size=1, max_size=3)))
-        return rows, seeds, fanouts, draw(st.integers(0, 2 ** 64 - 1)), draw(st.integers(0, 2 ** 32 - 1)), draw(st.booleans())
+        return (rows, seeds, fanouts, draw(st.integers(0, 2 ** 64 - 1)), draw(st.integers(0, 2 ** 32 - 1)), draw(st.booleans()),
+                draw(st.booleans()))
 
     @settings(max_examples=120, deadline=None, derandomize=True, suppress_health_check=list(HealthCheck))
     @given(case())
     def run(c):
-        rows, seeds, fanouts, seed, epoch, wide = c
+        rows, seeds, fanouts, seed, epoch, wide, first_seen = c
         rp = np.zeros(len(rows) + 1, dtype=np.int64)
         rp[1:] = np.cumsum([len(r) for r in rows])
         ci = np.array([u for r in rows for u in r], dtype=np.int32)
         csr = B.CsrGraph(torch.as_tensor(rp, device=DEV).to(torch.int64 if wide else torch.int32),
                          _i32(ci) if ci.size else torch.empty(0, dtype=torch.int32, device=DEV))
-        hip = _run_blocks(B, ctx, csr, np.array(seeds, dtype=np.int32), fanouts, seed, epoch)
-        orc = oracle.sample_blocks(rp, ci, np.array(seeds, dtype=np.int32), fanouts, seed, epoch)
-        assert_batch_equal(hip, orc, len(fanouts), f"fanouts={fanouts} seeds={seeds}")
+        hip = _run_blocks(B, ctx, csr, np.array(seeds, dtype=np.int32), fanouts, seed, epoch, first_seen=first_seen)
+        orc = oracle.sample_blocks(rp, ci, np.array(seeds, dtype=np.int32), fanouts, seed, epoch,
+                                   oracle.ORDER_FIRST_SEEN if first_seen else oracle.ORDER_ASCENDING)
+        assert_batch_equal(hip, orc, len(fanouts), f"fanouts={fanouts} seeds={seeds} first_seen={first_seen}")
 
     run()
 
 
+@pytest.mark.parametrize("first_seen", [False, True])
 @pytest.mark.parametrize("group", [1, 2, 3, 8])
 @pytest.mark.parametrize("fanouts", [(5, 3), (40, 2), (-1, 4)])
-def test_blocks_group_equals_separate_batches(B, ctx, group, fanouts):
+def test_blocks_group_equals_separate_batches(B, ctx, group, fanouts, first_seen):
     """One call for several batches (different seed counts, one of them empty) gives each batch exactly the block
     of a call of its own; a smaller group after a larger one on the same context is unaffected by the earlier run."""
-    log(f"[blocks group] group={group} fanouts={fanouts}")
+    log(f"[blocks group] group={group} fanouts={fanouts} first_seen={first_seen}")
+    order = oracle.ORDER_FIRST_SEEN if first_seen else oracle.ORDER_ASCENDING
     rng = np.random.default_rng(group * 10 + len(fanouts))
     rp, ci = _handmade_graph(700, 0.7, 35, 0.015, rng)
     csr = B.CsrGraph(torch.as_tensor(rp, device=DEV), _i32(ci))
@@ -126,14 +136,27 @@ def test_blocks_group_equals_separate_batches(B, ctx, group, fanouts):
     seeds_np = [rng.choice(700, size=n, replace=False).astype(np.int32) for n in sizes]
     outs = [B.BlockBuffers(700, ci.size, max(n, 1), fanouts, DEV) for n in sizes]
     ctx.sample_blocks_group(csr, [_i32(x) if x.size else torch.empty(0, dtype=torch.int32, device=DEV) for x in seeds_np],
-                            fanouts, 99, 4, outs)
+                            fanouts, 99, 4, outs, node_order=B.RG_ORDER_FIRST_SEEN if first_seen else B.RG_ORDER_ASCENDING)
+    # the group's membership bitmaps as access counts, with the first batch that names each node
+    counts = torch.zeros(700, dtype=torch.int32, device=DEV)
+    first = torch.full((700,), -1, dtype=torch.int32, device=DEV)
+    ctx.access_histogram_sampled(group, counts, batch_index=range(10, 10 + group), first_batch=first)
+    counts_orc = np.zeros(700, dtype=np.uint32)
+    first_orc = np.full(700, 0xFFFFFFFF, dtype=np.uint32)
     for g in range(group):
         hip = HipBatch(outs[g], len(fanouts))
-        orc = oracle.sample_blocks(rp, ci, seeds_np[g], fanouts, 99, 4)
+        orc = oracle.sample_blocks(rp, ci, seeds_np[g], fanouts, 99, 4, order)
         assert_batch_equal(hip, orc, len(fanouts), f"batch {g} of {group}")
+        oracle.access_histogram(orc.input_nodes, counts_orc)
+        first_orc[orc.input_nodes] = np.minimum(first_orc[orc.input_nodes], 10 + g)
+    assert np.array_equal(counts.cpu().numpy().view(np.uint32), counts_orc), "counts from the membership bitmaps"
+    assert np.array_equal(first.cpu().numpy().view(np.uint32), first_orc), "first batch from the membership bitmaps"
+    with pytest.raises(B.RgError) as e:                    # a group size that is not the sampled one is refused
+        ctx.access_histogram_sampled(group % 8 + 1, counts)
+    assert e.value.status == B.RG_ERR_STATE
     # a single batch afterwards on the same context
-    hip = _run_blocks(B, ctx, csr, seeds_np[0], fanouts, 7, 1)
-    orc = oracle.sample_blocks(rp, ci, seeds_np[0], fanouts, 7, 1)
+    hip = _run_blocks(B, ctx, csr, seeds_np[0], fanouts, 7, 1, first_seen=first_seen)
+    orc = oracle.sample_blocks(rp, ci, seeds_np[0], fanouts, 7, 1, order)
     assert_batch_equal(hip, orc, len(fanouts), "single batch after the group")
 
 
@@ -338,11 +361,17 @@ def test_prefetch_by_first_use_matches_bulk_fill(B, ctx, planned):
     assert not cache.cache_rows.any()
 
 
+@pytest.mark.parametrize("histogram,node_order", [("epoch", "ascending"), ("sampled", "ascending"), ("sampled", "first_seen"),
+                                                  ("batch", "first_seen")])
 @pytest.mark.parametrize("full_cache", [False, True])
 @pytest.mark.parametrize("double_buffer", [False, True])
-def test_pipeline_epochs_back_to_back(B, double_buffer, full_cache):
+def test_pipeline_epochs_back_to_back(B, double_buffer, full_cache, histogram, node_order):
     """Three epochs through EpochPipeline.run_epochs; with double buffering epoch e+1 is precomputed and its rows
-    pulled while epoch e is served.  Every batch's rows and statistics and every epoch's cache are checked."""
+    pulled while epoch e is served.  Every batch's rows and statistics and every epoch's cache are checked, with the
+    access counts taken by the epoch pass over the id lists, straight from the sampler's bitmaps, or batch by batch,
+    and with either node order."""
+    log(f"[pipeline epochs] double_buffer={double_buffer} full_cache={full_cache} histogram={histogram} node_order={node_order}")
+    order = oracle.ORDER_FIRST_SEEN if node_order == "first_seen" else oracle.ORDER_ASCENDING
     import dataclasses
     from paper_2505_10806_amd.pipeline import EpochPipeline
     base = synth.get_config("tiny")
@@ -352,7 +381,7 @@ def test_pipeline_epochs_back_to_back(B, double_buffer, full_cache):
     rp, ci = host_graph(wl)
     X = wl.features.cpu().numpy()
     home_np, train_np = wl.home.cpu().numpy(), wl.train_ids.cpu().numpy()
-    pipe = EpochPipeline(wl, device=DEV, double_buffer=double_buffer)
+    pipe = EpochPipeline(wl, device=DEV, double_buffer=double_buffer, histogram=histogram, node_order=node_order)
     nb = pipe.batches_per_epoch
     expected = {}
 
@@ -361,11 +390,13 @@ def test_pipeline_epochs_back_to_back(B, double_buffer, full_cache):
         counts = np.zeros(cfg.num_nodes, dtype=np.uint32)
         inputs = []
         for seeds in batches:
-            blk = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, k)
+            blk = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, k, order)
             oracle.access_histogram(blk.input_nodes, counts)
             inputs.append(blk.input_nodes)
         ids, loc = oracle.build_cache(counts, home_np, wl.capacity_rows)
         expected[k] = (inputs, counts, ids, loc)
+        for b, nodes in enumerate(inputs):
+            assert np.array_equal(p.arena[b, :nodes.size].cpu().numpy(), nodes), f"input nodes of epoch {k} batch {b}"
         assert np.array_equal(p.counts.cpu().numpy().view(np.uint32), counts)
         assert np.array_equal(p.cache.cache_ids[:ids.size].cpu().numpy(), ids)
         assert np.array_equal(p.cache.loc.cpu().numpy(), loc)

@@ -68,7 +68,8 @@ def _epoch_parity(pipe, wl, host, epoch, row_batches):
     pipe.precompute(epoch, nb)
     sizes = pipe.read_sizes()
     st = pipe.state
-    ahead = OracleAhead(lambda seeds: oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, epoch), batches)
+    order = oracle.ORDER_FIRST_SEEN if pipe.node_order == 1 else oracle.ORDER_ASCENDING
+    ahead = OracleAhead(lambda seeds: oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, epoch, order), batches)
     counts_orc = np.zeros(cfg.num_nodes, dtype=np.uint32)
     inputs = []
     try:
@@ -154,6 +155,24 @@ def test_large_workload_both_epochs(name):
             first = inputs[0][:cfg.batch_size].copy()
         else:
             assert not np.array_equal(first, inputs[0][:cfg.batch_size])    # the second epoch has its own schedule
+
+
+def test_large_workload_first_seen_order_and_bitmap_counts():
+    """The second canonical node order at full size, with the access counts (and the first batch of every node, which
+    drives the prefetch plan) taken straight from the sampler's membership bitmaps: one epoch of sparse_copurchase."""
+    from paper_2505_10806_amd.pipeline import EpochPipeline
+    wl = synth.build_workload("sparse_copurchase", seed=2025, device=DEV)
+    host = _host_inputs(wl)
+    pipe = EpochPipeline(wl, device=DEV, keep_blocks=True, node_order="first_seen", histogram="sampled")
+    assert pipe.planned
+    nb = pipe.batches_per_epoch
+    inputs, tot = _epoch_parity(pipe, wl, host, 0, range(0, nb, 4))
+    assert tot[2] > 0
+    # the tiers really are in another order than ascending somewhere
+    H = len(wl.cfg.fanouts)
+    tier = pipe.tier_offs[0].cpu().numpy()
+    last = pipe.arena[0, tier[H]:tier[H + 1]].cpu().numpy()
+    assert np.any(np.diff(last) < 0)
 
 
 def test_stress_workload():
