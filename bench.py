@@ -63,17 +63,20 @@ def run_steps(pipe, steps, totals=None, first_epoch=0):
     def account(p, _k):
         if totals is not None:
             nb = p.n_batches
+            per = nb // p.period_epochs
+            for e in range(p.period_epochs):              # hits and misses of every epoch of the period
+                totals["per_epoch"].append(p.stats[e * per:(e + 1) * per].sum(0))
             totals["stats"] += p.stats[:nb].sum(0)
             totals["rows"] += sum(p.sizes[:nb])
             totals["edges"] += p.edge_counts[:nb].sum()
             totals["cached"] += p.cache.num_cached.clone()
             totals["epochs"] += 1
-    bpe = pipe.batches_per_epoch
-    full, rem = divmod(steps, bpe)
+    bpe, E = pipe.batches_per_epoch, pipe.period_epochs
+    full, rem = divmod(steps, bpe * E)                    # whole periods, then a shorter one
     if full:
         pipe.run_epochs(first_epoch, full, bpe, on_epoch_done=account)
     if rem:
-        pipe.run_epochs(first_epoch + full, 1, rem, on_epoch_done=account)
+        pipe.run_epochs(first_epoch + full * E, 1, max(1, rem // E), on_epoch_done=account)
     torch.cuda.current_stream().synchronize()
 
 
@@ -81,7 +84,7 @@ def new_totals(dev):
     import torch
     return {"stats": torch.zeros(3, dtype=torch.int64, device=dev), "rows": 0,
             "edges": torch.zeros((), dtype=torch.int64, device=dev),
-            "cached": torch.zeros(1, dtype=torch.int64, device=dev), "epochs": 0}
+            "cached": torch.zeros(1, dtype=torch.int64, device=dev), "epochs": 0, "per_epoch": []}
 
 
 def timed_reps(pipe, steps, reps):
@@ -212,6 +215,9 @@ def main():
                          "membership bitmaps after every group, or one global-atomic pass per batch")
     ap.add_argument("--node-order", choices=["ascending", "first_seen"], default="ascending",
                     help="order of the nodes inside a tier of a block")
+    ap.add_argument("--period-epochs", type=int, default=1,
+                    help="epochs precomputed, counted and cached together (1: a cache per epoch from that epoch's counts; "
+                         "E: one cache from the counts of E epochs, as Alg. 1 lines 1-4 read)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the extra passes (whole-epoch rate, gather kernel without concurrent pulls, hit curve)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -252,17 +258,21 @@ def main():
         f"(generated in {time.perf_counter() - t_gen:.1f} s)")
 
     bpe = wl.batches_per_epoch()
-    steps = args.steps if args.steps is not None else bpe
+    per_period = bpe * max(1, args.period_epochs)
+    steps = args.steps if args.steps is not None else per_period
+    if steps % max(1, args.period_epochs):
+        print("bench.py: --steps must be a multiple of --period-epochs", file=sys.stderr)
+        sys.exit(2)
     warmup, reps = args.warmup, max(1, args.reps)
     row_bytes = 4 * cfg.feat_dim
-    multi_epoch = steps > bpe
+    multi_epoch = steps > per_period
     main_stream = torch.cuda.Stream()
 
     def make_pipeline(prefetch):
         return EpochPipeline(wl, device=dev, two_streams=not args.one_stream, prefetch=prefetch,
                              sampler_streams=args.sampler_streams, double_buffer=(multi_epoch and not args.no_double_buffer),
                              planned_prefetch=not args.no_plan, sample_group=args.sample_group,
-                             histogram=args.histogram, node_order=args.node_order,
+                             histogram=args.histogram, node_order=args.node_order, period_epochs=args.period_epochs,
                              consumer=None if args.consumer == "none" else args.consumer,
                              queue_depth=args.queue_depth if args.consumer != "none" else 1)
 
@@ -276,7 +286,7 @@ def main():
         roof = gather_roofline(prof, totals, row_bytes)
 
         full_epoch = None
-        if not args.no_extras and steps != bpe and not multi_epoch:
+        if not args.no_extras and steps != per_period and not multi_epoch and args.period_epochs == 1:
             run_steps(pipe, bpe)                                     # warm-up at the whole epoch's sizes
             full_times = timed_reps(pipe, bpe, 3)
             f_dt, f_prof, f_totals = profiled_pass(pipe, bpe, dev)
@@ -319,7 +329,7 @@ def main():
                    "sampler_streams": args.sampler_streams, "sample_group": args.sample_group,
                    "double_buffered_cache": bool(multi_epoch and not args.no_double_buffer),
                    "planned_prefetch": pipe.planned, "consumer": args.consumer, "queue_depth": pipe.queue_depth,
-                   "histogram": pipe.histogram, "node_order": args.node_order,
+                   "histogram": pipe.histogram, "node_order": args.node_order, "period_epochs": pipe.period_epochs,
                    "GPU_MAX_HW_QUEUES": os.environ.get("GPU_MAX_HW_QUEUES"), "GPU_MAX_HW_QUEUES_set_by": "user" if HWQ_SET_BY_USER else "bench.py"},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": roof["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": roof["frac"],
@@ -343,10 +353,13 @@ def main():
                      "achieved": row_bytes * cached_rows / (f_ms * 1e-3) / 1e9 if f_ms > 0 and cached_rows else None,
                      "note": "sum of pull-kernel durations; the pulls run beside the gathers on their own stream"},
         "kernel_ms": {k: {"total_ms": v[0], "launches": v[1]} for k, v in prof.items()},
+        # hits and misses of each epoch served in the profiled pass (with --period-epochs E, E epochs share one cache)
+        "per_epoch": [{"n_local": int(a), "n_hit": int(b), "n_miss": int(c), "hit_pct": 100.0 * int(b) / max(1, int(b) + int(c))}
+                      for a, b, c in (t.cpu().tolist() for t in totals["per_epoch"])],
     }
     if full_epoch is not None:
         result["full_epoch"] = full_epoch
-    elif not multi_epoch and steps == bpe:
+    elif not multi_epoch and steps == per_period and args.period_epochs == 1:
         result["full_epoch"] = dict(spread(times, bpe), batches=bpe, k_gather_hbm_frac=roof["frac"],
                                     k_gather_hbm_avg_launch_ms=roof["avg_launch_ms"])
 
@@ -362,7 +375,7 @@ def main():
                                      "points": [{"capacity_frac_of_remote": f, "capacity_rows": c,
                                                  "hit_pct": 100.0 * int(h) / max(total, 1), "remote_fetches": total - int(h)}
                                                 for f, c, h in zip(fracs, caps, hits.cpu().tolist())]}
-        if not args.bulk_fill and not multi_epoch:
+        if not args.bulk_fill and not multi_epoch and args.period_epochs == 1:
             # the same gathers with all rows pulled beforehand: the copy kernel with nothing beside it
             n_b = min(steps, bpe)
             del pipe

@@ -52,14 +52,19 @@ class EpochPipeline:
     def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True,
                  histogram="epoch", sampler_streams=2, double_buffer=False,
                  queue_depth=1, consumer=None, planned_prefetch=True, sample_group=8, keep_blocks=False,
-                 node_order="ascending"):
+                 node_order="ascending", period_epochs=1):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
         self.ctx = ctx or B.Context(torch.device(device).index or 0)
         self.csr = B.CsrGraph(wl.row_ptr, wl.col_idx)
         self.batches_per_epoch = wl.batches_per_epoch()
-        self.max_batches = min(max_batches or self.batches_per_epoch, self.batches_per_epoch)
+        # period_epochs = E: the batches of E consecutive epochs are precomputed together, counted together and served
+        # from one cache (Alg. 1 lines 1-4 as written: N, the frequencies and C_s cover every precomputed epoch); E = 1
+        # builds a cache per epoch from that epoch's counts alone (the C_sec of Alg. 1 line 8).  A period's batches
+        # occupy consecutive slots: epoch by epoch, batch by batch.
+        self.period_epochs = max(1, int(period_epochs))
+        self.max_batches = min(max_batches or self.batches_per_epoch, self.batches_per_epoch) * self.period_epochs
         # Batches are independent, and most sampler kernels of one batch are far smaller than the GPU: several
         # batches are sampled side by side, each lane with its own stream, context (scratch) and hop buffers.
         # node order inside a tier: "ascending" by id, or "first_seen" (the order in which the hop's neighbour list first
@@ -107,7 +112,8 @@ class EpochPipeline:
                     if consumer else None)
         self._gathered = 0
         self._tickets = {}                         # ticket -> (epoch state, batch) it is prepared for
-        self.order = torch.empty_like(wl.train_ids)
+        self.orders = [torch.empty_like(wl.train_ids) for _ in range(self.period_epochs)]
+        self.order = self.orders[0]
         self.side = torch.cuda.Stream(device=device) if two_streams else None
         # prefetch = pull cached rows batch by batch, in order of first use, on a stream of their own so the
         # host-link transfer overlaps the gathers; otherwise one bulk pull right after TopHot
@@ -170,14 +176,17 @@ class EpochPipeline:
         return ms, launches
 
     # ---- offline stage
-    def _offline(self, st, epoch, ids, lanes):
-        """Queue schedule, sampling, histogram and TopHot of one epoch.  lanes = [(ctx, bufs, stream or None)];
-        lane 0's stream (None = the current stream) also runs the schedule, the histogram and TopHot."""
+    def _offline(self, st, epoch, batch_ids, lanes):
+        """Queue schedule, sampling, histogram and TopHot of one period (the listed batches of period_epochs epochs
+        starting at `epoch`).  lanes = [(ctx, bufs, stream or None)]; lane 0's stream (None = the current stream) also
+        runs the schedules, the histogram and TopHot."""
         cfg = self.cfg
         head_ctx, _, head_stream = lanes[0]
         head = head_stream or torch.cuda.current_stream()
+        ids = [(k, b) for k in range(self.period_epochs) for b in batch_ids]          # slot -> (epoch of the period, batch)
         with torch.cuda.stream(head):
-            head_ctx.epoch_schedule(self.wl.train_ids, self.wl.seed, epoch, self.order)
+            for k in range(self.period_epochs):
+                head_ctx.epoch_schedule(self.wl.train_ids, self.wl.seed, epoch + k, self.orders[k])
             st.counts.zero_()
             if self.planned:
                 st.first_batch.fill_(-1)
@@ -185,24 +194,27 @@ class EpochPipeline:
                 s.wait_stream(head)
             n_train = self.order.numel()
             gsz = self.sample_group
-            for call, i0 in enumerate(range(0, len(ids), gsz)):
+            # a sampling call takes batches of one epoch (the epoch is part of the draw's key)
+            calls = [(k, i0, min(i0 + gsz, (k + 1) * len(batch_ids)))
+                     for k in range(self.period_epochs) for i0 in range(k * len(batch_ids), (k + 1) * len(batch_ids), gsz)]
+            for call, (k, i0, i1) in enumerate(calls):
                 c, bufs_list, s = lanes[call % len(lanes)]
                 seeds_list, outs = [], []
-                for k, i in enumerate(range(i0, min(i0 + gsz, len(ids)))):
-                    b = ids[i]
-                    seeds_list.append(self.order[b * cfg.batch_size:min((b + 1) * cfg.batch_size, n_train)])
-                    bufs = bufs_list[k]
+                for j, i in enumerate(range(i0, i1)):
+                    b = ids[i][1]
+                    seeds_list.append(self.orders[k][b * cfg.batch_size:min((b + 1) * cfg.batch_size, n_train)])
+                    bufs = bufs_list[j]
                     bufs.set_outputs(st.arena[i], st.tier_offs[i], st.edge_counts[i])
                     for h, (ip, nb, nl) in st.blk.items():
                         bufs.set_hop(h, ip[i], nb[i], nl[i])
                     outs.append(bufs)
-                c.sample_blocks_group(self.csr, seeds_list, cfg.fanouts, self.wl.seed, epoch, outs, stream=s or head,
+                c.sample_blocks_group(self.csr, seeds_list, cfg.fanouts, self.wl.seed, epoch + k, outs, stream=s or head,
                                       node_order=self.node_order)
                 if self.histogram == "sampled":           # the group's membership bitmaps go straight into the counts
                     c.access_histogram_sampled(len(outs), st.counts, batch_index=range(i0, i0 + len(outs)),
                                                first_batch=st.first_batch, stream=s or head)
                 elif self.histogram == "batch":
-                    for i in range(i0, min(i0 + gsz, len(ids))):
+                    for i in range(i0, i1):
                         head_ctx.access_histogram(st.arena[i], self.slot, st.counts, n_dev=st.tier_offs[i, self.H + 1:], stream=head)
             for _, _, s in lanes[1:]:
                 head.wait_stream(s)
@@ -225,9 +237,10 @@ class EpochPipeline:
 
     def precompute(self, epoch, n_batches=None, batch_ids=None):
         """Offline stage (asynchronous) for the first n_batches batches of `epoch`, or for the listed
-        batch indices; slot i of the arena holds the i-th of them.  Uses every sampler lane."""
+        batch indices; slot i of the arena holds the i-th of them.  With period_epochs = E the same batches of the
+        E epochs starting at `epoch` follow each other, epoch by epoch.  Uses every sampler lane."""
         ids = list(batch_ids) if batch_ids is not None else list(range(n_batches))
-        assert len(ids) <= self.max_batches and all(0 <= b < self.batches_per_epoch for b in ids)
+        assert len(ids) * self.period_epochs <= self.max_batches and all(0 <= b < self.batches_per_epoch for b in ids)
         lanes = [(self.lane_ctx[k], self.lane_bufs[k], self.lane_stream[k]) for k in range(self.n_lanes)]
         self._offline(self.state, epoch, ids, lanes)
 
@@ -327,21 +340,24 @@ class EpochPipeline:
         st.served.record(main)
 
     def run_epoch(self, epoch, n_batches, on_batch=None):
-        """One epoch from a cold start: offline stage, size read-back, online stage."""
+        """One period (period_epochs epochs of n_batches batches each) from a cold start: offline stage, size
+        read-back, online stage."""
         self.precompute(epoch, n_batches)
         self.read_sizes()
-        self.online(n_batches, on_batch)
+        self.online(n_batches * self.period_epochs, on_batch)
 
-    def run_epochs(self, first_epoch, n_epochs, n_batches, on_epoch_done=None, on_batch=None, on_epoch_start=None):
-        """Several epochs back to back.  With double buffering, epoch e+1 is precomputed on the build stream
-        (one sampler lane) and its rows are pulled behind epoch e's while epoch e is being served."""
-        if not self.double_buffer or n_epochs == 1:
-            for k in range(n_epochs):
-                self.precompute(first_epoch + k, n_batches)
+    def run_epochs(self, first_epoch, n_periods, n_batches, on_epoch_done=None, on_batch=None, on_epoch_start=None):
+        """Several periods back to back (a period is one epoch unless period_epochs says otherwise; the callbacks get
+        the period's index).  With double buffering, period p+1 is precomputed on the build stream (one sampler lane)
+        and its rows are pulled behind period p's while period p is being served."""
+        E = self.period_epochs
+        if not self.double_buffer or n_periods == 1:
+            for k in range(n_periods):
+                self.precompute(first_epoch + k * E, n_batches)
                 self.read_sizes()
                 if on_epoch_start:
                     on_epoch_start(self, k)
-                self.online(n_batches, on_batch)
+                self.online(n_batches * E, on_batch)
                 if on_epoch_done:
                     on_epoch_done(self, k)
             return
@@ -349,22 +365,22 @@ class EpochPipeline:
         ids = list(range(n_batches))
         self.precompute(first_epoch, n_batches)                      # cold start: every lane
         build_lane = [(self.lane_ctx[1], self.lane_bufs[1], self.build_stream)]
-        for k in range(n_epochs):
+        for k in range(n_periods):
             self.read_sizes()
             if self.prefetch:
                 self._queue_pulls(self.state)
             nxt = self.states[1 - self.cur]
-            if k + 1 < n_epochs:
-                # the other buffer set is free once the epoch that used it has been served
+            if k + 1 < n_periods:
+                # the other buffer set is free once the period that used it has been served
                 self.build_stream.wait_event(nxt.served)
-                self.build_stream.wait_stream(main)                  # and after anything already queued that reads `order`
-                self._offline(nxt, first_epoch + k + 1, ids, build_lane)
+                self.build_stream.wait_stream(main)                  # and after anything already queued that reads the orders
+                self._offline(nxt, first_epoch + (k + 1) * E, ids, build_lane)
             if on_epoch_start:
                 on_epoch_start(self, k)
-            self.online(n_batches, on_batch)
-            if k + 1 < n_epochs and self.prefetch:
-                self._queue_pulls(nxt)                               # behind this epoch's pulls on the prefetch stream
+            self.online(n_batches * E, on_batch)
+            if k + 1 < n_periods and self.prefetch:
+                self._queue_pulls(nxt)                               # behind this period's pulls on the prefetch stream
             if on_epoch_done:
                 on_epoch_done(self, k)
             self.cur = 1 - self.cur
-        self.cur = 1 - self.cur                                      # leave the last served epoch current
+        self.cur = 1 - self.cur                                      # leave the last served period current

@@ -19,12 +19,15 @@ class WorkloadConfig:
     batch_size: int
     train_frac: float
     epochs: int
-    partition: str              # "mod2" | "random4" | "mod4"
+    partition: str              # "mod2" | "random4" | "mod4" | "groups4" (local = planted group 0)
     cache_frac: Optional[float]  # fraction of remote rows; None -> cache_bytes governs
     cache_bytes: Optional[int] = None
     offsets64: bool = False     # CSR row offsets as int64
     max_batches: Optional[int] = None  # only the first max_batches of each epoch are used
     num_classes: int = 2
+    communities: int = 0        # > 0: planted groups in the graph (degree-corrected planted partition)
+    p_in: float = 0.0           # probability that an edge's second endpoint is drawn inside the first one's group
+    local_seeds: bool = False   # train ids are restricted to the local partition (one trainer per partition)
 
     def cache_capacity_rows(self, n_remote: int) -> int:
         if self.cache_frac is not None:
@@ -63,8 +66,25 @@ CONFIGS = {
 }
 
 
+EXTRA_CONFIGS = {
+    # Two more presets, outside the five measured configurations: the `small` shapes on a graph with four planted
+    # groups, once partitioned at random and once along the groups (a stand-in for an edge-cut-minimising
+    # partitioner), seeds taken from the local partition as a trainer does.  They show how much of the remote traffic
+    # the partitioner removes before the cache sees it.
+    "small_groups_random": WorkloadConfig(
+        name="small_groups_random", num_nodes=200_000, mean_degree=50, gamma=2.1, feat_dim=128,
+        fanouts=(25, 10), batch_size=1024, train_frac=0.60, epochs=1,
+        partition="random4", cache_frac=0.15, communities=4, p_in=0.85, local_seeds=True),
+    "small_groups_local": WorkloadConfig(
+        name="small_groups_local", num_nodes=200_000, mean_degree=50, gamma=2.1, feat_dim=128,
+        fanouts=(25, 10), batch_size=1024, train_frac=0.60, epochs=1,
+        partition="groups4", cache_frac=0.15, communities=4, p_in=0.85, local_seeds=True),
+}
+
+
 def get_config(name: str) -> WorkloadConfig:
-    try:
+    if name in CONFIGS:
         return CONFIGS[name]
-    except KeyError:
-        raise KeyError(f"unknown workload {name!r}; choose from {sorted(CONFIGS)}")
+    if name in EXTRA_CONFIGS:
+        return EXTRA_CONFIGS[name]
+    raise KeyError(f"unknown workload {name!r}; choose from {sorted(CONFIGS) + sorted(EXTRA_CONFIGS)}")

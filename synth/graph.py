@@ -24,8 +24,13 @@ def _expected_degree_weights(num_nodes, target_nnz, gamma):
 
 
 def chung_lu_csr(num_nodes, mean_degree, gamma, seed, device="cpu", offsets64=False,
-                 chunk=1 << 26):
+                 chunk=1 << 26, communities=0, p_in=0.0, return_communities=False):
     """Return (row_ptr, col_idx) of an undirected simple graph stored as a directed CSR.
+
+    With communities = C > 0 the nodes fall into C equal groups (every group gets its share of hubs) and the second
+    endpoint of an edge is drawn inside the first endpoint's group with probability p_in, anywhere otherwise: a
+    degree-corrected planted partition, which gives a locality-aware partitioner something to find.  With
+    return_communities the group label of every node (int64 [N]) is returned as a third value.
 
     Both endpoints of each of target_nnz/2 undirected edges are drawn with probability
     proportional to the expected-degree weights; node ranks are relabelled by a seeded
@@ -46,6 +51,19 @@ def chung_lu_csr(num_nodes, mean_degree, gamma, seed, device="cpu", offsets64=Fa
     cdf = cdf.to(device)
     del w
     perm = torch.randperm(n, generator=gen, device=device)
+    C = int(communities)
+    labels = None
+    group_idx, group_cdf = [], []
+    if C > 0:
+        # rank r belongs to group r % C; per group, the ranks and the cumulative weights for draws inside it
+        labels = torch.empty(n, dtype=torch.int64, device=device)
+        labels[perm] = torch.arange(n, device=device) % C
+        w_dev = torch.diff(cdf, prepend=cdf.new_zeros(1))
+        for c in range(C):
+            idx = torch.arange(c, n, C, device=device)
+            gc = torch.cumsum(w_dev[idx], 0)
+            group_idx.append(idx)
+            group_cdf.append(gc / gc[-1].clone())
 
     keys = []
     done = 0
@@ -53,8 +71,17 @@ def chung_lu_csr(num_nodes, mean_degree, gamma, seed, device="cpu", offsets64=Fa
         m = min(chunk, n_und - done)
         a = torch.searchsorted(cdf, torch.rand(m, dtype=torch.float64, generator=gen, device=device))
         b = torch.searchsorted(cdf, torch.rand(m, dtype=torch.float64, generator=gen, device=device))
-        a = perm[a.clamp_(max=n - 1)]
-        b = perm[b.clamp_(max=n - 1)]
+        a.clamp_(max=n - 1)
+        b.clamp_(max=n - 1)
+        if C > 0:
+            inside = torch.rand(m, dtype=torch.float64, generator=gen, device=device) < p_in
+            u = torch.rand(m, dtype=torch.float64, generator=gen, device=device)
+            for c in range(C):
+                sel = inside & (a % C == c)
+                pick = torch.searchsorted(group_cdf[c], u[sel]).clamp_(max=group_idx[c].numel() - 1)
+                b[sel] = group_idx[c][pick]
+        a = perm[a]
+        b = perm[b]
         keep = a != b
         a, b = a[keep], b[keep]
         lo, hi = torch.minimum(a, b), torch.maximum(a, b)
@@ -78,4 +105,6 @@ def chung_lu_csr(num_nodes, mean_degree, gamma, seed, device="cpu", offsets64=Fa
     if not offsets64:
         assert int(row_ptr[-1]) < 2 ** 31
         row_ptr = row_ptr.to(torch.int32)
+    if return_communities:
+        return row_ptr, col_idx, labels
     return row_ptr, col_idx

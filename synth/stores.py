@@ -37,9 +37,13 @@ def make_train_ids(num_nodes, frac, seed, device="cpu"):
     return perm[: int(frac * num_nodes)].to(torch.int32).contiguous()
 
 
-def make_partition(num_nodes, scheme, seed, device="cpu"):
+def make_partition(num_nodes, scheme, seed, device="cpu", groups=None):
     """Boolean mask of the nodes whose features are local (resident in HBM)."""
     ids = torch.arange(num_nodes, device=device)
+    if scheme == "groups4":
+        if groups is None:
+            raise ValueError("partition 'groups4' needs the graph's planted group labels")
+        return groups.to(device) == 0
     if scheme == "mod2":
         return ids % 2 == 0
     if scheme == "mod4":
@@ -110,10 +114,13 @@ def build_workload(name_or_cfg, seed=2025, device="cpu", keep_features=True, pin
     device = torch.device(device)
     if pin_remote is None:
         pin_remote = device.type == "cuda"
-    row_ptr, col_idx = chung_lu_csr(cfg.num_nodes, cfg.mean_degree, cfg.gamma, seed, device, cfg.offsets64)
+    row_ptr, col_idx, groups = chung_lu_csr(cfg.num_nodes, cfg.mean_degree, cfg.gamma, seed, device, cfg.offsets64,
+                                            communities=cfg.communities, p_in=cfg.p_in, return_communities=True)
     feats = make_features(cfg.num_nodes, cfg.feat_dim, seed, device)
     train_ids = make_train_ids(cfg.num_nodes, cfg.train_frac, seed, device)
-    is_local = make_partition(cfg.num_nodes, cfg.partition, seed, device)
+    is_local = make_partition(cfg.num_nodes, cfg.partition, seed, device, groups)
+    if cfg.local_seeds:          # a trainer draws its seeds from its own partition
+        train_ids = train_ids[is_local[train_ids.long()]].contiguous()
     home = make_home(is_local)
     stride = row_stride(cfg.feat_dim)
     local_store = _pack(feats, is_local, stride, device, pinned=False)

@@ -422,6 +422,121 @@ def test_pipeline_epochs_back_to_back(B, double_buffer, full_cache, histogram, n
     assert not np.array_equal(expected[0][0][0], expected[1][0][0])       # epochs differ
 
 
+def _oracle_period(wl, rp, ci, home_np, train_np, first_epoch, epochs):
+    """Oracle input nodes of every batch of the listed epochs, and the counts over all of them."""
+    cfg = wl.cfg
+    counts = np.zeros(cfg.num_nodes, dtype=np.uint32)
+    inputs = []
+    for e in range(first_epoch, first_epoch + epochs):
+        for seeds in oracle.epoch_batches(train_np, cfg.batch_size, wl.seed, e, cfg.max_batches):
+            blk = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, e)
+            oracle.access_histogram(blk.input_nodes, counts)
+            inputs.append(blk.input_nodes)
+    return inputs, counts
+
+
+@pytest.mark.parametrize("double_buffer", [False, True])
+def test_pipeline_period_of_two_epochs_shares_one_cache(B, double_buffer):
+    """Alg. 1 lines 1-4 as written: the batches of all precomputed epochs are counted together and one steady cache
+    serves them.  Two periods of two epochs each; every slot's input nodes, the period's counts, cache and location
+    table, and every batch's rows and statistics against the oracle; then the comparison with a cache per epoch:
+    the per-epoch caches serve at least as many requests, the shared cache is filled once instead of twice."""
+    from paper_2505_10806_amd.pipeline import EpochPipeline
+    wl = synth.build_workload("tiny", seed=5, device=DEV)
+    cfg = wl.cfg
+    rp, ci = host_graph(wl)
+    X = wl.features.cpu().numpy()
+    home_np, train_np = wl.home.cpu().numpy(), wl.train_ids.cpu().numpy()
+    pipe = EpochPipeline(wl, device=DEV, double_buffer=double_buffer, period_epochs=2)
+    nb = pipe.batches_per_epoch
+    expected, hits = {}, {}
+
+    def period_start(p, k):
+        inputs, counts = _oracle_period(wl, rp, ci, home_np, train_np, 2 * k, 2)
+        ids, loc = oracle.build_cache(counts, home_np, wl.capacity_rows)
+        expected[k] = (inputs, counts, ids, loc)
+        assert p.n_batches == 2 * nb == len(inputs)
+        for i, nodes in enumerate(inputs):
+            assert np.array_equal(p.arena[i, :nodes.size].cpu().numpy(), nodes), f"period {k} slot {i}"
+        assert np.array_equal(p.counts.cpu().numpy().view(np.uint32), counts)
+        assert np.array_equal(p.cache.cache_ids[:ids.size].cpu().numpy(), ids)
+        assert np.array_equal(p.cache.loc.cpu().numpy(), loc)
+        p._period = k
+        hits[k] = [0, 0]
+
+    def batch_done(p, i):
+        torch.cuda.synchronize()
+        inputs, _, _, loc = expected[p._period]
+        want, st = oracle.gather_features(X, inputs[i], loc)
+        assert np.array_equal(p.out[:inputs[i].size, :cfg.feat_dim].cpu().numpy(), want), f"period {p._period} slot {i}"
+        assert tuple(p.stats[i].cpu().tolist()) == st
+        hits[p._period][0] += st[1]
+        hits[p._period][1] += st[2]
+
+    pipe.run_epochs(0, 2, nb, on_batch=batch_done, on_epoch_start=period_start)
+    torch.cuda.synchronize()
+    remote = ((home_np.astype(np.int64) & 0xFFFFFFFF) >> 30) == 2
+    for k in (0, 1):
+        _, counts, ids, _ = expected[k]
+        assert hits[k][0] == int(counts[ids].sum()) and sum(hits[k]) == int(counts[remote].sum())   # closed form
+    # the same two epochs with a cache per epoch (oracle): at least as many hits, twice the fill
+    per_epoch_hits = per_epoch_fill = 0
+    for e in (0, 1):
+        _, c_e = _oracle_period(wl, rp, ci, home_np, train_np, e, 1)
+        ids_e, _ = oracle.build_cache(c_e, home_np, wl.capacity_rows)
+        per_epoch_hits += int(c_e[ids_e].sum())
+        per_epoch_fill += ids_e.size
+    assert per_epoch_hits >= hits[0][0] and per_epoch_fill == 2 * expected[0][2].size
+
+
+def test_group_partition_cuts_remote_requests(B):
+    """The `small` shapes on a graph with four planted groups, partitioned at random and along the groups (the stand-in
+    for an edge-cut-minimising partitioner), seeds from the local partition: the whole path against the oracle on
+    three batches of each, then the comparison the paper draws between its partitioners: far fewer requests for
+    remote rows, and fewer remote fetches after the cache, along the groups."""
+    from paper_2505_10806_amd.pipeline import EpochPipeline
+    remote_requests, misses = {}, {}
+    for name in ("small_groups_random", "small_groups_local"):
+        wl = synth.build_workload(name, seed=2025, device=DEV)
+        cfg = wl.cfg
+        rp, ci = host_graph(wl)
+        X = wl.features.cpu().numpy()
+        home_np, train_np = wl.home.cpu().numpy(), wl.train_ids.cpu().numpy()
+        pipe = EpochPipeline(wl, device=DEV)
+        nb = pipe.batches_per_epoch
+        pipe.run_epoch(0, nb)
+        torch.cuda.synchronize()
+        stats = pipe.stats[:nb].cpu().numpy()
+        counts = pipe.counts.cpu().numpy().view(np.uint32)
+        remote = ((home_np.astype(np.int64) & 0xFFFFFFFF) >> 30) == 2
+        k = int(pipe.cache.num_cached.item())
+        ids = pipe.cache.cache_ids[:k].cpu().numpy()
+        assert stats[:, 1].sum() == int(counts[ids].sum()) and stats[:, 1:].sum() == int(counts[remote].sum())
+        batches = oracle.epoch_batches(train_np, cfg.batch_size, wl.seed, 0)
+        assert len(batches) == nb
+        counts_orc = np.zeros(cfg.num_nodes, dtype=np.uint32)
+        inputs = []
+        for seeds in batches:
+            blk = oracle.sample_blocks(rp, ci, seeds, cfg.fanouts, wl.seed, 0)
+            oracle.access_histogram(blk.input_nodes, counts_orc)
+            inputs.append(blk.input_nodes)
+        assert np.array_equal(counts, counts_orc)
+        ids_orc, loc_orc = oracle.build_cache(counts_orc, home_np, wl.capacity_rows)
+        assert np.array_equal(ids, ids_orc) and np.array_equal(pipe.cache.loc.cpu().numpy(), loc_orc)
+        for b in (0, nb // 2, nb - 1):
+            assert np.array_equal(pipe.arena[b, :inputs[b].size].cpu().numpy(), inputs[b])
+            _, st = oracle.gather_features(X[:, :1], inputs[b], loc_orc)
+            assert tuple(stats[b].tolist()) == st
+        want, _ = oracle.gather_features(X, inputs[nb - 1], loc_orc)          # the last gather's rows are still in pipe.out
+        assert np.array_equal(pipe.out[:inputs[nb - 1].size, :cfg.feat_dim].cpu().numpy(), want)
+        remote_requests[name] = int(stats[:, 1:].sum())
+        misses[name] = int(stats[:, 2].sum())
+        log(f"[partition] {name}: rows {int(stats.sum())}, requests for remote rows {remote_requests[name]}, "
+            f"hits {int(stats[:, 1].sum())}, remote fetches {misses[name]}, cached rows {k}")
+    assert remote_requests["small_groups_local"] < 0.5 * remote_requests["small_groups_random"]
+    assert misses["small_groups_local"] < misses["small_groups_random"]
+
+
 @pytest.mark.parametrize("num_batches", [0, 1, 7, 1023, 1500])
 def test_prefetch_plan_groups_slots_by_first_batch(B, ctx, num_batches):
     """rg_plan_prefetch on a synthetic first-use array: segment b holds exactly the slots whose node is first

@@ -67,3 +67,27 @@ def test_partitions():
     assert torch.equal(r, synth.make_partition(100_000, "random4", 5))
     with pytest.raises(ValueError):
         synth.make_partition(8, "metis", 0)
+
+
+def test_planted_groups_and_group_partition():
+    """The two extra presets share one graph; along the planted groups far fewer edges of local nodes leave the
+    partition than under a random partition, and the seeds come from the local partition."""
+    assert sorted(synth.EXTRA_CONFIGS) == ["small_groups_local", "small_groups_random"]
+    import dataclasses
+    small = {k: dataclasses.replace(synth.get_config(k), num_nodes=20_000) for k in synth.EXTRA_CONFIGS}
+    r = synth.build_workload(small["small_groups_random"], seed=9)
+    g = synth.build_workload(small["small_groups_local"], seed=9)
+    assert torch.equal(r.row_ptr, g.row_ptr) and torch.equal(r.col_idx, g.col_idx)
+    assert g.n_local == 5_000 and abs(r.n_local - 5_000) < 300
+
+    def leaving(wl):
+        rp, ci, loc = wl.row_ptr.numpy(), wl.col_idx.numpy(), wl.is_local.numpy()
+        src = np.repeat(np.arange(rp.size - 1), np.diff(rp))
+        return (loc[src] & ~loc[ci]).sum() / loc[src].sum()
+    assert leaving(r) > 0.7 and leaving(g) < 0.2
+    for wl in (r, g):
+        assert bool(wl.is_local[wl.train_ids.long()].all()) and wl.train_ids.numel() > 2_000
+    # graphs without planted groups are what they were before the option existed
+    rp, ci = synth.chung_lu_csr(3000, 10, 2.1, seed=4)
+    rp2, ci2, labels = synth.chung_lu_csr(3000, 10, 2.1, seed=4, communities=0, return_communities=True)
+    assert labels is None and torch.equal(rp, rp2) and torch.equal(ci, ci2)
