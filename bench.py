@@ -285,6 +285,18 @@ def main():
         prof_dt, prof, totals = profiled_pass(pipe, steps, dev)
         roof = gather_roofline(prof, totals, row_bytes)
 
+        # the offline stage alone (schedule, sampling, histogram, TopHot, plan), same batches, device idle otherwise
+        offline_ms = None
+        if not multi_epoch:
+            ts = []
+            for _ in range(3):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                pipe.precompute(0, min(steps, per_period) // pipe.period_epochs)
+                torch.cuda.synchronize()
+                ts.append((time.perf_counter() - t0) * 1e3)
+            offline_ms = statistics.median(ts)
+
         full_epoch = None
         if not args.no_extras and steps != per_period and not multi_epoch and args.period_epochs == 1:
             run_steps(pipe, bpe)                                     # warm-up at the whole epoch's sizes
@@ -319,7 +331,7 @@ def main():
                        step_definition=("one batch of a %d-batch epoch taken from a cold cache through schedule, sampling, histogram, "
                                         "TopHot, pulls and gather" % min(steps, bpe)) if not multi_epoch else
                                        "one batch of %d epochs run back to back with the double-buffered cache" % -(-steps // bpe),
-                       profiled_pass_ms=prof_dt * 1e3,
+                       profiled_pass_ms=prof_dt * 1e3, offline_stage_alone_ms=offline_ms,
                        note="value = steps / median; kernel durations come from the extra profiled pass"),
         "config": {"workload": cfg.name, "num_nodes": cfg.num_nodes, "nnz": wl.nnz, "feat_dim": cfg.feat_dim,
                    "fanouts": list(cfg.fanouts), "batch_size": cfg.batch_size, "batches_per_epoch": bpe,

@@ -42,7 +42,8 @@
  *    lane of the HBM gather), RG_GATHER_BLOCKS_PER_CU (grid cap of the HBM gather, default
  *    none), RG_PULL_BLOCKS / RG_PULL_THREADS (grid of the host-link pull kernels, default
  *    16 x 1024), RG_PULL_ROWS (rows in flight per lane group of the pull kernel, 4 or 8), RG_MISS_BLOCKS /
- *    RG_MISS_THREADS (grid of the miss-row kernel, default 192 x 256).
+ *    RG_MISS_THREADS (grid of the miss-row kernel, default 192 x 256), RG_XCD_MAP=0 (sampler workgroups in
+ *    batch-major order instead of one batch of a group per XCD).
  */
 #ifndef RAPIDGNN_H
 #define RAPIDGNN_H
@@ -81,7 +82,7 @@ typedef enum {
 #define RG_FANOUT_ALL (-1)
 #define RG_MAX_HOPS 8
 /* Most batches one rg_sample_blocks_group call samples side by side. */
-#define RG_MAX_GROUP 8
+#define RG_MAX_GROUP 16
 
 typedef struct rg_ctx rg_ctx;
 

@@ -17,7 +17,7 @@ RG_OK, RG_ERR_INVALID_ARG, RG_ERR_CAPACITY, RG_ERR_OOM, RG_ERR_HIP, RG_ERR_STATE
 RG_MAX_FANOUT = 1024
 RG_FANOUT_ALL = -1
 RG_MAX_HOPS = 8
-RG_MAX_GROUP = 8
+RG_MAX_GROUP = 16
 RG_GATHER_TICKETS = 8
 RG_ORDER_ASCENDING, RG_ORDER_FIRST_SEEN = 0, 1
 RG_STATIC_GATHER_MAX_ROWS = 1 << 20

@@ -124,6 +124,7 @@ rg_status rg_create(int device, rg_ctx** out) {
     const int threads = env_int("RG_PULL_THREADS", k.pull_threads);
     if (threads == 64 || threads == 256 || threads == 1024) k.pull_threads = threads;
     k.miss_blocks = env_int("RG_MISS_BLOCKS", k.miss_blocks);
+    { const char* v = getenv("RG_XCD_MAP"); if (v && *v == '0') k.xcd_map = 0; }
     const int mthreads = env_int("RG_MISS_THREADS", k.miss_threads);
     if (mthreads == 64 || mthreads == 256 || mthreads == 1024) k.miss_threads = mthreads;
     if (env_int("RG_PULL_ROWS", k.pull_rows) == 8) k.pull_rows = 8;
@@ -135,7 +136,7 @@ void rg_destroy(rg_ctx* ctx) {
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
-    RgBuf* bufs[] = {&ctx->visited, &ctx->fresh, &ctx->pos, &ctx->chunk_sum, &ctx->row_start, &ctx->row_deg, &ctx->first_key, &ctx->sched_keys, &ctx->sched_ids,
+    RgBuf* bufs[] = {&ctx->visited, &ctx->marked, &ctx->pos, &ctx->chunk_sum, &ctx->row_start, &ctx->row_deg, &ctx->first_key, &ctx->sched_keys, &ctx->sched_ids,
                      &ctx->topk_ctl, &ctx->topk_blk, &ctx->topk_caps, &ctx->pf_list, &ctx->pf_ctl, &ctx->plan_cursor, &ctx->gather_src, &ctx->miss_list,
                      &ctx->gather_ctl};
     for (RgBuf* b : bufs)

@@ -29,6 +29,7 @@ struct RgKnobs {
     int pull_rows = 4;                // RG_PULL_ROWS: rows in flight per lane group of the pull kernel (4 or 8)
     int miss_blocks = 192;            // RG_MISS_BLOCKS / RG_MISS_THREADS: grid of the miss-row kernel
     int miss_threads = 256;
+    int xcd_map = 1;                  // RG_XCD_MAP=0: batch-major workgroup order in the sampler instead of one batch per XCD
 };
 
 struct rg_ctx {
@@ -39,7 +40,7 @@ struct rg_ctx {
 
     // sampler scratch
     RgBuf visited;      // uint32[ceil(N/32)] bitmap of cumulative-frontier members
-    RgBuf fresh;        // uint32[ceil(N/32)] bitmap of ids first seen in the current hop (kept all-zero between hops)
+    RgBuf marked;       // uint32[ceil(N/32)] bitmap of every id a batch has met: frontier members and the current hop's picks
     RgBuf pos;          // int32[N] position of a node in the cumulative frontier (valid for members only)
     RgBuf chunk_sum;    // int32[] per-256-node chunk edge counts / bitmap block counts
     RgBuf row_start;    // int64[max_frontier] adjacency row start of every frontier node (current hop)
@@ -47,7 +48,7 @@ struct rg_ctx {
     RgBuf first_key;    // int32[N] per batch, first-seen node order only (see SampleScratch)
     int last_sample_group = 0;     // batches of the last completed sampling call: their `visited` bitmaps are the batches'
     int64_t last_sample_nodes = 0; // input-node sets (rg_access_histogram_sampled), on graphs of this many nodes
-    bool sampler_dirty = false;   // a sampling call was cut short by an error: `fresh` may hold stale bits
+    bool sampler_dirty = false;   // a sampling call was cut short by an error: the first-edge keys may hold stale entries
     // schedule scratch
     RgBuf sched_keys;   // uint64[npad]
     RgBuf sched_ids;    // int32[npad]

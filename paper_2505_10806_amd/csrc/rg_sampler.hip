@@ -2,7 +2,7 @@
 //
 // Data layout in HBM: CSR (row_ptr int32/int64, col_idx int32) is read-only; the batch's cumulative
 // frontier `nodes` grows tier by tier; membership lives in two N-bit bitmaps (`visited` = members of
-// the cumulative frontier, `fresh` = ids first seen in the current hop) and `pos[v]` maps a member to
+// the cumulative frontier, `marked` = those plus the ids the current hop has sampled) and `pos[v]` maps a member to
 // its position.  All sizes that depend on the data (frontier and edge counts) stay on the device:
 // launches are sized by static upper bounds and kernels read the actual counts.
 #include "rg_internal.h"
@@ -119,7 +119,7 @@ struct SampleGroup {
 
 struct SampleScratch {
     uint32_t* visited;                // [group][words]
-    uint32_t* fresh;                  // [group][words]
+    uint32_t* marked;                 // [group][words]
     int32_t* pos;                     // [group][num_nodes]
     int32_t* chunk_sum;               // [group][chunk_stride]
     int64_t* row_start;               // [group][frontier_stride]
@@ -127,7 +127,22 @@ struct SampleScratch {
     int32_t* first_key;               // [group][num_nodes], first-seen order only: 0x7FFFFFFF - (index of the first edge of
                                       // the current hop that names the node), 0 = not named (kept all-zero between hops)
     int64_t words, num_nodes, chunk_stride, frontier_stride;
+    int group;                        // batches in this call
+    int xcd_map;                      // 1: consecutive workgroups belong to consecutive batches (see rg_batch)
 };
+
+// Workgroup -> (batch, block within the batch) for the per-batch kernels, launched as one 1-D grid of blocks x group
+// workgroups.  The device hands consecutive workgroup ids to its 8 XCDs in turn, and every XCD has an L2 of its own.
+// With xcd_map, workgroup id w works on batch w % group: with a group of 8 all workgroups of one batch run on one XCD,
+// whose L2 then holds that batch's membership bitmaps (2 x N/8 bytes, probed at random by every sampled edge) instead
+// of every XCD holding a share of all eight.
+__device__ __forceinline__ int rg_batch(const SampleScratch& S) {
+    return S.xcd_map ? (int)(blockIdx.x % (unsigned)S.group) : (int)(blockIdx.x / (gridDim.x / (unsigned)S.group));
+}
+__device__ __forceinline__ unsigned rg_block(const SampleScratch& S) {
+    return S.xcd_map ? blockIdx.x / (unsigned)S.group : blockIdx.x % (gridDim.x / (unsigned)S.group);
+}
+__device__ __forceinline__ unsigned rg_blocks_per_batch(const SampleScratch& S) { return gridDim.x / (unsigned)S.group; }
 
 // ---------------------------------------------------------------------------- batch start
 __global__ void __launch_bounds__(256) k_clear_words(uint32_t* __restrict__ w, int64_t n) {
@@ -136,15 +151,17 @@ __global__ void __launch_bounds__(256) k_clear_words(uint32_t* __restrict__ w, i
 }
 
 __global__ void __launch_bounds__(256) k_mark_seeds(const SampleGroup G, const SampleScratch S) {
-    const int g = blockIdx.y;
+    const int g = rg_batch(S);
+    const unsigned blk = rg_block(S);
     const int num_seeds = G.num_seeds[g];
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = blk * blockDim.x + threadIdx.x;
     if (i == 0) { G.tier_off[g][0] = 0; G.tier_off[g][1] = num_seeds; }
     if (i >= num_seeds) return;
     const int32_t v = G.seeds[g][i];
     G.nodes[g][i] = v;
     S.pos[g * S.num_nodes + v] = i;
     atomicOr(&S.visited[g * S.words + ((uint32_t)v >> 5)], 1u << (v & 31));
+    atomicOr(&S.marked[g * S.words + ((uint32_t)v >> 5)], 1u << (v & 31));
 }
 
 // ---------------------------------------------------------------------------- per hop: sizes
@@ -154,9 +171,10 @@ template <typename RP>
 __global__ void __launch_bounds__(kChunk) k_hop_count(const RP* __restrict__ row_ptr, const SampleGroup G, const SampleScratch S,
                                                       int hop, int fanout) {
     __shared__ int smem[kChunk / RG_WAVE + 1];
-    const int g = blockIdx.y;
+    const int g = rg_batch(S);
+    const unsigned blk = rg_block(S);
     const int n_h = G.tier_off[g][hop + 1];
-    const int64_t first = (int64_t)blockIdx.x * kChunk;
+    const int64_t first = (int64_t)blk * kChunk;
     if (first >= n_h) return;                       // uniform per workgroup
     const int64_t i = first + threadIdx.x;
     int m = 0;
@@ -170,7 +188,7 @@ __global__ void __launch_bounds__(kChunk) k_hop_count(const RP* __restrict__ row
     int total;
     const int excl = rg_block_excl_scan<kChunk / RG_WAVE>(m, smem, &total);
     if (i < n_h) G.indptr[g][i] = excl;
-    if (threadIdx.x == 0) S.chunk_sum[g * S.chunk_stride + blockIdx.x] = total;
+    if (threadIdx.x == 0) S.chunk_sum[g * S.chunk_stride + blk] = total;
 }
 
 // In-place exclusive scan of data[0..n) by one workgroup; returns (to thread 0) the grand total.
@@ -195,7 +213,7 @@ __device__ __forceinline__ int rg_scan_in_place(int32_t* __restrict__ data, int6
 
 // Chunk totals of a hop -> exclusive offsets; the hop's edge total goes behind the last indptr entry.
 __global__ void __launch_bounds__(1024) k_scan_hop(const SampleGroup G, const SampleScratch S, int hop) {
-    const int g = blockIdx.y;
+    const int g = rg_batch(S);
     const int n_h = G.tier_off[g][hop + 1];
     const int total = rg_scan_in_place(S.chunk_sum + g * S.chunk_stride, ((int64_t)n_h + kChunk - 1) / kChunk);
     if (threadIdx.x == 0) {
@@ -206,17 +224,18 @@ __global__ void __launch_bounds__(1024) k_scan_hop(const SampleGroup G, const Sa
 
 // Per-block counts of fresh ids -> exclusive offsets; the end of the new tier goes to tier_off[hop + 2].
 __global__ void __launch_bounds__(1024) k_scan_tier(const SampleGroup G, const SampleScratch S, int hop, int tier_blocks) {
-    const int g = blockIdx.y;
+    const int g = rg_batch(S);
     const int total = rg_scan_in_place(S.chunk_sum + g * S.chunk_stride, tier_blocks);
     if (threadIdx.x == 0) G.tier_off[g][hop + 2] = G.tier_off[g][hop + 1] + total;
 }
 
 // ---------------------------------------------------------------------------- per hop: draw + read
-__device__ __forceinline__ void rg_mark_fresh(int32_t u, const uint32_t* __restrict__ visited, uint32_t* __restrict__ fresh) {
+// `marked` holds every id a batch has met so far: the frontier members (`visited`) plus the ids the current hop has
+// sampled.  One probe per sampled edge; the hop's new tier is marked & ~visited.
+__device__ __forceinline__ void rg_mark(int32_t u, uint32_t* __restrict__ marked) {
     const uint32_t w = (uint32_t)u >> 5, bit = 1u << (u & 31);
-    if (visited[w] & bit) return;
-    if (fresh[w] & bit) return;                       // a stale read only costs a redundant atomic
-    atomicOr(&fresh[w], bit);
+    if (marked[w] & bit) return;                      // a stale read only costs a redundant atomic
+    atomicOr(&marked[w], bit);
 }
 
 // First-seen order: instead of a bit, remember the first edge of the hop that names a node outside the frontier.
@@ -237,7 +256,8 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int32_t* __re
                                                             uint32_t k1, uint32_t epoch) {
     __shared__ uint32_t draws[RG_MAX_FANOUT];
     __shared__ uint32_t chosen[RG_MAX_FANOUT];
-    const int g = blockIdx.y;
+    const int g = rg_batch(S);
+    const unsigned blk = rg_block(S);
     const int n_h = G.tier_off[g][hop + 1];
     const int32_t* __restrict__ nodes = G.nodes[g];
     int32_t* __restrict__ indptr = G.indptr[g];
@@ -246,10 +266,10 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int32_t* __re
     const int64_t* __restrict__ row_start = S.row_start + g * S.frontier_stride;
     const int32_t* __restrict__ row_deg = S.row_deg + g * S.frontier_stride;
     const uint32_t* __restrict__ visited = S.visited + g * S.words;
-    uint32_t* __restrict__ fresh = S.fresh + g * S.words;
+    uint32_t* __restrict__ marked = S.marked + g * S.words;
     int32_t* __restrict__ first_key = FIRST_SEEN ? S.first_key + g * S.num_nodes : nullptr;
     const int lane = threadIdx.x;
-    for (int64_t i = blockIdx.x; i < n_h; i += gridDim.x) {
+    for (int64_t i = blk; i < n_h; i += rg_blocks_per_batch(S)) {
         const int32_t v = nodes[i];
         const int64_t start = row_start[i], deg = row_deg[i];
         const int base = indptr[i] + chunk_sum[i / kChunk];
@@ -259,7 +279,7 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int32_t* __re
             for (int64_t t = lane; t < deg; t += RG_WAVE) {
                 const int32_t u = col_idx[start + t];
                 nbr[base + t] = u;
-                if (FIRST_SEEN) rg_note_first_edge(u, base + t, visited, first_key); else rg_mark_fresh(u, visited, fresh);
+                if (FIRST_SEEN) rg_note_first_edge(u, base + t, visited, first_key); else rg_mark(u, marked);
             }
             continue;
         }
@@ -285,7 +305,7 @@ __global__ void __launch_bounds__(RG_WAVE) k_hop_sample_wave(const int32_t* __re
         for (int t = lane; t < k; t += RG_WAVE) {
             const int32_t u = col_idx[start + (int64_t)chosen[t]];
             nbr[base + t] = u;
-            if (FIRST_SEEN) rg_note_first_edge(u, base + t, visited, first_key); else rg_mark_fresh(u, visited, fresh);
+            if (FIRST_SEEN) rg_note_first_edge(u, base + t, visited, first_key); else rg_mark(u, marked);
         }
     }
 }
@@ -299,23 +319,24 @@ __global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const int32_t* __r
                                                               const SampleScratch S, int fanout, uint32_t hop, uint32_t k0,
                                                               uint32_t k1, uint32_t epoch) {
     extern __shared__ uint32_t staged[];                 // kChunk * fanout col_idx offsets
-    const int g = blockIdx.y;
+    const int g = rg_batch(S);
+    const unsigned blk = rg_block(S);
     const int n_h = G.tier_off[g][hop + 1];
-    const int64_t first = (int64_t)blockIdx.x * kChunk;
+    const int64_t first = (int64_t)blk * kChunk;
     if (first >= n_h) return;                            // uniform per workgroup
     int32_t* __restrict__ indptr = G.indptr[g];
     int32_t* __restrict__ nbr = G.nbr[g];
     const int32_t* __restrict__ chunk_sum = S.chunk_sum + g * S.chunk_stride;
     const uint32_t* __restrict__ visited = S.visited + g * S.words;
-    uint32_t* __restrict__ fresh = S.fresh + g * S.words;
+    uint32_t* __restrict__ marked = S.marked + g * S.words;
     int32_t* __restrict__ first_key = FIRST_SEEN ? S.first_key + g * S.num_nodes : nullptr;
     const int64_t i = first + threadIdx.x;
     const int k = fanout;
     // chunk_sum[b] is the exclusive offset of chunk b; the chunk's edge count follows from its successor
     // (or from the hop total behind the last indptr entry for the last chunk)
-    const int base = chunk_sum[blockIdx.x];
+    const int base = chunk_sum[blk];
     const bool last_chunk = first + kChunk >= n_h;
-    const int chunk_edges = (last_chunk ? indptr[n_h] : chunk_sum[blockIdx.x + 1]) - base;
+    const int chunk_edges = (last_chunk ? indptr[n_h] : chunk_sum[blk + 1]) - base;
     if (i < n_h) {
         const int32_t v = G.nodes[g][i];
         const int64_t start = S.row_start[g * S.frontier_stride + i], deg = S.row_deg[g * S.frontier_stride + i];
@@ -353,53 +374,55 @@ __global__ void __launch_bounds__(kChunk) k_hop_sample_thread(const int32_t* __r
     for (int e = threadIdx.x; e < chunk_edges; e += kChunk) {
         const int32_t u = col_idx[staged[e]];
         nbr[base + e] = u;
-        if (FIRST_SEEN) rg_note_first_edge(u, base + e, visited, first_key); else rg_mark_fresh(u, visited, fresh);
+        if (FIRST_SEEN) rg_note_first_edge(u, base + e, visited, first_key); else rg_mark(u, marked);
     }
 }
 
 // ---------------------------------------------------------------------------- per hop: new tier
 __global__ void __launch_bounds__(256) k_tier_count(const SampleScratch S) {
-    const int g = blockIdx.y;
-    const uint32_t* __restrict__ fresh = S.fresh + g * S.words;
-    const int64_t w0 = (int64_t)blockIdx.x * kWordsPerBlock + threadIdx.x * 4;
+    const int g = rg_batch(S);
+    const unsigned blk = rg_block(S);
+    const uint32_t* __restrict__ marked = S.marked + g * S.words;
+    const uint32_t* __restrict__ visited = S.visited + g * S.words;
+    const int64_t w0 = (int64_t)blk * kWordsPerBlock + threadIdx.x * 4;
     int c = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-        if (w0 + q < S.words) c += __popc(fresh[w0 + q]);
+        if (w0 + q < S.words) c += __popc(marked[w0 + q] & ~visited[w0 + q]);
     c = rg_wave_sum(c);
     __shared__ int part[4];
     if (rg_lane() == 0) part[threadIdx.x >> 6] = c;
     __syncthreads();
-    if (threadIdx.x == 0) S.chunk_sum[g * S.chunk_stride + blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+    if (threadIdx.x == 0) S.chunk_sum[g * S.chunk_stride + blk] = part[0] + part[1] + part[2] + part[3];
 }
 
-// Emit the ids of `fresh` in ascending order behind the current frontier, record their positions,
-// fold `fresh` into `visited` and leave `fresh` all-zero.  chunk_sum holds exclusive block offsets.
+// Emit the new ids (marked, not yet visited) in ascending order behind the current frontier, record their positions
+// and make them frontier members (visited = marked).  chunk_sum holds exclusive block offsets.
 __global__ void __launch_bounds__(256) k_tier_emit(const SampleGroup G, const SampleScratch S, int hop) {
     __shared__ int smem[256 / RG_WAVE + 1];
-    const int g = blockIdx.y;
-    uint32_t* __restrict__ fresh = S.fresh + g * S.words;
+    const int g = rg_batch(S);
+    const unsigned blk = rg_block(S);
+    const uint32_t* __restrict__ marked = S.marked + g * S.words;
     uint32_t* __restrict__ visited = S.visited + g * S.words;
     int32_t* __restrict__ nodes = G.nodes[g];
     int32_t* __restrict__ pos = S.pos + g * S.num_nodes;
-    const int64_t w0 = (int64_t)blockIdx.x * kWordsPerBlock + threadIdx.x * 4;
+    const int64_t w0 = (int64_t)blk * kWordsPerBlock + threadIdx.x * 4;
     uint32_t bits[4];
     int c = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        bits[q] = (w0 + q < S.words) ? fresh[w0 + q] : 0u;
+        bits[q] = (w0 + q < S.words) ? marked[w0 + q] & ~visited[w0 + q] : 0u;
         c += __popc(bits[q]);
     }
     int total;
     const int excl = rg_block_excl_scan<256 / RG_WAVE>(c, smem, &total);
     if (total == 0) return;                          // uniform: nothing fresh in this block
-    int out = G.tier_off[g][hop + 1] + S.chunk_sum[g * S.chunk_stride + blockIdx.x] + excl;
+    int out = G.tier_off[g][hop + 1] + S.chunk_sum[g * S.chunk_stride + blk] + excl;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         uint32_t b = bits[q];
         if (b == 0u) continue;
         visited[w0 + q] |= b;
-        fresh[w0 + q] = 0u;
         const int32_t id0 = (int32_t)((w0 + q) << 5);
         while (b) {
             const int bit = __ffs(b) - 1;
@@ -422,11 +445,12 @@ __device__ __forceinline__ bool rg_opens_node(const int32_t* __restrict__ nbr, c
 }
 
 __global__ void __launch_bounds__(256) k_first_seen_count(const SampleGroup G, const SampleScratch S, int hop) {
-    const int g = blockIdx.y;
+    const int g = rg_batch(S);
+    const unsigned blk = rg_block(S);
     const int32_t* __restrict__ nbr = G.nbr[g];
     const int32_t* __restrict__ first_key = S.first_key + g * S.num_nodes;
     const int64_t n_edges = G.indptr[g][G.tier_off[g][hop + 1]];
-    const int64_t e0 = (int64_t)blockIdx.x * kEdgesPerBlock + threadIdx.x * 4;
+    const int64_t e0 = (int64_t)blk * kEdgesPerBlock + threadIdx.x * 4;
     int c = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
@@ -435,22 +459,23 @@ __global__ void __launch_bounds__(256) k_first_seen_count(const SampleGroup G, c
     __shared__ int part[4];
     if (rg_lane() == 0) part[threadIdx.x >> 6] = c;
     __syncthreads();
-    if (threadIdx.x == 0) S.chunk_sum[g * S.chunk_stride + blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+    if (threadIdx.x == 0) S.chunk_sum[g * S.chunk_stride + blk] = part[0] + part[1] + part[2] + part[3];
 }
 
 // Appends the opened nodes behind the current frontier in edge order, records their positions, marks them visited
 // and clears their first-edge keys (the array is all-zero again when the hop is done).
 __global__ void __launch_bounds__(256) k_first_seen_emit(const SampleGroup G, const SampleScratch S, int hop) {
     __shared__ int smem[256 / RG_WAVE + 1];
-    const int g = blockIdx.y;
+    const int g = rg_batch(S);
+    const unsigned blk = rg_block(S);
     const int32_t* __restrict__ nbr = G.nbr[g];
     int32_t* __restrict__ first_key = S.first_key + g * S.num_nodes;
     uint32_t* __restrict__ visited = S.visited + g * S.words;
     int32_t* __restrict__ nodes = G.nodes[g];
     int32_t* __restrict__ pos = S.pos + g * S.num_nodes;
     const int64_t n_edges = G.indptr[g][G.tier_off[g][hop + 1]];
-    const int64_t e0 = (int64_t)blockIdx.x * kEdgesPerBlock + threadIdx.x * 4;
-    if ((int64_t)blockIdx.x * kEdgesPerBlock >= n_edges) return;          // uniform per workgroup
+    const int64_t e0 = (int64_t)blk * kEdgesPerBlock + threadIdx.x * 4;
+    if ((int64_t)blk * kEdgesPerBlock >= n_edges) return;          // uniform per workgroup
     int32_t u[4];
     bool opens[4];
     int c = 0;
@@ -466,7 +491,7 @@ __global__ void __launch_bounds__(256) k_first_seen_emit(const SampleGroup G, co
     int total;
     const int excl = rg_block_excl_scan<256 / RG_WAVE>(c, smem, &total);
     if (total == 0) return;                                               // uniform
-    int out = G.tier_off[g][hop + 1] + S.chunk_sum[g * S.chunk_stride + blockIdx.x] + excl;
+    int out = G.tier_off[g][hop + 1] + S.chunk_sum[g * S.chunk_stride + blk] + excl;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
         if (opens[q]) {
@@ -480,13 +505,14 @@ __global__ void __launch_bounds__(256) k_first_seen_emit(const SampleGroup G, co
 
 // nbr_local[e] = position of nbr[e] in the extended frontier; the hop's edge count is indptr[n_h].
 __global__ void __launch_bounds__(256) k_relabel(const SampleGroup G, const SampleScratch S, int hop) {
-    const int g = blockIdx.y;
+    const int g = rg_batch(S);
+    const unsigned blk = rg_block(S);
     int32_t* __restrict__ nbr_local = G.nbr_local[g];
     if (!nbr_local) return;
     const int32_t* __restrict__ nbr = G.nbr[g];
     const int32_t* __restrict__ pos = S.pos + g * S.num_nodes;
     const int n = G.indptr[g][G.tier_off[g][hop + 1]];
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x)
+    for (int64_t e = (int64_t)blk * blockDim.x + threadIdx.x; e < n; e += (int64_t)rg_blocks_per_batch(S) * blockDim.x)
         nbr_local[e] = pos[nbr[e]];
 }
 
@@ -499,6 +525,8 @@ void sampler_scratch_shape(int64_t N, int64_t frontier, int64_t max_edges, Sampl
     S.chunk_stride = rg_max64(rg_max64(rg_div_up(S.frontier_stride, kChunk), rg_div_up(max_edges, kEdgesPerBlock)),
                               rg_max64(1, rg_div_up(S.words, kWordsPerBlock))) + 2;
     S.first_key = nullptr;
+    S.group = 1;
+    S.xcd_map = 1;
 }
 
 // ---------------------------------------------------------------------------- access counts straight from the bitmaps
@@ -552,13 +580,12 @@ rg_status rg_sampler_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontie
     const size_t g = (size_t)group;
     rg_status st;
     if ((st = rg_ensure(ctx, ctx->visited, g * S.words * 4)) != RG_OK) return st;
-    // `fresh` must be all-zero between hops: a new allocation starts zeroed and every hop leaves it zeroed
-    if ((st = rg_ensure(ctx, ctx->fresh, g * S.words * 4, true)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->marked, g * S.words * 4)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->pos, g * (size_t)num_nodes * 4)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->chunk_sum, g * S.chunk_stride * 4)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->row_start, g * S.frontier_stride * 8)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->row_deg, g * S.frontier_stride * 4)) != RG_OK) return st;
-    // first-seen order: the first-edge keys must be all-zero between hops, like `fresh`
+    // first-seen order: the first-edge keys must be all-zero between hops (every hop leaves them zeroed)
     if (first_seen && (st = rg_ensure(ctx, ctx->first_key, g * (size_t)num_nodes * 4, true)) != RG_OK) return st;
     return RG_OK;
 }
@@ -668,8 +695,10 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
     rg_status st = rg_sampler_reserve(ctx, N, fub_max[num_hops], group, max_edges, first_seen);
     if (st != RG_OK) return st;
     S.first_key = first_seen ? (int32_t*)ctx->first_key.p : nullptr;
+    S.group = group;
+    S.xcd_map = ctx->knobs.xcd_map;
     S.visited = (uint32_t*)ctx->visited.p;
-    S.fresh = (uint32_t*)ctx->fresh.p;
+    S.marked = (uint32_t*)ctx->marked.p;
     S.pos = (int32_t*)ctx->pos.p;
     S.chunk_sum = (int32_t*)ctx->chunk_sum.p;
     S.row_start = (int64_t*)ctx->row_start.p;
@@ -689,22 +718,21 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
     const unsigned ug = (unsigned)group;
 
     if (words > 0) {
-        // the whole allocation is cleared: a smaller group after a larger one must not find stale bits
-        const int64_t fresh_words = (int64_t)(ctx->fresh.bytes / 4), visited_words = (int64_t)group * words;
-        if (ctx->sampler_dirty) {        // an earlier call stopped between a draw kernel and its tier emit
-            k_clear_words<<<(int)rg_div_up(fresh_words, 256), 256, 0, s>>>(S.fresh, fresh_words);
-            RG_LAUNCH_CHECK(ctx, "k_clear_words");
+        if (ctx->sampler_dirty && ctx->first_key.bytes) {   // an earlier first-seen call stopped between a draw kernel and its emit
             const int64_t key_words = (int64_t)(ctx->first_key.bytes / 4);
-            if (key_words > 0) {
-                k_clear_words<<<(int)rg_div_up(key_words, 256), 256, 0, s>>>((uint32_t*)ctx->first_key.p, key_words);
-                RG_LAUNCH_CHECK(ctx, "k_clear_words");
-            }
+            k_clear_words<<<(int)rg_div_up(key_words, 256), 256, 0, s>>>((uint32_t*)ctx->first_key.p, key_words);
+            RG_LAUNCH_CHECK(ctx, "k_clear_words");
         }
         ctx->sampler_dirty = true;       // cleared again when every launch of this call has been queued
-        k_clear_words<<<(int)rg_div_up(visited_words, 256), 256, 0, s>>>(S.visited, visited_words);
+        const int64_t group_words = (int64_t)group * words;
+        k_clear_words<<<(int)rg_div_up(group_words, 256), 256, 0, s>>>(S.visited, group_words);
         RG_LAUNCH_CHECK(ctx, "k_clear_words");
+        if (!first_seen) {
+            k_clear_words<<<(int)rg_div_up(group_words, 256), 256, 0, s>>>(S.marked, group_words);
+            RG_LAUNCH_CHECK(ctx, "k_clear_words");
+        }
     }
-    k_mark_seeds<<<dim3((unsigned)grid_for(seeds_max, 256, 1 << 30), ug), 256, 0, s>>>(G, S);
+    k_mark_seeds<<<(unsigned)(grid_for(seeds_max, 256, 1 << 30)) * ug, 256, 0, s>>>(G, S);
     RG_LAUNCH_CHECK(ctx, "k_mark_seeds");
 
     for (int h = 0; h < num_hops; ++h) {
@@ -718,12 +746,12 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
         }
         const unsigned count_blocks = (unsigned)grid_for(fub_max[h], kChunk, 1ll << 30);
         if (rp64)
-            k_hop_count<int64_t><<<dim3(count_blocks, ug), kChunk, 0, s>>>((const int64_t*)csr->row_ptr, G, S, h, fanouts[h]);
+            k_hop_count<int64_t><<<count_blocks * ug, kChunk, 0, s>>>((const int64_t*)csr->row_ptr, G, S, h, fanouts[h]);
         else
-            k_hop_count<int32_t><<<dim3(count_blocks, ug), kChunk, 0, s>>>((const int32_t*)csr->row_ptr, G, S, h, fanouts[h]);
+            k_hop_count<int32_t><<<count_blocks * ug, kChunk, 0, s>>>((const int32_t*)csr->row_ptr, G, S, h, fanouts[h]);
         RG_LAUNCH_CHECK(ctx, "k_hop_count");
         // chunk sums -> exclusive offsets; total edge count -> indptr[n_h]
-        k_scan_hop<<<dim3(1, ug), 1024, 0, s>>>(G, S, h);
+        k_scan_hop<<<ug, 1024, 0, s>>>(G, S, h);
         RG_LAUNCH_CHECK(ctx, "k_scan_hop");
 
         const int tok = rg_prof_begin(ctx, RG_K_SAMPLE, s);
@@ -732,16 +760,16 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
             const int kmax = F <= 8 ? 8 : (F <= 16 ? 16 : 32);
             const size_t lds = (size_t)kChunk * F * sizeof(uint32_t);
 #define RG_LAUNCH_FAST(KM, FS)                                                                                        \
-    k_hop_sample_thread<KM, FS><<<dim3(count_blocks, ug), kChunk, lds, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch)
+    k_hop_sample_thread<KM, FS><<<count_blocks * ug, kChunk, lds, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch)
             if (first_seen) { if (kmax == 8) RG_LAUNCH_FAST(8, true); else if (kmax == 16) RG_LAUNCH_FAST(16, true); else RG_LAUNCH_FAST(32, true); }
             else { if (kmax == 8) RG_LAUNCH_FAST(8, false); else if (kmax == 16) RG_LAUNCH_FAST(16, false); else RG_LAUNCH_FAST(32, false); }
 #undef RG_LAUNCH_FAST
         } else {
             const unsigned sample_blocks = (unsigned)grid_for(fub_max[h], 1, (int64_t)ctx->num_cus * 64);
             if (first_seen)
-                k_hop_sample_wave<true><<<dim3(sample_blocks, ug), RG_WAVE, 0, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch);
+                k_hop_sample_wave<true><<<sample_blocks * ug, RG_WAVE, 0, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch);
             else
-                k_hop_sample_wave<false><<<dim3(sample_blocks, ug), RG_WAVE, 0, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch);
+                k_hop_sample_wave<false><<<sample_blocks * ug, RG_WAVE, 0, s>>>(csr->col_idx, G, S, F, (uint32_t)h, k0, k1, epoch);
         }
         rg_prof_end(ctx, tok, s);
         RG_LAUNCH_CHECK(ctx, "k_hop_sample");
@@ -749,24 +777,24 @@ rg_status rg_sample_blocks_group(rg_ctx* ctx, const rg_csr* csr, int32_t group, 
         if (first_seen) {
             // new tier: edges that open a node, counted per block of the edge list, scanned, emitted in edge order
             const int fs_blocks = (int)rg_max64(1, rg_div_up(eub_max[h], kEdgesPerBlock));
-            k_first_seen_count<<<dim3((unsigned)fs_blocks, ug), 256, 0, s>>>(G, S, h);
+            k_first_seen_count<<<(unsigned)(fs_blocks) * ug, 256, 0, s>>>(G, S, h);
             RG_LAUNCH_CHECK(ctx, "k_first_seen_count");
-            k_scan_tier<<<dim3(1, ug), 1024, 0, s>>>(G, S, h, fs_blocks);
+            k_scan_tier<<<ug, 1024, 0, s>>>(G, S, h, fs_blocks);
             RG_LAUNCH_CHECK(ctx, "k_scan_tier");
-            k_first_seen_emit<<<dim3((unsigned)fs_blocks, ug), 256, 0, s>>>(G, S, h);
+            k_first_seen_emit<<<(unsigned)(fs_blocks) * ug, 256, 0, s>>>(G, S, h);
             RG_LAUNCH_CHECK(ctx, "k_first_seen_emit");
         } else {
             // new tier: count fresh bits per block, scan, emit ascending
-            k_tier_count<<<dim3((unsigned)tier_blocks, ug), 256, 0, s>>>(S);
+            k_tier_count<<<(unsigned)(tier_blocks) * ug, 256, 0, s>>>(S);
             RG_LAUNCH_CHECK(ctx, "k_tier_count");
-            k_scan_tier<<<dim3(1, ug), 1024, 0, s>>>(G, S, h, tier_blocks);
+            k_scan_tier<<<ug, 1024, 0, s>>>(G, S, h, tier_blocks);
             RG_LAUNCH_CHECK(ctx, "k_scan_tier");
-            k_tier_emit<<<dim3((unsigned)tier_blocks, ug), 256, 0, s>>>(G, S, h);
+            k_tier_emit<<<(unsigned)(tier_blocks) * ug, 256, 0, s>>>(G, S, h);
             RG_LAUNCH_CHECK(ctx, "k_tier_emit");
         }
 
         if (any_local && eub_max[h] > 0) {
-            k_relabel<<<dim3((unsigned)grid_for(eub_max[h], 256, (int64_t)ctx->num_cus * 16), ug), 256, 0, s>>>(G, S, h);
+            k_relabel<<<(unsigned)(grid_for(eub_max[h], 256, (int64_t)ctx->num_cus * 16)) * ug, 256, 0, s>>>(G, S, h);
             RG_LAUNCH_CHECK(ctx, "k_relabel");
         }
     }

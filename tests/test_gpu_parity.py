@@ -122,7 +122,7 @@ def test_blocks_on_generated_csr(B, ctx):
 
 
 @pytest.mark.parametrize("first_seen", [False, True])
-@pytest.mark.parametrize("group", [1, 2, 3, 8])
+@pytest.mark.parametrize("group", [1, 2, 3, 8, 16])
 @pytest.mark.parametrize("fanouts", [(5, 3), (40, 2), (-1, 4)])
 def test_blocks_group_equals_separate_batches(B, ctx, group, fanouts, first_seen):
     """One call for several batches (different seed counts, one of them empty) gives each batch exactly the block
@@ -132,7 +132,7 @@ def test_blocks_group_equals_separate_batches(B, ctx, group, fanouts, first_seen
     rng = np.random.default_rng(group * 10 + len(fanouts))
     rp, ci = _handmade_graph(700, 0.7, 35, 0.015, rng)
     csr = B.CsrGraph(torch.as_tensor(rp, device=DEV), _i32(ci))
-    sizes = [64, 0, 200, 1, 37, 128, 5, 90][:group]
+    sizes = [64, 0, 200, 1, 37, 128, 5, 90, 17, 300, 2, 64, 9, 111, 40, 256][:group]
     seeds_np = [rng.choice(700, size=n, replace=False).astype(np.int32) for n in sizes]
     outs = [B.BlockBuffers(700, ci.size, max(n, 1), fanouts, DEV) for n in sizes]
     ctx.sample_blocks_group(csr, [_i32(x) if x.size else torch.empty(0, dtype=torch.int32, device=DEV) for x in seeds_np],
@@ -152,7 +152,7 @@ def test_blocks_group_equals_separate_batches(B, ctx, group, fanouts, first_seen
     assert np.array_equal(counts.cpu().numpy().view(np.uint32), counts_orc), "counts from the membership bitmaps"
     assert np.array_equal(first.cpu().numpy().view(np.uint32), first_orc), "first batch from the membership bitmaps"
     with pytest.raises(B.RgError) as e:                    # a group size that is not the sampled one is refused
-        ctx.access_histogram_sampled(group % 8 + 1, counts)
+        ctx.access_histogram_sampled(group % 16 + 1, counts)
     assert e.value.status == B.RG_ERR_STATE
     # a single batch afterwards on the same context
     hip = _run_blocks(B, ctx, csr, seeds_np[0], fanouts, 7, 1, first_seen=first_seen)
