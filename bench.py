@@ -215,6 +215,11 @@ def main():
                          "membership bitmaps after every group, or one global-atomic pass per batch")
     ap.add_argument("--node-order", choices=["ascending", "first_seen"], default="ascending",
                     help="order of the nodes inside a tier of a block")
+    ap.add_argument("--no-mirror", action="store_true",
+                    help="do not lay a cache that can hold the whole remote partition out as its mirror (rows are then pulled "
+                         "after TopHot, from the prefetch plan, instead of while the batches are being sampled)")
+    ap.add_argument("--keep-rows", action="store_true",
+                    help="mirrored cache only: rows pulled in an earlier epoch stay resident instead of every epoch starting cold")
     ap.add_argument("--period-epochs", type=int, default=1,
                     help="epochs precomputed, counted and cached together (1: a cache per epoch from that epoch's counts; "
                          "E: one cache from the counts of E epochs, as Alg. 1 lines 1-4 read)")
@@ -273,6 +278,7 @@ def main():
                              sampler_streams=args.sampler_streams, double_buffer=(multi_epoch and not args.no_double_buffer),
                              planned_prefetch=not args.no_plan, sample_group=args.sample_group,
                              histogram=args.histogram, node_order=args.node_order, period_epochs=args.period_epochs,
+                             mirror_cache=False if args.no_mirror else None, keep_rows=args.keep_rows,
                              consumer=None if args.consumer == "none" else args.consumer,
                              queue_depth=args.queue_depth if args.consumer != "none" else 1)
 
@@ -310,7 +316,7 @@ def main():
     n_local, n_hit, n_miss = [int(x) for x in totals["stats"].cpu().tolist()]
     rows = totals["rows"]
     assert rows == n_local + n_hit + n_miss, "gather statistics do not add up"
-    cached_rows = int(totals["cached"].item())
+    cached_rows = int(totals["cached"].item()) if not args.keep_rows else 0    # with kept rows fewer than the selected rows are pulled
     m_ms, _ = prof["gather_miss"]
     f_ms, _ = prof["cache_fill"]
     per_row_traffic, traffic_source = recorded_traffic(cfg.name)
@@ -337,11 +343,12 @@ def main():
                    "fanouts": list(cfg.fanouts), "batch_size": cfg.batch_size, "batches_per_epoch": bpe,
                    "epochs_per_rep": totals["epochs"],
                    "cache_capacity_rows": wl.capacity_rows, "miss_stream": "shared" if args.one_stream else "separate",
-                   "cache_fill": "bulk" if args.bulk_fill else "prefetch by first use",
+                   "cache_fill": "bulk" if args.bulk_fill else ("pulled as the batches are sampled" if pipe.mirror else "prefetch by first use"),
                    "sampler_streams": args.sampler_streams, "sample_group": args.sample_group,
                    "double_buffered_cache": bool(multi_epoch and not args.no_double_buffer),
                    "planned_prefetch": pipe.planned, "consumer": args.consumer, "queue_depth": pipe.queue_depth,
                    "histogram": pipe.histogram, "node_order": args.node_order, "period_epochs": pipe.period_epochs,
+                   "mirrored_cache": pipe.mirror, "rows_kept_across_epochs": pipe.keep_rows,
                    "GPU_MAX_HW_QUEUES": os.environ.get("GPU_MAX_HW_QUEUES"), "GPU_MAX_HW_QUEUES_set_by": "user" if HWQ_SET_BY_USER else "bench.py"},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": roof["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": roof["frac"],

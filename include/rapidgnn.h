@@ -234,6 +234,7 @@ RG_API rg_status rg_access_histogram_sampled(rg_ctx* ctx, int32_t group, const i
  * the node (one bulk pull over the host link) and, if `filled` is given, every selected slot is
  * marked resident.  With remote_store == NULL only the selection is made and `filled` (required
  * then) is cleared: rows are pulled later, batch by batch, by rg_prefetch_cache_rows.
+ * (A mirrored cache, see rg_cache.mirror_rows, is select-only and keeps `filled`.)
  */
 typedef struct {
     int32_t* cache_ids;       /* device int32[capacity_rows] */
@@ -243,6 +244,17 @@ typedef struct {
     int32_t* loc;             /* device int32[num_nodes] location words */
     int64_t* num_cached;      /* device int64[1], written by rg_build_cache */
     uint32_t* filled;         /* device uint32[ceil(min(capacity_rows, num_nodes) / 32)] or NULL: bit s set = row of slot s is resident */
+    /* Mirrored layout, for a cache that can hold the whole remote partition (capacity_rows >= number of rows of the
+     * remote store).  Every remote row a batch names will be selected then, so where it goes can be fixed before
+     * TopHot has run: mirror_rows = number of rows of the remote store (0 = the layout above) puts the row of a
+     * cached node at cache_rows[its remote-store row] instead of cache_rows[its slot]; cache_ids, loc, num_cached
+     * and the statistics keep their meaning.  `filled` is then indexed by remote-store row; rg_build_cache (select
+     * only) leaves it alone, so rows pulled while the batches were still being sampled, or in an earlier period,
+     * stay valid: the caller clears it to start cold.  rg_prefetch_cache_rows pulls the not-yet-resident remote rows
+     * a batch names and needs no TopHot result; the planned prefetch does not apply.  home: the home words
+     * (device int32[num_nodes]), required when mirror_rows > 0. */
+    int64_t mirror_rows;
+    const int32_t* home;
 } rg_cache;
 
 /* counts: device uint32[num_nodes]; home: device int32[num_nodes] (never modified);

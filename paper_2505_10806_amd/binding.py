@@ -50,7 +50,8 @@ class rg_blocks(ctypes.Structure):
 
 class rg_cache(ctypes.Structure):
     _fields_ = [("cache_ids", c_p), ("cache_rows", c_p), ("capacity_rows", c_i64),
-                ("row_stride", c_i64), ("loc", c_p), ("num_cached", c_p), ("filled", c_p)]
+                ("row_stride", c_i64), ("loc", c_p), ("num_cached", c_p), ("filled", c_p),
+                ("mirror_rows", c_i64), ("home", c_p)]
 
 
 class rg_prefetch_plan(ctypes.Structure):
@@ -434,15 +435,43 @@ class BlockBuffers:
 class FeatureCache:
     """rg_cache over caller-owned cuda tensors."""
 
-    def __init__(self, num_nodes, capacity_rows, row_stride, device):
+    def __init__(self, num_nodes, capacity_rows, row_stride, device, mirror_rows=0, home=None):
+        """mirror_rows > 0 (with the home words): the cache holds the whole remote partition and is laid out as its
+        mirror (row of a cached node = its remote-store row)."""
         self.capacity_rows = int(capacity_rows)
+        if mirror_rows and (home is None or mirror_rows > self.capacity_rows):
+            raise ValueError("a mirrored cache needs the home words and capacity_rows >= mirror_rows")
+        self.mirror_rows, self.home = int(mirror_rows), home
         self.cache_ids = torch.empty(max(self.capacity_rows, 1), dtype=torch.int32, device=device)
         self.cache_rows = torch.empty(max(self.capacity_rows, 1), int(row_stride), dtype=torch.float32, device=device)
         self.loc = torch.empty(max(num_nodes, 1), dtype=torch.int32, device=device)
         self.num_cached = torch.zeros(1, dtype=torch.int64, device=device)
         self.filled = torch.zeros(max((min(self.capacity_rows, num_nodes) + 31) // 32, 1), dtype=torch.int32, device=device)
         self.c_struct = rg_cache(self.cache_ids.data_ptr(), self.cache_rows.data_ptr(), self.capacity_rows,
-                                 int(row_stride), self.loc.data_ptr(), self.num_cached.data_ptr(), self.filled.data_ptr())
+                                 int(row_stride), self.loc.data_ptr(), self.num_cached.data_ptr(), self.filled.data_ptr(),
+                                 self.mirror_rows, _ptr(home, torch.int32, "cuda", "home") if self.mirror_rows else None)
+
+    @classmethod
+    def sharing_rows(cls, other, num_nodes, device):
+        """A second mirrored cache (own ids, location table and count) over the rows and resident bits of `other`."""
+        self = cls.__new__(cls)
+        self.capacity_rows, self.mirror_rows, self.home = other.capacity_rows, other.mirror_rows, other.home
+        if not self.mirror_rows:
+            raise ValueError("only mirrored caches can share their rows")
+        self.cache_ids = torch.empty_like(other.cache_ids)
+        self.cache_rows, self.filled = other.cache_rows, other.filled
+        self.loc = torch.empty(max(num_nodes, 1), dtype=torch.int32, device=device)
+        self.num_cached = torch.zeros(1, dtype=torch.int64, device=device)
+        self.c_struct = rg_cache(self.cache_ids.data_ptr(), self.cache_rows.data_ptr(), self.capacity_rows,
+                                 other.c_struct.row_stride, self.loc.data_ptr(), self.num_cached.data_ptr(), self.filled.data_ptr(),
+                                 self.mirror_rows, other.c_struct.home)
+        return self
+
+    def rows_of(self, node_ids):
+        """Rows of cache_rows that hold the listed cached nodes (int64 cuda tensor), for either layout."""
+        ids = node_ids.long()
+        words = (self.home if self.mirror_rows else self.loc)[ids].long() & 0x3FFFFFFF
+        return words
 
 
 class PrefetchPlan:

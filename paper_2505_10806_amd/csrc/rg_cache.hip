@@ -501,7 +501,7 @@ __global__ void k_prefetch_reset(uint32_t* __restrict__ pctl) {
 __global__ void __launch_bounds__(256) k_prefetch_select(const int32_t* __restrict__ nodes, int64_t n, const int32_t* __restrict__ n_dev,
                                                          const int32_t* __restrict__ loc, const int32_t* __restrict__ home,
                                                          uint32_t* __restrict__ filled, int32_t* __restrict__ list,
-                                                         uint32_t* __restrict__ pctl) {
+                                                         uint32_t* __restrict__ pctl, int mirror) {
     __shared__ int smem[256 / RG_WAVE + 1];
     __shared__ uint32_t base_s;
     int64_t n_act = n;
@@ -512,9 +512,17 @@ __global__ void __launch_bounds__(256) k_prefetch_select(const int32_t* __restri
     uint32_t slot = 0u, rrow = 0u;
     if (i < n_act) {
         const int32_t v = nodes[i];
-        const uint32_t w = (uint32_t)loc[v];
-        if ((w >> RG_TAG_SHIFT) == RG_TAG_CACHE) {
+        bool wanted;
+        if (mirror) {       // every remote row a batch names will be cached, at the row it has in the remote store
+            const uint32_t hw = (uint32_t)home[v];
+            wanted = (hw >> RG_TAG_SHIFT) == RG_TAG_REMOTE;
+            slot = rrow = hw & RG_ROW_MASK;
+        } else {
+            const uint32_t w = (uint32_t)loc[v];
+            wanted = (w >> RG_TAG_SHIFT) == RG_TAG_CACHE;
             slot = w & RG_ROW_MASK;
+        }
+        if (wanted) {
             const uint32_t bit = 1u << (slot & 31u);
             if (!(filled[slot >> 5] & bit)) {
                 const uint32_t old = atomicOr(&filled[slot >> 5], bit);
@@ -812,6 +820,10 @@ rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32_t* hom
     RG_REQUIRE(ctx, remote_store || cache->filled || cache->capacity_rows == 0 || num_nodes == 0,
                "rg_build_cache: select-only mode (remote_store == NULL) needs cache->filled");
     RG_REQUIRE(ctx, cache->num_cached, "rg_build_cache: num_cached is NULL");
+    RG_REQUIRE(ctx, cache->mirror_rows >= 0 && cache->mirror_rows <= cache->capacity_rows,
+               "rg_build_cache: mirror_rows = %lld exceeds capacity_rows = %lld", (long long)cache->mirror_rows, (long long)cache->capacity_rows);
+    RG_REQUIRE(ctx, cache->mirror_rows == 0 || (!remote_store && cache->home),
+               "rg_build_cache: a mirrored cache is filled by rg_prefetch_cache_rows (remote_store must be NULL) and needs cache->home");
     RG_REQUIRE(ctx, num_nodes == 0 || (counts && home && cache->loc), "rg_build_cache: null node array");
     const bool may_select = cache->capacity_rows > 0 && num_nodes > 0;
     RG_REQUIRE(ctx, !may_select || (cache->cache_ids && cache->cache_rows), "rg_build_cache: null cache buffer");
@@ -869,7 +881,7 @@ rg_status rg_build_cache(rg_ctx* ctx, const uint32_t* counts, const int32_t* hom
         rg_prof_end(ctx, tok, s);
         RG_LAUNCH_CHECK(ctx, "k_cache_fill");
     }
-    if (cache->filled && filled_words > 0) {
+    if (cache->filled && filled_words > 0 && cache->mirror_rows == 0) {
         k_set_filled<<<(int)rg_div_up(filled_words, 256), 256, 0, s>>>(cache->filled, filled_words, cache->num_cached, remote_store ? 1 : 0);
         RG_LAUNCH_CHECK(ctx, "k_set_filled");
     }
@@ -934,7 +946,10 @@ rg_status rg_prefetch_cache_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_
     if (!ctx) return RG_ERR_INVALID_ARG;
     RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "rg_prefetch_cache_rows: n = %lld out of range", (long long)n);
     if (n == 0) return RG_OK;
-    RG_REQUIRE(ctx, cache && cache->loc && cache->filled && cache->cache_rows, "rg_prefetch_cache_rows: cache needs loc, filled and cache_rows");
+    RG_REQUIRE(ctx, cache && cache->filled && cache->cache_rows && (cache->loc || cache->mirror_rows > 0),
+               "rg_prefetch_cache_rows: cache needs filled, cache_rows and (unless mirrored) loc");
+    RG_REQUIRE(ctx, cache->mirror_rows >= 0 && cache->mirror_rows <= cache->capacity_rows,
+               "rg_prefetch_cache_rows: mirror_rows = %lld exceeds capacity_rows = %lld", (long long)cache->mirror_rows, (long long)cache->capacity_rows);
     RG_REQUIRE(ctx, input_nodes && home && remote_store, "rg_prefetch_cache_rows: null pointer");
     RG_REQUIRE(ctx, dim >= 1 && cache->row_stride >= dim && remote_stride >= dim, "rg_prefetch_cache_rows: bad dim / stride");
     RG_HIP(ctx, hipSetDevice(ctx->device));
@@ -947,16 +962,18 @@ rg_status rg_prefetch_cache_rows(rg_ctx* ctx, const int32_t* input_nodes, int64_
     int32_t* list = (int32_t*)ctx->pf_list.p;
     k_prefetch_reset<<<1, 64, 0, s>>>(pctl);
     RG_LAUNCH_CHECK(ctx, "k_prefetch_reset");
-    k_prefetch_select<<<(int)rg_div_up(n, 256), 256, 0, s>>>(input_nodes, n, n_dev, cache->loc, home, cache->filled, list, pctl);
+    const bool mirror = cache->mirror_rows > 0;
+    k_prefetch_select<<<(int)rg_div_up(n, 256), 256, 0, s>>>(input_nodes, n, n_dev, cache->loc, home, cache->filled, list, pctl, mirror ? 1 : 0);
     RG_LAUNCH_CHECK(ctx, "k_prefetch_select");
     return launch_list_copy(ctx, list, pctl, remote_store, remote_stride, cache->cache_rows, cache->row_stride,
-                            cache->capacity_rows, dim, n, ctx->knobs.pull_blocks, ctx->knobs.pull_threads, s);
+                            mirror ? cache->mirror_rows : cache->capacity_rows, dim, n, ctx->knobs.pull_blocks, ctx->knobs.pull_threads, s);
 }
 
 rg_status rg_plan_prefetch(rg_ctx* ctx, const rg_cache* cache, const int32_t* home, const uint32_t* first_batch,
                            int64_t num_nodes, const rg_prefetch_plan* plan, void* stream) {
     if (!ctx) return RG_ERR_INVALID_ARG;
     RG_REQUIRE(ctx, cache && cache->num_cached && plan && plan->offsets, "rg_plan_prefetch: null cache / plan");
+    RG_REQUIRE(ctx, cache->mirror_rows == 0, "rg_plan_prefetch: a mirrored cache is filled by rg_prefetch_cache_rows");
     RG_REQUIRE(ctx, plan->num_batches >= 0 && plan->num_batches <= 65535, "rg_plan_prefetch: num_batches not in [0, 65535]");
     RG_REQUIRE(ctx, num_nodes >= 0 && cache->capacity_rows >= 0, "rg_plan_prefetch: negative size");
     const int64_t rows_ub = rg_min64(cache->capacity_rows, num_nodes);
@@ -1012,6 +1029,7 @@ rg_status rg_prefetch_planned(rg_ctx* ctx, const rg_prefetch_plan* plan, int32_t
     RG_REQUIRE(ctx, plan && plan->offsets && plan->list, "rg_prefetch_planned: incomplete plan");
     RG_REQUIRE(ctx, batch >= 0 && batch <= plan->num_batches, "rg_prefetch_planned: batch = %d not in [0, %d]", batch, plan->num_batches);
     RG_REQUIRE(ctx, cache && cache->cache_rows && cache->filled && remote_store, "rg_prefetch_planned: null cache rows / filled / store");
+    RG_REQUIRE(ctx, cache->mirror_rows == 0, "rg_prefetch_planned: a mirrored cache is filled by rg_prefetch_cache_rows");
     RG_REQUIRE(ctx, dim >= 1 && cache->row_stride >= dim && remote_stride >= dim, "rg_prefetch_planned: bad dim / stride");
     RG_HIP(ctx, hipSetDevice(ctx->device));
     { const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_prefetch_planned: remote_store"); if (chk != RG_OK) return chk; }

@@ -78,7 +78,10 @@ __global__ void k_gather_reset(const ClassifyGroup C) {
 // loc[] lookups in flight; the miss pairs of a workgroup are appended in that visiting order (any order is valid).
 constexpr int kClassifyRows = 4;
 
-__global__ void __launch_bounds__(256) k_classify(const ClassifyGroup C, const int32_t* __restrict__ loc) {
+// mirror_home != NULL: the cache is laid out as a mirror of the remote store, so a cached node's row is found at its
+// remote-store row (from its home word) instead of at its slot.
+__global__ void __launch_bounds__(256) k_classify(const ClassifyGroup C, const int32_t* __restrict__ loc,
+                                                  const int32_t* __restrict__ mirror_home) {
     __shared__ int smem[256 / RG_WAVE + 1];
     __shared__ int cls[3][4];
     __shared__ uint32_t miss_base;
@@ -100,6 +103,12 @@ __global__ void __launch_bounds__(256) k_classify(const ClassifyGroup C, const i
     }
 #pragma unroll
     for (int k = 0; k < kClassifyRows; ++k) w[k] = v[k] >= 0 ? (uint32_t)loc[v[k]] : 0xFFFFFFFFu;   // tag 3 = no row
+    if (mirror_home) {
+#pragma unroll
+        for (int k = 0; k < kClassifyRows; ++k)
+            if ((w[k] >> RG_TAG_SHIFT) == RG_TAG_CACHE)
+                w[k] = (RG_TAG_CACHE << RG_TAG_SHIFT) | ((uint32_t)mirror_home[v[k]] & RG_ROW_MASK);
+    }
     int c_local = 0, c_hit = 0, n_miss = 0;
 #pragma unroll
     for (int k = 0; k < kClassifyRows; ++k) {
@@ -256,7 +265,8 @@ rg_status launch_classify(rg_ctx* ctx, int count, const int32_t* const* input_no
     k_gather_reset<<<count, 64, 0, s>>>(C);
     RG_LAUNCH_CHECK(ctx, "k_gather_reset");
     if (n_max > 0) {
-        k_classify<<<dim3((unsigned)rg_div_up(n_max, 256 * kClassifyRows), (unsigned)count), 256, 0, s>>>(C, cache->loc);
+        k_classify<<<dim3((unsigned)rg_div_up(n_max, 256 * kClassifyRows), (unsigned)count), 256, 0, s>>>(
+            C, cache->loc, cache->mirror_rows > 0 ? cache->home : nullptr);
         RG_LAUNCH_CHECK(ctx, "k_classify");
     }
     return RG_OK;
@@ -323,6 +333,8 @@ rg_status check_copy_args(rg_ctx* ctx, const char* fn, int64_t n, int32_t dim, c
     RG_REQUIRE(ctx, n >= 0 && n <= (1ll << 31) - 1, "%s: n = %lld out of range", fn, (long long)n);
     RG_REQUIRE(ctx, dim >= 1, "%s: dim = %d must be positive", fn, dim);
     RG_REQUIRE(ctx, cache && cache->loc, "%s: cache / cache->loc is NULL", fn);
+    RG_REQUIRE(ctx, cache->mirror_rows == 0 || (cache->home && cache->mirror_rows <= cache->capacity_rows),
+               "%s: a mirrored cache needs cache->home and mirror_rows <= capacity_rows", fn);
     RG_REQUIRE(ctx, out_stride >= dim, "%s: out_stride < dim", fn);
     RG_REQUIRE(ctx, !local_store || local_stride >= dim, "%s: local_stride < dim", fn);
     RG_REQUIRE(ctx, !remote_store || remote_stride >= dim, "%s: remote_stride < dim", fn);
@@ -348,6 +360,7 @@ rg_status rg_gather_prepare(rg_ctx* ctx, int32_t first_ticket, int32_t count, co
     if (count == 0) return RG_OK;
     RG_REQUIRE(ctx, input_nodes && n && stats, "rg_gather_prepare: null argument array");
     RG_REQUIRE(ctx, cache && cache->loc, "rg_gather_prepare: cache / cache->loc is NULL");
+    RG_REQUIRE(ctx, cache->mirror_rows == 0 || cache->home, "rg_gather_prepare: a mirrored cache needs cache->home");
     int64_t n_max = 0;
     for (int k = 0; k < count; ++k) {
         RG_REQUIRE(ctx, n[k] >= 0 && n[k] <= (1ll << 31) - 1, "rg_gather_prepare: n = %lld out of range (batch %d)", (long long)n[k], k);

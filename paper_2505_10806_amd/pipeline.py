@@ -21,7 +21,7 @@ from . import binding as B
 class _EpochState:
     """Everything one precomputed epoch owns: input-node lists, tier offsets, counts and the cache."""
 
-    def __init__(self, wl, H, slot, max_batches, device, keep_hops=None):
+    def __init__(self, wl, H, slot, max_batches, device, keep_hops=None, mirror=False):
         cfg = wl.cfg
         # per-batch blocks that outlive the sampling call: hop -> (indptr, nbr, nbr_local), each [max_batches, cap].
         # The outermost hop is kept for the consumer of the gathered rows; all hops when every block is wanted.
@@ -33,7 +33,8 @@ class _EpochState:
         self.tier_offs = torch.zeros(max_batches, H + 2, dtype=torch.int32, device=device)
         self.edge_counts = torch.zeros(max_batches, H, dtype=torch.int32, device=device)
         self.counts = torch.zeros(cfg.num_nodes, dtype=torch.int32, device=device)
-        self.cache = B.FeatureCache(cfg.num_nodes, min(wl.capacity_rows, wl.n_remote), wl.stride, device)
+        self.cache = B.FeatureCache(cfg.num_nodes, min(wl.capacity_rows, wl.n_remote), wl.stride, device,
+                                    mirror_rows=wl.n_remote if mirror else 0, home=wl.home if mirror else None)
         self.stats = torch.zeros(max_batches, 3, dtype=torch.int64, device=device)
         self.pf_events = [torch.cuda.Event() for _ in range(max_batches)]
         self.sampled = [torch.cuda.Event() for _ in range(max_batches)]
@@ -52,7 +53,7 @@ class EpochPipeline:
     def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True,
                  histogram="epoch", sampler_streams=2, double_buffer=False,
                  queue_depth=1, consumer=None, planned_prefetch=True, sample_group=8, keep_blocks=False,
-                 node_order="ascending", period_epochs=1):
+                 node_order="ascending", period_epochs=1, mirror_cache=None, keep_rows=False):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -100,7 +101,21 @@ class EpochPipeline:
         # directly), e.g. to hand whole message-flow graphs to a trainer or to compare them after the epoch
         hops = range(self.H) if keep_blocks else ([self.H - 1] if consumer else [])
         keep = {h: (self.bufs.frontier_ub[h] + 1, self.bufs.edges_ub[h]) for h in hops}
-        self.states = [_EpochState(wl, self.H, self.slot, self.max_batches, device, keep) for _ in range(2 if double_buffer else 1)]
+        # When the cache can hold the whole remote partition, every remote row a batch names will be cached, so its
+        # place can be fixed before TopHot has run: the cache is laid out as a mirror of the remote store and each
+        # batch's rows are pulled as soon as the batch has been sampled, while the rest of the period is still being
+        # sampled.  The host link then works through the offline stage instead of idling until TopHot is done.
+        # keep_rows: rows pulled in an earlier period stay resident (features do not change), so later periods only
+        # pull rows no period has named before; off = every period starts from a cold cache.
+        can_mirror = bool(prefetch and wl.n_remote > 0 and wl.capacity_rows >= wl.n_remote)
+        self.mirror = can_mirror if mirror_cache is None else bool(mirror_cache and can_mirror)
+        self.keep_rows = bool(keep_rows and self.mirror)
+        self.states = [_EpochState(wl, self.H, self.slot, self.max_batches, device, keep, mirror=self.mirror)
+                       for _ in range(2 if double_buffer else 1)]
+        if self.keep_rows and len(self.states) > 1:
+            # one physical mirror serves both buffer sets: the location tables, counts and cache ids are per period, the rows are not
+            for st in self.states[1:]:
+                st.cache = B.FeatureCache.sharing_rows(self.states[0].cache, cfg.num_nodes, device)
         self.cur = 0
         self.out_ring = [torch.empty(max(self.slot, 1), wl.stride, dtype=torch.float32, device=device)
                          for _ in range(self.queue_depth)]
@@ -121,7 +136,7 @@ class EpochPipeline:
         self.pf_stream = torch.cuda.Stream(device=device) if prefetch else None
         # planned prefetch: the epoch histogram also records the first batch that needs each node, the selected
         # slots are grouped by that batch once, and the prefetch stream then carries nothing but pulls
-        self.planned = bool(prefetch and planned_prefetch and histogram != "batch")
+        self.planned = bool(prefetch and planned_prefetch and histogram != "batch" and not self.mirror)
         if self.planned:
             for st in self.states:
                 st.first_batch = torch.empty(cfg.num_nodes, dtype=torch.int32, device=device)
@@ -129,7 +144,7 @@ class EpochPipeline:
         # The sampler lanes reuse the streams that are idle during the offline stage (miss and prefetch streams);
         # only lanes beyond those get streams of their own.  The device exposes few hardware queues, and streams
         # that end up sharing one would serialise work that is meant to overlap.
-        spare = [st for st in (self.side, self.pf_stream) if st is not None]
+        spare = [st for st in (self.side, None if self.mirror else self.pf_stream) if st is not None]
         self.lane_stream = [None] + spare[:self.n_lanes - 1]
         while len(self.lane_stream) < self.n_lanes:
             self.lane_stream.append(torch.cuda.Stream(device=device))
@@ -190,6 +205,10 @@ class EpochPipeline:
             st.counts.zero_()
             if self.planned:
                 st.first_batch.fill_(-1)
+            if self.mirror:
+                if not self.keep_rows:
+                    st.cache.filled.zero_()               # a cold cache: no row of the mirror is resident
+                self.pf_stream.wait_stream(head)
             for _, _, s in lanes[1:]:
                 s.wait_stream(head)
             n_train = self.order.numel()
@@ -213,7 +232,14 @@ class EpochPipeline:
                 if self.histogram == "sampled":           # the group's membership bitmaps go straight into the counts
                     c.access_histogram_sampled(len(outs), st.counts, batch_index=range(i0, i0 + len(outs)),
                                                first_batch=st.first_batch, stream=s or head)
-                elif self.histogram == "batch":
+                if self.mirror:                           # this group's remote rows start crossing the link now
+                    st.sampled[i0].record(s or head)
+                    self.pf_stream.wait_event(st.sampled[i0])
+                    for i in range(i0, i1):
+                        self.ctx.prefetch_cache_rows(st.arena[i], self.slot, st.cache, self.wl.home, self.wl.remote_store,
+                                                     cfg.feat_dim, n_dev=st.tier_offs[i, self.H + 1:], stream=self.pf_stream)
+                        st.pf_events[i].record(self.pf_stream)
+                if self.histogram == "batch":
                     for i in range(i0, i1):
                         head_ctx.access_histogram(st.arena[i], self.slot, st.counts, n_dev=st.tier_offs[i, self.H + 1:], stream=head)
             for _, _, s in lanes[1:]:
@@ -233,7 +259,7 @@ class EpochPipeline:
             st.built.record(head)
         st.n_batches = len(ids)
         st.sizes = None
-        st.pulls_queued = False
+        st.pulls_queued = self.mirror
 
     def precompute(self, epoch, n_batches=None, batch_ids=None):
         """Offline stage (asynchronous) for the first n_batches batches of `epoch`, or for the listed

@@ -361,6 +361,74 @@ def test_prefetch_by_first_use_matches_bulk_fill(B, ctx, planned):
     assert not cache.cache_rows.any()
 
 
+def test_mirrored_cache_is_filled_before_tophot(B, ctx):
+    """A cache that can hold the whole remote partition, laid out as its mirror: each batch's remote rows are pulled right
+    after the batch is sampled (no TopHot result needed), TopHot then selects exactly the nodes that were pulled, and
+    the gathers read a cached node's row at its remote-store row.  Rows, statistics and selection against the oracle;
+    a second period keeps the resident rows and pulls only rows it is the first to name."""
+    wl = synth.build_workload("tiny", seed=21, device=DEV)
+    cfg, H = wl.cfg, len(wl.cfg.fanouts)
+    rp, ci = host_graph(wl)
+    X = wl.features.cpu().numpy()
+    home_np = wl.home.cpu().numpy()
+    csr = B.CsrGraph(wl.row_ptr, wl.col_idx)
+    cache = B.FeatureCache(cfg.num_nodes, wl.n_remote, wl.stride, DEV, mirror_rows=wl.n_remote, home=wl.home)
+    cache.cache_rows.fill_(float("nan"))
+    with pytest.raises(B.RgError):                       # a mirror is never filled in bulk
+        ctx.build_cache(torch.zeros(cfg.num_nodes, dtype=torch.int32, device=DEV), wl.home, wl.remote_store, cfg.feat_dim, cache)
+    out = torch.empty(cfg.num_nodes, wl.stride, device=DEV)
+    stats = torch.zeros(3, dtype=torch.int64, device=DEV)
+    pulled_before = 0
+    for epoch in (0, 1):
+        order = ctx.epoch_schedule(wl.train_ids, wl.seed, epoch)
+        counts = torch.zeros(cfg.num_nodes, dtype=torch.int32, device=DEV)
+        counts_orc = np.zeros(cfg.num_nodes, dtype=np.uint32)
+        inputs, inputs_dev = [], []
+        for b in range(4):
+            bufs = B.BlockBuffers(cfg.num_nodes, wl.nnz, cfg.batch_size, cfg.fanouts, DEV)
+            seeds = order[b * cfg.batch_size:(b + 1) * cfg.batch_size]
+            ctx.sample_blocks(csr, seeds, seeds.numel(), cfg.fanouts, wl.seed, epoch, bufs)
+            ctx.access_histogram(bufs.nodes, bufs.frontier_ub[H], counts, n_dev=bufs.tier_off[H + 1:])
+            # the batch's remote rows cross the link now, before any selection exists
+            ctx.prefetch_cache_rows(bufs.nodes, bufs.frontier_ub[H], cache, wl.home, wl.remote_store, cfg.feat_dim,
+                                    n_dev=bufs.tier_off[H + 1:])
+            torch.cuda.synchronize()
+            n = int(bufs.tier_off[H + 1].item())
+            inputs_dev.append(bufs.nodes[:n].clone())
+            orc = oracle.sample_blocks(rp, ci, seeds.cpu().numpy(), cfg.fanouts, wl.seed, epoch)
+            assert np.array_equal(inputs_dev[-1].cpu().numpy(), orc.input_nodes)
+            oracle.access_histogram(orc.input_nodes, counts_orc)
+            inputs.append(orc.input_nodes)
+        ctx.build_cache(counts, wl.home, None, cfg.feat_dim, cache)
+        torch.cuda.synchronize()
+        ids_orc, loc_orc = oracle.build_cache(counts_orc, home_np, wl.n_remote)
+        k = int(cache.num_cached.item())
+        assert k == ids_orc.size and np.array_equal(cache.cache_ids[:k].cpu().numpy(), ids_orc)
+        assert np.array_equal(cache.loc.cpu().numpy(), loc_orc)
+        # resident rows = every remote row named so far, each at its remote-store row; nothing else was written
+        bits = np.unpackbits(cache.filled.cpu().numpy().view(np.uint8), bitorder="little")[:wl.n_remote]
+        rows_now = (home_np[ids_orc].astype(np.int64) & 0x3FFFFFFF)
+        assert bits[rows_now].all()
+        resident = np.flatnonzero(bits)
+        got = cache.cache_rows.cpu().numpy()
+        remote_ids = np.flatnonzero(((home_np.astype(np.int64) & 0xFFFFFFFF) >> 30) == 2)
+        assert np.array_equal(got[resident, :cfg.feat_dim], X[remote_ids[resident]])
+        assert np.isnan(got[np.flatnonzero(bits == 0)]).all()
+        if epoch == 0:
+            assert resident.size == k
+            pulled_before = resident.size
+        else:
+            assert pulled_before < resident.size < pulled_before + k      # only rows no earlier batch had named were pulled
+        for b in range(4):
+            ctx.gather_features(inputs_dev[b], inputs_dev[b].numel(), cache, wl.local_store, wl.remote_store, cfg.feat_dim, out, stats)
+            torch.cuda.synchronize()
+            want, st = oracle.gather_features(X, inputs[b], loc_orc)
+            assert st[2] == 0 and tuple(stats.cpu().tolist()) == st
+            assert np.array_equal(out[:inputs[b].size, :cfg.feat_dim].cpu().numpy(), want)
+    with pytest.raises(B.RgError):                       # the per-period plan does not apply to a mirror
+        ctx.plan_prefetch(cache, wl.home, torch.zeros(cfg.num_nodes, dtype=torch.int32, device=DEV), B.PrefetchPlan(wl.n_remote, 4, DEV))
+
+
 @pytest.mark.parametrize("histogram,node_order", [("epoch", "ascending"), ("sampled", "ascending"), ("sampled", "first_seen"),
                                                   ("batch", "first_seen")])
 @pytest.mark.parametrize("full_cache", [False, True])
@@ -414,7 +482,11 @@ def test_pipeline_epochs_back_to_back(B, double_buffer, full_cache, histogram, n
     def epoch_done(p, k):
         torch.cuda.synchronize()
         _, _, ids, _ = expected[k]
-        assert np.array_equal(p.cache.cache_rows[:ids.size, :cfg.feat_dim].cpu().numpy(), X[ids])
+        rows = p.cache.rows_of(torch.as_tensor(ids, device=DEV))      # slots, or remote-store rows for a mirrored cache
+        assert p.mirror == full_cache
+        if not p.mirror:
+            assert np.array_equal(rows.cpu().numpy(), np.arange(ids.size))
+        assert np.array_equal(p.cache.cache_rows[rows, :cfg.feat_dim].cpu().numpy(), X[ids])
 
     pipe.run_epochs(0, 3, nb, on_epoch_done=epoch_done, on_batch=batch_done, on_epoch_start=epoch_start)
     torch.cuda.synchronize()

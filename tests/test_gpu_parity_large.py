@@ -42,17 +42,21 @@ def _assert_block_equal(st, b, orc, H, tag):
 
 
 def _check_cache_resident(pipe, X, ids_orc, dim):
-    """Every selected node was requested by some batch of the period, so after the gathers every slot has
-    been pulled exactly once: all resident bits set and every cached row equal to the node's feature row."""
+    """Every selected node was requested by some batch of the period, so after the gathers every selected row has
+    been pulled exactly once: its resident bit is set, no other is, and the cached row equals the node's feature
+    row.  A cached node's row sits at its slot, or at its remote-store row when the cache mirrors the remote store."""
     torch.cuda.synchronize()
     k = ids_orc.size
     bits = pipe.cache.filled.cpu().numpy().view(np.uint32)
     resident = np.unpackbits(bits.view(np.uint8), bitorder="little")
-    assert resident[:k].all(), "a selected slot was never pulled"
-    assert not resident[k:].any()
+    rows = pipe.cache.rows_of(torch.as_tensor(ids_orc, device=DEV)).cpu().numpy()
+    assert pipe.mirror or np.array_equal(rows, np.arange(k))
+    assert resident[rows].all(), "a selected row was never pulled"
+    assert int(resident.sum()) == k
     for lo in range(0, k, 1 << 20):
         hi = min(k, lo + (1 << 20))
-        assert np.array_equal(pipe.cache.cache_rows[lo:hi, :dim].cpu().numpy(), X[ids_orc[lo:hi]]), "cached rows"
+        got = pipe.cache.cache_rows[torch.as_tensor(rows[lo:hi], device=DEV), :dim].cpu().numpy()
+        assert np.array_equal(got, X[ids_orc[lo:hi]]), "cached rows"
 
 
 def _epoch_parity(pipe, wl, host, epoch, row_batches):
