@@ -187,6 +187,93 @@ def cpu_baseline(wl, n_batches=None, target_s=12.0):
             "phase_seconds": {k: round(v, 4) for k, v in phases.items()}, "host_cpus": os.cpu_count()}
 
 
+def link_probe(workload, seed, dev):
+    """Host-link rates, one JSON line: plain runtime copies pinned -> HBM (whole, in pieces, strided), one runtime copy per
+    run of consecutive rows of the first batch's pull plan, and the library's pull kernels on the same plan with nothing
+    beside them."""
+    import numpy as np
+    import torch
+    import synth
+    from paper_2505_10806_amd import binding as B
+    from paper_2505_10806_amd.pipeline import EpochPipeline
+
+    def best_ms(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        return best
+    out = {}
+    src = torch.empty(1 << 28, dtype=torch.float32).pin_memory()
+    src.normal_()
+    dst = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    ms = best_ms(lambda: dst.copy_(src, non_blocking=True))
+    out["runtime_copy_1GiB"] = {"ms": ms, "GBps": (1 << 30) / ms / 1e6}
+    pieces = [(dst[i << 24:(i + 1) << 24], src[i << 24:(i + 1) << 24]) for i in range(16)]
+    ms = best_ms(lambda: [d.copy_(s, non_blocking=True) for d, s in pieces])
+    out["runtime_copy_16x64MiB"] = {"ms": ms, "GBps": (1 << 30) / ms / 1e6}
+    s2, d2 = src.view(-1, 256), dst.view(-1, 256)
+    half = s2.shape[0] // 2
+    ms = best_ms(lambda: d2[:half].copy_(s2[::2], non_blocking=True))
+    out["runtime_copy_every_other_1KiB_row"] = {"ms": ms, "GBps": half * 1024 / ms / 1e6}
+    del src, dst, pieces, s2, d2
+    torch.cuda.empty_cache()
+
+    wl = synth.build_workload(workload, seed=seed, device=dev, keep_features=False)
+    row_bytes = 4 * wl.cfg.feat_dim
+    pipe = EpochPipeline(wl, device=dev, mirror_cache=False)
+    pipe.precompute(0, pipe.batches_per_epoch)
+    pipe.read_sizes()
+    torch.cuda.synchronize()
+    st = pipe.state
+    off = st.plan.offsets.cpu().numpy()
+    pairs = st.plan.list.cpu().numpy().reshape(-1, 2)
+    runs = {}
+    for b in (0, 1, 8, 32, 100, 200):
+        if b < pipe.batches_per_epoch:
+            seg = pairs[off[b]:off[b + 1]]
+            n_runs = int(((np.diff(seg[:, 0]) != 1) | (np.diff(seg[:, 1]) != 1)).sum()) + 1 if len(seg) else 0
+            runs[str(b)] = {"rows": int(len(seg)), "runs_of_consecutive_rows": n_runs}
+    out["plan_segments"] = runs
+    seg = pairs[off[0]:off[1]]
+    brk = np.flatnonzero((np.diff(seg[:, 0]) != 1) | (np.diff(seg[:, 1]) != 1)) + 1
+    starts, ends = np.concatenate([[0], brk]), np.concatenate([brk, [len(seg)]])
+    n_run = min(20000, len(starts))
+    rows_copied = int((ends[:n_run] - starts[:n_run]).sum())
+    cache_rows, remote = st.cache.cache_rows, wl.remote_store
+    t0 = time.perf_counter()
+    for i in range(n_run):
+        s0, r0, ln = int(seg[starts[i], 0]), int(seg[starts[i], 1]), int(ends[i] - starts[i])
+        cache_rows[s0:s0 + ln].copy_(remote[r0:r0 + ln], non_blocking=True)
+    t_issue = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    t_all = time.perf_counter() - t0
+    out["one_runtime_copy_per_run"] = {"runs": n_run, "rows": rows_copied, "issue_ms": t_issue * 1e3, "done_ms": t_all * 1e3,
+                                       "GBps": rows_copied * row_bytes / t_all / 1e9}
+    ctx = pipe.ctx
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    for _ in range(3):
+        ctx.prefetch_planned(st.plan, 0, st.cache, wl.remote_store, wl.cfg.feat_dim)
+    torch.cuda.synchronize()
+    ms, cnt = ctx.profile_read(B.RG_K_CACHE_FILL)
+    out["pull_kernel_on_batch0_segment_alone"] = {"rows": int(len(seg)), "ms": ms / cnt, "GBps": len(seg) * row_bytes / (ms / cnt) / 1e6}
+    cache2 = B.FeatureCache(wl.cfg.num_nodes, min(wl.capacity_rows, wl.n_remote), wl.stride, dev)
+    ctx.profile_reset()
+    ctx.build_cache(st.counts, wl.home, wl.remote_store, wl.cfg.feat_dim, cache2)
+    torch.cuda.synchronize()
+    ms, _ = ctx.profile_read(B.RG_K_CACHE_FILL)
+    k = int(cache2.num_cached.item())
+    out["bulk_fill_kernel_alone"] = {"rows": k, "ms": ms, "GBps": k * row_bytes / ms / 1e6}
+    print(json.dumps({"link_probe": workload, "peak_GBps": HOSTLINK_PEAK_GBS, **out}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -225,6 +312,9 @@ def main():
                          "E: one cache from the counts of E epochs, as Alg. 1 lines 1-4 read)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the extra passes (whole-epoch rate, gather kernel without concurrent pulls, hit curve)")
+    ap.add_argument("--link-probe", action="store_true",
+                    help="only measure the host link: runtime (SDMA) copies from pinned memory against the library's zero-copy "
+                         "pull kernels on the workload's own pull plan")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -253,6 +343,9 @@ def main():
         ms = e0.elapsed_time(e1) / 5
         print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "ms": ms,
                           "GBps_read_plus_write": 2 * (1 << 30) / (ms * 1e-3) / 1e9}), flush=True)
+        return
+    if args.link_probe:
+        link_probe(args.workload, args.seed, dev)
         return
     t_gen = time.perf_counter()
     wl = synth.build_workload(args.workload, seed=args.seed, device=dev)
