@@ -302,6 +302,8 @@ def main():
                          "membership bitmaps after every group, or one global-atomic pass per batch")
     ap.add_argument("--node-order", choices=["ascending", "first_seen"], default="ascending",
                     help="order of the nodes inside a tier of a block")
+    ap.add_argument("--mirror-pulls", choices=("group", "batch"), default="group",
+                    help="mirrored cache only: one pull per sampler call with its list read off the sampler's bitmaps, or one per batch")
     ap.add_argument("--no-mirror", action="store_true",
                     help="do not lay a cache that can hold the whole remote partition out as its mirror (rows are then pulled "
                          "after TopHot, from the prefetch plan, instead of while the batches are being sampled)")
@@ -371,7 +373,7 @@ def main():
                              sampler_streams=args.sampler_streams, double_buffer=(multi_epoch and not args.no_double_buffer),
                              planned_prefetch=not args.no_plan, sample_group=args.sample_group,
                              histogram=args.histogram, node_order=args.node_order, period_epochs=args.period_epochs,
-                             mirror_cache=False if args.no_mirror else None, keep_rows=args.keep_rows,
+                             mirror_cache=False if args.no_mirror else None, keep_rows=args.keep_rows, mirror_pulls=args.mirror_pulls,
                              consumer=None if args.consumer == "none" else args.consumer,
                              queue_depth=args.queue_depth if args.consumer != "none" else 1)
 
@@ -441,7 +443,7 @@ def main():
                    "double_buffered_cache": bool(multi_epoch and not args.no_double_buffer),
                    "planned_prefetch": pipe.planned, "consumer": args.consumer, "queue_depth": pipe.queue_depth,
                    "histogram": pipe.histogram, "node_order": args.node_order, "period_epochs": pipe.period_epochs,
-                   "mirrored_cache": pipe.mirror, "rows_kept_across_epochs": pipe.keep_rows,
+                   "mirrored_cache": pipe.mirror, "mirror_pulls": args.mirror_pulls if pipe.mirror else None, "rows_kept_across_epochs": pipe.keep_rows,
                    "GPU_MAX_HW_QUEUES": os.environ.get("GPU_MAX_HW_QUEUES"), "GPU_MAX_HW_QUEUES_set_by": "user" if HWQ_SET_BY_USER else "bench.py"},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": roof["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": roof["frac"],

@@ -251,7 +251,8 @@ typedef struct {
      * and the statistics keep their meaning.  `filled` is then indexed by remote-store row; rg_build_cache (select
      * only) leaves it alone, so rows pulled while the batches were still being sampled, or in an earlier period,
      * stay valid: the caller clears it to start cold.  rg_prefetch_cache_rows pulls the not-yet-resident remote rows
-     * a batch names and needs no TopHot result; the planned prefetch does not apply.  home: the home words
+     * a batch names and needs no TopHot result; rg_plan_sampled + rg_prefetch_planned do the same per sampler
+     * group from the sampler's bitmaps; rg_plan_prefetch does not apply.  home: the home words
      * (device int32[num_nodes]), required when mirror_rows > 0. */
     int64_t mirror_rows;
     const int32_t* home;
@@ -308,12 +309,26 @@ typedef struct {
     int32_t num_batches;      /* 0..65535 */
 } rg_prefetch_plan;
 
+/* With a mirrored cache (rg_cache.mirror_rows) a plan can also be grown while the period is being sampled, one segment
+ * per sampler call, by rg_plan_sampled below; rg_prefetch_planned then pulls segment by segment as for a planned period. */
 /* after rg_build_cache (select only) on the same stream; first_batch: device uint32[num_nodes]. */
 RG_API rg_status rg_plan_prefetch(rg_ctx* ctx, const rg_cache* cache, const int32_t* home, const uint32_t* first_batch,
                                   int64_t num_nodes, const rg_prefetch_plan* plan, void* stream);
 /* 0 <= batch <= plan->num_batches. */
 RG_API rg_status rg_prefetch_planned(rg_ctx* ctx, const rg_prefetch_plan* plan, int32_t batch, const rg_cache* cache,
                                      const float* remote_store, int64_t remote_stride, int32_t dim, void* stream);
+
+/* Mirrored cache only: appends segment `segment` to the plan = the remote rows that the group of batches sampled
+ * last on this context (rg_sample_blocks / rg_sample_blocks_group) is the first to name, as (row, row) pairs in
+ * ascending row order, read off the sampler's membership bitmaps (no pass over the batches' id lists).
+ * `claimed` (device uint32[ceil(num_nodes / 32)]) holds every node an earlier call has named; the call adds the
+ * group's; the caller zeroes it to start cold, or keeps it to keep the rows of earlier periods.  Segments are
+ * appended in order: the caller sets offsets[0] = 0 at the start of a period, the call reads offsets[segment] and
+ * writes offsets[segment + 1]; calls on one plan / bitmap are ordered by the caller (one stream).  It must follow the
+ * sampling call before the context samples again; group and num_nodes must match it (RG_ERR_STATE otherwise).
+ * plan->list_capacity >= cache->mirror_rows, 0 <= segment < plan->num_batches. */
+RG_API rg_status rg_plan_sampled(rg_ctx* ctx, int32_t group, const rg_cache* cache, uint32_t* claimed,
+                                 const rg_prefetch_plan* plan, int32_t segment, int64_t num_nodes, void* stream);
 
 /* ---- Alg. 1 lines 12-14: feature assembly for one batch ---------------------------------
  * out[i][0:dim] = feature row of input_nodes[i], read from the store loc[] names: local

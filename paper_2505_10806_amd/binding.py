@@ -81,6 +81,7 @@ def _load():
     L.rg_access_histogram.argtypes = [c_p, c_p, c_i64, c_p, c_p, c_i64, c_p]
     L.rg_access_histogram_epoch.argtypes = [c_p, c_p, c_i64, c_p, c_i32, c_i32, c_i32, c_p, c_p, c_i64, c_p]
     L.rg_plan_prefetch.argtypes = [c_p, ctypes.POINTER(rg_cache), c_p, c_p, c_i64, ctypes.POINTER(rg_prefetch_plan), c_p]
+    L.rg_plan_sampled.argtypes = [c_p, c_i32, ctypes.POINTER(rg_cache), c_p, ctypes.POINTER(rg_prefetch_plan), c_i32, c_i64, c_p]
     L.rg_prefetch_planned.argtypes = [c_p, ctypes.POINTER(rg_prefetch_plan), c_i32, ctypes.POINTER(rg_cache), c_p, c_i64, c_i32, c_p]
     L.rg_build_cache.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i64, c_i32, ctypes.POINTER(rg_cache), c_p]
     L.rg_cache_hit_curve.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i32, c_p, c_p, c_p]
@@ -98,7 +99,7 @@ def _load():
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group",
                  "rg_access_histogram", "rg_access_histogram_epoch", "rg_access_histogram_sampled", "rg_build_cache", "rg_cache_hit_curve",
-                 "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_prefetch_planned", "rg_gather_features",
+                 "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_plan_sampled", "rg_prefetch_planned", "rg_gather_features",
                  "rg_gather_features_static", "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable",
                  "rg_profile_reset", "rg_profile_read"):
         getattr(L, name).restype = ctypes.c_int
@@ -111,7 +112,7 @@ EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "r
                     "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group", "rg_access_histogram",
                     "rg_access_histogram_epoch", "rg_access_histogram_sampled",
                     "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_plan_prefetch",
-                    "rg_prefetch_planned", "rg_gather_features", "rg_gather_features_static", "rg_gather_prepare",
+                    "rg_plan_sampled", "rg_prefetch_planned", "rg_gather_features", "rg_gather_features_static", "rg_gather_prepare",
                     "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
 
 
@@ -237,6 +238,11 @@ class Context:
         self._check(_lib.rg_plan_prefetch(self._h, ctypes.byref(cache.c_struct), _ptr(home, torch.int32, "cuda", "home"),
                                           _ptr(first_batch, torch.int32, "cuda", "first_batch"), home.numel(),
                                           ctypes.byref(plan.c_struct), _stream_handle(stream)))
+
+    def plan_sampled(self, group, cache, claimed, plan, segment, stream=None):
+        self._check(_lib.rg_plan_sampled(self._h, int(group), ctypes.byref(cache.c_struct),
+                                         _ptr(claimed, torch.int32, "cuda", "claimed"), ctypes.byref(plan.c_struct), int(segment),
+                                         cache.loc.numel(), _stream_handle(stream)))
 
     def prefetch_planned(self, plan, batch, cache, remote_store, dim, stream=None):
         self._check(_lib.rg_prefetch_planned(self._h, ctypes.byref(plan.c_struct), int(batch), ctypes.byref(cache.c_struct),

@@ -137,7 +137,7 @@ void rg_destroy(rg_ctx* ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
     RgBuf* bufs[] = {&ctx->visited, &ctx->marked, &ctx->pos, &ctx->chunk_sum, &ctx->row_start, &ctx->row_deg, &ctx->first_key, &ctx->sched_keys, &ctx->sched_ids,
-                     &ctx->topk_ctl, &ctx->topk_blk, &ctx->topk_caps, &ctx->pf_list, &ctx->pf_ctl, &ctx->plan_cursor, &ctx->gather_src, &ctx->miss_list,
+                     &ctx->topk_ctl, &ctx->topk_blk, &ctx->topk_caps, &ctx->pf_list, &ctx->pf_ctl, &ctx->plan_cursor, &ctx->claim_bits, &ctx->claim_blk, &ctx->gather_src, &ctx->miss_list,
                      &ctx->gather_ctl};
     for (RgBuf* b : bufs)
         if (b->p) (void)hipFree(b->p);

@@ -729,6 +729,109 @@ __global__ void __launch_bounds__(1024) k_plan_block_scatter(const int32_t* __re
         }
 }
 
+// ---------------------------------------------------------------------------- plan segments straight from the sampler's bitmaps
+// After the last hop the `visited` bitmaps of a sampler group are its batches' input-node sets.  The remote rows the
+// group is the first to name are the new bits of their union against `claimed` (all nodes any earlier group named)
+// whose home is the remote store: two streaming passes over N/32 words and one home[] lookup per new node, instead of
+// one lookup and one probe per input node of every batch.  The pairs come out ascending by node id, i.e. by remote row.
+constexpr int kClaimWordsPerBlock = 1024;   // 256 threads x 4 words
+
+__device__ __forceinline__ int rg_count_remote(uint32_t bits, int64_t word, const int32_t* __restrict__ home) {
+    int c = 0;
+    while (bits) {
+        const int j = __ffs(bits) - 1;
+        bits &= bits - 1u;
+        c += ((uint32_t)home[(word << 5) + j] >> RG_TAG_SHIFT) == RG_TAG_REMOTE;
+    }
+    return c;
+}
+
+__global__ void __launch_bounds__(256) k_claim_count(const uint32_t* __restrict__ visited, int64_t words, int group,
+                                                     uint32_t* __restrict__ claimed, uint32_t* __restrict__ newbits,
+                                                     const int32_t* __restrict__ home, int32_t* __restrict__ blk_count) {
+    const int64_t w0 = (int64_t)blockIdx.x * kClaimWordsPerBlock + threadIdx.x * 4;
+    int c = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int64_t w = w0 + q;
+        if (w >= words) break;
+        uint32_t u = 0u;
+        for (int g = 0; g < group; ++g) u |= visited[g * words + w];
+        const uint32_t old = claimed[w];
+        const uint32_t nw = u & ~old;
+        newbits[w] = nw;
+        if (nw) {
+            claimed[w] = old | nw;
+            c += rg_count_remote(nw, w, home);
+        }
+    }
+    c = rg_wave_sum(c);
+    __shared__ int part[4];
+    if (rg_lane() == 0) part[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) blk_count[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+}
+
+// One workgroup: block counts -> exclusive offsets; the segment's end goes behind its start in the plan's offsets.
+__global__ void __launch_bounds__(1024) k_claim_scan(int32_t* __restrict__ blk_count, int nblocks, int32_t* __restrict__ seg_off,
+                                                     int64_t list_capacity) {
+    __shared__ int smem[1024 / RG_WAVE + 1];
+    __shared__ int carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int base = 0; base < nblocks; base += 1024) {
+        const int i = base + threadIdx.x;
+        const int x = i < nblocks ? blk_count[i] : 0;
+        int total;
+        const int excl = rg_block_excl_scan<1024 / RG_WAVE>(x, smem, &total);
+        const int carry = carry_s;
+        if (i < nblocks) blk_count[i] = carry + excl;
+        __syncthreads();
+        if (threadIdx.x == 0) carry_s = carry + total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        // a list that cannot take the segment (it holds one pair per remote row, so this means a caller error) gets an
+        // empty segment instead of an overrun
+        const int64_t end = (int64_t)seg_off[0] + carry_s;
+        seg_off[1] = end <= list_capacity ? (int32_t)end : seg_off[0];
+    }
+}
+
+__global__ void __launch_bounds__(256) k_claim_emit(const uint32_t* __restrict__ newbits, int64_t words, const int32_t* __restrict__ home,
+                                                    const int32_t* __restrict__ blk_off, const int32_t* __restrict__ seg_off,
+                                                    int32_t* __restrict__ list) {
+    __shared__ int smem[256 / RG_WAVE + 1];
+    if (seg_off[1] == seg_off[0]) return;                             // nothing new (or refused): uniform
+    const int64_t w0 = (int64_t)blockIdx.x * kClaimWordsPerBlock + threadIdx.x * 4;
+    uint32_t bits[4];
+    int c = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        bits[q] = w0 + q < words ? newbits[w0 + q] : 0u;
+        if (bits[q]) c += rg_count_remote(bits[q], w0 + q, home);
+    }
+    int total;
+    const int excl = rg_block_excl_scan<256 / RG_WAVE>(c, smem, &total);
+    if (total == 0) return;                                           // uniform
+    int64_t j = (int64_t)seg_off[0] + blk_off[blockIdx.x] + excl;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t b = bits[q];
+        while (b) {
+            const int bit = __ffs(b) - 1;
+            b &= b - 1u;
+            const uint32_t hw = (uint32_t)home[((w0 + q) << 5) + bit];
+            if ((hw >> RG_TAG_SHIFT) == RG_TAG_REMOTE) {
+                const int32_t row = (int32_t)(hw & RG_ROW_MASK);
+                list[2 * j] = row;                                    // mirrored cache: the row's place is its remote-store row
+                list[2 * j + 1] = row;
+                ++j;
+            }
+        }
+    }
+}
+
 __global__ void __launch_bounds__(256) k_zero_i32(int32_t* __restrict__ p, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0;
@@ -1029,17 +1132,48 @@ rg_status rg_prefetch_planned(rg_ctx* ctx, const rg_prefetch_plan* plan, int32_t
     RG_REQUIRE(ctx, plan && plan->offsets && plan->list, "rg_prefetch_planned: incomplete plan");
     RG_REQUIRE(ctx, batch >= 0 && batch <= plan->num_batches, "rg_prefetch_planned: batch = %d not in [0, %d]", batch, plan->num_batches);
     RG_REQUIRE(ctx, cache && cache->cache_rows && cache->filled && remote_store, "rg_prefetch_planned: null cache rows / filled / store");
-    RG_REQUIRE(ctx, cache->mirror_rows == 0, "rg_prefetch_planned: a mirrored cache is filled by rg_prefetch_cache_rows");
+    RG_REQUIRE(ctx, cache->mirror_rows >= 0 && cache->mirror_rows <= cache->capacity_rows, "rg_prefetch_planned: mirror_rows out of range");
     RG_REQUIRE(ctx, dim >= 1 && cache->row_stride >= dim && remote_stride >= dim, "rg_prefetch_planned: bad dim / stride");
     RG_HIP(ctx, hipSetDevice(ctx->device));
     { const rg_status chk = rg_check_device_readable(ctx, remote_store, "rg_prefetch_planned: remote_store"); if (chk != RG_OK) return chk; }
     hipStream_t s = (hipStream_t)stream;
+    const int64_t dst_rows = cache->mirror_rows > 0 ? cache->mirror_rows : cache->capacity_rows;
     rg_status st = launch_list_copy(ctx, plan->list, nullptr, remote_store, remote_stride, cache->cache_rows, cache->row_stride,
-                                    cache->capacity_rows, dim, rg_max64(plan->list_capacity, 1), ctx->knobs.pull_blocks,
+                                    dst_rows, dim, rg_max64(plan->list_capacity, 1), ctx->knobs.pull_blocks,
                                     ctx->knobs.pull_threads, s, plan->offsets + batch);
     if (st != RG_OK) return st;
-    k_mark_segment<<<ctx->num_cus, 256, 0, s>>>(plan->list, plan->offsets + batch, cache->filled, cache->capacity_rows);
+    k_mark_segment<<<ctx->num_cus, 256, 0, s>>>(plan->list, plan->offsets + batch, cache->filled, dst_rows);
     RG_LAUNCH_CHECK(ctx, "k_mark_segment");
+    return RG_OK;
+}
+
+rg_status rg_plan_sampled(rg_ctx* ctx, int32_t group, const rg_cache* cache, uint32_t* claimed, const rg_prefetch_plan* plan,
+                          int32_t segment, int64_t num_nodes, void* stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, group >= 1 && group <= RG_MAX_GROUP, "rg_plan_sampled: group = %d not in [1,%d]", group, RG_MAX_GROUP);
+    RG_REQUIRE(ctx, cache && cache->mirror_rows > 0 && cache->home, "rg_plan_sampled: needs a mirrored cache with its home words");
+    RG_REQUIRE(ctx, claimed && plan && plan->list && plan->offsets, "rg_plan_sampled: null claimed bitmap / plan");
+    RG_REQUIRE(ctx, segment >= 0 && segment < plan->num_batches, "rg_plan_sampled: segment = %d not in [0, %d)", segment, plan->num_batches);
+    RG_REQUIRE(ctx, plan->list_capacity >= cache->mirror_rows, "rg_plan_sampled: plan list holds %lld pairs, %lld required",
+               (long long)plan->list_capacity, (long long)cache->mirror_rows);
+    if (ctx->last_sample_group != group || ctx->last_sample_nodes != num_nodes)
+        return rg_set_error(ctx, RG_ERR_STATE, "rg_plan_sampled: the last sampling call of this context covered %d batches on %lld "
+                            "nodes, not %d on %lld", ctx->last_sample_group, (long long)ctx->last_sample_nodes, group, (long long)num_nodes);
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t words = rg_div_up(num_nodes, 32);
+    const int nblocks = (int)rg_max64(1, rg_div_up(words, kClaimWordsPerBlock));
+    rg_status st;
+    if ((st = rg_ensure(ctx, ctx->claim_bits, (size_t)rg_max64(words, 1) * 4)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->claim_blk, (size_t)nblocks * 4)) != RG_OK) return st;
+    uint32_t* newbits = (uint32_t*)ctx->claim_bits.p;
+    int32_t* blk = (int32_t*)ctx->claim_blk.p;
+    k_claim_count<<<nblocks, 256, 0, s>>>((const uint32_t*)ctx->visited.p, words, group, claimed, newbits, cache->home, blk);
+    RG_LAUNCH_CHECK(ctx, "k_claim_count");
+    k_claim_scan<<<1, 1024, 0, s>>>(blk, nblocks, plan->offsets + segment, plan->list_capacity);
+    RG_LAUNCH_CHECK(ctx, "k_claim_scan");
+    k_claim_emit<<<nblocks, 256, 0, s>>>(newbits, words, cache->home, blk, plan->offsets + segment, plan->list);
+    RG_LAUNCH_CHECK(ctx, "k_claim_emit");
     return RG_OK;
 }
 

@@ -59,6 +59,7 @@ struct rg_ctx {
     // prefetch scratch
     RgBuf pf_list;      // int32[2 * n]: (slot, remote row) pairs still to pull
     RgBuf pf_ctl;       // uint32[4]: [0] = number of pairs
+    RgBuf claim_bits, claim_blk;     // rg_plan_sampled: the group's new-node bits and per-block pair counts
     RgBuf plan_cursor;               // rg_plan_prefetch: per-chunk per-batch counts (ordered plan) or scatter cursors
     // gather scratch
     // RG_GATHER_TICKETS entries each, so that several batches can be classified by one launch ahead of their copies

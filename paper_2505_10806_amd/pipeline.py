@@ -53,7 +53,7 @@ class EpochPipeline:
     def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True,
                  histogram="epoch", sampler_streams=2, double_buffer=False,
                  queue_depth=1, consumer=None, planned_prefetch=True, sample_group=8, keep_blocks=False,
-                 node_order="ascending", period_epochs=1, mirror_cache=None, keep_rows=False):
+                 node_order="ascending", period_epochs=1, mirror_cache=None, keep_rows=False, mirror_pulls="group"):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -110,12 +110,25 @@ class EpochPipeline:
         can_mirror = bool(prefetch and wl.n_remote > 0 and wl.capacity_rows >= wl.n_remote)
         self.mirror = can_mirror if mirror_cache is None else bool(mirror_cache and can_mirror)
         self.keep_rows = bool(keep_rows and self.mirror)
+        # mirror_pulls: "group" = one pull per sampler call, its list read off the sampler's membership bitmaps (the
+        # remote nodes the call's batches are the first of the period to name); "batch" = one pull per batch, each
+        # preceded by a pass over the batch's id list that claims its not-yet-resident rows
+        if mirror_pulls not in ("group", "batch"):
+            raise ValueError("mirror_pulls must be 'group' or 'batch'")
+        self.group_pulls = self.mirror and mirror_pulls == "group"
         self.states = [_EpochState(wl, self.H, self.slot, self.max_batches, device, keep, mirror=self.mirror)
                        for _ in range(2 if double_buffer else 1)]
         if self.keep_rows and len(self.states) > 1:
             # one physical mirror serves both buffer sets: the location tables, counts and cache ids are per period, the rows are not
             for st in self.states[1:]:
                 st.cache = B.FeatureCache.sharing_rows(self.states[0].cache, cfg.num_nodes, device)
+        if self.group_pulls:
+            words = (cfg.num_nodes + 31) // 32
+            for j, st in enumerate(self.states):
+                st.plan = B.PrefetchPlan(wl.n_remote, self.max_batches, device)
+                st.claimed = (self.states[0].claimed if self.keep_rows and j > 0 else
+                              torch.zeros(words, dtype=torch.int32, device=device))
+                st.claim_done = [torch.cuda.Event() for _ in range(self.max_batches)]
         self.cur = 0
         self.out_ring = [torch.empty(max(self.slot, 1), wl.stride, dtype=torch.float32, device=device)
                          for _ in range(self.queue_depth)]
@@ -208,11 +221,17 @@ class EpochPipeline:
             if self.mirror:
                 if not self.keep_rows:
                     st.cache.filled.zero_()               # a cold cache: no row of the mirror is resident
+                    if self.group_pulls:
+                        st.claimed.zero_()
+                if self.group_pulls:
+                    st.plan.offsets[:1].zero_()
                 self.pf_stream.wait_stream(head)
             for _, _, s in lanes[1:]:
                 s.wait_stream(head)
             n_train = self.order.numel()
             gsz = self.sample_group
+            if self.group_pulls:
+                st.plan.set_num_batches(self.max_batches)
             # a sampling call takes batches of one epoch (the epoch is part of the draw's key)
             calls = [(k, i0, min(i0 + gsz, (k + 1) * len(batch_ids)))
                      for k in range(self.period_epochs) for i0 in range(k * len(batch_ids), (k + 1) * len(batch_ids), gsz)]
@@ -232,7 +251,16 @@ class EpochPipeline:
                 if self.histogram == "sampled":           # the group's membership bitmaps go straight into the counts
                     c.access_histogram_sampled(len(outs), st.counts, batch_index=range(i0, i0 + len(outs)),
                                                first_batch=st.first_batch, stream=s or head)
-                if self.mirror:                           # this group's remote rows start crossing the link now
+                if self.group_pulls:                      # this call's new remote rows start crossing the link now
+                    if call > 0:                          # claims go in call order: each builds on the nodes claimed so far
+                        (s or head).wait_event(st.claim_done[call - 1])
+                    c.plan_sampled(len(outs), st.cache, st.claimed, st.plan, call, stream=s or head)
+                    st.claim_done[call].record(s or head)
+                    self.pf_stream.wait_event(st.claim_done[call])
+                    self.ctx.prefetch_planned(st.plan, call, st.cache, self.wl.remote_store, cfg.feat_dim, stream=self.pf_stream)
+                    for i in range(i0, i1):
+                        st.pf_events[i].record(self.pf_stream)
+                elif self.mirror:                         # each batch's not-yet-resident remote rows, batch by batch
                     st.sampled[i0].record(s or head)
                     self.pf_stream.wait_event(st.sampled[i0])
                     for i in range(i0, i1):

@@ -425,8 +425,70 @@ def test_mirrored_cache_is_filled_before_tophot(B, ctx):
             want, st = oracle.gather_features(X, inputs[b], loc_orc)
             assert st[2] == 0 and tuple(stats.cpu().tolist()) == st
             assert np.array_equal(out[:inputs[b].size, :cfg.feat_dim].cpu().numpy(), want)
-    with pytest.raises(B.RgError):                       # the per-period plan does not apply to a mirror
+    with pytest.raises(B.RgError):                       # the plan made from TopHot's selection does not apply to a mirror
         ctx.plan_prefetch(cache, wl.home, torch.zeros(cfg.num_nodes, dtype=torch.int32, device=DEV), B.PrefetchPlan(wl.n_remote, 4, DEV))
+
+
+def test_plan_segments_from_sampler_bitmaps(B, ctx):
+    """rg_plan_sampled on a mirrored cache: after each sampler call the plan gains one segment = the remote rows the
+    call's batches are the first to name, ascending, each paired with itself; rg_prefetch_planned pulls exactly those.
+    Expected segments come from the oracle's input-node lists."""
+    wl = synth.build_workload("tiny", seed=33, device=DEV)
+    cfg, H = wl.cfg, len(wl.cfg.fanouts)
+    rp, ci = host_graph(wl)
+    X = wl.features.cpu().numpy()
+    home_np = wl.home.cpu().numpy().astype(np.int64) & 0xFFFFFFFF
+    csr = B.CsrGraph(wl.row_ptr, wl.col_idx)
+    cache = B.FeatureCache(cfg.num_nodes, wl.n_remote, wl.stride, DEV, mirror_rows=wl.n_remote, home=wl.home)
+    cache.cache_rows.fill_(float("nan"))
+    cache.filled.zero_()
+    groups = [3, 1, 4, 2]
+    plan = B.PrefetchPlan(wl.n_remote, len(groups), DEV)
+    plan.set_num_batches(len(groups))
+    claimed = torch.zeros((cfg.num_nodes + 31) // 32, dtype=torch.int32, device=DEV)
+    order = ctx.epoch_schedule(wl.train_ids, wl.seed, 0)
+    order_np = order.cpu().numpy()
+    seen = np.zeros(cfg.num_nodes, dtype=bool)
+    b0, start = 0, 0
+    remote_ids = np.flatnonzero((home_np >> 30) == 2)
+    for seg, g in enumerate(groups):
+        bufs = [B.BlockBuffers(cfg.num_nodes, wl.nnz, cfg.batch_size, cfg.fanouts, DEV) for _ in range(g)]
+        seeds = [order[(b0 + j) * cfg.batch_size:(b0 + j + 1) * cfg.batch_size] for j in range(g)]
+        ctx.sample_blocks_group(csr, seeds, cfg.fanouts, wl.seed, 0, bufs)
+        with pytest.raises(B.RgError):                   # the call must name the group the context sampled last
+            ctx.plan_sampled(g + 1, cache, claimed, plan, seg)
+        ctx.plan_sampled(g, cache, claimed, plan, seg)
+        ctx.prefetch_planned(plan, seg, cache, wl.remote_store, cfg.feat_dim)
+        torch.cuda.synchronize()
+        new = np.zeros(cfg.num_nodes, dtype=bool)
+        for j in range(g):
+            sd = order_np[(b0 + j) * cfg.batch_size:(b0 + j + 1) * cfg.batch_size]
+            new[oracle.sample_blocks(rp, ci, sd, cfg.fanouts, wl.seed, 0).input_nodes] = True
+        new &= ~seen
+        seen |= new
+        ids = np.flatnonzero(new & ((home_np >> 30) == 2))
+        rows = home_np[ids] & 0x3FFFFFFF
+        offs = plan.offsets.cpu().numpy()
+        assert offs[seg] == start and offs[seg + 1] == start + rows.size, (seg, offs[:seg + 2], rows.size)
+        pairs = plan.list.cpu().numpy()[2 * start:2 * (start + rows.size)].reshape(-1, 2)
+        assert np.array_equal(pairs[:, 0], rows) and np.array_equal(pairs[:, 1], rows)
+        start += rows.size
+        b0 += g
+        # the claim bitmap = every node named so far; resident rows = every remote row named so far
+        cl = np.unpackbits(claimed.cpu().numpy().view(np.uint8), bitorder="little")[:cfg.num_nodes].astype(bool)
+        assert np.array_equal(cl, seen)
+        bits = np.unpackbits(cache.filled.cpu().numpy().view(np.uint8), bitorder="little")[:wl.n_remote].astype(bool)
+        assert np.array_equal(bits, seen[remote_ids])
+        got = cache.cache_rows.cpu().numpy()
+        assert np.array_equal(got[bits, :cfg.feat_dim], X[remote_ids[bits]]) and np.isnan(got[~bits]).all()
+    assert start > 0
+    # argument checks: not a mirror, segment out of range, list too short
+    plain = B.FeatureCache(cfg.num_nodes, wl.n_remote, wl.stride, DEV)
+    for bad in (lambda: ctx.plan_sampled(groups[-1], plain, claimed, plan, 0),
+                lambda: ctx.plan_sampled(groups[-1], cache, claimed, plan, len(groups)),
+                lambda: ctx.plan_sampled(groups[-1], cache, claimed, B.PrefetchPlan(max(wl.n_remote - 1, 0), 4, DEV), 0)):
+        with pytest.raises(B.RgError):
+            bad()
 
 
 @pytest.mark.parametrize("histogram,node_order", [("epoch", "ascending"), ("sampled", "ascending"), ("sampled", "first_seen"),
@@ -449,7 +511,9 @@ def test_pipeline_epochs_back_to_back(B, double_buffer, full_cache, histogram, n
     rp, ci = host_graph(wl)
     X = wl.features.cpu().numpy()
     home_np, train_np = wl.home.cpu().numpy(), wl.train_ids.cpu().numpy()
-    pipe = EpochPipeline(wl, device=DEV, double_buffer=double_buffer, histogram=histogram, node_order=node_order)
+    # a mirrored cache is filled by one pull per sampler call (lists off the bitmaps) or one per batch: cover both
+    pulls = "batch" if (full_cache and histogram == "epoch") else "group"
+    pipe = EpochPipeline(wl, device=DEV, double_buffer=double_buffer, histogram=histogram, node_order=node_order, mirror_pulls=pulls)
     nb = pipe.batches_per_epoch
     expected = {}
 
