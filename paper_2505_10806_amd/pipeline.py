@@ -233,8 +233,12 @@ class EpochPipeline:
             if self.group_pulls:
                 st.plan.set_num_batches(self.max_batches)
             # a sampling call takes batches of one epoch (the epoch is part of the draw's key)
-            calls = [(k, i0, min(i0 + gsz, (k + 1) * len(batch_ids)))
-                     for k in range(self.period_epochs) for i0 in range(k * len(batch_ids), (k + 1) * len(batch_ids), gsz)]
+            calls = []
+            for k in range(self.period_epochs):
+                i0 = k * len(batch_ids)
+                for size in self._call_sizes(len(batch_ids), gsz, first=k == 0, last=k == self.period_epochs - 1):
+                    calls.append((k, i0, i0 + size))
+                    i0 += size
             for call, (k, i0, i1) in enumerate(calls):
                 c, bufs_list, s = lanes[call % len(lanes)]
                 seeds_list, outs = [], []
@@ -288,6 +292,22 @@ class EpochPipeline:
         st.n_batches = len(ids)
         st.sizes = None
         st.pulls_queued = self.mirror
+
+    def _call_sizes(self, n, gsz, first, last):
+        """Batches per sampler call for the n batches of one epoch of a period.  Groups of gsz, except that with one pull
+        per call the period opens with a single batch (its rows start crossing the link while the next calls sample)
+        and closes with calls of 2, 1 and 1 batches (the gathers of a call's batches wait for its pull, so a short
+        last pull leaves a short tail behind the link's last byte)."""
+        if not self.group_pulls or gsz == 1:
+            return [min(gsz, n - i) for i in range(0, n, gsz)]
+        head = [1] if first and n > 1 else []
+        tail = []
+        if last:
+            for size in (1, 1, 2):
+                if sum(head) + sum(tail) + size < n:
+                    tail.insert(0, size)
+        body = n - sum(head) - sum(tail)
+        return head + [min(gsz, body - i) for i in range(0, body, gsz)] + tail
 
     def precompute(self, epoch, n_batches=None, batch_ids=None):
         """Offline stage (asynchronous) for the first n_batches batches of `epoch`, or for the listed
