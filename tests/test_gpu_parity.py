@@ -518,6 +518,7 @@ def test_pipeline_epochs_back_to_back(B, double_buffer, full_cache, histogram, n
     expected = {}
 
     def epoch_start(p, k):                      # oracle results for the epoch that is about to be served
+        torch.cuda.synchronize()                # its offline stage runs on streams of its own
         batches = oracle.epoch_batches(train_np, cfg.batch_size, wl.seed, k, cfg.max_batches)
         counts = np.zeros(cfg.num_nodes, dtype=np.uint32)
         inputs = []
@@ -588,6 +589,7 @@ def test_pipeline_period_of_two_epochs_shares_one_cache(B, double_buffer):
     expected, hits = {}, {}
 
     def period_start(p, k):
+        torch.cuda.synchronize()                # the period's offline stage runs on streams of its own
         inputs, counts = _oracle_period(wl, rp, ci, home_np, train_np, 2 * k, 2)
         ids, loc = oracle.build_cache(counts, home_np, wl.capacity_rows)
         expected[k] = (inputs, counts, ids, loc)

@@ -90,6 +90,7 @@ def _epoch_parity(pipe, wl, host, epoch, row_batches):
         ahead.close()
     assert len(batches[-1]) == train_np.size - (nb - 1) * cfg.batch_size          # the partial last batch is a batch
 
+    torch.cuda.synchronize()                    # histogram and TopHot may run on a stream of the pipeline's own
     assert np.array_equal(pipe.counts.cpu().numpy().view(np.uint32), counts_orc), "histogram"
     assert int(counts_orc.sum()) == sum(sizes) and int(counts_orc.max()) <= nb
     ids_orc, loc_orc = oracle.build_cache(counts_orc, home_np, wl.capacity_rows)
@@ -216,3 +217,32 @@ def test_stress_workload():
     assert tuple(stats.cpu().tolist()) == st_orc and st_orc[2] > 100_000
     assert np.array_equal(pipe.out[:n, :cfg.feat_dim].cpu().numpy(), want)
     log(f"[stress] small-cache gather ok: local/hit/miss = {st_orc}")
+
+    # (3) the same epoch once more, the way bench.py runs it: run_epoch from a cold cache with no host synchronisation
+    # between the batches (one pull per sampler call, its rows listed from the sampler's bitmaps).  Statistics of every
+    # batch against those verified in (1), rows of a few batches against the features of the oracle's input nodes.
+    assert pipe.mirror and pipe.group_pulls
+    stats1 = pipe.stats[:nb].clone()
+    ids1 = pipe.cache.cache_ids.clone()
+    loc1 = pipe.cache.loc.clone()
+    pipe.stats.zero_()
+    pipe.cache.cache_rows.fill_(float("nan"))
+    keep = {0: None, 1: None, 9: None, 130: None, nb - 1: None}
+    sizes_seen = []
+
+    def capture(p, b):
+        sizes_seen.append(p.sizes[b])
+        if b in keep:
+            keep[b] = p.out[:p.sizes[b], :cfg.feat_dim].clone()
+
+    log("[stress] second pass: start")
+    pipe.run_epoch(0, nb, on_batch=capture)
+    torch.cuda.synchronize()
+    assert sizes_seen == [x.size for x in inputs]
+    assert torch.equal(pipe.stats[:nb], stats1), "statistics of the second pass"
+    assert torch.equal(pipe.cache.cache_ids, ids1) and torch.equal(pipe.cache.loc, loc1)
+    for b, rows in keep.items():
+        assert np.array_equal(rows.cpu().numpy(), X[inputs[b]]), f"second pass batch {b} gathered rows"
+    ids_orc = ids1[:int(pipe.cache.num_cached.item())].cpu().numpy()
+    _check_cache_resident(pipe, X, ids_orc, cfg.feat_dim)
+    log("[stress] second pass ok")
