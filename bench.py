@@ -304,6 +304,8 @@ def main():
                     help="order of the nodes inside a tier of a block")
     ap.add_argument("--mirror-pulls", choices=("group", "batch"), default="group",
                     help="mirrored cache only: one pull per sampler call with its list read off the sampler's bitmaps, or one per batch")
+    ap.add_argument("--pull-cus", type=int, default=16,
+                    help="compute units reserved for the host-link pull kernels (0 = no split): their stream runs on these, every other stream on the rest")
     ap.add_argument("--no-mirror", action="store_true",
                     help="do not lay a cache that can hold the whole remote partition out as its mirror (rows are then pulled "
                          "after TopHot, from the prefetch plan, instead of while the batches are being sampled)")
@@ -327,6 +329,7 @@ def main():
 
     import torch
     import synth
+    from paper_2505_10806_amd import binding as B
     from paper_2505_10806_amd.pipeline import EpochPipeline
 
     dev = "cuda:0"
@@ -366,19 +369,20 @@ def main():
     warmup, reps = args.warmup, max(1, args.reps)
     row_bytes = 4 * cfg.feat_dim
     multi_epoch = steps > per_period
-    main_stream = torch.cuda.Stream()
-
     def make_pipeline(prefetch):
         return EpochPipeline(wl, device=dev, two_streams=not args.one_stream, prefetch=prefetch,
                              sampler_streams=args.sampler_streams, double_buffer=(multi_epoch and not args.no_double_buffer),
                              planned_prefetch=not args.no_plan, sample_group=args.sample_group,
                              histogram=args.histogram, node_order=args.node_order, period_epochs=args.period_epochs,
                              mirror_cache=False if args.no_mirror else None, keep_rows=args.keep_rows, mirror_pulls=args.mirror_pulls,
+                             pull_cus=args.pull_cus,
                              consumer=None if args.consumer == "none" else args.consumer,
                              queue_depth=args.queue_depth if args.consumer != "none" else 1)
 
+    pipe = make_pipeline(not args.bulk_fill)
+    # the gathers run on the stream this with-block makes current: one of the pipeline's own when it splits the compute units
+    main_stream = pipe.work_stream or torch.cuda.Stream()
     with torch.cuda.stream(main_stream):
-        pipe = make_pipeline(not args.bulk_fill)
         ctx = pipe.ctx
         if warmup > 0:
             run_steps(pipe, warmup)
@@ -443,7 +447,7 @@ def main():
                    "double_buffered_cache": bool(multi_epoch and not args.no_double_buffer),
                    "planned_prefetch": pipe.planned, "consumer": args.consumer, "queue_depth": pipe.queue_depth,
                    "histogram": pipe.histogram, "node_order": args.node_order, "period_epochs": pipe.period_epochs,
-                   "mirrored_cache": pipe.mirror, "mirror_pulls": args.mirror_pulls if pipe.mirror else None, "rows_kept_across_epochs": pipe.keep_rows,
+                   "pull_cus": pipe.pull_cus, "mirrored_cache": pipe.mirror, "mirror_pulls": args.mirror_pulls if pipe.mirror else None, "rows_kept_across_epochs": pipe.keep_rows,
                    "GPU_MAX_HW_QUEUES": os.environ.get("GPU_MAX_HW_QUEUES"), "GPU_MAX_HW_QUEUES_set_by": "user" if HWQ_SET_BY_USER else "bench.py"},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": roof["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": roof["frac"],
@@ -492,10 +496,11 @@ def main():
         if not args.bulk_fill and not multi_epoch and args.period_epochs == 1:
             # the same gathers with all rows pulled beforehand: the copy kernel with nothing beside it
             n_b = min(steps, bpe)
+            pipe.close()
             del pipe
             torch.cuda.empty_cache()
-            with torch.cuda.stream(main_stream):
-                bulk = make_pipeline(False)
+            bulk = make_pipeline(False)
+            with torch.cuda.stream(bulk.work_stream or torch.cuda.Stream()):
                 run_steps(bulk, n_b)
                 _, b_prof, b_totals = profiled_pass(bulk, n_b, dev)
             b_roof = gather_roofline(b_prof, b_totals, row_bytes)
@@ -506,12 +511,15 @@ def main():
     if a_launches:
         result["consumer"] = {"kernel": "k_mean_aggregate", "total_ms": a_ms, "launches": a_launches}
     n_cpu = args.cpu_batches
+    pipe.close()
+    del pipe
     if n_cpu is None or n_cpu > 0:
-        del pipe
         torch.cuda.empty_cache()
         log("[bench] timing the CPU oracle on a bounded sample ...")
         result["cpu_baseline"] = cpu_baseline(wl, n_cpu)
     print(json.dumps(result), flush=True)
+    del wl
+    B.close_shared_streams()
 
 
 if __name__ == "__main__":

@@ -420,6 +420,18 @@ RG_API rg_status rg_profile_enable(rg_ctx* ctx, int on);
 RG_API rg_status rg_profile_reset(rg_ctx* ctx);
 RG_API rg_status rg_profile_read(rg_ctx* ctx, int kernel_id, double* total_ms, int64_t* launches);
 
+/* ---- streams bound to a share of the compute units ----------------------------------------
+ * A HIP stream whose kernels are placed only on compute units [first_cu, first_cu + num_cus) of
+ * the device's enumeration (the runtime's compute-unit mask; how the enumeration maps to XCDs is
+ * the driver's business).  Kernels that pull rows over the host link keep their few wavefronts
+ * waiting on the link; giving their stream a few compute units of its own, and every other stream
+ * the rest, keeps other kernels' wavefronts from sharing, and stalling behind, those units.
+ * The stream synchronises with the NULL stream like any stream created without
+ * hipStreamNonBlocking.  rg_stream_destroy waits for the stream's work, then destroys it; rg_destroy
+ * does the same for the streams still alive, so none may be used after its context is gone. */
+RG_API rg_status rg_stream_create(rg_ctx* ctx, int32_t first_cu, int32_t num_cus, void** stream);
+RG_API rg_status rg_stream_destroy(rg_ctx* ctx, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

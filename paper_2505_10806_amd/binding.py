@@ -81,6 +81,8 @@ def _load():
     L.rg_access_histogram.argtypes = [c_p, c_p, c_i64, c_p, c_p, c_i64, c_p]
     L.rg_access_histogram_epoch.argtypes = [c_p, c_p, c_i64, c_p, c_i32, c_i32, c_i32, c_p, c_p, c_i64, c_p]
     L.rg_plan_prefetch.argtypes = [c_p, ctypes.POINTER(rg_cache), c_p, c_p, c_i64, ctypes.POINTER(rg_prefetch_plan), c_p]
+    L.rg_stream_create.argtypes = [c_p, c_i32, c_i32, ctypes.POINTER(c_p)]
+    L.rg_stream_destroy.argtypes = [c_p, c_p]
     L.rg_plan_sampled.argtypes = [c_p, c_i32, ctypes.POINTER(rg_cache), c_p, ctypes.POINTER(rg_prefetch_plan), c_i32, c_i64, c_p]
     L.rg_prefetch_planned.argtypes = [c_p, ctypes.POINTER(rg_prefetch_plan), c_i32, ctypes.POINTER(rg_cache), c_p, c_i64, c_i32, c_p]
     L.rg_build_cache.argtypes = [c_p, c_p, c_p, c_i64, c_p, c_i64, c_i32, ctypes.POINTER(rg_cache), c_p]
@@ -101,7 +103,7 @@ def _load():
                  "rg_access_histogram", "rg_access_histogram_epoch", "rg_access_histogram_sampled", "rg_build_cache", "rg_cache_hit_curve",
                  "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_plan_sampled", "rg_prefetch_planned", "rg_gather_features",
                  "rg_gather_features_static", "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable",
-                 "rg_profile_reset", "rg_profile_read"):
+                 "rg_profile_reset", "rg_profile_read", "rg_stream_create", "rg_stream_destroy"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -112,7 +114,8 @@ EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "r
                     "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group", "rg_access_histogram",
                     "rg_access_histogram_epoch", "rg_access_histogram_sampled",
                     "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_plan_prefetch",
-                    "rg_plan_sampled", "rg_prefetch_planned", "rg_gather_features", "rg_gather_features_static", "rg_gather_prepare",
+                    "rg_plan_sampled", "rg_prefetch_planned", "rg_gather_features", "rg_gather_features_static",
+                    "rg_stream_create", "rg_stream_destroy", "rg_gather_prepare",
                     "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
 
 
@@ -238,6 +241,19 @@ class Context:
         self._check(_lib.rg_plan_prefetch(self._h, ctypes.byref(cache.c_struct), _ptr(home, torch.int32, "cuda", "home"),
                                           _ptr(first_batch, torch.int32, "cuda", "first_batch"), home.numel(),
                                           ctypes.byref(plan.c_struct), _stream_handle(stream)))
+
+    def stream_on_cus(self, first_cu, num_cus):
+        """A torch stream whose kernels run only on compute units [first_cu, first_cu + num_cus).  It belongs to this
+        context and goes with it (or with rg_stream_destroy): by then nothing may refer to it any more, neither events
+        recorded on it nor pinned tensors copied on it (torch records an event on their streams when they are freed).
+        Pipelines take theirs from shared_stream_on_cus, which keeps them for the life of the process."""
+        h = c_p()
+        self._check(_lib.rg_stream_create(self._h, int(first_cu), int(num_cus), ctypes.byref(h)))
+        return torch.cuda.ExternalStream(h.value, device=torch.device("cuda", self.device))
+
+    @property
+    def num_cus(self):
+        return torch.cuda.get_device_properties(self.device).multi_processor_count
 
     def plan_sampled(self, group, cache, claimed, plan, segment, stream=None):
         self._check(_lib.rg_plan_sampled(self._h, int(group), ctypes.byref(cache.c_struct),
@@ -436,6 +452,38 @@ class BlockBuffers:
         self.c_struct.nodes = nodes.data_ptr()
         self.c_struct.nodes_cap = nodes.numel()
         self.c_struct.tier_off = tier_off.data_ptr()
+
+
+# Streams bound to a share of the compute units, one per (device, range, role), kept for the life of the process: torch
+# objects of any pipeline may refer to them (events, pinned buffers), so they are never destroyed while pipelines live.
+_shared_streams = {}
+_stream_owner = {}
+
+
+def shared_stream_on_cus(device, first_cu, num_cus, role):
+    """The process-wide stream of `role` (any hashable) on compute units [first_cu, first_cu + num_cus) of `device`."""
+    device = int(device)
+    key = (device, int(first_cu), int(num_cus), role)
+    if key not in _shared_streams:
+        if device not in _stream_owner:
+            _stream_owner[device] = Context(device)
+        _shared_streams[key] = _stream_owner[device].stream_on_cus(first_cu, num_cus)
+    return _shared_streams[key]
+
+
+def close_shared_streams():
+    """Gives the shared streams back.  Only for a program's last lines, once every pipeline and every torch object that
+    worked on them is gone (a profiler that wraps the runtime wants the streams destroyed before the process exits)."""
+    import gc
+    gc.collect()
+    for device, owner in list(_stream_owner.items()):
+        try:
+            torch.cuda.synchronize(device)
+        except Exception:
+            pass
+        owner.close()
+    _shared_streams.clear()
+    _stream_owner.clear()
 
 
 class FeatureCache:

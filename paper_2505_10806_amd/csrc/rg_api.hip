@@ -4,6 +4,8 @@
 #include <string.h>
 
 #include "rg_internal.h"
+#include <algorithm>
+#include <vector>
 
 static char g_create_error[512];
 
@@ -145,6 +147,7 @@ void rg_destroy(rg_ctx* ctx) {
     for (auto& p : ctx->free_events) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
     if (ctx->ev_classified) (void)hipEventDestroy(ctx->ev_classified);
     if (ctx->ev_miss_done) (void)hipEventDestroy(ctx->ev_miss_done);
+    for (hipStream_t s : ctx->streams) (void)hipStreamDestroy(s);       // after the events that may have been recorded on them
     delete ctx;
 }
 
@@ -218,6 +221,33 @@ rg_status rg_profile_read(rg_ctx* ctx, int kernel_id, double* total_ms, int64_t*
     if (st != RG_OK) return st;
     *total_ms = ctx->prof_ms[kernel_id];
     *launches = ctx->prof_launches[kernel_id];
+    return RG_OK;
+}
+
+rg_status rg_stream_create(rg_ctx* ctx, int32_t first_cu, int32_t num_cus, void** stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, stream, "rg_stream_create: stream is NULL");
+    RG_REQUIRE(ctx, first_cu >= 0 && num_cus >= 1 && first_cu + num_cus <= ctx->num_cus,
+               "rg_stream_create: compute units [%d, %d) are not within the device's %d", first_cu, first_cu + num_cus, ctx->num_cus);
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    const int words = (ctx->num_cus + 31) / 32;
+    std::vector<uint32_t> mask((size_t)words, 0u);
+    for (int cu = first_cu; cu < first_cu + num_cus; ++cu) mask[(size_t)(cu >> 5)] |= 1u << (cu & 31);
+    hipStream_t s = nullptr;
+    RG_HIP(ctx, hipExtStreamCreateWithCUMask(&s, (uint32_t)words, mask.data()));
+    ctx->streams.push_back(s);
+    *stream = (void*)s;
+    return RG_OK;
+}
+
+rg_status rg_stream_destroy(rg_ctx* ctx, void* stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    auto it = std::find(ctx->streams.begin(), ctx->streams.end(), (hipStream_t)stream);
+    RG_REQUIRE(ctx, it != ctx->streams.end(), "rg_stream_destroy: not a stream of this context's rg_stream_create");
+    ctx->streams.erase(it);
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    RG_HIP(ctx, hipStreamSynchronize((hipStream_t)stream));
+    RG_HIP(ctx, hipStreamDestroy((hipStream_t)stream));
     return RG_OK;
 }
 

@@ -70,6 +70,7 @@ struct rg_ctx {
     int64_t gather_rows[RG_GATHER_TICKETS] = {-1, -1, -1, -1, -1, -1, -1, -1};   // rows a ticket was prepared for (-1: none)
     hipEvent_t ev_classified = nullptr, ev_miss_done = nullptr;
     void* static_scratch = nullptr;   // device address of the library's file-scope gather scratch on ctx->device
+    std::vector<hipStream_t> streams;   // streams made by rg_stream_create and not yet destroyed (rg_destroy takes the rest)
 
     // profiling
     bool profiling = false;

@@ -53,7 +53,8 @@ class EpochPipeline:
     def __init__(self, wl, device="cuda:0", max_batches=None, ctx=None, two_streams=True, prefetch=True,
                  histogram="epoch", sampler_streams=2, double_buffer=False,
                  queue_depth=1, consumer=None, planned_prefetch=True, sample_group=8, keep_blocks=False,
-                 node_order="ascending", period_epochs=1, mirror_cache=None, keep_rows=False, mirror_pulls="group"):
+                 node_order="ascending", period_epochs=1, mirror_cache=None, keep_rows=False, mirror_pulls="group",
+                 pull_cus=0):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -142,11 +143,25 @@ class EpochPipeline:
         self._tickets = {}                         # ticket -> (epoch state, batch) it is prepared for
         self.orders = [torch.empty_like(wl.train_ids) for _ in range(self.period_epochs)]
         self.order = self.orders[0]
-        self.side = torch.cuda.Stream(device=device) if two_streams else None
+        # pull_cus > 0: the prefetch stream gets that many compute units to itself and every other stream of the pipeline
+        # (and self.work_stream, for the caller's gathers) the rest, so that no other kernel's wavefronts share a unit
+        # with the few wavefronts that sit waiting on the host link
+        self.pull_cus = int(pull_cus) if prefetch else 0
+        n_cus = self.ctx.num_cus
+        if self.pull_cus and not 0 < self.pull_cus < n_cus:
+            raise ValueError("pull_cus must leave compute units for the other streams")
+        def new_stream(role):
+            if not self.pull_cus:
+                return torch.cuda.Stream(device=device)
+            # (process-wide streams, shared by all pipelines: torch objects may refer to a stream for longer than a pipeline lives)
+            lo, n = (0, self.pull_cus) if role == "pulls" else (self.pull_cus, n_cus - self.pull_cus)
+            return B.shared_stream_on_cus(self.ctx.device, lo, n, role)
+        self.work_stream = new_stream("work") if self.pull_cus else None
+        self.side = new_stream("side") if two_streams else None
         # prefetch = pull cached rows batch by batch, in order of first use, on a stream of their own so the
         # host-link transfer overlaps the gathers; otherwise one bulk pull right after TopHot
         self.prefetch = prefetch
-        self.pf_stream = torch.cuda.Stream(device=device) if prefetch else None
+        self.pf_stream = new_stream("pulls") if prefetch else None
         # planned prefetch: the epoch histogram also records the first batch that needs each node, the selected
         # slots are grouped by that batch once, and the prefetch stream then carries nothing but pulls
         self.planned = bool(prefetch and planned_prefetch and histogram != "batch" and not self.mirror)
@@ -160,11 +175,17 @@ class EpochPipeline:
         spare = [st for st in (self.side, None if self.mirror else self.pf_stream) if st is not None]
         self.lane_stream = [None] + spare[:self.n_lanes - 1]
         while len(self.lane_stream) < self.n_lanes:
-            self.lane_stream.append(torch.cuda.Stream(device=device))
+            self.lane_stream.append(new_stream(("lane", len(self.lane_stream))))
         # with double buffering the next epoch is precomputed on one stream of its own while the current one is served
-        self.build_stream = torch.cuda.Stream(device=device) if double_buffer else None
+        self.build_stream = new_stream("build") if double_buffer else None
         for c in self.lane_ctx:
             c.reserve(cfg.num_nodes, self.slot, self.slot if c is self.ctx else 0, self.sample_group)
+
+    def close(self):
+        """Waits for the device and releases the sampler lanes' contexts.  The pipeline cannot be used afterwards."""
+        torch.cuda.synchronize(self.device)
+        for c in self.lane_ctx:
+            c.close()
 
     # ---- the current epoch's buffers under their historical names
     @property

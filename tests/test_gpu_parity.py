@@ -572,6 +572,87 @@ def _oracle_period(wl, rp, ci, home_np, train_np, first_epoch, epochs):
     return inputs, counts
 
 
+@pytest.mark.parametrize("full_cache", [False, True])
+def test_pipeline_with_compute_units_split_between_pulls_and_the_rest(B, full_cache):
+    """pull_cus: the prefetch stream is bound to a few compute units, every other stream of the pipeline (and the
+    stream the gathers run on) to the rest.  Placement changes nothing in the results: two epochs, double buffered,
+    every batch's rows and statistics and each epoch's cache against the oracle."""
+    import dataclasses
+    from paper_2505_10806_amd.pipeline import EpochPipeline
+    base = synth.CONFIGS["tiny"]
+    wl = synth.build_workload(dataclasses.replace(base, cache_frac=1.0) if full_cache else base, seed=9, device=DEV)
+    cfg = wl.cfg
+    rp, ci = host_graph(wl)
+    X = wl.features.cpu().numpy()
+    home_np, train_np = wl.home.cpu().numpy(), wl.train_ids.cpu().numpy()
+    pipe = EpochPipeline(wl, device=DEV, double_buffer=True, pull_cus=16)
+    assert pipe.work_stream is not None and pipe.mirror == full_cache
+    nb = pipe.batches_per_epoch
+    expected, seen = {}, []
+
+    def epoch_start(p, k):
+        torch.cuda.synchronize()
+        inputs, counts = _oracle_period(wl, rp, ci, home_np, train_np, k, 1)
+        ids, loc = oracle.build_cache(counts, home_np, wl.capacity_rows)
+        expected[k] = (inputs, loc)
+        assert np.array_equal(p.counts.cpu().numpy().view(np.uint32), counts)
+        assert np.array_equal(p.cache.cache_ids[:ids.size].cpu().numpy(), ids)
+        assert np.array_equal(p.cache.loc.cpu().numpy(), loc)
+        p._epoch = k
+
+    def batch_done(p, b):
+        torch.cuda.synchronize()
+        inputs, loc = expected[p._epoch]
+        want, st = oracle.gather_features(X, inputs[b], loc)
+        assert np.array_equal(p.out[:inputs[b].size, :cfg.feat_dim].cpu().numpy(), want), f"epoch {p._epoch} batch {b}"
+        assert tuple(p.stats[b].cpu().tolist()) == st
+        seen.append((p._epoch, b))
+
+    with torch.cuda.stream(pipe.work_stream):
+        pipe.run_epochs(0, 2, nb, on_batch=batch_done, on_epoch_start=epoch_start)
+    torch.cuda.synchronize()
+    assert seen == [(k, b) for k in (0, 1) for b in range(nb)]
+    pipe.close()
+
+
+def test_streams_on_a_share_of_the_compute_units(B):
+    """rg_stream_create / rg_stream_destroy: a gather on a stream bound to 8 compute units gives the oracle's rows; ranges
+    outside the device and foreign streams are refused."""
+    c = B.Context(0)
+    n_cus = c.num_cus
+    s = c.stream_on_cus(n_cus - 8, 8)
+    wl = synth.build_workload("tiny", seed=4, device=DEV)
+    cfg = wl.cfg
+    X = wl.features.cpu().numpy()
+    home_np = wl.home.cpu().numpy()
+    g = torch.Generator().manual_seed(1)
+    nodes = torch.randint(0, cfg.num_nodes, (5000,), generator=g, dtype=torch.int32)
+    counts_orc = np.zeros(cfg.num_nodes, dtype=np.uint32)
+    oracle.access_histogram(nodes.numpy(), counts_orc)
+    ids_orc, loc_orc = oracle.build_cache(counts_orc, home_np, wl.capacity_rows)
+    nodes_dev = nodes.to(DEV)
+    counts = torch.zeros(cfg.num_nodes, dtype=torch.int32, device=DEV)
+    cache = B.FeatureCache(cfg.num_nodes, wl.capacity_rows, wl.stride, DEV)
+    out = torch.zeros(nodes.numel(), wl.stride, device=DEV)
+    stats = torch.zeros(3, dtype=torch.int64, device=DEV)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        c.access_histogram(nodes_dev, nodes.numel(), counts)
+        c.build_cache(counts, wl.home, wl.remote_store, cfg.feat_dim, cache)
+        c.gather_features(nodes_dev, nodes.numel(), cache, wl.local_store, wl.remote_store, cfg.feat_dim, out, stats)
+    s.synchronize()
+    want, st = oracle.gather_features(X, nodes.numpy(), loc_orc)
+    assert tuple(stats.cpu().tolist()) == st and st[1] > 0 and st[2] > 0
+    assert np.array_equal(out[:, :cfg.feat_dim].cpu().numpy(), want)
+    for first, n in ((0, 0), (-1, 4), (n_cus - 3, 4), (0, n_cus + 1)):
+        with pytest.raises(B.RgError):
+            c.stream_on_cus(first, n)
+    assert B._lib.rg_stream_destroy(c._h, 0x1234) != B.RG_OK           # not one of this context's streams
+    assert B._lib.rg_stream_destroy(c._h, s.cuda_stream) == B.RG_OK
+    assert B._lib.rg_stream_destroy(c._h, s.cuda_stream) != B.RG_OK           # already gone
+    c.close()
+
+
 @pytest.mark.parametrize("double_buffer", [False, True])
 def test_pipeline_period_of_two_epochs_shares_one_cache(B, double_buffer):
     """Alg. 1 lines 1-4 as written: the batches of all precomputed epochs are counted together and one steady cache
