@@ -95,7 +95,7 @@ RG_API void rg_destroy(rg_ctx* ctx);
 RG_API const char* rg_last_error(const rg_ctx* ctx);
 RG_API const char* rg_version(void);
 
-/* Pre-size the scratch so later sampling, histogram, TopHot and gather calls allocate nothing:
+/* Pre-size the scratch so later sampling, histogram, TopHot, plan and gather calls allocate nothing:
  * graphs of up to num_nodes nodes, cumulative frontiers of up to max_frontier nodes, sampler
  * calls of up to sample_group batches (1 for rg_sample_blocks), gathers and per-batch prefetch
  * passes of up to max_rows rows.  Optional: every call grows the scratch on demand (a

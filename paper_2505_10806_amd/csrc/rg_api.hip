@@ -165,6 +165,10 @@ rg_status rg_reserve(rg_ctx* ctx, int64_t num_nodes, int64_t max_frontier, int64
     if ((st = rg_gather_reserve(ctx, max_rows)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->pf_list, (size_t)max_rows * 8)) != RG_OK) return st;
     if ((st = rg_ensure(ctx, ctx->pf_ctl, 64)) != RG_OK) return st;
+    // rg_plan_sampled: one word of new-node bits per 32 nodes, one pair count per 1024 words
+    const int64_t words = rg_max64(1, rg_div_up(num_nodes, 32));
+    if ((st = rg_ensure(ctx, ctx->claim_bits, (size_t)words * 4)) != RG_OK) return st;
+    if ((st = rg_ensure(ctx, ctx->claim_blk, (size_t)rg_max64(1, rg_div_up(words, 1024)) * 4)) != RG_OK) return st;
     return RG_OK;
 }
 
