@@ -572,6 +572,68 @@ def _oracle_period(wl, rp, ci, home_np, train_np, first_epoch, epochs):
     return inputs, counts
 
 
+@pytest.mark.parametrize("mirror_pulls", ["group", "batch"])
+@pytest.mark.parametrize("double_buffer", [False, True])
+def test_pipeline_keeps_rows_of_earlier_epochs(B, double_buffer, mirror_pulls):
+    """keep_rows on a cache that mirrors the remote store: features do not change, so an epoch pulls only the rows that
+    no earlier epoch has named.  Three epochs; every batch's rows and statistics and each epoch's TopHot result against
+    the oracle (which knows nothing of kept rows: the result must not depend on them); after each epoch the resident
+    rows are exactly the remote nodes named so far, each holding its feature row, and nothing else was written."""
+    import dataclasses
+    from paper_2505_10806_amd.pipeline import EpochPipeline
+    wl = synth.build_workload(dataclasses.replace(synth.CONFIGS["tiny"], cache_frac=1.0), seed=12, device=DEV)
+    cfg = wl.cfg
+    rp, ci = host_graph(wl)
+    X = wl.features.cpu().numpy()
+    home_np, train_np = wl.home.cpu().numpy(), wl.train_ids.cpu().numpy()
+    tag = (home_np.astype(np.int64) & 0xFFFFFFFF) >> 30
+    remote_ids = np.flatnonzero(tag == 2)
+    assert np.array_equal(home_np[remote_ids].astype(np.int64) & 0x3FFFFFFF, np.arange(remote_ids.size))   # row = rank among the remote ids
+    pipe = EpochPipeline(wl, device=DEV, double_buffer=double_buffer, keep_rows=True, mirror_pulls=mirror_pulls)
+    assert pipe.mirror and pipe.keep_rows
+    pipe.cache.cache_rows.fill_(float("nan"))
+    nb = pipe.batches_per_epoch
+    expected, named, resident_counts = {}, np.zeros(cfg.num_nodes, dtype=bool), []
+
+    def epoch_start(p, k):
+        torch.cuda.synchronize()
+        inputs, counts = _oracle_period(wl, rp, ci, home_np, train_np, k, 1)
+        ids, loc = oracle.build_cache(counts, home_np, wl.capacity_rows)
+        expected[k] = (inputs, loc)
+        assert np.array_equal(p.cache.cache_ids[:ids.size].cpu().numpy(), ids) and int(p.cache.num_cached.item()) == ids.size
+        assert np.array_equal(p.cache.loc.cpu().numpy(), loc)
+        p._epoch = k
+
+    def batch_done(p, b):
+        torch.cuda.synchronize()
+        inputs, loc = expected[p._epoch]
+        want, st = oracle.gather_features(X, inputs[b], loc)
+        assert st[2] == 0 and tuple(p.stats[b].cpu().tolist()) == st
+        assert np.array_equal(p.out[:inputs[b].size, :cfg.feat_dim].cpu().numpy(), want), f"epoch {p._epoch} batch {b}"
+
+    def epoch_done(p, k):
+        torch.cuda.synchronize()
+        for nodes in expected[k][0]:
+            named[nodes] = True
+        bits = np.unpackbits(p.cache.filled.cpu().numpy().view(np.uint8), bitorder="little")[:wl.n_remote].astype(bool)
+        if not double_buffer:                     # (with the double buffer the next epoch's pulls are already under way)
+            assert np.array_equal(bits, named[remote_ids])
+            got = p.cache.cache_rows.cpu().numpy()
+            assert np.array_equal(got[bits, :cfg.feat_dim], X[remote_ids[bits]]) and np.isnan(got[~bits]).all()
+        else:
+            assert bits[named[remote_ids]].all()
+        resident_counts.append(int(named[remote_ids].sum()))
+
+    pipe.run_epochs(0, 3, nb, on_epoch_done=epoch_done, on_batch=batch_done, on_epoch_start=epoch_start)
+    torch.cuda.synchronize()
+    bits = np.unpackbits(pipe.cache.filled.cpu().numpy().view(np.uint8), bitorder="little")[:wl.n_remote].astype(bool)
+    assert np.array_equal(bits, named[remote_ids])
+    got = pipe.cache.cache_rows.cpu().numpy()
+    assert np.array_equal(got[bits, :cfg.feat_dim], X[remote_ids[bits]]) and np.isnan(got[~bits]).all()
+    assert resident_counts[0] < resident_counts[1] < resident_counts[2] < wl.n_remote     # each epoch added rows, none named them all
+    pipe.close()
+
+
 @pytest.mark.parametrize("full_cache", [False, True])
 def test_pipeline_with_compute_units_split_between_pulls_and_the_rest(B, full_cache):
     """pull_cus: the prefetch stream is bound to a few compute units, every other stream of the pipeline (and the
