@@ -58,6 +58,7 @@ class EpochPipeline:
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
+        self._own_ctx = ctx is None
         self.ctx = ctx or B.Context(torch.device(device).index or 0)
         self.csr = B.CsrGraph(wl.row_ptr, wl.col_idx)
         self.batches_per_epoch = wl.batches_per_epoch()
@@ -185,7 +186,8 @@ class EpochPipeline:
         """Waits for the device and releases the sampler lanes' contexts.  The pipeline cannot be used afterwards."""
         torch.cuda.synchronize(self.device)
         for c in self.lane_ctx:
-            c.close()
+            if c is not self.ctx or self._own_ctx:       # a context the caller passed in stays the caller's
+                c.close()
 
     # ---- the current epoch's buffers under their historical names
     @property

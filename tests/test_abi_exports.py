@@ -58,3 +58,23 @@ def test_create_without_gpu_fails_loudly():
     with pytest.raises(binding.RgError) as e:
         binding.Context(0)
     assert e.value.status == binding.RG_ERR_HIP
+
+
+def test_pipeline_call_sizes_cover_every_batch_once():
+    """Host logic of the epoch driver: the batches of an epoch are dealt to sampler calls of at most `group` batches;
+    with one pull per call a period opens with a single batch and closes with calls of 2, 1 and 1."""
+    import types
+    from paper_2505_10806_amd.pipeline import EpochPipeline
+    grouped = types.SimpleNamespace(group_pulls=True)
+    plain = types.SimpleNamespace(group_pulls=False)
+    for group in (1, 2, 8, 16):
+        for n in list(range(1, 40)) + [245, 1000]:
+            for first in (False, True):
+                for last in (False, True):
+                    sizes = EpochPipeline._call_sizes(grouped, n, group, first, last)
+                    assert sum(sizes) == n and all(1 <= x <= group for x in sizes), (group, n, first, last, sizes)
+                    if group > 1 and n > 1 and first:
+                        assert sizes[0] == 1
+                    if group > 1 and n >= 6 and last:
+                        assert sizes[-3:] == [2, 1, 1]
+            assert EpochPipeline._call_sizes(plain, n, group, True, True) == [group] * (n // group) + ([n % group] if n % group else [])
