@@ -417,6 +417,10 @@ typedef enum {
 } rg_kernel_id;
 
 RG_API rg_status rg_profile_enable(rg_ctx* ctx, int on);
+/* Brackets only the kernels whose bit (1u << rg_kernel_id) is set in kernel_mask (default: all).  Two event
+ * records per launch on every stream shift what runs beside what; a pass that brackets one kernel alone times
+ * that kernel closest to an unbracketed run. */
+RG_API rg_status rg_profile_select(rg_ctx* ctx, uint32_t kernel_mask);
 RG_API rg_status rg_profile_reset(rg_ctx* ctx);
 RG_API rg_status rg_profile_read(rg_ctx* ctx, int kernel_id, double* total_ms, int64_t* launches);
 

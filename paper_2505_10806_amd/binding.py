@@ -98,12 +98,13 @@ def _load():
     L.rg_gather_features_static.argtypes = L.rg_gather_features.argtypes
     L.rg_profile_enable.argtypes = [c_p, ctypes.c_int]
     L.rg_profile_reset.argtypes = [c_p]
+    L.rg_profile_select.argtypes = [c_p, ctypes.c_uint32]
     L.rg_profile_read.argtypes = [c_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_i64)]
     for name in ("rg_create", "rg_reserve", "rg_epoch_schedule", "rg_blocks_bounds", "rg_sample_blocks", "rg_sample_blocks_group",
                  "rg_access_histogram", "rg_access_histogram_epoch", "rg_access_histogram_sampled", "rg_build_cache", "rg_cache_hit_curve",
                  "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_plan_sampled", "rg_prefetch_planned", "rg_gather_features",
                  "rg_gather_features_static", "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable",
-                 "rg_profile_reset", "rg_profile_read", "rg_stream_create", "rg_stream_destroy"):
+                 "rg_profile_reset", "rg_profile_read", "rg_profile_select", "rg_stream_create", "rg_stream_destroy"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -116,7 +117,7 @@ EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "r
                     "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_plan_prefetch",
                     "rg_plan_sampled", "rg_prefetch_planned", "rg_gather_features", "rg_gather_features_static",
                     "rg_stream_create", "rg_stream_destroy", "rg_gather_prepare",
-                    "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_reset", "rg_profile_read"]
+                    "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_select", "rg_profile_reset", "rg_profile_read"]
 
 
 def _ptr(t, dtype=None, device_type=None, name="tensor"):
@@ -349,6 +350,11 @@ class Context:
     # -- rg_profile_*
     def profile_enable(self, on=True):
         self._check(_lib.rg_profile_enable(self._h, 1 if on else 0))
+
+    def profile_select(self, kernel_ids=None):
+        """Bracket only the listed kernel ids while profiling is on (None = all)."""
+        mask = 0xFFFFFFFF if kernel_ids is None else sum(1 << int(k) for k in set(kernel_ids))
+        self._check(_lib.rg_profile_select(self._h, mask))
 
     def profile_reset(self):
         self._check(_lib.rg_profile_reset(self._h))

@@ -218,6 +218,12 @@ rg_status rg_profile_reset(rg_ctx* ctx) {
     return RG_OK;
 }
 
+rg_status rg_profile_select(rg_ctx* ctx, uint32_t kernel_mask) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    ctx->prof_mask = kernel_mask;
+    return RG_OK;
+}
+
 rg_status rg_profile_read(rg_ctx* ctx, int kernel_id, double* total_ms, int64_t* launches) {
     if (!ctx) return RG_ERR_INVALID_ARG;
     RG_REQUIRE(ctx, kernel_id >= 0 && kernel_id < RG_K_COUNT_ && total_ms && launches, "rg_profile_read: bad argument");
@@ -258,7 +264,7 @@ rg_status rg_stream_destroy(rg_ctx* ctx, void* stream) {
 }  // extern "C"
 
 int rg_prof_begin(rg_ctx* ctx, int kernel, hipStream_t s) {
-    if (!ctx->profiling) return -1;
+    if (!ctx->profiling || !((ctx->prof_mask >> kernel) & 1u)) return -1;
     RgProfSpan span;
     span.kernel = kernel;
     if (!ctx->free_events.empty()) {

@@ -74,6 +74,7 @@ struct rg_ctx {
 
     // profiling
     bool profiling = false;
+    uint32_t prof_mask = 0xFFFFFFFFu;  // bit k: launches of kernel id k are bracketed while profiling is on
     std::vector<RgProfSpan> spans;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> free_events;
     double prof_ms[RG_K_COUNT_] = {0};

@@ -215,6 +215,10 @@ class EpochPipeline:
         for c in self.lane_ctx:
             c.profile_enable(on)
 
+    def profile_select(self, kernel_ids=None):
+        for c in self.lane_ctx:
+            c.profile_select(kernel_ids)
+
     def profile_reset(self):
         for c in self.lane_ctx:
             c.profile_reset()
