@@ -491,6 +491,56 @@ def test_plan_segments_from_sampler_bitmaps(B, ctx):
             bad()
 
 
+@pytest.mark.parametrize("first_seen", [False, True])
+@pytest.mark.parametrize("n_nodes,group", [(33, 1), (33, 5), (700, 16), (70_001, 3), (70_001, 8)])
+def test_plan_segments_ragged_sizes(B, ctx, n_nodes, group, first_seen):
+    """rg_plan_sampled where the bitmaps end inside a word, span one or several 1024-word blocks and a ragged last one,
+    for groups of 1 to 16 batches (one of them empty) in either node order; home words drawn at random.  Two calls:
+    the second segment holds only what the first has not claimed."""
+    log(f"[plan ragged] N={n_nodes} group={group} first_seen={first_seen}")
+    rng = np.random.default_rng(n_nodes + group)
+    if n_nodes <= 1000:
+        rp, ci = _handmade_graph(n_nodes, 0.5, min(8, n_nodes), 0.02 if n_nodes > 100 else 0.2, rng)
+    else:
+        rp_t, ci_t = synth.chung_lu_csr(n_nodes, 12, 2.3, seed=3)
+        rp, ci = rp_t.numpy().astype(np.int64), ci_t.numpy()
+    csr = B.CsrGraph(torch.as_tensor(rp, device=DEV), _i32(ci))
+    remote = rng.random(n_nodes) < 0.6
+    remote[rng.integers(n_nodes)] = True
+    home_np = np.where(remote, (2 << 30) | (np.cumsum(remote) - 1), np.cumsum(~remote) - 1).astype(np.int64)
+    home = torch.as_tensor(home_np.astype(np.uint32).view(np.int32), device=DEV)
+    n_remote = int(remote.sum())
+    cache = B.FeatureCache(n_nodes, n_remote, 4, DEV, mirror_rows=n_remote, home=home)
+    plan = B.PrefetchPlan(n_remote, 2, DEV)
+    plan.set_num_batches(2)
+    claimed = torch.zeros((n_nodes + 31) // 32, dtype=torch.int32, device=DEV)
+    fanouts = (4, 3)
+    order = oracle.ORDER_FIRST_SEEN if first_seen else oracle.ORDER_ASCENDING
+    seen = np.zeros(n_nodes, dtype=bool)
+    start = 0
+    for seg in range(2):
+        sizes = [min(n_nodes, x) for x in ([40, 0, 17, 64, 5, 1, 33, 80, 2, 9, 50, 12, 7, 3, 21, 60][:group])]
+        seeds_np = [rng.choice(n_nodes, size=k, replace=False).astype(np.int32) for k in sizes]
+        outs = [B.BlockBuffers(n_nodes, ci.size, max(k, 1), fanouts, DEV) for k in sizes]
+        ctx.sample_blocks_group(csr, [_i32(x) if x.size else torch.empty(0, dtype=torch.int32, device=DEV) for x in seeds_np],
+                                fanouts, 11, seg, outs, node_order=B.RG_ORDER_FIRST_SEEN if first_seen else B.RG_ORDER_ASCENDING)
+        ctx.plan_sampled(group, cache, claimed, plan, seg)
+        torch.cuda.synchronize()
+        new = np.zeros(n_nodes, dtype=bool)
+        for x in seeds_np:
+            new[oracle.sample_blocks(rp, ci, x, fanouts, 11, seg, order).input_nodes] = True
+        new &= ~seen
+        seen |= new
+        rows = home_np[np.flatnonzero(new & remote)] & 0x3FFFFFFF
+        offs = plan.offsets.cpu().numpy()
+        assert offs[seg] == start and offs[seg + 1] == start + rows.size, (seg, offs[:3], rows.size)
+        pairs = plan.list.cpu().numpy()[2 * start:2 * (start + rows.size)].reshape(-1, 2)
+        assert np.array_equal(pairs[:, 0], rows) and np.array_equal(pairs[:, 1], rows)
+        cl = np.unpackbits(claimed.cpu().numpy().view(np.uint8), bitorder="little")
+        assert np.array_equal(cl[:n_nodes].astype(bool), seen) and not cl[n_nodes:].any()
+        start += rows.size
+
+
 @pytest.mark.parametrize("histogram,node_order", [("epoch", "ascending"), ("sampled", "ascending"), ("sampled", "first_seen"),
                                                   ("batch", "first_seen")])
 @pytest.mark.parametrize("full_cache", [False, True])
