@@ -106,3 +106,55 @@ def test_static_gather_matches_allocating_gather(name, two_streams):
     torch.cuda.synchronize()
     assert tuple(got_st.cpu().tolist()) == refs[1][1] and torch.equal(got_out[:n1], refs[1][0])
     ctx.close()
+
+
+def test_static_gather_replays_from_a_hip_graph():
+    """What the entry point is for: the call is captured into a HIP graph (nothing in it allocates, and its scratch sits at
+    a fixed address) and replayed for new inputs written into the same buffers.  Each of three replays, with eager work
+    and synchronisations between them, must give the rows and statistics of the eager call on the same input."""
+    from paper_2505_10806_amd import binding as B
+    wl = synth.build_workload("tiny", seed=13, device=DEV)
+    cfg = wl.cfg
+    ctx = B.Context(0)
+    nodes, counts = _sampled_batches(B, ctx, wl, 3)
+    cache = B.FeatureCache(cfg.num_nodes, min(wl.capacity_rows, wl.n_remote), wl.stride, DEV)
+    ctx.build_cache(counts, wl.home, wl.remote_store, cfg.feat_dim, cache)
+    cap = max(x.numel() for x in nodes)
+    ids_buf = torch.zeros(cap, dtype=torch.int32, device=DEV)      # the graph reads its input here ...
+    n_dev = torch.zeros(1, dtype=torch.int32, device=DEV)          # ... and the row count here
+    out = torch.empty(cap, wl.stride, device=DEV)
+    stats = torch.zeros(3, dtype=torch.int64, device=DEV)
+    eager_out = torch.empty(cap, wl.stride, device=DEV)
+    eager_stats = torch.zeros(3, dtype=torch.int64, device=DEV)
+
+    def load(ids):
+        ids_buf[:ids.numel()].copy_(ids)
+        n_dev.fill_(ids.numel())
+
+    load(nodes[0])
+    ctx.gather_features_static(ids_buf, cap, cache, wl.local_store, wl.remote_store, cfg.feat_dim, out, stats, n_dev=n_dev)   # warm-up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph.capture_begin(capture_error_mode="relaxed")
+        ctx.gather_features_static(ids_buf, cap, cache, wl.local_store, wl.remote_store, cfg.feat_dim, out, stats, n_dev=n_dev)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for replay, ids in enumerate((nodes[1], nodes[2], nodes[0])):
+        n = ids.numel()
+        log(f"[no-alloc] graph replay {replay}: n = {n}")
+        eager_out.fill_(-7.0)
+        ctx.gather_features(ids, n, cache, wl.local_store, wl.remote_store, cfg.feat_dim, eager_out, eager_stats)   # eager work between replays
+        torch.cuda.synchronize()
+        load(ids)
+        out.fill_(-7.0)
+        stats.fill_(99)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert tuple(stats.cpu().tolist()) == tuple(eager_stats.cpu().tolist())
+        assert torch.equal(out[:n], eager_out[:n]) and bool((out[n:] == -7.0).all())
+    del graph
+    ctx.close()
