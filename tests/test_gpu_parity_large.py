@@ -19,6 +19,7 @@ import synth
 from gpu_common import OracleAhead, host_graph, log
 
 pytestmark = pytest.mark.gpu
+PULL_CUS = 16                   # bench.py's default: the launch configuration it times
 DEV = "cuda:0"
 
 
@@ -60,8 +61,14 @@ def _check_cache_resident(pipe, X, ids_orc, dim):
 
 
 def _epoch_parity(pipe, wl, host, epoch, row_batches):
-    """One whole epoch as bench.py runs it (offline stage, then prefetch stream ahead of the gathers), every
-    output against the oracle.  row_batches: the batches whose gathered rows are compared in full."""
+    """One whole epoch as bench.py runs it (offline stage, then prefetch stream ahead of the gathers; the pull stream on
+    compute units of its own and the caller on the pipeline's work stream), every output against the oracle.
+    row_batches: the batches whose gathered rows are compared in full."""
+    with torch.cuda.stream(pipe.work_stream):
+        return _epoch_parity_on_current_stream(pipe, wl, host, epoch, row_batches)
+
+
+def _epoch_parity_on_current_stream(pipe, wl, host, epoch, row_batches):
     cfg, H = wl.cfg, len(wl.cfg.fanouts)
     rp, ci, X, X1, home_np, train_np = host
     nb = pipe.batches_per_epoch
@@ -149,7 +156,7 @@ def test_large_workload_both_epochs(name):
     cfg = wl.cfg
     log(f"[large] {name}: N={cfg.num_nodes} nnz={wl.nnz} D={cfg.feat_dim} capacity={wl.capacity_rows}")
     host = _host_inputs(wl)
-    pipe = EpochPipeline(wl, device=DEV, keep_blocks=True)
+    pipe = EpochPipeline(wl, device=DEV, keep_blocks=True, pull_cus=PULL_CUS)
     nb = pipe.batches_per_epoch
     assert cfg.epochs == 2
     first = None
@@ -168,7 +175,7 @@ def test_large_workload_first_seen_order_and_bitmap_counts():
     from paper_2505_10806_amd.pipeline import EpochPipeline
     wl = synth.build_workload("sparse_copurchase", seed=2025, device=DEV)
     host = _host_inputs(wl)
-    pipe = EpochPipeline(wl, device=DEV, keep_blocks=True, node_order="first_seen", histogram="sampled")
+    pipe = EpochPipeline(wl, device=DEV, keep_blocks=True, node_order="first_seen", histogram="sampled", pull_cus=PULL_CUS)
     assert pipe.planned
     nb = pipe.batches_per_epoch
     inputs, tot = _epoch_parity(pipe, wl, host, 0, range(0, nb, 4))
@@ -188,7 +195,7 @@ def test_stress_workload():
     log(f"[stress] N={cfg.num_nodes} nnz={wl.nnz} D={cfg.feat_dim} capacity={wl.capacity_rows}")
     host = _host_inputs(wl)
     rp, ci, X, X1, home_np, train_np = host
-    pipe = EpochPipeline(wl, device=DEV, keep_blocks=True)
+    pipe = EpochPipeline(wl, device=DEV, keep_blocks=True, pull_cus=PULL_CUS)
     nb = pipe.batches_per_epoch
     assert nb == 245 and train_np.size == 1_000_000
 
@@ -236,7 +243,8 @@ def test_stress_workload():
             keep[b] = p.out[:p.sizes[b], :cfg.feat_dim].clone()
 
     log("[stress] second pass: start")
-    pipe.run_epoch(0, nb, on_batch=capture)
+    with torch.cuda.stream(pipe.work_stream):
+        pipe.run_epoch(0, nb, on_batch=capture)
     torch.cuda.synchronize()
     assert sizes_seen == [x.size for x in inputs]
     assert torch.equal(pipe.stats[:nb], stats1), "statistics of the second pass"
