@@ -318,7 +318,9 @@ RG_API rg_status rg_plan_prefetch(rg_ctx* ctx, const rg_cache* cache, const int3
 RG_API rg_status rg_prefetch_planned(rg_ctx* ctx, const rg_prefetch_plan* plan, int32_t batch, const rg_cache* cache,
                                      const float* remote_store, int64_t remote_stride, int32_t dim, void* stream);
 
-/* Mirrored cache only: appends segment `segment` to the plan = the remote rows that the group of batches sampled
+/* ---- the prefetcher's row lists straight from the sampler (Section III, prefetcher; Alg. 1 line 4, VectorPull:
+ * the rows go over the link in a few vectorised pulls instead of one request per row) ----
+ * Mirrored cache only: appends segment `segment` to the plan = the remote rows that the group of batches sampled
  * last on this context (rg_sample_blocks / rg_sample_blocks_group) is the first to name, as (row, row) pairs in
  * ascending row order, read off the sampler's membership bitmaps (no pass over the batches' id lists).
  * `claimed` (device uint32[ceil(num_nodes / 32)]) holds every node an earlier call has named; the call adds the
