@@ -1338,6 +1338,59 @@ def test_pipeline_with_mean_consumer_and_output_ring(B):
     assert len(seen) == 2 * nb and len(set(seen)) == 3                      # the ring's three buffers were cycled
 
 
+def test_kernel_timing_brackets_follow_the_selection(B):
+    """rg_profile_*: launches are bracketed only while profiling is on and only for the selected kernel ids; durations
+    are positive and the counts are those of the launches made; results are unaffected."""
+    wl = synth.build_workload("tiny", seed=6, device=DEV)
+    cfg = wl.cfg
+    c = B.Context(0)
+    X = wl.features.cpu().numpy()
+    g = torch.Generator().manual_seed(3)
+    nodes = torch.randint(0, cfg.num_nodes, (3000,), generator=g, dtype=torch.int32)
+    nodes_dev = nodes.to(DEV)
+    counts = torch.zeros(cfg.num_nodes, dtype=torch.int32, device=DEV)
+    cache = B.FeatureCache(cfg.num_nodes, wl.capacity_rows, wl.stride, DEV)
+    out = torch.zeros(nodes.numel(), wl.stride, device=DEV)
+    stats = torch.zeros(3, dtype=torch.int64, device=DEV)
+
+    def work():
+        counts.zero_()
+        c.access_histogram(nodes_dev, nodes.numel(), counts)
+        c.build_cache(counts, wl.home, wl.remote_store, cfg.feat_dim, cache)
+        c.gather_features(nodes_dev, nodes.numel(), cache, wl.local_store, wl.remote_store, cfg.feat_dim, out, stats)
+        c.gather_features(nodes_dev, nodes.numel(), cache, wl.local_store, wl.remote_store, cfg.feat_dim, out, stats)
+        torch.cuda.synchronize()
+
+    def launches():
+        return {k: c.profile_read(k) for k in (B.RG_K_GATHER_HBM, B.RG_K_GATHER_MISS, B.RG_K_HISTOGRAM, B.RG_K_CACHE_FILL)}
+
+    work()                                                # profiling off: nothing is recorded
+    assert all(n == 0 for _, n in launches().values())
+    c.profile_enable(True)
+    c.profile_reset()
+    work()
+    got = launches()
+    assert got[B.RG_K_GATHER_HBM][1] == 2 and got[B.RG_K_GATHER_MISS][1] == 2 and got[B.RG_K_HISTOGRAM][1] == 1 and got[B.RG_K_CACHE_FILL][1] == 1
+    assert all(ms > 0 for ms, _ in got.values())
+    c.profile_select([B.RG_K_GATHER_HBM])                 # this kernel alone
+    c.profile_reset()
+    work()
+    got = launches()
+    assert got[B.RG_K_GATHER_HBM][1] == 2 and got[B.RG_K_GATHER_HBM][0] > 0
+    assert got[B.RG_K_GATHER_MISS][1] == 0 and got[B.RG_K_HISTOGRAM][1] == 0 and got[B.RG_K_CACHE_FILL][1] == 0
+    c.profile_select(None)
+    c.profile_enable(False)
+    c.profile_reset()
+    work()
+    assert all(n == 0 for _, n in launches().values())
+    counts_orc = np.zeros(cfg.num_nodes, dtype=np.uint32)
+    oracle.access_histogram(nodes.numpy(), counts_orc)
+    _, loc_orc = oracle.build_cache(counts_orc, wl.home.cpu().numpy(), wl.capacity_rows)
+    want, st = oracle.gather_features(X, nodes.numpy(), loc_orc)
+    assert tuple(stats.cpu().tolist()) == st and np.array_equal(out[:, :cfg.feat_dim].cpu().numpy(), want)
+    c.close()
+
+
 # ------------------------------------------------------------------------------ argument errors
 def test_argument_errors_are_reported_not_launched(B, ctx):
     rp = torch.tensor([0, 1, 2], dtype=torch.int32, device=DEV)
