@@ -542,25 +542,15 @@ __global__ void __launch_bounds__(256) k_prefetch_select(const int32_t* __restri
     }
 }
 
-// dst_rows[list[2j]] = src_rows[list[2j+1]] for every pair of the list (host link or HBM source alike).
-// Marks the slots of list[seg_off[0]..seg_off[1]) resident (queued behind the pull of the same segment).
-__global__ void __launch_bounds__(256) k_mark_segment(const int32_t* __restrict__ list, const int32_t* __restrict__ seg_off,
-                                                      uint32_t* __restrict__ filled, int64_t dst_rows) {
-    const int64_t n = seg_off[1] - seg_off[0];
-    list += 2 * (int64_t)seg_off[0];
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t slot = list[2 * j];
-        if (slot >= 0 && slot < dst_rows) atomicOr(&filled[slot >> 5], 1u << (slot & 31));
-    }
-}
-
+// dst_rows[list[2j]] = src_rows[list[2j+1]] for every pair of the list (host link or HBM source alike); with `mark` the
+// destination rows' resident bits are set by the same kernel.
 // The pairs are list[0..pctl[0]) or, when seg_off is given, list[seg_off[0]..seg_off[1]).
 template <int VEC, int U>
 __global__ void __launch_bounds__(1024) k_prefetch_pull(const int32_t* __restrict__ list, const uint32_t* __restrict__ pctl,
                                                        const int32_t* __restrict__ seg_off,
                                                        const float* __restrict__ remote_store, int64_t remote_stride,
                                                        float* __restrict__ cache_rows, int64_t cache_stride, int64_t dst_rows,
-                                                       int cpr, int log2L, int tail) {
+                                                       int cpr, int log2L, int tail, uint32_t* __restrict__ mark) {
     typedef typename RgVec<VEC>::type V;
     int64_t n;
     if (seg_off) { list += 2 * (int64_t)seg_off[0]; n = seg_off[1] - seg_off[0]; } else { n = pctl[0]; }
@@ -587,6 +577,8 @@ __global__ void __launch_bounds__(1024) k_prefetch_pull(const int32_t* __restric
                 if (slot >= 0 && slot < dst_rows) {      // a list built for another destination must not write outside this one
                     src[u] = (const V*)(remote_store + rrow * remote_stride);
                     dst[u] = (V*)(cache_rows + slot * cache_stride);
+                    // the row's resident bit, by the first lane of its group (whoever reads the bits waits for this kernel)
+                    if (mark && c0 == 0) atomicOr(&mark[slot >> 5], 1u << (slot & 31));
                 }
             }
         }
@@ -840,7 +832,7 @@ __global__ void __launch_bounds__(256) k_zero_i32(int32_t* __restrict__ p, int n
 // Launches the list-driven row copy.  `blocks` and `threads` bound the wavefronts in flight.
 rg_status launch_list_copy(rg_ctx* ctx, const int32_t* list, const uint32_t* pctl, const float* src, int64_t src_stride,
                            float* dst, int64_t dst_stride, int64_t dst_rows, int32_t dim, int64_t n_upper, int64_t blocks,
-                           int threads, hipStream_t s, const int32_t* seg_off = nullptr) {
+                           int threads, hipStream_t s, const int32_t* seg_off = nullptr, uint32_t* mark = nullptr) {
     const void* ptrs[2] = {src, dst};
     const int64_t strides[2] = {src_stride, dst_stride};
     const int vec = rg_pick_vec(dim, ptrs, 2, strides, 2);
@@ -851,7 +843,7 @@ rg_status launch_list_copy(rg_ctx* ctx, const int32_t* list, const uint32_t* pct
     const int tok = rg_prof_begin(ctx, RG_K_CACHE_FILL, s);
 #define RG_LAUNCH_PULL(V, UU)                                                                                          \
     k_prefetch_pull<V, UU><<<grid, threads, 0, s>>>(list, pctl, seg_off, src, src_stride, dst, dst_stride, dst_rows, shp.cpr, \
-                                                    shp.log2L, shp.tail)
+                                                    shp.log2L, shp.tail, mark)
     if (vec == 4) { if (U == 8) RG_LAUNCH_PULL(4, 8); else RG_LAUNCH_PULL(4, 4); }
     else if (vec == 2) RG_LAUNCH_PULL(2, 4);
     else RG_LAUNCH_PULL(1, 4);
@@ -1140,11 +1132,8 @@ rg_status rg_prefetch_planned(rg_ctx* ctx, const rg_prefetch_plan* plan, int32_t
     const int64_t dst_rows = cache->mirror_rows > 0 ? cache->mirror_rows : cache->capacity_rows;
     rg_status st = launch_list_copy(ctx, plan->list, nullptr, remote_store, remote_stride, cache->cache_rows, cache->row_stride,
                                     dst_rows, dim, rg_max64(plan->list_capacity, 1), ctx->knobs.pull_blocks,
-                                    ctx->knobs.pull_threads, s, plan->offsets + batch);
-    if (st != RG_OK) return st;
-    k_mark_segment<<<ctx->num_cus, 256, 0, s>>>(plan->list, plan->offsets + batch, cache->filled, dst_rows);
-    RG_LAUNCH_CHECK(ctx, "k_mark_segment");
-    return RG_OK;
+                                    ctx->knobs.pull_threads, s, plan->offsets + batch, cache->filled);   // marks the slots resident too
+    return st;
 }
 
 rg_status rg_plan_sampled(rg_ctx* ctx, int32_t group, const rg_cache* cache, uint32_t* claimed, const rg_prefetch_plan* plan,
