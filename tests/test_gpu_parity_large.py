@@ -10,6 +10,8 @@ batches {0, every 16th, last} (the rows are a pure function of the input-node li
 both compared on every batch).  The oracle runs on a few host threads ahead of the comparisons; that only
 changes when its results are ready.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -20,6 +22,7 @@ from gpu_common import OracleAhead, host_graph, log
 
 pytestmark = pytest.mark.gpu
 PULL_CUS = 16                   # bench.py's default: the launch configuration it times
+SEED = int(os.environ.get("RG_TEST_SEED", "2025"))   # master seed of the generated workloads (another graph, split and schedule per value)
 DEV = "cuda:0"
 
 
@@ -152,7 +155,7 @@ def _host_inputs(wl):
 @pytest.mark.parametrize("name", ["dense_social", "sparse_copurchase"])
 def test_large_workload_both_epochs(name):
     from paper_2505_10806_amd.pipeline import EpochPipeline
-    wl = synth.build_workload(name, seed=2025, device=DEV)
+    wl = synth.build_workload(name, seed=SEED, device=DEV)
     cfg = wl.cfg
     log(f"[large] {name}: N={cfg.num_nodes} nnz={wl.nnz} D={cfg.feat_dim} capacity={wl.capacity_rows}")
     host = _host_inputs(wl)
@@ -173,7 +176,7 @@ def test_large_workload_first_seen_order_and_bitmap_counts():
     """The second canonical node order at full size, with the access counts (and the first batch of every node, which
     drives the prefetch plan) taken straight from the sampler's membership bitmaps: one epoch of sparse_copurchase."""
     from paper_2505_10806_amd.pipeline import EpochPipeline
-    wl = synth.build_workload("sparse_copurchase", seed=2025, device=DEV)
+    wl = synth.build_workload("sparse_copurchase", seed=SEED, device=DEV)
     host = _host_inputs(wl)
     pipe = EpochPipeline(wl, device=DEV, keep_blocks=True, node_order="first_seen", histogram="sampled", pull_cus=PULL_CUS)
     assert pipe.planned
@@ -190,7 +193,7 @@ def test_large_workload_first_seen_order_and_bitmap_counts():
 def test_stress_workload():
     from paper_2505_10806_amd import binding as B
     from paper_2505_10806_amd.pipeline import EpochPipeline
-    wl = synth.build_workload("stress", seed=2025, device=DEV)
+    wl = synth.build_workload("stress", seed=SEED, device=DEV)
     cfg = wl.cfg
     log(f"[stress] N={cfg.num_nodes} nnz={wl.nnz} D={cfg.feat_dim} capacity={wl.capacity_rows}")
     host = _host_inputs(wl)
