@@ -109,6 +109,7 @@ class EpochPipeline:
         # sampled.  The host link then works through the offline stage instead of idling until TopHot is done.
         # keep_rows: rows pulled in an earlier period stay resident (features do not change), so later periods only
         # pull rows no period has named before; off = every period starts from a cold cache.
+        self.no_misses = wl.capacity_rows >= wl.n_remote      # every remote row a period names is selected and pulled
         can_mirror = bool(prefetch and wl.n_remote > 0 and wl.capacity_rows >= wl.n_remote)
         self.mirror = can_mirror if mirror_cache is None else bool(mirror_cache and can_mirror)
         self.keep_rows = bool(keep_rows and self.mirror)
@@ -373,8 +374,11 @@ class EpochPipeline:
         ticket = b % B.RG_GATHER_TICKETS
         if self._tickets.get(ticket) != (id(st), b):
             self._prepare(st, [b])
+        # With a cache that can hold the whole remote partition no batch has miss rows once its pulls are done, so the
+        # (empty) miss pass stays on this stream: the fork to the miss stream and the join back cost every gather more
+        # than the pass itself.
         self.ctx.gather_run(ticket, n, st.cache, self.wl.local_store, self.wl.remote_store, self.cfg.feat_dim, self.out,
-                            hit_stream=main, miss_stream=self.side)
+                            hit_stream=main, miss_stream=main if self.no_misses else self.side)
         self._tickets.pop(ticket, None)
         if self.consumer:
             self.ready[q].record(main)
