@@ -89,8 +89,11 @@ def new_totals(dev):
 
 def timed_reps(pipe, steps, reps):
     """`reps` repetitions of `steps` batches, each from a cold cache, each bracketed by a device synchronisation."""
+    import gc
     import torch
     times = []
+    gc.collect()
+    gc.freeze()            # the workload's and the pipeline's objects are here to stay: keep full collections off the timed region
     for _ in range(reps):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -136,6 +139,7 @@ def gather_roofline(prof, totals, row_bytes):
 def spread(times, steps):
     med = statistics.median(times)
     return {"reps": len(times), "median_ms": med * 1e3, "min_ms": min(times) * 1e3, "max_ms": max(times) * 1e3,
+            "times_ms": [round(t * 1e3, 3) for t in times],
             "batches_per_s_median": steps / med, "batches_per_s_min": steps / max(times), "batches_per_s_max": steps / min(times)}
 
 
@@ -309,6 +313,8 @@ def main():
                     help="mirrored cache only: one pull per sampler call with its list read off the sampler's bitmaps, or one per batch")
     ap.add_argument("--pull-cus", type=int, default=16,
                     help="compute units reserved for the host-link pull kernels (0 = no split): their stream runs on these, every other stream on the rest")
+    ap.add_argument("--coupled-misses", action="store_true",
+                    help="fork to the miss stream and join back for every batch instead of letting the miss rows of consecutive batches follow each other")
     ap.add_argument("--no-mirror", action="store_true",
                     help="do not lay a cache that can hold the whole remote partition out as its mirror (rows are then pulled "
                          "after TopHot, from the prefetch plan, instead of while the batches are being sampled)")
@@ -378,7 +384,7 @@ def main():
                              planned_prefetch=not args.no_plan, sample_group=args.sample_group,
                              histogram=args.histogram, node_order=args.node_order, period_epochs=args.period_epochs,
                              mirror_cache=False if args.no_mirror else None, keep_rows=args.keep_rows, mirror_pulls=args.mirror_pulls,
-                             pull_cus=args.pull_cus,
+                             pull_cus=args.pull_cus, decoupled_misses=not args.coupled_misses,
                              consumer=None if args.consumer == "none" else args.consumer,
                              queue_depth=args.queue_depth if args.consumer != "none" else 1)
 
@@ -453,7 +459,7 @@ def main():
                    "double_buffered_cache": bool(multi_epoch and not args.no_double_buffer),
                    "planned_prefetch": pipe.planned, "consumer": args.consumer, "queue_depth": pipe.queue_depth,
                    "histogram": pipe.histogram, "node_order": args.node_order, "period_epochs": pipe.period_epochs,
-                   "pull_cus": pipe.pull_cus, "mirrored_cache": pipe.mirror, "mirror_pulls": args.mirror_pulls if pipe.mirror else None, "rows_kept_across_epochs": pipe.keep_rows,
+                   "pull_cus": pipe.pull_cus, "decoupled_misses": pipe.decoupled, "mirrored_cache": pipe.mirror, "mirror_pulls": args.mirror_pulls if pipe.mirror else None, "rows_kept_across_epochs": pipe.keep_rows,
                    "GPU_MAX_HW_QUEUES": os.environ.get("GPU_MAX_HW_QUEUES"), "GPU_MAX_HW_QUEUES_set_by": "user" if HWQ_SET_BY_USER else "bench.py"},
         "roofline": {"bound": "hbm", "kernel": "k_gather_hbm", "achieved": roof["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": roof["frac"],

@@ -371,6 +371,19 @@ RG_API rg_status rg_gather_run(rg_ctx* ctx, int32_t ticket, int64_t n, const int
                                const float* remote_store, int64_t remote_stride,
                                int32_t dim, float* out, int64_t out_stride, void* hit_stream, void* miss_stream);
 
+/* One half of rg_gather_run on one stream, with no fork or join: part = RG_GATHER_PART_HBM copies the rows served
+ * from the local store and the cache, RG_GATHER_PART_MISS the miss rows (Section III: the fallback pulls of a batch
+ * overlap other work).  A caller that runs the miss halves of consecutive batches on a stream of their own keeps the
+ * host link busy from one batch to the next instead of forking and joining per batch; it orders the streams itself:
+ * both halves after the ticket's rg_gather_prepare, the batch complete when both are done, and a reused output buffer
+ * free of the earlier batch's halves.  Arguments as for rg_gather_run. */
+#define RG_GATHER_PART_HBM 1
+#define RG_GATHER_PART_MISS 2
+RG_API rg_status rg_gather_run_part(rg_ctx* ctx, int32_t ticket, int32_t part, int64_t n, const int32_t* n_dev,
+                                    const rg_cache* cache, const float* local_store, int64_t local_stride,
+                                    const float* remote_store, int64_t remote_stride, int32_t dim, float* out,
+                                    int64_t out_stride, void* stream);
+
 /* ---- feature assembly for callers that cannot allocate -----------------------------------
  * The same result as rg_gather_features (same arguments, same stream semantics), for callers
  * that must not trigger a device allocation: code under HIP graph capture, tight serving loops,

@@ -21,6 +21,7 @@ RG_MAX_GROUP = 16
 RG_GATHER_TICKETS = 8
 RG_ORDER_ASCENDING, RG_ORDER_FIRST_SEEN = 0, 1
 RG_STATIC_GATHER_MAX_ROWS = 1 << 20
+RG_GATHER_PART_HBM, RG_GATHER_PART_MISS = 1, 2
 RG_K_GATHER_HBM, RG_K_GATHER_MISS, RG_K_SAMPLE, RG_K_HISTOGRAM, RG_K_CACHE_FILL, RG_K_AGGREGATE = range(6)
 
 _STATUS_NAMES = {0: "RG_OK", 1: "RG_ERR_INVALID_ARG", 2: "RG_ERR_CAPACITY", 3: "RG_ERR_OOM",
@@ -96,6 +97,7 @@ def _load():
     L.rg_gather_features.argtypes = [c_p, c_p, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_i64, c_p, c_i64,
                                      c_i32, c_p, c_i64, c_p, c_p, c_p]
     L.rg_gather_features_static.argtypes = L.rg_gather_features.argtypes
+    L.rg_gather_run_part.argtypes = [c_p, c_i32, c_i32, c_i64, c_p, ctypes.POINTER(rg_cache), c_p, c_i64, c_p, c_i64, c_i32, c_p, c_i64, c_p]
     L.rg_profile_enable.argtypes = [c_p, ctypes.c_int]
     L.rg_profile_reset.argtypes = [c_p]
     L.rg_profile_select.argtypes = [c_p, ctypes.c_uint32]
@@ -104,7 +106,7 @@ def _load():
                  "rg_access_histogram", "rg_access_histogram_epoch", "rg_access_histogram_sampled", "rg_build_cache", "rg_cache_hit_curve",
                  "rg_prefetch_cache_rows", "rg_plan_prefetch", "rg_plan_sampled", "rg_prefetch_planned", "rg_gather_features",
                  "rg_gather_features_static", "rg_gather_prepare", "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable",
-                 "rg_profile_reset", "rg_profile_read", "rg_profile_select", "rg_stream_create", "rg_stream_destroy"):
+                 "rg_profile_reset", "rg_profile_read", "rg_profile_select", "rg_stream_create", "rg_stream_destroy", "rg_gather_run_part"):
         getattr(L, name).restype = ctypes.c_int
     return L
 
@@ -116,7 +118,7 @@ EXPORTED_SYMBOLS = ["rg_create", "rg_destroy", "rg_last_error", "rg_version", "r
                     "rg_access_histogram_epoch", "rg_access_histogram_sampled",
                     "rg_build_cache", "rg_cache_hit_curve", "rg_prefetch_cache_rows", "rg_plan_prefetch",
                     "rg_plan_sampled", "rg_prefetch_planned", "rg_gather_features", "rg_gather_features_static",
-                    "rg_stream_create", "rg_stream_destroy", "rg_gather_prepare",
+                    "rg_stream_create", "rg_stream_destroy", "rg_gather_prepare", "rg_gather_run_part",
                     "rg_gather_run", "rg_mean_aggregate", "rg_profile_enable", "rg_profile_select", "rg_profile_reset", "rg_profile_read"]
 
 
@@ -338,6 +340,13 @@ class Context:
             _ptr(remote_store, torch.float32, "mapped", "remote_store"), remote_store.stride(0),
             int(dim), _ptr(out, torch.float32, "cuda", "out"), out.stride(0), _stream_handle(hit_stream),
             None if miss_stream is None else _stream_handle(miss_stream)))
+
+    def gather_run_part(self, ticket, part, n, cache, local_store, remote_store, dim, out, n_dev=None, stream=None):
+        self._check(_lib.rg_gather_run_part(
+            self._h, int(ticket), int(part), int(n), _ptr(n_dev, torch.int32, "cuda", "n_dev"), ctypes.byref(cache.c_struct),
+            _ptr(local_store, torch.float32, "cuda", "local_store"), local_store.stride(0),
+            _ptr(remote_store, torch.float32, "mapped", "remote_store"), remote_store.stride(0),
+            int(dim), _ptr(out, torch.float32, "cuda", "out"), out.stride(0), _stream_handle(stream)))
 
     # -- rg_mean_aggregate
     def mean_aggregate(self, indptr, nbr_local, n_dst, feat, dim, agg, n_dst_dev=None, stream=None):

@@ -276,8 +276,10 @@ rg_status launch_classify(rg_ctx* ctx, int count, const int32_t* const* input_no
 // Every argument has been validated by the caller; `timed` brackets the kernels for rg_profile_read.
 rg_status launch_copies(rg_ctx* ctx, const GatherScratch& scr, int64_t n, const int32_t* n_dev, const rg_cache* cache,
                         const float* local_store, int64_t local_stride, const float* remote_store, int64_t remote_stride,
-                        int32_t dim, float* out, int64_t out_stride, hipStream_t sh, hipStream_t sm, bool timed) {
-    const bool two_streams = sm != sh;
+                        int32_t dim, float* out, int64_t out_stride, hipStream_t sh, hipStream_t sm, bool timed,
+                        int parts = RG_GATHER_PART_HBM | RG_GATHER_PART_MISS) {
+    const bool do_hbm = parts & RG_GATHER_PART_HBM, do_miss = parts & RG_GATHER_PART_MISS;
+    const bool two_streams = sm != sh && do_hbm && do_miss;      // one part alone: no fork, no join, the caller orders the streams
     if (two_streams) {
         RG_HIP(ctx, hipEventRecord(ctx->ev_classified, sh));
         RG_HIP(ctx, hipStreamWaitEvent(sm, ctx->ev_classified, 0));
@@ -297,28 +299,33 @@ rg_status launch_copies(rg_ctx* ctx, const GatherScratch& scr, int64_t n, const 
     const float inv_cpr = 1.0f / (float)shp.cpr;
     const float* cache_rows = cache->cache_rows ? cache->cache_rows : local_store;   // never dereferenced without cache words
 
-    int tok = timed ? rg_prof_begin(ctx, RG_K_GATHER_HBM, sh) : -1;
+    int tok = -1;
+    if (do_hbm) {
+        tok = timed ? rg_prof_begin(ctx, RG_K_GATHER_HBM, sh) : -1;
 #define RG_LAUNCH_HBM(V, TT)                                                                                            \
-    k_gather_hbm<V, TT><<<grid, 256, 0, sh>>>(scr.src, n, n_dev, local_store, local_stride, cache_rows, cache->row_stride, \
-                                              out, out_stride, shp.cpr, inv_cpr, shp.tail)
-    if (vec == 4) { if (T == 2) RG_LAUNCH_HBM(4, 2); else if (T == 8) RG_LAUNCH_HBM(4, 8); else RG_LAUNCH_HBM(4, 4); }
-    else if (vec == 2) RG_LAUNCH_HBM(2, 4);
-    else RG_LAUNCH_HBM(1, 4);
+        k_gather_hbm<V, TT><<<grid, 256, 0, sh>>>(scr.src, n, n_dev, local_store, local_stride, cache_rows, cache->row_stride, \
+                                                  out, out_stride, shp.cpr, inv_cpr, shp.tail)
+        if (vec == 4) { if (T == 2) RG_LAUNCH_HBM(4, 2); else if (T == 8) RG_LAUNCH_HBM(4, 8); else RG_LAUNCH_HBM(4, 4); }
+        else if (vec == 2) RG_LAUNCH_HBM(2, 4);
+        else RG_LAUNCH_HBM(1, 4);
 #undef RG_LAUNCH_HBM
-    rg_prof_end(ctx, tok, sh);
-    RG_LAUNCH_CHECK(ctx, "k_gather_hbm");
+        rg_prof_end(ctx, tok, sh);
+        RG_LAUNCH_CHECK(ctx, "k_gather_hbm");
+    }
 
-    const int miss_threads = ctx->knobs.miss_threads;
-    const int miss_rows_per_block = (miss_threads / RG_WAVE) * (RG_WAVE >> shp.log2L) * U;
-    const int miss_grid = (int)rg_max64(1, rg_min64(rg_div_up(n, miss_rows_per_block), ctx->knobs.miss_blocks));
-    tok = timed ? rg_prof_begin(ctx, RG_K_GATHER_MISS, sm) : -1;
+    if (do_miss) {
+        const int miss_threads = ctx->knobs.miss_threads;
+        const int miss_rows_per_block = (miss_threads / RG_WAVE) * (RG_WAVE >> shp.log2L) * U;
+        const int miss_grid = (int)rg_max64(1, rg_min64(rg_div_up(n, miss_rows_per_block), ctx->knobs.miss_blocks));
+        tok = timed ? rg_prof_begin(ctx, RG_K_GATHER_MISS, sm) : -1;
 #define RG_LAUNCH_MISS(V)                                                                                               \
-    k_gather_miss<V, U><<<miss_grid, miss_threads, 0, sm>>>(scr.miss_list, scr.gctl, remote_store, remote_stride, out, out_stride, \
-                                                            shp.cpr, shp.log2L, shp.tail)
-    if (vec == 4) RG_LAUNCH_MISS(4); else if (vec == 2) RG_LAUNCH_MISS(2); else RG_LAUNCH_MISS(1);
+        k_gather_miss<V, U><<<miss_grid, miss_threads, 0, sm>>>(scr.miss_list, scr.gctl, remote_store, remote_stride, out, out_stride, \
+                                                                shp.cpr, shp.log2L, shp.tail)
+        if (vec == 4) RG_LAUNCH_MISS(4); else if (vec == 2) RG_LAUNCH_MISS(2); else RG_LAUNCH_MISS(1);
 #undef RG_LAUNCH_MISS
-    rg_prof_end(ctx, tok, sm);
-    RG_LAUNCH_CHECK(ctx, "k_gather_miss");
+        rg_prof_end(ctx, tok, sm);
+        RG_LAUNCH_CHECK(ctx, "k_gather_miss");
+    }
     if (two_streams) {
         RG_HIP(ctx, hipEventRecord(ctx->ev_miss_done, sm));
         RG_HIP(ctx, hipStreamWaitEvent(sh, ctx->ev_miss_done, 0));
@@ -419,6 +426,26 @@ rg_status rg_gather_features(rg_ctx* ctx, const int32_t* input_nodes, int64_t n,
     if (st != RG_OK) return st;
     return rg_gather_run(ctx, 0, n, n_dev, cache, local_store, local_stride, remote_store, remote_stride, dim, out, out_stride,
                          hit_stream, miss_stream);
+}
+
+rg_status rg_gather_run_part(rg_ctx* ctx, int32_t ticket, int32_t part, int64_t n, const int32_t* n_dev, const rg_cache* cache,
+                             const float* local_store, int64_t local_stride, const float* remote_store, int64_t remote_stride,
+                             int32_t dim, float* out, int64_t out_stride, void* stream) {
+    if (!ctx) return RG_ERR_INVALID_ARG;
+    RG_REQUIRE(ctx, ticket >= 0 && ticket < RG_GATHER_TICKETS, "rg_gather_run_part: ticket = %d not in [0,%d)", ticket, RG_GATHER_TICKETS);
+    RG_REQUIRE(ctx, part == RG_GATHER_PART_HBM || part == RG_GATHER_PART_MISS, "rg_gather_run_part: part = %d is neither "
+               "RG_GATHER_PART_HBM nor RG_GATHER_PART_MISS", part);
+    rg_status st = check_copy_args(ctx, "rg_gather_run_part", n, dim, cache, local_store, local_stride, remote_store, remote_stride, out, out_stride);
+    if (st != RG_OK) return st;
+    if (ctx->gather_rows[ticket] != n)
+        return rg_set_error(ctx, RG_ERR_STATE, "rg_gather_run_part: ticket %d was prepared for %lld rows, not %lld", ticket,
+                            (long long)ctx->gather_rows[ticket], (long long)n);
+    if (n == 0) return RG_OK;
+    RG_HIP(ctx, hipSetDevice(ctx->device));
+    if ((st = rg_check_device_readable(ctx, remote_store, "rg_gather_run_part: remote_store")) != RG_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    return launch_copies(ctx, ticket_scratch(ctx, ticket), n, n_dev, cache, local_store, local_stride, remote_store, remote_stride,
+                         dim, out, out_stride, s, s, true, part);
 }
 
 rg_status rg_gather_features_static(rg_ctx* ctx, const int32_t* input_nodes, int64_t n, const int32_t* n_dev,

@@ -54,7 +54,7 @@ class EpochPipeline:
                  histogram="epoch", sampler_streams=2, double_buffer=False,
                  queue_depth=1, consumer=None, planned_prefetch=True, sample_group=8, keep_blocks=False,
                  node_order="ascending", period_epochs=1, mirror_cache=None, keep_rows=False, mirror_pulls="group",
-                 pull_cus=0):
+                 pull_cus=0, decoupled_misses=True):
         cfg = wl.cfg
         self.wl, self.cfg, self.device = wl, cfg, device
         self.H = len(cfg.fanouts)
@@ -99,6 +99,12 @@ class EpochPipeline:
             raise ValueError("consumer must be None or 'mean'")
         self.consumer = consumer
         self.queue_depth = max(1, int(queue_depth))
+        # decoupled misses: when batches can have miss rows, their copies over the host link run on the miss stream one
+        # batch behind the other with nothing between them (forked once per group of lookups instead of once per batch,
+        # joined per batch on the gather stream only), which needs a second output buffer to write ahead into
+        self.decoupled = bool(decoupled_misses and two_streams and wl.capacity_rows < wl.n_remote)
+        if self.decoupled:
+            self.queue_depth = max(self.queue_depth, 2)
         # keep_blocks: every hop's block of every batch stays in per-batch buffers (the sampler writes them there
         # directly), e.g. to hand whole message-flow graphs to a trainer or to compare them after the epoch
         hops = range(self.H) if keep_blocks else ([self.H - 1] if consumer else [])
@@ -139,6 +145,9 @@ class EpochPipeline:
         self.consumer_stream = torch.cuda.Stream(device=device) if consumer else None
         self.ready = [torch.cuda.Event() for _ in range(self.queue_depth)]
         self.consumed = [torch.cuda.Event() for _ in range(self.queue_depth)]
+        self.rows_done = [torch.cuda.Event() for _ in range(self.queue_depth)]   # HBM-served half of the slot's batch copied
+        self.miss_done = [torch.cuda.Event() for _ in range(self.queue_depth)]   # miss half copied
+        self.prep_done = torch.cuda.Event()                                      # lookups of the current group of tickets made
         self.agg = (torch.empty(max(self.bufs.frontier_ub[self.H - 1], 1), wl.stride, dtype=torch.float32, device=device)
                     if consumer else None)
         self._gathered = 0
@@ -377,8 +386,19 @@ class EpochPipeline:
         # With a cache that can hold the whole remote partition no batch has miss rows once its pulls are done, so the
         # (empty) miss pass stays on this stream: the fork to the miss stream and the join back cost every gather more
         # than the pass itself.
-        self.ctx.gather_run(ticket, n, st.cache, self.wl.local_store, self.wl.remote_store, self.cfg.feat_dim, self.out,
-                            hit_stream=main, miss_stream=main if self.no_misses else self.side)
+        if self.decoupled:
+            side, args = self.side, (n, st.cache, self.wl.local_store, self.wl.remote_store, self.cfg.feat_dim, self.out)
+            side.wait_event(self.rows_done[q])          # the buffer's earlier batch: its HBM half (its miss half ran on this stream)
+            if self.consumer:
+                side.wait_event(self.consumed[q])
+            self.ctx.gather_run_part(ticket, B.RG_GATHER_PART_MISS, *args, stream=side)
+            self.miss_done[q].record(side)
+            self.ctx.gather_run_part(ticket, B.RG_GATHER_PART_HBM, *args, stream=main)
+            self.rows_done[q].record(main)
+            main.wait_event(self.miss_done[q])          # the batch is whole on this stream
+        else:
+            self.ctx.gather_run(ticket, n, st.cache, self.wl.local_store, self.wl.remote_store, self.cfg.feat_dim, self.out,
+                                hit_stream=main, miss_stream=main if self.no_misses else self.side)
         self._tickets.pop(ticket, None)
         if self.consumer:
             self.ready[q].record(main)
@@ -397,6 +417,10 @@ class EpochPipeline:
                                 [st.stats[b] for b in batches])
         for b in batches:
             self._tickets[b % B.RG_GATHER_TICKETS] = (id(st), b)
+        if self.decoupled:                              # the one fork of the group: the miss stream reads the lookups' lists
+            main = torch.cuda.current_stream()
+            self.prep_done.record(main)
+            self.side.wait_event(self.prep_done)
 
     def prefetch_rows(self, b, stream=None, st=None):
         """Pull the not-yet-resident cached rows batch b needs (asynchronous on `stream`).  The row count is

@@ -1177,6 +1177,64 @@ def test_gather_prepare_group_then_run(B, ctx):
     c2.close()
 
 
+def test_gather_halves_on_streams_of_their_own(B, ctx):
+    """rg_gather_run_part: the HBM-served rows of each batch on one stream, the miss rows on another with the miss halves
+    of consecutive batches queued one behind the other (forked once after the lookups, joined per batch), each half
+    writing only its own rows; together they give the oracle's rows.  Wrong part values and unprepared tickets are refused."""
+    rng = np.random.default_rng(21)
+    n_nodes, dim = 5000, 37
+    stride = synth.stores.row_stride(dim)
+    X = rng.standard_normal((n_nodes, dim)).astype(np.float32)
+    is_local = torch.from_numpy(rng.random(n_nodes) < 0.5)
+    home = synth.stores.make_home(is_local)
+    home_np = home.numpy()
+    local = torch.zeros(int(is_local.sum()), stride, device=DEV)
+    local[:, :dim] = torch.from_numpy(X)[is_local].to(DEV)
+    remote = torch.zeros(int((~is_local).sum()), stride, pin_memory=True)
+    remote[:, :dim] = torch.from_numpy(X)[~is_local]
+    sizes = (900, 3000, 0, 1, 4097, 64)
+    batches = [rng.integers(0, n_nodes, size=k).astype(np.int32) for k in sizes]
+    counts_orc = np.zeros(n_nodes, dtype=np.uint32)
+    for b in batches:
+        oracle.access_histogram(b, counts_orc)
+    cap = 400
+    ids_orc, loc_orc = oracle.build_cache(counts_orc, home_np, cap)
+    counts = torch.as_tensor(counts_orc.view(np.int32), device=DEV)
+    cache = B.FeatureCache(n_nodes, cap, stride, DEV)
+    ctx.build_cache(counts, home.to(DEV), remote, dim, cache)
+    nodes_dev = [torch.as_tensor(b, device=DEV) if b.size else torch.empty(1, dtype=torch.int32, device=DEV) for b in batches]
+    stats = torch.full((len(sizes), 3), -1, dtype=torch.int64, device=DEV)
+    outs = [torch.full((max(k, 1), stride), float("nan"), device=DEV) for k in sizes]
+    rows_s, miss_s = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(rows_s):
+        ctx.gather_prepare(0, nodes_dev, sizes, cache, [stats[t] for t in range(len(sizes))])
+    ready = torch.cuda.Event()
+    ready.record(rows_s)
+    miss_s.wait_event(ready)                              # the one fork
+    for t, k in enumerate(sizes):                         # every miss half first: they follow each other on their stream
+        ctx.gather_run_part(t, B.RG_GATHER_PART_MISS, k, cache, local, remote, dim, outs[t], stream=miss_s)
+    miss_s.synchronize()
+    want1, st1 = oracle.gather_features(X, batches[1], loc_orc)
+    got1 = outs[1][:sizes[1], :dim].cpu().numpy()
+    is_miss = ((loc_orc[batches[1]].astype(np.int64) & 0xFFFFFFFF) >> 30) == 2
+    assert st1[2] == int(is_miss.sum()) > 0 and np.array_equal(got1[is_miss], want1[is_miss]) and np.isnan(got1[~is_miss]).all()
+    for t, k in enumerate(sizes):
+        ctx.gather_run_part(t, B.RG_GATHER_PART_HBM, k, cache, local, remote, dim, outs[t], stream=rows_s)
+    torch.cuda.synchronize()
+    for t, k in enumerate(sizes):
+        want, st = oracle.gather_features(X, batches[t], loc_orc)
+        assert tuple(stats[t].cpu().tolist()) == st, t
+        assert np.array_equal(outs[t][:k, :dim].cpu().numpy(), want), t
+    for bad in (0, 3, 4):
+        with pytest.raises(B.RgError) as e:
+            ctx.gather_run_part(0, bad, sizes[0], cache, local, remote, dim, outs[0])
+        assert e.value.status == B.RG_ERR_INVALID_ARG
+    with pytest.raises(B.RgError) as e:
+        ctx.gather_run_part(0, B.RG_GATHER_PART_MISS, sizes[0] + 1, cache, local, remote, dim, outs[1])
+    assert e.value.status == B.RG_ERR_STATE
+
+
 # ------------------------------------------------------------------------------ histogram
 def test_histogram_with_repeats_and_device_count(B, ctx):
     rng = np.random.default_rng(4)
