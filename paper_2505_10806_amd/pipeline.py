@@ -147,7 +147,8 @@ class EpochPipeline:
         self.consumed = [torch.cuda.Event() for _ in range(self.queue_depth)]
         self.rows_done = [torch.cuda.Event() for _ in range(self.queue_depth)]   # HBM-served half of the slot's batch copied
         self.miss_done = [torch.cuda.Event() for _ in range(self.queue_depth)]   # miss half copied
-        self.prep_done = torch.cuda.Event()                                      # lookups of the current group of tickets made
+        self.prep_done = [torch.cuda.Event(), torch.cuda.Event()]                # lookups of a group made (one per half of the tickets)
+        self._fork_due = {}                                                      # first ticket of a prepared group -> its half
         self.agg = (torch.empty(max(self.bufs.frontier_ub[self.H - 1], 1), wl.stride, dtype=torch.float32, device=device)
                     if consumer else None)
         self._gathered = 0
@@ -388,6 +389,9 @@ class EpochPipeline:
         # than the pass itself.
         if self.decoupled:
             side, args = self.side, (n, st.cache, self.wl.local_store, self.wl.remote_store, self.cfg.feat_dim, self.out)
+            half = self._fork_due.pop(ticket, None)
+            if half is not None:
+                side.wait_event(self.prep_done[half])   # the one fork of the group: the miss stream reads the lookups' lists
             side.wait_event(self.rows_done[q])          # the buffer's earlier batch: its HBM half (its miss half ran on this stream)
             if self.consumer:
                 side.wait_event(self.consumed[q])
@@ -417,10 +421,10 @@ class EpochPipeline:
                                 [st.stats[b] for b in batches])
         for b in batches:
             self._tickets[b % B.RG_GATHER_TICKETS] = (id(st), b)
-        if self.decoupled:                              # the one fork of the group: the miss stream reads the lookups' lists
-            main = torch.cuda.current_stream()
-            self.prep_done.record(main)
-            self.side.wait_event(self.prep_done)
+        if self.decoupled:                              # the miss stream waits for it when it reaches the group's first batch
+            half = (first * 2) // B.RG_GATHER_TICKETS
+            self.prep_done[half].record(torch.cuda.current_stream())
+            self._fork_due[first] = half
 
     def prefetch_rows(self, b, stream=None, st=None):
         """Pull the not-yet-resident cached rows batch b needs (asynchronous on `stream`).  The row count is
@@ -451,9 +455,17 @@ class EpochPipeline:
         if self.prefetch and not st.pulls_queued:
             self.pf_stream.wait_stream(main)
         main.wait_event(st.built)                       # the offline stage may have run on other streams
+        # Lookups are made for a group of batches at a time.  With decoupled misses the groups are half the tickets and
+        # the lookups of the next group are queued before the current group's gathers (its tickets are those of the
+        # group before, which is complete), so the miss stream finds the next group's lists ready when it gets there.
+        G = B.RG_GATHER_TICKETS // 2 if self.decoupled else B.RG_GATHER_TICKETS
+        group_of = lambda b0: list(range(b0, min(b0 + G, n_batches)))
         for b in range(n_batches):
-            if b % B.RG_GATHER_TICKETS == 0:
-                self._prepare(st, list(range(b, min(b + B.RG_GATHER_TICKETS, n_batches))))
+            if b % G == 0:
+                if not self.decoupled or b == 0:
+                    self._prepare(st, group_of(b))
+                if self.decoupled and b + G < n_batches:
+                    self._prepare(st, group_of(b + G))
             if self.prefetch:
                 if not st.pulls_queued:
                     self.prefetch_rows(b, stream=self.pf_stream)
