@@ -8,6 +8,16 @@ batches, count accesses, TopHot, VectorPull) followed by the online per-batch fe
   precomputed on another stream into the second buffer set, its rows are pulled behind epoch e's, and the
   buffers are swapped at the epoch boundary.
 
+Further choices of the driver, each a constructor argument:
+
+* a cache that can hold the whole remote partition is laid out as its mirror and filled while the batches are still
+  being sampled, one pull per sampler call, its rows read off the sampler's membership bitmaps (mirror_cache,
+  mirror_pulls, keep_rows);
+* the pull stream can be bound to a few compute units of its own, every other stream to the rest (pull_cus; the
+  caller then works on work_stream);
+* when batches can have miss rows, their copies follow each other on the miss stream instead of being forked and
+  joined per batch (decoupled_misses); when they cannot, the empty miss pass stays on the gather stream.
+
 Host code only sequences library calls and owns the buffers; every step runs in the library's kernels.
 No host synchronisation happens inside the offline stage: frontier sizes stay on the device.  They are
 copied to pinned host memory as soon as the last batch has been sampled, so the host can size and queue the
